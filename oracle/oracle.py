@@ -1,0 +1,364 @@
+"""Python face of the CPU oracle -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes marshalling over `psc_oracle.c` (all arithmetic of the search path
+is in that file, in double precision), plus the two training steps that are
+naturally array code: Lloyd k-means for the product quantizer and the loop over
+sub-quantizers around the annealing of the index assignment.
+
+Nothing in the product path may import this module.
+
+Unpinned (only invariants are tested): the k-means codebook and the annealing
+trajectory; see the tests named test_oracle_*.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+__all__ = [
+    "hamming", "hamming_matrix", "encode", "decode", "build_lut", "query_codes", "scan",
+    "search_flat", "ivf_search", "knn_graph", "exact_knn", "recall_at", "train_pq",
+    "centroid_distances", "distance_stats", "f_map", "targets_weights", "polyd_loss",
+    "swap_delta", "anneal", "apply_assignment", "optimize_index_assignment", "draw_u64",
+    "ivf_train_coarse", "ivf_build_lists", "kmeans", "nearest", "num_threads",
+]
+
+_lib = None
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(_build.build())
+        _lib.orc_f.restype = C.c_double
+        _lib.orc_polyd_loss.restype = C.c_double
+        _lib.orc_swap_delta.restype = C.c_double
+        _lib.orc_draw_u64.restype = C.c_uint64
+        _lib.orc_draw_u64.argtypes = [C.c_uint64, C.c_uint64]
+    return _lib
+
+
+def num_threads() -> int:
+    """Threads the OpenMP loops of the oracle use (OMP_NUM_THREADS or the core count)."""
+    v = os.environ.get("OMP_NUM_THREADS")
+    if v:
+        try:
+            return int(v.split(",")[0])
+        except ValueError:
+            pass
+    return os.cpu_count() or 1
+
+
+def _p(a, t=C.c_void_p):
+    return a.ctypes.data_as(t) if a is not None else None
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _u8(a):
+    return np.ascontiguousarray(a, dtype=np.uint8)
+
+
+# ----------------------------------------------------------------------------- Hamming
+def hamming(a, b) -> int:
+    a, b = _u8(a).ravel(), _u8(b).ravel()
+    assert a.size == b.size
+    return int(_L().orc_hamming(_p(a), _p(b), C.c_int(a.size)))
+
+
+def hamming_matrix(qcodes, codes) -> np.ndarray:
+    qcodes, codes = _u8(qcodes), _u8(codes)
+    nq, m = qcodes.shape
+    n = codes.shape[0]
+    out = np.empty((nq, n), dtype=np.int32)
+    _L().orc_hamming_matrix(_p(qcodes), C.c_int64(nq), _p(codes), C.c_int64(n), C.c_int(m), _p(out))
+    return out
+
+
+# ----------------------------------------------------------------------------- PQ codes, tables
+def encode(x, codebook) -> np.ndarray:
+    """codes [n, m] uint8; codebook [m, 256, dsub]."""
+    x, cb = _f64(x), _f64(codebook)
+    m, nc, dsub = cb.shape
+    assert nc == 256 and x.shape[1] == m * dsub
+    codes = np.empty((x.shape[0], m), dtype=np.uint8)
+    _L().orc_encode(_p(x), C.c_int64(x.shape[0]), C.c_int(m * dsub), C.c_int(m), _p(cb), _p(codes))
+    return codes
+
+
+def decode(codes, codebook) -> np.ndarray:
+    codes, cb = _u8(codes), _f64(codebook)
+    m, _, dsub = cb.shape
+    x = np.empty((codes.shape[0], m * dsub), dtype=np.float64)
+    _L().orc_decode(_p(codes), C.c_int64(codes.shape[0]), C.c_int(m * dsub), C.c_int(m), _p(cb), _p(x))
+    return x
+
+
+def build_lut(queries, codebook) -> np.ndarray:
+    """lut [nq, m, 256] float64: squared distance of query sub-vector j to centroid c."""
+    q, cb = _f64(queries), _f64(codebook)
+    m, _, dsub = cb.shape
+    assert q.shape[1] == m * dsub
+    lut = np.empty((q.shape[0], m, 256), dtype=np.float64)
+    _L().orc_build_lut(_p(q), C.c_int64(q.shape[0]), C.c_int(m * dsub), C.c_int(m), _p(cb), _p(lut))
+    return lut
+
+
+def query_codes(lut) -> np.ndarray:
+    lut = _f64(lut)
+    nq, m, _ = lut.shape
+    qc = np.empty((nq, m), dtype=np.uint8)
+    _L().orc_query_codes(_p(lut), C.c_int64(nq), C.c_int(m), _p(qc))
+    return qc
+
+
+# ----------------------------------------------------------------------------- scans
+def scan(lut, qcodes, codes, ht: int, k: int, ext_ids=None, skip_id=None, want_bitmap=False):
+    """Hamming filter (keep iff distance <= ht), ADC on survivors, first k by (dist, id).
+
+    Returns dict(ids [nq,k] int64, dists [nq,k] float64, nsurv [nq] int64[, bitmap [nq,n] uint8]).
+    """
+    lut, qcodes, codes = _f64(lut), _u8(qcodes), _u8(codes)
+    nq, m, _ = lut.shape
+    n = codes.shape[0]
+    assert qcodes.shape == (nq, m) and (n == 0 or codes.shape[1] == m)
+    ids = np.empty((nq, k), dtype=np.int64)
+    dists = np.empty((nq, k), dtype=np.float64)
+    nsurv = np.zeros(nq, dtype=np.int64)
+    ext = np.ascontiguousarray(ext_ids, dtype=np.int64) if ext_ids is not None else None
+    skip = np.ascontiguousarray(skip_id, dtype=np.int64) if skip_id is not None else None
+    bitmap = np.zeros((nq, n), dtype=np.uint8) if want_bitmap else None
+    rc = _L().orc_scan(C.c_int(m), _p(lut), _p(qcodes), C.c_int64(nq), _p(codes), C.c_int64(n),
+                       C.c_int(ht), C.c_int(k), _p(ext), _p(skip), _p(ids), _p(dists), _p(nsurv),
+                       _p(bitmap))
+    if rc != 0:
+        raise MemoryError("oracle scan")
+    out = dict(ids=ids, dists=dists, nsurv=nsurv)
+    if want_bitmap:
+        out["bitmap"] = bitmap
+    return out
+
+
+def search_flat(queries, codebook, codes, ht: int, k: int, **kw):
+    """Whole flat path: tables from the raw queries, query codes, then `scan`."""
+    lut = build_lut(queries, codebook)
+    return scan(lut, query_codes(lut), codes, ht, k, **kw)
+
+
+def ivf_search(queries, codebook, coarse, offsets, codes, list_ids, nprobe: int, ht: int, k: int):
+    q, cb, cc = _f64(queries), _f64(codebook), _f64(coarse)
+    m, _, dsub = cb.shape
+    D = m * dsub
+    nlist = cc.shape[0]
+    offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+    codes = _u8(codes)
+    list_ids = np.ascontiguousarray(list_ids, dtype=np.int32)
+    nq = q.shape[0]
+    npb = min(nprobe, nlist)
+    ids = np.empty((nq, k), dtype=np.int64)
+    dists = np.empty((nq, k), dtype=np.float64)
+    nsurv = np.zeros(nq, dtype=np.int64)
+    probed = np.empty((nq, npb), dtype=np.int32)
+    rc = _L().orc_ivf_search(C.c_int(D), C.c_int(m), _p(cb), _p(cc), C.c_int(nlist), _p(offsets),
+                             _p(codes), _p(list_ids), _p(q), C.c_int64(nq), C.c_int(nprobe),
+                             C.c_int(ht), C.c_int(k), _p(ids), _p(dists), _p(nsurv), _p(probed))
+    if rc != 0:
+        raise MemoryError("oracle ivf search")
+    return dict(ids=ids, dists=dists, nsurv=nsurv, probed=probed)
+
+
+def knn_graph(x, codebook, codes, ht: int, k: int, rows=None, chunk: int = 1024):
+    """k-NN graph mode (Section 5): every database vector in turn is the query; its bit
+    string is its own stored code, its tables come from the raw vector, and it is not
+    its own neighbour.  `rows` restricts the computation to those row numbers."""
+    x = np.asarray(x)
+    codes = _u8(codes)
+    rows = np.arange(x.shape[0], dtype=np.int64) if rows is None else np.asarray(rows, dtype=np.int64)
+    ids = np.empty((rows.size, k), dtype=np.int64)
+    dists = np.empty((rows.size, k), dtype=np.float64)
+    nsurv = np.empty(rows.size, dtype=np.int64)
+    for s in range(0, rows.size, chunk):
+        r = rows[s:s + chunk]
+        lut = build_lut(x[r], codebook)
+        o = scan(lut, codes[r], codes, ht, k, skip_id=r)
+        ids[s:s + r.size], dists[s:s + r.size], nsurv[s:s + r.size] = o["ids"], o["dists"], o["nsurv"]
+    return dict(ids=ids, dists=dists, nsurv=nsurv)
+
+
+def exact_knn(x, queries, k: int, skip_self: bool = False):
+    x, q = _f64(x), _f64(queries)
+    ids = np.empty((q.shape[0], k), dtype=np.int64)
+    dists = np.empty((q.shape[0], k), dtype=np.float64)
+    rc = _L().orc_exact_knn(_p(x), C.c_int64(x.shape[0]), _p(q), C.c_int64(q.shape[0]),
+                            C.c_int(x.shape[1]), C.c_int(k), C.c_int(int(skip_self)), _p(ids), _p(dists))
+    if rc != 0:
+        raise MemoryError("oracle exact knn")
+    return ids, dists
+
+
+def recall_at(result_ids, true_nn, R: int) -> float:
+    """Fraction of queries whose true nearest neighbour is among the first R results
+    (Section 4.1)."""
+    result_ids = np.asarray(result_ids)[:, :R]
+    true_nn = np.asarray(true_nn).reshape(-1, 1)
+    return float((result_ids == true_nn).any(axis=1).mean())
+
+
+# ----------------------------------------------------------------------------- training
+def nearest(x, cent):
+    """Index of the nearest centroid (lowest index on ties) and squared distance to it."""
+    x, cent = _f64(x), _f64(cent)
+    assign = np.empty(x.shape[0], dtype=np.int64)
+    dmin = np.empty(x.shape[0], dtype=np.float64)
+    _L().orc_nearest(_p(x), C.c_int64(x.shape[0]), C.c_int(x.shape[1]), _p(cent),
+                     C.c_int(cent.shape[0]), _p(assign), _p(dmin))
+    return assign, dmin
+
+
+def kmeans(x, ncent: int, iters: int, seed: int):
+    """Lloyd k-means.  Start: `ncent` distinct training rows drawn with numpy's default
+    generator seeded by `seed`.  An empty cluster is re-seeded with the point of the most
+    populated cluster that lies farthest from that cluster's centroid.  Returns
+    (centroids [ncent, d] float64, objective after each assignment step)."""
+    x = _f64(x)
+    n, _ = x.shape
+    rng = np.random.default_rng(seed)
+    cent = x[rng.choice(n, size=ncent, replace=False)].copy()
+    objective = []
+    for _ in range(iters):
+        assign, dmin = nearest(x, cent)
+        objective.append(float(dmin.sum()))
+        counts = np.bincount(assign, minlength=ncent)
+        for c in range(ncent):
+            if counts[c] > 0:
+                cent[c] = x[assign == c].mean(axis=0)
+        for c in np.flatnonzero(counts == 0):
+            big = int(counts.argmax())
+            members = np.flatnonzero(assign == big)
+            far = members[dmin[members].argmax()]
+            cent[c] = x[far]
+            assign[far] = c
+            counts[big] -= 1
+            counts[c] += 1
+            dmin[far] = 0.0
+    return cent, objective
+
+
+def train_pq(x, m: int, iters: int = 20, seed: int = 0):
+    """Product quantizer: one k-means of 256 centroids per sub-space (Section 3, opening).
+    Returns codebook [m, 256, dsub] float64."""
+    x = _f64(x)
+    dsub = x.shape[1] // m
+    cb = np.empty((m, 256, dsub), dtype=np.float64)
+    for j in range(m):
+        cb[j], _ = kmeans(x[:, j * dsub:(j + 1) * dsub], 256, iters, seed + j)
+    return cb
+
+
+def ivf_train_coarse(x, nlist: int, iters: int = 10, seed: int = 0):
+    cent, _ = kmeans(x, nlist, iters, seed)
+    return cent
+
+
+def ivf_build_lists(x, coarse, codebook, base_id: int = 0):
+    """Assign each vector to its nearest coarse centroid (lowest list on ties), encode the
+    residual, group by list keeping the original order inside a list.
+    Returns offsets [nlist+1] int64, codes [n, m] uint8, ids [n] int32, list_no [n] int32."""
+    x, cc = _f64(x), _f64(coarse)
+    nlist = cc.shape[0]
+    list_no = nearest(x, cc)[0].astype(np.int32)
+    res = x - cc[list_no]
+    codes = encode(res, codebook)
+    order = np.argsort(list_no, kind="stable")
+    counts = np.bincount(list_no, minlength=nlist)
+    offsets = np.zeros(nlist + 1, dtype=np.int64)
+    offsets[1:] = np.cumsum(counts)
+    return offsets, codes[order], (order + base_id).astype(np.int32), list_no
+
+
+# ----------------------------------------------------------------------------- index assignment
+def centroid_distances(cent) -> np.ndarray:
+    cent = _f64(cent)
+    assert cent.shape[0] == 256
+    dmat = np.empty((256, 256), dtype=np.float64)
+    _L().orc_centroid_distances(_p(cent), C.c_int(cent.shape[1]), _p(dmat))
+    return dmat
+
+
+def distance_stats(dmat):
+    dmat = _f64(dmat)
+    mu, sigma = C.c_double(), C.c_double()
+    _L().orc_distance_stats(_p(dmat), C.byref(mu), C.byref(sigma))
+    return mu.value, sigma.value
+
+
+def f_map(x: float, mu: float, sigma: float, nbit: int = 8) -> float:
+    return float(_L().orc_f(C.c_double(x), C.c_double(mu), C.c_double(sigma), C.c_int(nbit)))
+
+
+def targets_weights(dmat, mu, sigma, alpha=0.5, nbit=8):
+    dmat = _f64(dmat)
+    target = np.empty((256, 256), dtype=np.float64)
+    weight = np.empty((256, 256), dtype=np.float64)
+    _L().orc_targets_weights(_p(dmat), C.c_double(mu), C.c_double(sigma), C.c_double(alpha),
+                             C.c_int(nbit), _p(target), _p(weight))
+    return target, weight
+
+
+def polyd_loss(target, weight, pi) -> float:
+    return float(_L().orc_polyd_loss(_p(_f64(target)), _p(_f64(weight)), _p(_u8(pi))))
+
+
+def swap_delta(target, weight, pi, a: int, b: int) -> float:
+    return float(_L().orc_swap_delta(_p(_f64(target)), _p(_f64(weight)), _p(_u8(pi)),
+                                     C.c_int(a), C.c_int(b)))
+
+
+def draw_u64(seed: int, c: int) -> int:
+    return int(_L().orc_draw_u64(seed, c))
+
+
+def anneal(cent, n_iter=500_000, t0=0.7, t_decay=0.9 ** (1.0 / 500.0), alpha=0.5, seed=0,
+           want_trace=False):
+    """Simulated annealing of the index assignment of one sub-quantizer (Section 3.2).
+    Returns dict(pi [256] uint8, loss_init, loss_final[, trace])."""
+    cent = _f64(cent)
+    pi = np.empty(256, dtype=np.uint8)
+    li, lf = C.c_double(), C.c_double()
+    trace = np.empty(n_iter + 1, dtype=np.float64) if want_trace else None
+    _L().orc_anneal(_p(cent), C.c_int(cent.shape[1]), C.c_int64(n_iter), C.c_double(t0),
+                    C.c_double(t_decay), C.c_double(alpha), C.c_uint64(seed), _p(pi),
+                    C.byref(li), C.byref(lf), _p(trace))
+    out = dict(pi=pi, loss_init=li.value, loss_final=lf.value)
+    if want_trace:
+        out["trace"] = trace
+    return out
+
+
+def apply_assignment(cent, pi) -> np.ndarray:
+    cent = _f64(cent)
+    out = np.empty_like(cent)
+    _L().orc_apply_assignment(_p(cent), C.c_int(cent.shape[1]), _p(_u8(pi)), _p(out))
+    return out
+
+
+def optimize_index_assignment(codebook, n_iter=500_000, t0=0.7, t_decay=0.9 ** (1.0 / 500.0),
+                              alpha=0.5, seed=0):
+    """Anneal every sub-quantizer independently (seed + j for sub-quantizer j) and renumber
+    its centroids.  Returns (new codebook, pis [m,256], (loss_init [m], loss_final [m]))."""
+    cb = _f64(codebook)
+    m = cb.shape[0]
+    out = np.empty_like(cb)
+    pis = np.empty((m, 256), dtype=np.uint8)
+    li, lf = np.empty(m), np.empty(m)
+    for j in range(m):
+        r = anneal(cb[j], n_iter, t0, t_decay, alpha, seed + j)
+        pis[j], li[j], lf[j] = r["pi"], r["loss_init"], r["loss_final"]
+        out[j] = apply_assignment(cb[j], r["pi"])
+    return out, pis, (li, lf)
