@@ -1,0 +1,142 @@
+/*
+ * psc.h -- C ABI of the polysemous-code search library for AMD MI355X (gfx950).
+ *
+ * The library implements the search path of "Polysemous codes" (Douze, Jegou,
+ * Perronnin, ECCV 2016): a scan over product-quantizer codes in which every
+ * code is first compared as a bit string with the query's own code (Hamming
+ * distance, Section 3.3 / Section 4.2 "dual"), codes farther than a threshold
+ * are dropped, the survivors are scored with the asymmetric distance estimator
+ * (a sum of per-sub-quantizer table entries, Section 4.2 "ADC") and the best k
+ * per query are returned; plus the inverted-file variant with residual codes
+ * (Section 4.3) and the all-against-all k-NN-graph mode (Section 5).
+ *
+ * General rules
+ *   - Pointers named *_dev are device (HBM) pointers, *_host are host pointers.
+ *     Every buffer is owned by the caller; the library allocates no device
+ *     memory on the search path (workspaces are passed in and sized by the
+ *     *_workspace_bytes functions).
+ *   - All arrays are dense, row-major.  A product quantizer has m sub-quantizers
+ *     (m = 8 or 16) of exactly 256 centroids; a code is m bytes, byte j holding
+ *     the index chosen by sub-quantizer j.  Code arrays and query-code arrays
+ *     must be 16-byte aligned.
+ *   - Device work is enqueued on `stream` (a hipStream_t, 0 = the null stream)
+ *     and the call returns without waiting, except where stated.
+ *   - Return value: 0 on success, negative on failure:
+ *        PSC_EINVAL  invalid argument (null pointer, unsupported m, k or size,
+ *                    misaligned codes, workspace too small)
+ *        PSC_ESTATE  the index lacks what the call needs (no codebook, no lists)
+ *        PSC_EHIP    a HIP call failed
+ *        PSC_ENOMEM  host allocation failed
+ *     psc_last_error() gives a message for the last failure on the calling thread.
+ *     Nothing throws or aborts across this boundary.
+ *   - n = 0 or nq = 0 succeed; with n = 0 every result row is padding.
+ */
+#ifndef PSC_H
+#define PSC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PSC_OK 0
+#define PSC_EINVAL (-1)
+#define PSC_ESTATE (-2)
+#define PSC_EHIP (-3)
+#define PSC_ENOMEM (-4)
+
+#define PSC_MAX_K 1024
+
+typedef struct psc_index psc_index; /* opaque: codebook (host + device copy), coarse centroids, list views */
+typedef void *psc_stream;           /* hipStream_t */
+
+/* Library version (major*10000 + minor*100 + patch). */
+int psc_version(void);
+/* Message describing the last failure on this thread ("" if none). */
+const char *psc_last_error(void);
+
+/* ------------------------------------------------------------------ lifecycle */
+/* New index for dim-dimensional vectors and m sub-quantizers (m in {8,16},
+ * dim % m == 0, dim/m one of 1,2,4,6,8,12,16,24,32,48,64).  Touches no device: the codebook is
+ * copied to the current HIP device by the first device operation that needs it. */
+int psc_create(psc_index **out, int dim, int m);
+void psc_destroy(psc_index *idx);
+
+/* ------------------------------------------------------------------ training (host side, synchronous) */
+/* Product quantizer (Section 3, opening): one k-means with 256 centroids per
+ * sub-space, `iters` Lloyd iterations, on n >= 256 training vectors
+ * x_host [n][dim] (float32).  Replaces the codebook. */
+int psc_train_pq(psc_index *idx, const float *x_host, int64_t n, int iters, uint64_t seed);
+
+/* Index assignment (Section 3.1 weighted distance-estimator objective, Section
+ * 3.2 simulated annealing): for each sub-quantizer, anneal a bijection pi from
+ * centroid numbers to 8-bit indices for n_iter iterations (start temperature
+ * t0, multiplied by t_decay after every iteration, weight alpha^f(d)); a
+ * proposal is accepted when it lowers the loss or, otherwise, with probability
+ * equal to the temperature.  The paper's values: n_iter = 500000, t0 = 0.7,
+ * t_decay = 0.9^(1/500), alpha = 0.5.  Sub-quantizer j uses seed + j; proposal
+ * number it takes SplitMix64 draws 3it, 3it+1, 3it+2 of that seed.
+ * The codebook rows are renumbered in place (new row pi[i] = old row i), so
+ * everything downstream works with the renumbered codebook only.
+ * perm_out_host (may be NULL) [m][256] receives pi; loss_out_host (may be NULL)
+ * [m][2] receives the loss before and after. */
+int psc_optimize_index_assignment(psc_index *idx, int64_t n_iter, double t0, double t_decay,
+                                  double alpha, uint64_t seed, uint8_t *perm_out_host,
+                                  double *loss_out_host);
+
+/* Install / read back the codebook, cb_host [m][256][dim/m] float32. */
+int psc_set_codebook(psc_index *idx, const float *cb_host);
+int psc_get_codebook(const psc_index *idx, float *cb_host);
+
+/* ------------------------------------------------------------------ device operations */
+/* PQ encoding: codes_dev [n][m], byte j = nearest centroid of sub-quantizer j
+ * to sub-vector j of x_dev [n][dim] (float32), lowest index on equal distance.
+ * Distances are accumulated in float32, coordinates in ascending order. */
+int psc_encode(const psc_index *idx, const float *x_dev, int64_t n, uint8_t *codes_dev,
+               psc_stream stream);
+
+/* ADC tables (Section 4.2 "ADC"): lut_dev [nq][m][256] float32,
+ * lut[q][j][c] = squared Euclidean distance between sub-vector j of query q and
+ * centroid c of sub-quantizer j.  qcodes_dev (may be NULL) [nq][m] receives the
+ * query's own code = per row the index of the smallest entry (lowest on ties). */
+int psc_build_lut(const psc_index *idx, const float *q_dev, int64_t nq, float *lut_dev,
+                  uint8_t *qcodes_dev, psc_stream stream);
+
+/* Hamming filter alone (Section 3.3 first step): nsurv_dev [nq] int64 receives,
+ * per query, the number of codes whose Hamming distance to the query code over
+ * all 8m bits is <= ht.  hdist_dev (may be NULL; small inputs) [nq][n] uint8
+ * receives every distance. */
+int psc_hamming_filter(int m, const uint8_t *qcodes_dev, int64_t nq, const uint8_t *codes_dev,
+                       int64_t n, int ht, int64_t *nsurv_dev, uint8_t *hdist_dev,
+                       psc_stream stream);
+
+/* The fused scan (Section 3.3; Section 4.2 "dual"): for every query q and code i,
+ * keep i iff hamming(qcodes[q], codes[i]) <= ht (ht >= 8m keeps everything = pure
+ * ADC search); score survivors with dist = sum_j lut[q][j][codes[i][j]] (float32,
+ * j ascending); return the k smallest by (dist, id) ascending, lower id first on
+ * equal distance, in ids_dev [nq][k] (int64) and dists_dev [nq][k] (float32),
+ * padded with id -1 / distance +inf when fewer than k survive.
+ * 1 <= k <= PSC_MAX_K, ht >= 0, n < 2^40.  Workspace: psc_scan_workspace_bytes. */
+size_t psc_scan_workspace_bytes(int m, int64_t nq, int64_t n, int k);
+int psc_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t nq,
+             const uint8_t *codes_dev, int64_t n, int ht, int k, int64_t *ids_dev,
+             float *dists_dev, void *workspace_dev, size_t workspace_bytes, psc_stream stream);
+
+/* Whole flat search from raw queries q_dev [nq][dim]: psc_build_lut + psc_scan,
+ * tables and query codes living in the workspace (psc_search_workspace_bytes). */
+size_t psc_search_workspace_bytes(const psc_index *idx, int64_t nq, int64_t n, int k);
+int psc_search(const psc_index *idx, const float *q_dev, int64_t nq, const uint8_t *codes_dev,
+               int64_t n, int ht, int k, int64_t *ids_dev, float *dists_dev, void *workspace_dev,
+               size_t workspace_bytes, psc_stream stream);
+
+/* Synchronise `stream` and report whether any scan that used this workspace since
+ * the last call gave up on an internal wait (never expected; results of such a
+ * scan are marked with id -2).  Returns 0 if clean, PSC_EHIP otherwise. */
+int psc_workspace_status(void *workspace_dev, psc_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PSC_H */

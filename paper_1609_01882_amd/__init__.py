@@ -1,0 +1,17 @@
+"""Polysemous-code search on AMD MI355X: Python face of libpsc.so (HIP, gfx950).
+
+The compute lives in `csrc/` behind the C ABI declared in `include/psc.h`; this package only
+marshals arguments (see `binding.py`).
+"""
+from .binding import (  # noqa: F401
+    Index,
+    PscError,
+    PSC_MAX_K,
+    exported_symbols,
+    hamming_filter,
+    lib_path,
+    scan,
+    scan_workspace_bytes,
+    version,
+    workspace_status,
+)

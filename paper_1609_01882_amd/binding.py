@@ -1,0 +1,212 @@
+"""Thin Python binding of libpsc.so: argument marshalling only.
+
+Every step of the search path runs in the library's HIP kernels; torch is used for device
+memory (tensors) and the current stream.  If the shared library is missing this module raises
+at import of the first call -- there is no CPU or eager fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libpsc.so")
+_lib = None
+
+PSC_MAX_K = 1024
+
+
+class PscError(RuntimeError):
+    pass
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise PscError(f"{_LIB_PATH} not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = C.CDLL(_LIB_PATH)
+    vp, i64, i32, u64, dbl, sz = C.c_void_p, C.c_int64, C.c_int, C.c_uint64, C.c_double, C.c_size_t
+    sigs = {
+        "psc_version": (i32, []),
+        "psc_last_error": (C.c_char_p, []),
+        "psc_create": (i32, [C.POINTER(vp), i32, i32]),
+        "psc_destroy": (None, [vp]),
+        "psc_train_pq": (i32, [vp, vp, i64, i32, u64]),
+        "psc_optimize_index_assignment": (i32, [vp, i64, dbl, dbl, dbl, u64, vp, vp]),
+        "psc_set_codebook": (i32, [vp, vp]),
+        "psc_get_codebook": (i32, [vp, vp]),
+        "psc_encode": (i32, [vp, vp, i64, vp, vp]),
+        "psc_build_lut": (i32, [vp, vp, i64, vp, vp, vp]),
+        "psc_hamming_filter": (i32, [i32, vp, i64, vp, i64, i32, vp, vp, vp]),
+        "psc_scan_workspace_bytes": (sz, [i32, i64, i64, i32]),
+        "psc_scan": (i32, [i32, vp, vp, i64, vp, i64, i32, i32, vp, vp, vp, sz, vp]),
+        "psc_search_workspace_bytes": (sz, [vp, i64, i64, i32]),
+        "psc_search": (i32, [vp, vp, i64, vp, i64, i32, i32, vp, vp, vp, sz, vp]),
+        "psc_workspace_status": (i32, [vp, vp]),
+    }
+    for name, (res, args) in sigs.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+def exported_symbols():
+    """Names this binding expects the library to export."""
+    _load()
+    return ["psc_version", "psc_last_error", "psc_create", "psc_destroy", "psc_train_pq",
+            "psc_optimize_index_assignment", "psc_set_codebook", "psc_get_codebook", "psc_encode",
+            "psc_build_lut", "psc_hamming_filter", "psc_scan_workspace_bytes", "psc_scan",
+            "psc_search_workspace_bytes", "psc_search", "psc_workspace_status"]
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise PscError(f"libpsc error {rc}: {_load().psc_last_error().decode()}")
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t: torch.Tensor, dtype, name: str):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise PscError(f"{name}: expected a contiguous CUDA tensor of {dtype}")
+    return C.c_void_p(t.data_ptr())
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def version() -> int:
+    return _load().psc_version()
+
+
+class Index:
+    """Owner of a product-quantizer codebook (host and device copies)."""
+
+    def __init__(self, dim: int, m: int):
+        lib = _load()
+        self.dim, self.m, self.dsub = dim, m, dim // m if m else 0
+        h = C.c_void_p()
+        _check(lib.psc_create(C.byref(h), dim, m))
+        self._h = h
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h is not None and _lib is not None:
+            _lib.psc_destroy(h)
+
+    # -- training, host side
+    def train_pq(self, x: np.ndarray, iters: int = 20, seed: int = 0):
+        x = np.ascontiguousarray(x, dtype=np.float32)
+        assert x.ndim == 2 and x.shape[1] == self.dim
+        _check(_load().psc_train_pq(self._h, x.ctypes.data_as(C.c_void_p), x.shape[0], iters, seed))
+
+    def optimize_index_assignment(self, n_iter: int = 500_000, t0: float = 0.7,
+                                  t_decay: float = 0.9 ** (1.0 / 500.0), alpha: float = 0.5,
+                                  seed: int = 0):
+        """Returns (pi [m,256] uint8, losses [m,2] float64 = before/after)."""
+        pi = np.empty((self.m, 256), dtype=np.uint8)
+        loss = np.empty((self.m, 2), dtype=np.float64)
+        _check(_load().psc_optimize_index_assignment(self._h, n_iter, t0, t_decay, alpha, seed,
+                                                     pi.ctypes.data_as(C.c_void_p),
+                                                     loss.ctypes.data_as(C.c_void_p)))
+        return pi, loss
+
+    def set_codebook(self, cb: np.ndarray):
+        cb = np.ascontiguousarray(cb, dtype=np.float32)
+        assert cb.shape == (self.m, 256, self.dsub)
+        _check(_load().psc_set_codebook(self._h, cb.ctypes.data_as(C.c_void_p)))
+
+    def get_codebook(self) -> np.ndarray:
+        cb = np.empty((self.m, 256, self.dsub), dtype=np.float32)
+        _check(_load().psc_get_codebook(self._h, cb.ctypes.data_as(C.c_void_p)))
+        return cb
+
+    # -- device operations
+    def encode(self, x: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+        n = x.shape[0]
+        if out is None:
+            out = torch.empty((n, self.m), dtype=torch.uint8, device=x.device)
+        _check(_load().psc_encode(self._h, _dev(x, torch.float32, "x"), n, _dev(out, torch.uint8, "codes"),
+                                  _stream()))
+        return out
+
+    def build_lut(self, q: torch.Tensor, want_codes: bool = True):
+        nq = q.shape[0]
+        lut = torch.empty((nq, self.m, 256), dtype=torch.float32, device=q.device)
+        qc = torch.empty((nq, self.m), dtype=torch.uint8, device=q.device) if want_codes else None
+        _check(_load().psc_build_lut(self._h, _dev(q, torch.float32, "q"), nq, _dev(lut, torch.float32, "lut"),
+                                     _dev(qc, torch.uint8, "qcodes") if want_codes else None, _stream()))
+        return lut, qc
+
+    def search(self, q: torch.Tensor, codes: torch.Tensor, ht: int, k: int, workspace=None, out=None):
+        nq, n = q.shape[0], codes.shape[0]
+        lib = _load()
+        need = lib.psc_search_workspace_bytes(self._h, nq, n, k)
+        if need == 0:
+            _check(-1)
+        ws = workspace if workspace is not None else _workspace(need, q.device)
+        ids, dists = out if out is not None else (
+            torch.empty((nq, k), dtype=torch.int64, device=q.device),
+            torch.empty((nq, k), dtype=torch.float32, device=q.device))
+        _check(lib.psc_search(self._h, _dev(q, torch.float32, "q"), nq, _dev(codes, torch.uint8, "codes"), n,
+                              ht, k, _dev(ids, torch.int64, "ids"), _dev(dists, torch.float32, "dists"),
+                              _dev(ws, torch.uint8, "workspace"), ws.numel(), _stream()))
+        return ids, dists
+
+    def search_workspace_bytes(self, nq: int, n: int, k: int) -> int:
+        return int(_load().psc_search_workspace_bytes(self._h, nq, n, k))
+
+
+def scan_workspace_bytes(m: int, nq: int, n: int, k: int) -> int:
+    return int(_load().psc_scan_workspace_bytes(m, nq, n, k))
+
+
+def scan(lut: torch.Tensor, qcodes: torch.Tensor, codes: torch.Tensor, ht: int, k: int,
+         workspace=None, out=None):
+    """Fused Hamming filter + ADC + top-k.  Returns (ids [nq,k] int64, dists [nq,k] float32)."""
+    lib = _load()
+    nq, m = qcodes.shape
+    n = codes.shape[0]
+    need = lib.psc_scan_workspace_bytes(m, nq, n, k)
+    if need == 0:
+        _check(lib.psc_scan(m, None, None, nq, None, n, ht, k, None, None, None, 0, None) or -1)
+    ws = workspace if workspace is not None else _workspace(need, qcodes.device)
+    ids, dists = out if out is not None else (
+        torch.empty((nq, k), dtype=torch.int64, device=qcodes.device),
+        torch.empty((nq, k), dtype=torch.float32, device=qcodes.device))
+    _check(lib.psc_scan(m, _dev(lut, torch.float32, "lut"), _dev(qcodes, torch.uint8, "qcodes"), nq,
+                        _dev(codes, torch.uint8, "codes"), n, ht, k, _dev(ids, torch.int64, "ids"),
+                        _dev(dists, torch.float32, "dists"), _dev(ws, torch.uint8, "workspace"),
+                        ws.numel(), _stream()))
+    return ids, dists
+
+
+def hamming_filter(qcodes: torch.Tensor, codes: torch.Tensor, ht: int, want_distances: bool = False):
+    """Per-query survivor counts (int64 [nq]) and optionally all distances (uint8 [nq,n])."""
+    nq, m = qcodes.shape
+    n = codes.shape[0]
+    nsurv = torch.empty(nq, dtype=torch.int64, device=qcodes.device)
+    hd = torch.empty((nq, n), dtype=torch.uint8, device=qcodes.device) if want_distances else None
+    _check(_load().psc_hamming_filter(m, _dev(qcodes, torch.uint8, "qcodes"), nq,
+                                      _dev(codes, torch.uint8, "codes"), n, ht,
+                                      _dev(nsurv, torch.int64, "nsurv"),
+                                      _dev(hd, torch.uint8, "hdist") if want_distances else None, _stream()))
+    return (nsurv, hd) if want_distances else nsurv
+
+
+def workspace_status(ws: torch.Tensor) -> None:
+    _check(_load().psc_workspace_status(_dev(ws, torch.uint8, "workspace"), _stream()))

@@ -1,0 +1,86 @@
+// Internal declarations shared by the translation units of libpsc (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <vector>
+
+#include "psc.h"
+
+namespace psc {
+
+void set_error(const char *fmt, ...) __attribute__((format(printf, 1, 2)));
+
+#define PSC_HIP_TRY(expr)                                                                    \
+    do {                                                                                     \
+        hipError_t e_ = (expr);                                                              \
+        if (e_ != hipSuccess) {                                                              \
+            ::psc::set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, \
+                             __LINE__);                                                      \
+            return PSC_EHIP;                                                                 \
+        }                                                                                    \
+    } while (0)
+
+#define PSC_REQUIRE(cond, ...)          \
+    do {                                \
+        if (!(cond)) {                  \
+            ::psc::set_error(__VA_ARGS__); \
+            return PSC_EINVAL;          \
+        }                               \
+    } while (0)
+
+constexpr int kCentroids = 256;  // centroids per sub-quantizer: one byte per index
+
+// ---- host-side training (host_train.cpp)
+// Lloyd k-means on x [n][d] -> cent [ncent][d].
+int host_kmeans(const float *x, int64_t n, int d, int ncent, int iters, uint64_t seed, float *cent);
+// Simulated annealing of the index assignment of one sub-quantizer; cent [256][dsub].
+void host_anneal(const float *cent, int dsub, int64_t n_iter, double t0, double t_decay,
+                 double alpha, uint64_t seed, uint8_t *pi, double *loss_before, double *loss_after);
+
+// ---- device launchers (kernels_lut.hip)
+// Row selection for tables / codes built from "virtual" rows:
+//   row r uses vector x[row_idx ? row_idx[r] : r] minus (sub ? sub[sub_idx[r]] : 0).
+struct RowMap {
+    const int32_t *row_idx = nullptr;
+    const float *sub = nullptr;       // [*][dim] vectors to subtract (coarse centroids)
+    const int32_t *sub_idx = nullptr; // which one, per row
+};
+int launch_lut(const float *cb_dev, int dim, int m, const float *x_dev, int64_t nrows,
+               const RowMap &map, float *lut_dev, hipStream_t s);
+int launch_encode(const float *cb_dev, int dim, int m, const float *x_dev, int64_t nrows,
+                  const RowMap &map, uint8_t *codes_dev, hipStream_t s);
+
+// ---- device launchers (kernels_scan.hip)
+struct ScanPlan {
+    int tq = 0;          // queries per workgroup tile
+    int nwaves = 0;      // waves per workgroup
+    int kpad = 0;        // k rounded up to a multiple of 64
+    int nslice = 0;      // database slices (one workgroup per (query tile, slice))
+    int64_t slice_len = 0;
+    int64_t ntiles = 0;
+    size_t lds_bytes = 0;
+    size_t part_bytes = 0;  // partial result lists
+    size_t total_bytes = 0; // whole workspace
+};
+int plan_scan(int m, int64_t nq, int64_t n, int k, ScanPlan *plan);
+int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t nq,
+                const uint8_t *codes_dev, int64_t n, int ht, int k, const int64_t *skip_id_dev,
+                int64_t skip_base, int64_t *ids_dev, float *dists_dev, void *ws, size_t ws_bytes,
+                hipStream_t s);
+int launch_hamming_filter(int m, const uint8_t *qcodes_dev, int64_t nq, const uint8_t *codes_dev,
+                          int64_t n, int ht, int64_t *nsurv_dev, uint8_t *hdist_dev, hipStream_t s);
+
+}  // namespace psc
+
+struct psc_index {
+    int dim = 0, m = 0, dsub = 0;
+    int device = 0;
+    bool has_codebook = false;
+    std::vector<float> cb_host;  // [m][256][dsub], the master copy
+    mutable float *cb_dev = nullptr;
+    mutable bool dev_current = false;  // device copy matches cb_host
+};

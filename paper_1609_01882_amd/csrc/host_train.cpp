@@ -1,0 +1,228 @@
+// Host-side training: Lloyd k-means for the product quantizer (Section 3, opening) and the
+// index-assignment optimisation by simulated annealing (Sections 3.1 and 3.2).
+// Runs once, offline; the search path never comes here.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <limits>
+#include <numeric>
+#include <thread>
+
+#include "common.h"
+
+namespace psc {
+namespace {
+
+// SplitMix64 output function on a counter: draw number `c` of stream `seed`.
+inline uint64_t counter_draw(uint64_t seed, uint64_t c)
+{
+    uint64_t z = seed + 0x9E3779B97F4A7C15ULL * (c + 1);
+    z ^= z >> 30;
+    z *= 0xBF58476D1CE4E5B9ULL;
+    z ^= z >> 27;
+    z *= 0x94D049BB133111EBULL;
+    z ^= z >> 31;
+    return z;
+}
+
+template <class F>
+void parallel_rows(int64_t n, F &&body)
+{
+    unsigned hw = std::thread::hardware_concurrency();
+    int nt = (int)std::min<int64_t>(std::max(1u, std::min(hw, 32u)), std::max<int64_t>(1, n / 1024));
+    if (nt <= 1) {
+        body(0, n);
+        return;
+    }
+    std::vector<std::thread> pool;
+    int64_t per = (n + nt - 1) / nt;
+    for (int t = 0; t < nt; ++t) {
+        int64_t lo = t * per, hi = std::min(n, lo + per);
+        if (lo >= hi) break;
+        pool.emplace_back([&body, lo, hi] { body(lo, hi); });
+    }
+    for (auto &th : pool) th.join();
+}
+
+}  // namespace
+
+int host_kmeans(const float *x, int64_t n, int d, int ncent, int iters, uint64_t seed, float *cent)
+{
+    if (n < ncent) {
+        set_error("k-means needs at least %d training vectors, got %lld", ncent, (long long)n);
+        return PSC_EINVAL;
+    }
+    // start: ncent distinct rows (partial Fisher-Yates on the row numbers)
+    {
+        std::vector<int64_t> perm(n);
+        std::iota(perm.begin(), perm.end(), (int64_t)0);
+        for (int c = 0; c < ncent; ++c) {
+            int64_t r = c + (int64_t)(counter_draw(seed, (uint64_t)c) % (uint64_t)(n - c));
+            std::swap(perm[c], perm[r]);
+            std::memcpy(cent + (size_t)c * d, x + (size_t)perm[c] * d, sizeof(float) * d);
+        }
+    }
+    std::vector<int32_t> assign(n);
+    std::vector<float> dmin(n);
+    std::vector<double> sum((size_t)ncent * d);
+    std::vector<int64_t> count(ncent);
+    for (int it = 0; it < iters; ++it) {
+        parallel_rows(n, [&](int64_t lo, int64_t hi) {
+            for (int64_t i = lo; i < hi; ++i) {
+                const float *xi = x + (size_t)i * d;
+                float best = std::numeric_limits<float>::infinity();
+                int bi = 0;
+                for (int c = 0; c < ncent; ++c) {
+                    const float *cc = cent + (size_t)c * d;
+                    float acc = 0.f;
+                    for (int t = 0; t < d; ++t) {
+                        float df = xi[t] - cc[t];
+                        acc += df * df;
+                    }
+                    if (acc < best) {
+                        best = acc;
+                        bi = c;
+                    }
+                }
+                assign[i] = bi;
+                dmin[i] = best;
+            }
+        });
+        std::fill(sum.begin(), sum.end(), 0.0);
+        std::fill(count.begin(), count.end(), (int64_t)0);
+        for (int64_t i = 0; i < n; ++i) {
+            double *s = sum.data() + (size_t)assign[i] * d;
+            const float *xi = x + (size_t)i * d;
+            for (int t = 0; t < d; ++t) s[t] += xi[t];
+            ++count[assign[i]];
+        }
+        for (int c = 0; c < ncent; ++c) {
+            if (count[c] == 0) {
+                // empty cell: take the member of the most populated cell that lies farthest
+                // from that cell's centroid
+                int big = (int)(std::max_element(count.begin(), count.end()) - count.begin());
+                int64_t far = -1;
+                float fd = -1.f;
+                for (int64_t i = 0; i < n; ++i)
+                    if (assign[i] == big && dmin[i] > fd) {
+                        fd = dmin[i];
+                        far = i;
+                    }
+                if (far < 0) continue;
+                const float *xf = x + (size_t)far * d;
+                for (int t = 0; t < d; ++t) {
+                    sum[(size_t)big * d + t] -= xf[t];
+                    sum[(size_t)c * d + t] = xf[t];
+                }
+                --count[big];
+                count[c] = 1;
+                assign[far] = c;
+                dmin[far] = 0.f;
+            }
+        }
+        for (int c = 0; c < ncent; ++c)
+            if (count[c] > 0)
+                for (int t = 0; t < d; ++t)
+                    cent[(size_t)c * d + t] = (float)(sum[(size_t)c * d + t] / (double)count[c]);
+    }
+    return PSC_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Index assignment.  State kept as the inverse view too would not help: the loss change of a
+// transposition touches one row/column pair, O(256).
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+struct Objective {
+    // target = f(d_ij): centroid distances mapped linearly onto the Hamming range so that they
+    // share the mean nbit/2 and variance nbit/4 of distances between random nbit-bit strings;
+    // weight = alpha^target (Section 3.1).
+    std::vector<double> target, weight;
+    uint8_t hd[kCentroids][kCentroids];  // Hamming distance between 8-bit indices
+
+    Objective(const float *cent, int dsub, double alpha)
+        : target((size_t)kCentroids * kCentroids), weight((size_t)kCentroids * kCentroids)
+    {
+        const int nbit = 8;
+        for (int a = 0; a < kCentroids; ++a)
+            for (int b = 0; b < kCentroids; ++b) hd[a][b] = (uint8_t)__builtin_popcount(a ^ b);
+        std::vector<double> dist((size_t)kCentroids * kCentroids);
+        double s1 = 0.0;
+        for (int i = 0; i < kCentroids; ++i)
+            for (int j = 0; j < kCentroids; ++j) {
+                double acc = 0.0;
+                for (int t = 0; t < dsub; ++t) {
+                    double df = (double)cent[(size_t)i * dsub + t] - (double)cent[(size_t)j * dsub + t];
+                    acc += df * df;
+                }
+                dist[(size_t)i * kCentroids + j] = std::sqrt(acc);
+                if (i != j) s1 += dist[(size_t)i * kCentroids + j];
+            }
+        const double npairs = (double)kCentroids * (kCentroids - 1);
+        const double mu = s1 / npairs;
+        double s2 = 0.0;
+        for (int i = 0; i < kCentroids; ++i)
+            for (int j = 0; j < kCentroids; ++j)
+                if (i != j) {
+                    double e = dist[(size_t)i * kCentroids + j] - mu;
+                    s2 += e * e;
+                }
+        const double sigma = std::sqrt(s2 / npairs);
+        const double slope = std::sqrt((double)nbit) / (2.0 * sigma);
+        for (size_t e = 0; e < dist.size(); ++e) {
+            target[e] = slope * (dist[e] - mu) + (double)nbit / 2.0;
+            weight[e] = std::pow(alpha, target[e]);
+        }
+    }
+
+    double loss(const uint8_t *pi) const
+    {
+        double L = 0.0;
+        for (int i = 0; i < kCentroids; ++i)
+            for (int j = 0; j < kCentroids; ++j) {
+                double e = (double)hd[pi[i]][pi[j]] - target[(size_t)i * kCentroids + j];
+                L += weight[(size_t)i * kCentroids + j] * e * e;
+            }
+        return L;
+    }
+
+    // Change of the loss when centroids a and b exchange their indices.
+    double transposition_delta(const uint8_t *pi, int a, int b) const
+    {
+        const double *ta = &target[(size_t)a * kCentroids], *tb = &target[(size_t)b * kCentroids];
+        const double *wa = &weight[(size_t)a * kCentroids], *wb = &weight[(size_t)b * kCentroids];
+        const uint8_t *ha = hd[pi[a]], *hb = hd[pi[b]];
+        double acc = 0.0;
+        for (int k = 0; k < kCentroids; ++k) {
+            if (k == a || k == b) continue;
+            double da = (double)ha[pi[k]], db = (double)hb[pi[k]];
+            acc += wa[k] * ((db - ta[k]) * (db - ta[k]) - (da - ta[k]) * (da - ta[k]));
+            acc += wb[k] * ((da - tb[k]) * (da - tb[k]) - (db - tb[k]) * (db - tb[k]));
+        }
+        return 2.0 * acc;
+    }
+};
+
+}  // namespace
+
+void host_anneal(const float *cent, int dsub, int64_t n_iter, double t0, double t_decay,
+                 double alpha, uint64_t seed, uint8_t *pi, double *loss_before, double *loss_after)
+{
+    Objective obj(cent, dsub, alpha);
+    for (int i = 0; i < kCentroids; ++i) pi[i] = (uint8_t)i;
+    if (loss_before) *loss_before = obj.loss(pi);
+    double temperature = t0;
+    for (int64_t it = 0; it < n_iter; ++it) {
+        const uint64_t c = 3 * (uint64_t)it;
+        const int a = (int)(counter_draw(seed, c) % kCentroids);
+        const int b = (int)((a + 1 + counter_draw(seed, c + 1) % (kCentroids - 1)) % kCentroids);
+        const double u = (double)(counter_draw(seed, c + 2) >> 11) * 0x1.0p-53;
+        const double delta = obj.transposition_delta(pi, a, b);
+        if (delta < 0.0 || u < temperature) std::swap(pi[a], pi[b]);
+        temperature *= t_decay;
+    }
+    if (loss_after) *loss_after = obj.loss(pi);
+}
+
+}  // namespace psc

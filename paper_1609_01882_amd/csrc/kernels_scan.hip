@@ -1,0 +1,660 @@
+// The fused polysemous scan (Section 3.3 two-step strategy; Section 4.2 "dual") for gfx950.
+//
+// One workgroup = one tile of TQ queries x one slice of the database.
+//   * the TQ ADC tables (TQ * m * 256 float32) and the TQ running top-k lists live in LDS for
+//     the lifetime of the workgroup;
+//   * the TQ query codes live in scalar registers;
+//   * every wave streams blocks of 64 x C codes from memory into vector registers (one 16-byte
+//     load per lane, the next block prefetched) and compares each code with all TQ query codes:
+//     xor + popcount-accumulate per 32-bit word, then one funnel shift that appends the
+//     "too far" bit to a per-lane mask: 5 integer instructions per (query, 64-bit code) pair;
+//   * lanes that hold survivors append (query slot, code position) entries to a per-wave ring
+//     in LDS, positions assigned with ballot + prefix popcount, so that the expensive step runs
+//     on full wavefronts;
+//   * whenever the ring holds 64 entries the wave drains them: re-reads the 64 codes, gathers
+//     m table entries each from LDS, sums them in float32 (j ascending) and compares with the
+//     query's current k-th best distance;
+//   * the few candidates that pass are inserted into the query's sorted list in LDS by the whole
+//     wave, under a per-query lock (waves of the workgroup share the lists).
+// Partial lists (one per query and slice) go to the workspace; a second kernel merges them.
+//
+// Ordering everywhere: (distance, id) ascending, lower id first on equal distance.
+#include "common.h"
+
+namespace psc {
+namespace {
+
+constexpr int kQueueCap = 128;        // ring entries per wave (power of two, >= 2*64)
+constexpr int kRelBits = 28;          // bits of a ring entry holding the position inside the slice
+constexpr uint32_t kRelMask = (1u << kRelBits) - 1;
+constexpr int64_t kMaxSliceLen = (int64_t)1 << kRelBits;
+constexpr int kSpinLimit = 1 << 22;   // bounded wait on a list lock (each turn sleeps)
+
+struct ScanArgs {
+    const float *lut;         // [nq][M][256]
+    const uint8_t *qcodes;    // [nq][M]
+    const uint8_t *codes;     // [n][M]
+    const int64_t *skip_id;   // optional [nq]: id never returned for that query
+    int64_t skip_base;        //   ... ids of this database are skip_base + position
+    int64_t nq, n;
+    int64_t slice_len;
+    int nslice;
+    int k, kpad;
+    uint32_t bias;            // 0x7fffffff - ht: bit 31 of (bias + distance) <=> distance > ht
+    float *part_d;            // [nq][nslice][k]
+    int64_t *part_i;          // [nq][nslice][k]
+    int *status;              // set non-zero if a bounded wait expired
+};
+
+__device__ __forceinline__ uint64_t ballot64(bool p) { return __ballot(p); }
+
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & 63); }
+
+__device__ __forceinline__ int prefix_count(uint64_t mask)
+{
+    return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                          __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+__device__ __forceinline__ float bcast_f(float v, int lane)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+__device__ __forceinline__ uint32_t bcast_u(uint32_t v, int lane)
+{
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, lane);
+}
+
+// Shared-memory view of one workgroup.  The pointers carry the LDS address space explicitly so
+// that every access is a ds_* instruction.
+#define PSC_LDS __attribute__((address_space(3)))
+typedef PSC_LDS float lds_f32;
+typedef PSC_LDS volatile float lds_vf32;
+typedef PSC_LDS volatile uint32_t lds_vu32;
+typedef PSC_LDS volatile int lds_vi32;
+typedef PSC_LDS int lds_i32;
+
+template <int M, int TQ>
+struct Lds {
+    lds_f32 *lut;    // [TQ][M][256]
+    lds_vf32 *topd;  // [TQ][kpad]
+    lds_vu32 *topi;  // [TQ][kpad]
+    lds_vf32 *thr;   // [TQ] current k-th best distance (+inf until the list is full)
+    lds_vi32 *cnt;   // [TQ] entries in the list
+    lds_i32 *lock;   // [TQ]
+    lds_vu32 *queue; // [nwaves][kQueueCap]
+    __device__ __forceinline__ Lds(PSC_LDS unsigned char *base, int kpad)
+    {
+        lut = (lds_f32 *)base;
+        topd = (lds_vf32 *)(lut + TQ * M * 256);
+        topi = (lds_vu32 *)(topd + TQ * kpad);
+        thr = (lds_vf32 *)(topi + TQ * kpad);
+        cnt = (lds_vi32 *)(thr + TQ);
+        lock = (lds_i32 *)(cnt + TQ);
+        queue = (lds_vu32 *)(lock + TQ);
+    }
+};
+
+// Insert the candidates held by the lanes in `mine` (all for query slot q) into q's list.
+// Executed by the whole wave; mine is wave-uniform.
+template <int M, int TQ>
+__device__ __forceinline__ void insert_candidates(const Lds<M, TQ> &s, const ScanArgs &a, int q, uint64_t mine,
+                                  float d, uint32_t id)
+{
+    const int lane = lane_id();
+    int got = 0;
+    if (lane == 0) {
+        int spins = 0;
+        while (true) {
+            if (__hip_atomic_exchange(&s.lock[q], 1, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0) {
+                got = 1;
+                break;
+            }
+            if (++spins > kSpinLimit) break;
+            __builtin_amdgcn_s_sleep(2);
+        }
+    }
+    got = __builtin_amdgcn_readfirstlane(got);
+    if (!got) {  // never expected: flag the run instead of waiting for ever
+        if (lane == 0) atomicExch(a.status, 1);
+        return;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    lds_vf32 *ld = s.topd + q * a.kpad;
+    lds_vu32 *li = s.topi + q * a.kpad;
+    int cnt = s.cnt[q];
+    const int k = a.k;
+    while (mine) {
+        const int src = __builtin_ctzll(mine);
+        mine &= mine - 1;
+        const float cd = bcast_f(d, src);
+        const uint32_t ci = bcast_u(id, src);
+        if (cnt == k) {
+            const float wd = ld[k - 1];
+            const uint32_t wi = li[k - 1];
+            if (!(cd < wd || (cd == wd && ci < wi))) continue;
+        }
+        // rank of the candidate = number of list entries ordered before it
+        int pos = 0;
+        for (int base = 0; base < cnt; base += 64) {
+            const int p = base + lane;
+            bool before = false;
+            if (p < cnt) {
+                const float pd = ld[p];
+                const uint32_t pi = li[p];
+                before = pd < cd || (pd == cd && pi < ci);
+            }
+            pos += __builtin_popcountll(ballot64(before));
+        }
+        // entries pos..last-1 move one place down the list (the k-th falls off when full)
+        const int last = cnt < k ? cnt : k - 1;
+        if (last > pos) {
+            for (int base = ((last - 1) >> 6) << 6; base >= ((pos >> 6) << 6); base -= 64) {
+                const int p = base + lane;
+                const bool mv = p >= pos && p < last;
+                float pd = 0.f;
+                uint32_t pi = 0;
+                if (mv) {
+                    pd = ld[p];
+                    pi = li[p];
+                }
+                __builtin_amdgcn_wave_barrier();
+                if (mv) {
+                    ld[p + 1] = pd;
+                    li[p + 1] = pi;
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
+        if (lane == 0) {
+            ld[pos] = cd;
+            li[pos] = ci;
+        }
+        if (cnt < k) ++cnt;
+        __builtin_amdgcn_wave_barrier();
+    }
+    if (lane == 0) {
+        s.cnt[q] = cnt;
+        if (cnt == k) s.thr[q] = ld[k - 1];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    if (lane == 0)
+        __hip_atomic_store(&s.lock[q], 0, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+// Score `nvalid` ring entries starting at `head` and feed the ones that beat the current
+// threshold to the lists.
+template <int M, int TQ>
+__device__ __forceinline__ void drain(const Lds<M, TQ> &s, const ScanArgs &a, lds_vu32 *ring, int head,
+                      int nvalid, int64_t slice_begin, int64_t q0)
+{
+    const int lane = lane_id();
+    const bool act = lane < nvalid;
+    float d = __builtin_inff();
+    uint32_t rel = 0;
+    int q = 0;
+    if (act) {
+        const uint32_t e = ring[(head + lane) & (kQueueCap - 1)];
+        q = (int)(e >> kRelBits);
+        rel = e & kRelMask;
+        const uint32_t *cw = (const uint32_t *)(a.codes + (slice_begin + rel) * M);
+        uint32_t w[M / 4];
+        if constexpr (M == 8) {
+            const uint2 v = *(const uint2 *)cw;
+            w[0] = v.x;
+            w[1] = v.y;
+        } else {
+            const uint4 v = *(const uint4 *)cw;
+            w[0] = v.x;
+            w[1] = v.y;
+            w[2] = v.z;
+            w[3] = v.w;
+        }
+        const lds_f32 *t = s.lut + q * (M * 256);
+        float acc = 0.f;
+#pragma unroll
+        for (int j = 0; j < M; ++j) {
+            const uint32_t byte = (w[j >> 2] >> (8 * (j & 3))) & 0xffu;
+            acc += t[j * 256 + byte];
+        }
+        d = acc;
+    }
+    bool pass = act && d <= s.thr[q];
+    if (pass && a.skip_id != nullptr)
+        pass = (a.skip_base + slice_begin + (int64_t)rel) != a.skip_id[q0 + q];
+    uint64_t pm = ballot64(pass);
+    while (pm) {
+        const int leader = __builtin_ctzll(pm);
+        const int qcur = __builtin_amdgcn_readlane(q, leader);
+        const uint64_t mine = ballot64(pass && q == qcur);
+        pm &= ~mine;
+        insert_candidates<M, TQ>(s, a, qcur, mine, d, rel);
+    }
+}
+
+template <int M, int TQ, int NW>
+__global__ void __launch_bounds__(NW * 64)
+scan_kernel(ScanArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const Lds<M, TQ> s((PSC_LDS unsigned char *)smem, a.kpad);
+    constexpr int WPC = M / 4;       // 32-bit words per code
+    constexpr int C = 4 / WPC;       // codes per 16-byte load: 2 (64-bit) or 1 (128-bit)
+    const int tid = (int)threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    const int64_t tile = blockIdx.x;
+    const int slice = (int)(tile % a.nslice);
+    const int64_t q0 = (tile / a.nslice) * TQ;
+    const int nvq = (int)((a.nq - q0) < TQ ? (a.nq - q0) : TQ);
+    const int64_t slice_begin = (int64_t)slice * a.slice_len;
+    const int64_t slice_end = (slice_begin + a.slice_len) < a.n ? (slice_begin + a.slice_len) : a.n;
+
+    // ---- stage the tables, reset the lists
+    {
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        const f32x4 *src = (const f32x4 *)(a.lut + q0 * (M * 256));
+        PSC_LDS f32x4 *dst = (PSC_LDS f32x4 *)s.lut;
+        const int nvec = nvq * (M * 256 / 4);
+        for (int e = tid; e < TQ * (M * 256 / 4); e += NW * 64) {
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if (e < nvec) v = src[e];
+            dst[e] = v;
+        }
+        if (tid < TQ) {
+            s.thr[tid] = __builtin_inff();
+            s.cnt[tid] = 0;
+            s.lock[tid] = 0;
+        }
+    }
+    // ---- query codes -> scalar registers
+    uint32_t qw[TQ][WPC];
+    {
+        const uint32_t *qc = (const uint32_t *)a.qcodes;
+#pragma unroll
+        for (int q = 0; q < TQ; ++q) {
+            const int64_t qq = (q < nvq) ? (q0 + q) : q0;
+#pragma unroll
+            for (int w = 0; w < WPC; ++w)
+                qw[q][w] = __builtin_amdgcn_readfirstlane(qc[qq * WPC + w]);
+        }
+    }
+    __syncthreads();
+
+    // bit b of a per-lane mask <-> query slot TQ-1-b; only the first nvq slots are real
+    const uint32_t qmask = (nvq == TQ) ? ((TQ == 32) ? 0xffffffffu : ((1u << TQ) - 1u))
+                                       : (((1u << TQ) - 1u) & ~((1u << (TQ - nvq)) - 1u));
+    lds_vu32 *ring = s.queue + wave * kQueueCap;
+    int head = 0, tail = 0;  // wave-uniform ring cursors (tail - head < 64 between steps)
+
+    const uint32_t bias = a.bias;
+    const int64_t stride = (int64_t)NW * 64 * C;
+    int64_t pos = slice_begin + (int64_t)wave * 64 * C + (int64_t)lane * C;
+
+    auto load_block = [&](int64_t p, uint32_t (&w)[4]) {
+        w[0] = w[1] = w[2] = w[3] = 0u;
+        if (p + C <= slice_end) {
+            const uint4 v = *(const uint4 *)(a.codes + p * M);
+            w[0] = v.x;
+            w[1] = v.y;
+            w[2] = v.z;
+            w[3] = v.w;
+        } else if (p < slice_end) {  // only when C == 2: the last, odd code
+            const uint2 v = *(const uint2 *)(a.codes + p * M);
+            w[0] = v.x;
+            w[1] = v.y;
+        }
+    };
+
+    uint32_t cur[4];
+    load_block(pos, cur);
+    for (int64_t blk = slice_begin + (int64_t)wave * 64 * C; blk < slice_end; blk += stride, pos += stride) {
+        uint32_t nxt[4];
+        load_block(pos + stride, nxt);
+
+        // ---- Hamming filter: per code, one "too far" bit per query
+        uint32_t far[C];
+#pragma unroll
+        for (int c = 0; c < C; ++c) far[c] = 0u;
+#pragma unroll
+        for (int q = 0; q < TQ; ++q) {
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                uint32_t acc = bias;
+#pragma unroll
+                for (int w = 0; w < WPC; ++w) acc += (uint32_t)__popc(cur[c * WPC + w] ^ qw[q][w]);
+                far[c] = __builtin_amdgcn_alignbit(far[c], acc, 31);
+            }
+        }
+        // ---- survivors -> ring, full wavefronts -> ADC
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            uint32_t sv = (pos + c < slice_end) ? (~far[c] & qmask) : 0u;
+            const uint32_t rel = (uint32_t)(pos + c - slice_begin);
+            while (true) {
+                const bool has = sv != 0u;
+                const uint64_t bal = ballot64(has);
+                if (bal == 0) break;
+                if (has) {
+                    const int b = __builtin_ctz(sv);
+                    sv &= sv - 1u;
+                    const uint32_t q = (uint32_t)(TQ - 1 - b);
+                    ring[(tail + prefix_count(bal)) & (kQueueCap - 1)] = (q << kRelBits) | rel;
+                }
+                tail += __builtin_popcountll(bal);
+                if (tail - head >= 64) {
+                    __builtin_amdgcn_wave_barrier();
+                    drain<M, TQ>(s, a, ring, head, 64, slice_begin, q0);
+                    head += 64;
+                }
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) cur[e] = nxt[e];
+    }
+    if (tail - head > 0) {
+        __builtin_amdgcn_wave_barrier();
+        drain<M, TQ>(s, a, ring, head, tail - head, slice_begin, q0);
+    }
+    __syncthreads();
+
+    // ---- write the tile's lists (padded) to the workspace
+    for (int e = tid; e < nvq * a.k; e += NW * 64) {
+        const int q = e / a.k, r = e - q * a.k;
+        const int64_t o = ((q0 + q) * a.nslice + slice) * a.k + r;
+        const bool have = r < s.cnt[q];
+        a.part_d[o] = have ? s.topd[q * a.kpad + r] : __builtin_inff();
+        a.part_i[o] = have ? (slice_begin + (int64_t)s.topi[q * a.kpad + r]) : (int64_t)-1;
+    }
+}
+
+// Merge the nslice sorted partial lists of each query into the final k (one wave per query).
+__global__ void __launch_bounds__(64)
+merge_kernel(const float *__restrict__ part_d, const int64_t *__restrict__ part_i, int nslice, int k,
+             int64_t id_base, const int *__restrict__ status, int64_t *__restrict__ ids,
+             float *__restrict__ dists)
+{
+    const int64_t q = blockIdx.x;
+    const int lane = lane_id();
+    const float *pd = part_d + q * nslice * k;
+    const int64_t *pi = part_i + q * nslice * k;
+    const bool poisoned = *status != 0;
+    // lane owns lists lane, lane+64, ...; head[] index into each (kept in a small loop instead of
+    // registers: nslice/64 is tiny)
+    constexpr int kMaxOwn = 16;  // up to 1024 slices
+    int hd[kMaxOwn];
+#pragma unroll
+    for (int t = 0; t < kMaxOwn; ++t) hd[t] = 0;
+    for (int r = 0; r < k; ++r) {
+        float bd = __builtin_inff();
+        int64_t bi = INT64_MAX;
+        int bl = -1;
+#pragma unroll
+        for (int t = 0; t < kMaxOwn; ++t) {
+            const int l = lane + 64 * t;
+            if (l < nslice && hd[t] < k) {
+                const float d = pd[l * k + hd[t]];
+                const int64_t i = pi[l * k + hd[t]];
+                if (i >= 0 && (d < bd || (d == bd && i < bi))) {
+                    bd = d;
+                    bi = i;
+                    bl = l;
+                }
+            }
+        }
+        // wave-wide arg-min of (bd, bi)
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const float od = __shfl_xor(bd, off, 64);
+            const int64_t oi = __shfl_xor(bi, off, 64);
+            const int ol = __shfl_xor(bl, off, 64);
+            if (od < bd || (od == bd && oi < bi)) {
+                bd = od;
+                bi = oi;
+                bl = ol;
+            }
+        }
+        if (bl >= 0) {
+#pragma unroll
+            for (int t = 0; t < kMaxOwn; ++t)
+                if (bl == lane + 64 * t) ++hd[t];
+        }
+        if (lane == 0) {
+            const bool have = bl >= 0;
+            ids[q * k + r] = poisoned ? (int64_t)-2 : (have ? bi + id_base : (int64_t)-1);
+            dists[q * k + r] = have ? bd : __builtin_inff();
+        }
+    }
+}
+
+__global__ void fill_padding_kernel(int64_t *ids, float *dists, int64_t total)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < total) {
+        ids[e] = -1;
+        dists[e] = __builtin_inff();
+    }
+}
+
+__global__ void clear_status_kernel(int *status) { *status = 0; }
+
+// Hamming filter alone: per query the number of codes within ht (and optionally every distance).
+template <int M>
+__global__ void __launch_bounds__(256)
+hamming_filter_kernel(const uint8_t *__restrict__ qcodes, int64_t nq, const uint8_t *__restrict__ codes,
+                      int64_t n, int ht, unsigned long long *__restrict__ nsurv,
+                      uint8_t *__restrict__ hdist)
+{
+    const int64_t q = blockIdx.y;
+    constexpr int WPC = M / 4;
+    uint32_t qw[WPC];
+#pragma unroll
+    for (int w = 0; w < WPC; ++w) qw[w] = ((const uint32_t *)qcodes)[q * WPC + w];
+    unsigned long long local = 0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        int h = 0;
+#pragma unroll
+        for (int w = 0; w < WPC; ++w) h += __popc(((const uint32_t *)codes)[i * WPC + w] ^ qw[w]);
+        if (hdist) hdist[q * n + i] = (uint8_t)h;
+        local += (h <= ht) ? 1u : 0u;
+    }
+    // wave reduction, then one atomic per wave
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) local += __shfl_xor(local, off, 64);
+    if ((threadIdx.x & 63) == 0 && local) atomicAdd(&nsurv[q], local);
+}
+
+__global__ void zero_u64_kernel(unsigned long long *p, int64_t n)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < n) p[e] = 0;
+}
+
+template <int M, int TQ, int NW>
+int run_scan(const ScanArgs &a, int64_t ntiles, size_t lds, hipStream_t s)
+{
+    static bool configured = false;  // raise the dynamic-LDS ceiling once per instantiation
+    if (!configured) {
+        PSC_HIP_TRY(hipFuncSetAttribute((const void *)scan_kernel<M, TQ, NW>,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        configured = true;
+    }
+    hipLaunchKernelGGL((scan_kernel<M, TQ, NW>), dim3((unsigned)ntiles), dim3(NW * 64), lds, s, a);
+    PSC_HIP_TRY(hipGetLastError());
+    return PSC_OK;
+}
+
+constexpr size_t kLdsBudget = 160 * 1024;
+
+}  // namespace
+
+// Tile shape: as many queries per tile as fit in LDS with their tables and lists.
+int plan_scan(int m, int64_t nq, int64_t n, int k, ScanPlan *plan)
+{
+    if (m != 8 && m != 16) {
+        set_error("m must be 8 or 16, got %d", m);
+        return PSC_EINVAL;
+    }
+    if (k < 1 || k > PSC_MAX_K) {
+        set_error("k must be in [1, %d], got %d", PSC_MAX_K, k);
+        return PSC_EINVAL;
+    }
+    if (nq < 0 || n < 0 || n >= ((int64_t)1 << 40)) {
+        set_error("bad sizes nq=%lld n=%lld", (long long)nq, (long long)n);
+        return PSC_EINVAL;
+    }
+    ScanPlan p;
+    p.kpad = (k + 63) / 64 * 64;
+    p.nwaves = 16;
+    const int tq_options[3] = {16, 8, 4};
+    p.tq = 0;
+    for (int t : tq_options) {
+        if (m == 16 && t == 16) continue;  // 16 tables of 16 KiB do not fit
+        size_t need = (size_t)t * m * 256 * 4 + (size_t)t * p.kpad * 8 + (size_t)t * 12 +
+                      (size_t)p.nwaves * kQueueCap * 4;
+        if (need <= kLdsBudget) {
+            p.tq = t;
+            p.lds_bytes = need;
+            break;
+        }
+    }
+    if (p.tq == 0) {
+        set_error("no tile shape fits LDS for m=%d k=%d", m, k);
+        return PSC_EINVAL;
+    }
+    const int64_t nqt = (nq + p.tq - 1) / p.tq;
+    // Slices: enough workgroups to fill 256 compute units a few times over, a whole number of
+    // 128-code blocks each, and short enough for the 28-bit position field.
+    const int64_t block = 128;
+    int64_t want = 1;
+    if (nqt > 0) {
+        const int64_t target_wg = 1024;
+        want = (target_wg + nqt - 1) / nqt;
+        // among want..want+3 prefer the count whose last round of workgroups is fullest
+        double best_eff = -1.0;
+        int64_t best = want;
+        for (int64_t sN = want; sN < want + 4; ++sN) {
+            const int64_t wg = nqt * sN;
+            const double eff = (double)wg / (double)(((wg + 255) / 256) * 256);
+            if (eff > best_eff + 1e-9) {
+                best_eff = eff;
+                best = sN;
+            }
+        }
+        want = best;
+    }
+    const int64_t min_slice = 16 * block;  // at least one block per wave
+    int64_t max_by_size = std::max<int64_t>(1, n / min_slice);
+    int64_t nslice = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, max_by_size), 1024));
+    int64_t slice_len = (((n + nslice - 1) / nslice) + block - 1) / block * block;
+    if (slice_len > kMaxSliceLen) {
+        slice_len = kMaxSliceLen;
+        nslice = (n + slice_len - 1) / slice_len;
+        if (nslice > 1024) {
+            set_error("database too large for one scan call");
+            return PSC_EINVAL;
+        }
+    }
+    if (slice_len == 0) slice_len = block;
+    nslice = std::max<int64_t>(1, (n + slice_len - 1) / slice_len);
+    p.nslice = (int)nslice;
+    p.slice_len = slice_len;
+    p.ntiles = nqt * nslice;
+    const size_t dist_bytes = ((size_t)nq * nslice * k * sizeof(float) + 255) / 256 * 256;
+    p.part_bytes = dist_bytes + (size_t)nq * nslice * k * sizeof(int64_t);
+    p.total_bytes = 256 + p.part_bytes;
+    *plan = p;
+    return PSC_OK;
+}
+
+int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t nq,
+                const uint8_t *codes_dev, int64_t n, int ht, int k, const int64_t *skip_id_dev,
+                int64_t skip_base, int64_t *ids_dev, float *dists_dev, void *ws, size_t ws_bytes,
+                hipStream_t s)
+{
+    ScanPlan p;
+    int rc = plan_scan(m, nq, n, k, &p);
+    if (rc != PSC_OK) return rc;
+    PSC_REQUIRE(ht >= 0, "ht must be >= 0, got %d", ht);
+    if (nq == 0) return PSC_OK;
+    PSC_REQUIRE(ids_dev && dists_dev, "null result pointer");
+    if (n == 0) {
+        const int64_t total = nq * k;
+        hipLaunchKernelGGL(fill_padding_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                           ids_dev, dists_dev, total);
+        PSC_HIP_TRY(hipGetLastError());
+        return PSC_OK;
+    }
+    PSC_REQUIRE(lut_dev && qcodes_dev && codes_dev, "null input pointer");
+    PSC_REQUIRE(((uintptr_t)codes_dev & 15) == 0 && ((uintptr_t)qcodes_dev & 15) == 0 &&
+                    ((uintptr_t)lut_dev & 15) == 0,
+                "codes, query codes and tables must be 16-byte aligned");
+    PSC_REQUIRE(ws && ws_bytes >= p.total_bytes, "workspace too small: need %zu bytes, got %zu",
+                p.total_bytes, ws_bytes);
+    PSC_REQUIRE(((uintptr_t)ws & 255) == 0, "workspace must be 256-byte aligned");
+    PSC_REQUIRE(p.ntiles <= 0x7fffffffLL, "too many tiles");
+
+    ScanArgs a;
+    a.lut = lut_dev;
+    a.qcodes = qcodes_dev;
+    a.codes = codes_dev;
+    a.skip_id = skip_id_dev;
+    a.skip_base = skip_base;
+    a.nq = nq;
+    a.n = n;
+    a.slice_len = p.slice_len;
+    a.nslice = p.nslice;
+    a.k = k;
+    a.kpad = p.kpad;
+    const int nbits = 8 * m;
+    const int ht_eff = ht > nbits ? nbits : ht;
+    a.bias = 0x7fffffffu - (uint32_t)ht_eff;
+    a.status = (int *)ws;
+    a.part_d = (float *)((char *)ws + 256);
+    a.part_i = (int64_t *)((char *)ws + 256 + (((size_t)nq * p.nslice * k * sizeof(float) + 255) / 256 * 256));
+
+    hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, s, a.status);
+    if (m == 8) {
+        if (p.tq == 16) rc = run_scan<8, 16, 16>(a, p.ntiles, p.lds_bytes, s);
+        else if (p.tq == 8) rc = run_scan<8, 8, 16>(a, p.ntiles, p.lds_bytes, s);
+        else rc = run_scan<8, 4, 16>(a, p.ntiles, p.lds_bytes, s);
+    } else {
+        if (p.tq == 8) rc = run_scan<16, 8, 16>(a, p.ntiles, p.lds_bytes, s);
+        else rc = run_scan<16, 4, 16>(a, p.ntiles, p.lds_bytes, s);
+    }
+    if (rc != PSC_OK) return rc;
+    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)nq), dim3(64), 0, s, a.part_d, a.part_i, p.nslice, k,
+                       (int64_t)0, a.status, ids_dev, dists_dev);
+    PSC_HIP_TRY(hipGetLastError());
+    return PSC_OK;
+}
+
+int launch_hamming_filter(int m, const uint8_t *qcodes_dev, int64_t nq, const uint8_t *codes_dev,
+                          int64_t n, int ht, int64_t *nsurv_dev, uint8_t *hdist_dev, hipStream_t s)
+{
+    if (m != 8 && m != 16) {
+        set_error("m must be 8 or 16, got %d", m);
+        return PSC_EINVAL;
+    }
+    PSC_REQUIRE(nq >= 0 && n >= 0 && ht >= 0, "bad sizes");
+    if (nq == 0) return PSC_OK;
+    PSC_REQUIRE(nsurv_dev && qcodes_dev, "null pointer");
+    PSC_REQUIRE(nq <= 65535, "at most 65535 queries per filter call");
+    hipLaunchKernelGGL(zero_u64_kernel, dim3((unsigned)((nq + 255) / 256)), dim3(256), 0, s,
+                       (unsigned long long *)nsurv_dev, nq);
+    if (n == 0) return PSC_OK;
+    PSC_REQUIRE(codes_dev, "null pointer");
+    PSC_REQUIRE(((uintptr_t)codes_dev & 3) == 0 && ((uintptr_t)qcodes_dev & 3) == 0, "codes must be 4-byte aligned");
+    const unsigned gx = (unsigned)std::min<int64_t>((n + 255) / 256, 2048);
+    if (m == 8)
+        hipLaunchKernelGGL((hamming_filter_kernel<8>), dim3(gx, (unsigned)nq), dim3(256), 0, s, qcodes_dev, nq,
+                           codes_dev, n, ht, (unsigned long long *)nsurv_dev, hdist_dev);
+    else
+        hipLaunchKernelGGL((hamming_filter_kernel<16>), dim3(gx, (unsigned)nq), dim3(256), 0, s, qcodes_dev, nq,
+                           codes_dev, n, ht, (unsigned long long *)nsurv_dev, hdist_dev);
+    PSC_HIP_TRY(hipGetLastError());
+    return PSC_OK;
+}
+
+}  // namespace psc

@@ -1,0 +1,140 @@
+"""Parity of the fused HIP scan with the CPU oracle, through the C ABI (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import workloads as W
+from gpu_util import RTOL, assert_topk_matches
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def psc():
+    import paper_1609_01882_amd as p
+    assert torch.cuda.is_available()
+    return p
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _rand_problem(m, n, nq, seed, lut_kind):
+    rng = np.random.default_rng(seed)
+    codes = W.random_codes(n, m, seed=seed)
+    # query codes near some database codes so that low thresholds still see survivors
+    qcodes = codes[rng.integers(0, max(n, 1), size=nq)].copy() if n > 0 else W.random_codes(nq, m, seed + 1)
+    flip = rng.integers(0, 256, size=qcodes.shape).astype(np.uint8) & rng.integers(0, 256, size=qcodes.shape).astype(np.uint8)
+    qcodes ^= flip
+    if lut_kind == "int":      # few small integers: sums exact in float32, many exact ties
+        lut = rng.integers(0, 4, size=(nq, m, 256)).astype(np.float32)
+    else:
+        lut = (rng.random(size=(nq, m, 256)) * 1000.0).astype(np.float32)
+    return codes, qcodes, lut
+
+
+def _run(psc, lut, qcodes, codes, ht, k):
+    ids, d = psc.scan(_dev(lut), _dev(qcodes), _dev(codes), ht, k)
+    torch.cuda.synchronize()
+    return ids.cpu().numpy(), d.cpu().numpy()
+
+
+@pytest.mark.parametrize("m,n,nq,k,lut_kind", [
+    (8, 100_003, 37, 10, "float"),      # ragged tail (odd n), ragged query tile
+    (8, 100_003, 37, 100, "int"),       # exact ties: ids must match exactly
+    (8, 4096, 16, 100, "float"),
+    (8, 70_001, 5, 1, "float"),
+    (16, 50_001, 19, 10, "float"),
+    (16, 50_001, 19, 100, "int"),
+    (8, 30_000, 3, 300, "int"),         # k > 128: smaller query tile
+    (16, 20_000, 9, 1024, "float"),     # maximum k
+])
+def test_scan_random_codes(psc, m, n, nq, k, lut_kind):
+    codes, qcodes, lut = _rand_problem(m, n, nq, seed=100 + m + k, lut_kind=lut_kind)
+    nb = 8 * m
+    for ht in sorted({0, nb // 4, nb * 3 // 8, nb // 2 - 4, nb // 2, nb, nb + 50}):
+        print(f"case m={m} n={n} nq={nq} k={k} lut={lut_kind} ht={ht}", flush=True)
+        got_ids, got_d = _run(psc, lut, qcodes, codes, ht, k)
+        ref = O.scan(lut.astype(np.float64), qcodes, codes, ht, k)
+        nd = assert_topk_matches(got_ids, got_d, ref, lut.astype(np.float64), qcodes, codes, min(ht, nb),
+                                 what=f"m={m} ht={ht} k={k}")
+        if lut_kind == "int":
+            assert nd == 0 and np.array_equal(got_d[ref["ids"] >= 0], ref["dists"][ref["ids"] >= 0])
+
+
+@pytest.mark.parametrize("m", [8, 16])
+def test_hamming_filter_is_bit_exact(psc, m):
+    codes, qcodes, _ = _rand_problem(m, 20_011, 23, seed=7 + m, lut_kind="int")
+    want = O.hamming_matrix(qcodes, codes)
+    for ht in (0, 2 * m, 3 * m, 4 * m, 8 * m):
+        ns, hd = psc.hamming_filter(_dev(qcodes), _dev(codes), ht, want_distances=True)
+        torch.cuda.synchronize()
+        assert np.array_equal(hd.cpu().numpy().astype(np.int32), want)
+        assert np.array_equal(ns.cpu().numpy(), (want <= ht).sum(axis=1))
+        ref = O.scan(np.zeros((23, m, 256)), qcodes, codes, ht, 1)
+        assert np.array_equal(ns.cpu().numpy(), ref["nsurv"])
+
+
+@pytest.mark.parametrize("m", [8, 16])
+def test_survivor_set_through_the_fused_scan(psc, m):
+    """With k above the number of survivors the result lists exactly the survivor set."""
+    codes, qcodes, lut = _rand_problem(m, 60_000, 11, seed=50 + m, lut_kind="float")
+    ht = 2 * m + 2
+    ref = O.scan(lut.astype(np.float64), qcodes, codes, ht, 1024, want_bitmap=True)
+    assert ref["nsurv"].max() < 1024 and ref["nsurv"].max() > 0
+    got_ids, got_d = _run(psc, lut, qcodes, codes, ht, 1024)
+    for q in range(11):
+        surv = np.flatnonzero(ref["bitmap"][q])
+        assert sorted(got_ids[q][got_ids[q] >= 0].tolist()) == surv.tolist()
+
+
+def test_hand_built_patterns_through_the_scan(psc):
+    """Row r of the database has exactly r bits set; the query code is zero; table = first byte."""
+    for m in (8, 16):
+        nb = 8 * m
+        codes = np.zeros((nb + 1, m), np.uint8)
+        for r in range(nb + 1):
+            full, rem = divmod(r, 8)
+            codes[r, :full] = 0xFF
+            if rem:
+                codes[r, full] = (1 << rem) - 1
+        lut = np.zeros((1, m, 256), np.float32)
+        lut[0, m - 1, :] = 1.0 + np.arange(256)
+        qc = np.zeros((1, m), np.uint8)
+        for ht in (0, 1, 7, 8, 9, nb // 2, nb - 1, nb):
+            got_ids, got_d = _run(psc, lut, qc, codes, ht, nb + 5)
+            ref = O.scan(lut.astype(np.float64), qc, codes, ht, nb + 5)
+            assert np.array_equal(got_ids, ref["ids"]) and (got_ids[0] >= 0).sum() == ht + 1
+            assert np.array_equal(got_d[got_ids >= 0], ref["dists"][ref["ids"] >= 0])
+
+
+def test_edge_sizes(psc):
+    m, k = 8, 5
+    lut = np.ones((3, m, 256), np.float32)
+    qc = np.zeros((3, m), np.uint8)
+    # empty database: all padding
+    ids, d = _run(psc, lut, qc, np.zeros((0, m), np.uint8), 64, k)
+    assert np.all(ids == -1) and np.all(np.isinf(d))
+    # no queries
+    ids, d = psc.scan(_dev(lut[:0]), _dev(qc[:0]), _dev(np.zeros((10, m), np.uint8)), 64, k)
+    assert ids.shape == (0, k)
+    # tiny databases
+    for n in (1, 2, 63, 64, 65, 127, 129):
+        codes = W.random_codes(n, m, seed=n)
+        ids, d = _run(psc, lut, qc, codes, 64, k)
+        ref = O.scan(lut.astype(np.float64), qc, codes, 64, k)
+        assert np.array_equal(ids, ref["ids"]), n
+    # bad arguments are errors, not crashes
+    with pytest.raises(psc.PscError):
+        psc.scan(_dev(lut), _dev(qc), _dev(W.random_codes(10, m, 1)), 64, 0)
+    with pytest.raises(psc.PscError):
+        psc.scan(_dev(lut), _dev(qc), _dev(W.random_codes(10, m, 1)), -1, 5)
+
+
+def test_scan_is_deterministic(psc):
+    codes, qcodes, lut = _rand_problem(8, 200_000, 64, seed=9, lut_kind="float")
+    a = _run(psc, lut, qcodes, codes, 26, 100)
+    b = _run(psc, lut, qcodes, codes, 26, 100)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])

@@ -1,0 +1,90 @@
+"""Parity of tables, encoding and the whole flat search with the oracle on the trained,
+SIFT-like workload (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import workloads as W
+from gpu_util import RTOL, assert_topk_matches
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def setup():
+    import paper_1609_01882_amd as psc
+    out = {}
+    for m in (8, 16):
+        xt = W.sift_like(4000, seed=60 + m, stream=1)
+        xb = W.sift_like(60_001, seed=60 + m, stream=2)
+        xq = W.sift_like(50, seed=60 + m, stream=3)
+        idx = psc.Index(128, m)
+        idx.train_pq(xt, iters=5, seed=1)
+        idx.optimize_index_assignment(n_iter=30_000, seed=2)
+        out[m] = dict(idx=idx, cb=idx.get_codebook(), xb=xb, xq=xq)
+    out["psc"] = psc
+    return out
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+@pytest.mark.parametrize("m", [8, 16])
+def test_tables_and_query_codes(setup, m):
+    s = setup[m]
+    lut, qc = s["idx"].build_lut(_dev(s["xq"]))
+    torch.cuda.synchronize()
+    lut, qc = lut.cpu().numpy(), qc.cpu().numpy()
+    ref = O.build_lut(s["xq"], s["cb"])
+    assert np.allclose(lut, ref, rtol=RTOL, atol=1e-4)
+    # the query code is the arg-min of the float32 table row (lowest index on ties) ...
+    assert np.array_equal(qc, lut.argmin(axis=2).astype(np.uint8))
+    # ... and a valid code in the oracle's eyes: its entry is within tolerance of the row minimum
+    pick = np.take_along_axis(ref, qc[:, :, None].astype(np.int64), axis=2)[:, :, 0]
+    assert np.all(pick <= ref.min(axis=2) * (1 + RTOL) + 1e-4)
+    assert (qc == O.query_codes(ref)).mean() > 0.999
+
+
+@pytest.mark.parametrize("m", [8, 16])
+def test_encode(setup, m):
+    s = setup[m]
+    codes = s["idx"].encode(_dev(s["xb"])).cpu().numpy()
+    ref = O.encode(s["xb"][:20_000], s["cb"])
+    got = codes[:20_000]
+    bad = np.argwhere(got != ref)
+    assert len(bad) < 20  # only near-ties may differ
+    dsub = 128 // m
+    for i, j in bad:
+        v = s["xb"][i, j * dsub:(j + 1) * dsub].astype(np.float64)
+        da = ((v - s["cb"][j, got[i, j]]) ** 2).sum()
+        db = ((v - s["cb"][j, ref[i, j]]) ** 2).sum()
+        assert abs(da - db) <= RTOL * db
+    s["codes"] = codes
+
+
+@pytest.mark.parametrize("m", [8, 16])
+def test_whole_search_matches_oracle(setup, m):
+    s = setup[m]
+    idx = s["idx"]
+    if "codes" not in s:
+        s["codes"] = idx.encode(_dev(s["xb"])).cpu().numpy()
+    codes = s["codes"]
+    q_dev, c_dev = _dev(s["xq"]), _dev(codes)
+    lut, qc = idx.build_lut(q_dev)
+    lut64, qc = lut.cpu().numpy().astype(np.float64), qc.cpu().numpy()
+    nb = 8 * m
+    for ht, k in ((nb // 4, 10), (nb * 3 // 8, 10), (nb * 3 // 8, 100), (nb // 2, 100), (nb, 100)):
+        print(f"search m={m} ht={ht} k={k}", flush=True)
+        ids, d = idx.search(q_dev, c_dev, ht, k)
+        torch.cuda.synchronize()
+        ref = O.scan(lut64, qc, codes, ht, k)
+        assert_topk_matches(ids.cpu().numpy(), d.cpu().numpy(), ref, lut64, qc, codes, ht, what=f"m={m} ht={ht}")
+        # and against the oracle's own double-precision tables: same ranking up to tolerance ties
+        ref2 = O.search_flat(s["xq"], s["cb"], codes, ht, k)
+        same_codes = np.all(O.query_codes(O.build_lut(s["xq"], s["cb"])) == qc, axis=1)
+        assert same_codes.mean() > 0.9
+        gd = d.cpu().numpy()[same_codes]
+        fin = np.isfinite(ref2["dists"][same_codes])
+        assert np.allclose(gd[fin], ref2["dists"][same_codes][fin], rtol=RTOL)

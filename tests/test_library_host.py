@@ -1,0 +1,95 @@
+"""CPU-side checks of the HIP library: it loads, exports every symbol the header declares,
+rejects bad arguments, and its host-side training obeys the same invariants as the oracle's.
+No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle as O
+import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def psc():
+    import paper_1609_01882_amd as p
+    if not os.path.exists(p.lib_path()):
+        import __graft_entry__ as g
+        g.build()
+    return p
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "psc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(psc_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(psc):
+    lib = C.CDLL(psc.lib_path())
+    names = _declared()
+    assert len(names) >= 16
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(psc.exported_symbols()) == names
+    assert psc.version() >= 100
+
+
+def test_argument_errors(psc):
+    with pytest.raises(psc.PscError):
+        psc.Index(128, 7)
+    with pytest.raises(psc.PscError):
+        psc.Index(130, 8)
+    idx = psc.Index(128, 8)
+    with pytest.raises(psc.PscError):
+        idx.get_codebook()  # nothing trained yet
+    with pytest.raises(psc.PscError):
+        idx.train_pq(np.zeros((10, 128), np.float32))  # too few vectors
+    assert psc.scan_workspace_bytes(8, 100, 1000, 10) > 0
+    assert psc.scan_workspace_bytes(12, 100, 1000, 10) == 0
+    assert psc.scan_workspace_bytes(8, 100, 1000, 0) == 0
+    assert psc.scan_workspace_bytes(8, 100, 1000, psc.PSC_MAX_K + 1) == 0
+
+
+def test_codebook_round_trip(psc):
+    idx = psc.Index(64, 16)
+    cb = np.random.default_rng(0).normal(size=(16, 256, 4)).astype(np.float32)
+    idx.set_codebook(cb)
+    assert np.array_equal(idx.get_codebook(), cb)
+
+
+def test_host_kmeans_quality(psc):
+    """The library's k-means must quantize about as well as the oracle's (different seeds and
+    start, so only the quantization error is compared)."""
+    xt = W.sift_like(4000, seed=11, stream=1)
+    idx = psc.Index(128, 8)
+    idx.train_pq(xt, iters=6, seed=3)
+    cb = idx.get_codebook().astype(np.float64)
+    cb_ref = O.train_pq(xt, 8, iters=6, seed=3)
+    xe = W.sift_like(2000, seed=11, stream=2)
+
+    def err(c):
+        return ((xe - O.decode(O.encode(xe, c), c)) ** 2).sum(axis=1).mean()
+    assert err(cb) < 1.05 * err(cb_ref)
+    assert np.isfinite(cb).all()
+
+
+def test_annealing_matches_oracle_trajectory(psc):
+    """Same counter-based draws, same double-precision objective: the library's annealing
+    must end on the oracle's permutation and renumber the codebook the same way."""
+    xt = W.sift_like(3000, seed=12, stream=1)
+    cb0 = O.train_pq(xt, 8, iters=3, seed=5).astype(np.float32)
+    idx = psc.Index(128, 8)
+    idx.set_codebook(cb0)
+    pi, loss = idx.optimize_index_assignment(n_iter=30_000, seed=77)
+    cb_ref, pis_ref, (li, lf) = O.optimize_index_assignment(cb0.astype(np.float64), n_iter=30_000, seed=77)
+    assert np.array_equal(pi, pis_ref)
+    assert np.allclose(loss[:, 0], li, rtol=1e-12) and np.allclose(loss[:, 1], lf, rtol=1e-9)
+    assert np.array_equal(idx.get_codebook(), cb_ref.astype(np.float32))
+    for j in range(8):
+        assert sorted(pi[j].tolist()) == list(range(256))
+    assert np.all(loss[:, 1] < loss[:, 0])
