@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the polysemous search hot path on one MI355X.
+
+One "step" = one pass of the whole flat search path over the flat 64-bit workload:
+ADC tables + query codes for the 10,000-query batch, the fused Hamming-filter + ADC + top-k
+scan over the 10,000,000 64-bit codes, and the merge of the partial lists -- with queries,
+codebook and codes already resident in HBM.  Inputs are seeded and synthetic (SIFT-like
+mixture, see workloads/).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--ht 24] [--small] [--no-sweep] [--no-cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3e12 32-bit integer lane-ops/s
+# (half of the 78.6 TFLOP/s non-packed fp32 vector rate, which counts an FMA as two).
+PEAK_INT_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+# Algorithmic integer work per (query, code) pair: per 32-bit word one xor and one
+# popcount-accumulate, plus one compare against the threshold.
+OPS_PER_PAIR = {8: 5, 16: 9}
+
+# HBM traffic per scan launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see
+# profiles/), keyed by (workload, ht); None until measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--ht", type=int, default=24)
+    ap.add_argument("--small", action="store_true", help="1M codes / 1000 queries (quick check)")
+    ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--cpu-queries", type=int, default=192)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py: this build measures one GPU only (the path shards without any exchange, "
+            "see DESIGN.md); run with --gpus 1")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_1609_01882_amd as psc
+    import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.backends.cuda.matmul.allow_tf32 = False
+    cfg = W.get_config("flat64")
+    n_db, nq, k, m = cfg.n_db, cfg.n_query, cfg.k, cfg.m
+    if args.small:
+        n_db, nq = 1_000_000, 1_000
+    threads = min(16, os.cpu_count() or 1)
+
+    # ------------------------------------------------------------------ set-up (untimed)
+    t0 = time.time()
+    xt = cfg.vectors("train", threads=threads)
+    idx = psc.Index(cfg.dim, m)
+    idx.train_pq(xt, iters=20, seed=cfg.seed)
+    pi, losses = idx.optimize_index_assignment(seed=cfg.seed)   # the paper's annealing constants
+    log(f"[setup] PQ trained + index assignment optimised in {time.time() - t0:.1f}s "
+        f"(loss {losses[:, 0].mean():.0f} -> {losses[:, 1].mean():.0f})")
+
+    xq = cfg.vectors("query", n=nq, threads=threads)
+    q_dev = torch.from_numpy(xq).to(dev)
+    qn = (q_dev * q_dev).sum(dim=1)
+
+    # database: generate, encode and compute the exact nearest neighbour chunk by chunk, so the
+    # raw vectors never have to be resident all at once
+    t0 = time.time()
+    codes = torch.empty((n_db, m), dtype=torch.uint8, device=dev)
+    best_d = torch.full((nq,), float("inf"), device=dev)
+    best_i = torch.full((nq,), -1, dtype=torch.int64, device=dev)
+    chunk = 1_000_000
+    for s in range(0, n_db, chunk):
+        c = min(chunk, n_db - s)
+        xb = torch.from_numpy(cfg.vectors("db", n=c, start=s, threads=threads)).to(dev)
+        idx.encode(xb, out=codes[s:s + c])
+        # exact squared L2 (integer-valued data: exact in float32)
+        d = qn[:, None] - 2.0 * (q_dev @ xb.T) + (xb * xb).sum(dim=1)[None, :]
+        dmin, imin = d.min(dim=1)
+        better = dmin < best_d
+        best_d = torch.where(better, dmin, best_d)
+        best_i = torch.where(better, imin + s, best_i)
+        del xb, d
+    torch.cuda.synchronize()
+    log(f"[setup] {n_db} vectors generated, encoded, ground truth done in {time.time() - t0:.1f}s")
+
+    ws = torch.empty(idx.search_workspace_bytes(nq, n_db, k), dtype=torch.uint8, device=dev)
+    ids = torch.empty((nq, k), dtype=torch.int64, device=dev)
+    dists = torch.empty((nq, k), dtype=torch.float32, device=dev)
+    scan_ws = torch.empty(psc.scan_workspace_bytes(m, nq, n_db, k), dtype=torch.uint8, device=dev)
+
+    def step(ht, ev=None):
+        """The whole path; the scan launch is bracketed by events when `ev` is given."""
+        lut, qc = idx.build_lut(q_dev)
+        if ev is not None:
+            ev[0].record()
+        psc.scan(lut, qc, codes, ht, k, workspace=scan_ws, out=(ids, dists))
+        if ev is not None:
+            ev[1].record()
+
+    def run(ht, steps, warmup):
+        for _ in range(warmup):
+            step(ht)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step(ht, evs[i])
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) / steps
+        scan_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+        psc.workspace_status(scan_ws)
+        return wall * 1e3, scan_ms
+
+    ms_step, scan_ms = run(args.ht, args.steps, args.warmup)
+    pairs = float(nq) * float(n_db)
+    recall10 = float((ids[:, :10] == best_i[:, None]).any(dim=1).float().mean())
+    nsurv = psc.hamming_filter(idx.build_lut(q_dev[:256])[1], codes, args.ht)
+    torch.cuda.synchronize()
+    surv_rate = float(nsurv.double().mean()) / n_db
+    log(f"[bench] ht={args.ht}: {ms_step:.2f} ms/step, scan {scan_ms:.2f} ms, "
+        f"{pairs / ms_step / 1e9:.1f} G pairs/s... recall@10 {recall10:.4f}, survivors {surv_rate:.4%}")
+
+    sweep = []
+    if not args.no_sweep:
+        for ht in cfg.hts:
+            w, sms = run(ht, 2, 1)
+            r10 = float((ids[:, :10] == best_i[:, None]).any(dim=1).float().mean())
+            r100 = float((ids[:, :100] == best_i[:, None]).any(dim=1).float().mean())
+            ns = psc.hamming_filter(idx.build_lut(q_dev[:256])[1], codes, ht)
+            torch.cuda.synchronize()
+            sweep.append(dict(ht=ht, ms_per_step=round(w, 3), scan_ms=round(sms, 3),
+                              pairs_per_s=pairs / (w * 1e-3), recall_at_10=r10, recall_at_100=r100,
+                              survivor_rate=float(ns.double().mean()) / n_db))
+            log(f"[sweep] {sweep[-1]}")
+
+    # ------------------------------------------------------------------ CPU baseline: the oracle
+    cpu = None
+    if not args.no_cpu:
+        import oracle as O
+        nqc = min(args.cpu_queries, nq)
+        lut, qc = idx.build_lut(q_dev[:nqc])
+        psc.scan(lut, qc, codes, args.ht, k, out=(ids[:nqc], dists[:nqc]))
+        torch.cuda.synchronize()
+        lut_h, qc_h, codes_h = lut.cpu().numpy().astype(np.float64), qc.cpu().numpy(), codes.cpu().numpy()
+        t0 = time.perf_counter()
+        ref = O.scan(lut_h, qc_h, codes_h, args.ht, k)
+        dt = time.perf_counter() - t0
+        agree = float((ref["ids"] == ids[:nqc].cpu().numpy()).mean())
+        cpu = dict(value=nqc * float(n_db) / dt, unit="pairs/s", cores=O.num_threads(), kind="oracle",
+                   sample=f"first {nqc} queries x all {n_db} codes, ht={args.ht}, k={k}, {dt:.1f}s",
+                   ids_agree_with_gpu=agree)
+        log(f"[cpu] oracle: {cpu}")
+
+    ops = OPS_PER_PAIR[m] * pairs
+    achieved = ops / (scan_ms * 1e-3) / 1e12
+    out = {
+        "metric": "codes scanned/sec (Hamming filter+ADC, 64-bit codes, 10M DB) + recall@10",
+        "value": pairs / (ms_step * 1e-3),
+        "unit": "pairs/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32 popcount + f32 ADC",
+        "data": "synthetic",
+        "config": {"workload": "flat64" + ("-small" if args.small else ""), "n_db": n_db, "n_query": nq,
+                   "code_bits": 8 * m, "ht": args.ht, "k": k},
+        "recall_at_10": recall10,
+        "survivor_rate": surv_rate,
+        "roofline": {"bound": "alu", "kernel": "scan_kernel<8,16,16>", "achieved": achieved,
+                     "peak": PEAK_INT_TOPS, "unit": "TOP/s (int32 lane-ops)", "frac": achieved / PEAK_INT_TOPS,
+                     "ops_per_pair": OPS_PER_PAIR[m], "kernel_ms": scan_ms,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(("flat64", args.ht))},
+        "cpu_baseline": cpu,
+        "sweep": sweep,
+        "paper_context": {"adc_evals_per_s_per_core": 222e6, "hamming_evals_per_s_per_core": 1.19e9,
+                          "note": "paper's CPU figures for 8-byte codes, one 2.8 GHz core (Fig. 1)"},
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

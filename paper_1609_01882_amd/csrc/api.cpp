@@ -2,6 +2,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <thread>
 
 #include "common.h"
 
@@ -115,21 +116,27 @@ int psc_optimize_index_assignment(psc_index *idx, int64_t n_iter, double t0, dou
     PSC_REQUIRE(n_iter >= 0 && t0 >= 0.0 && t_decay > 0.0 && t_decay <= 1.0 && alpha > 0.0,
                 "bad annealing parameters");
     const size_t sq = (size_t)kCentroids * idx->dsub;
-    std::vector<float> renum(sq);
+    // sub-quantizers are independent problems (Section 3, opening): one host thread each
+    std::vector<std::thread> pool;
     for (int j = 0; j < idx->m; ++j) {
-        float *cent = &idx->cb_host[(size_t)j * sq];
-        uint8_t pi[kCentroids];
-        double before = 0.0, after = 0.0;
-        host_anneal(cent, idx->dsub, n_iter, t0, t_decay, alpha, seed + (uint64_t)j, pi, &before, &after);
-        for (int i = 0; i < kCentroids; ++i)
-            std::memcpy(&renum[(size_t)pi[i] * idx->dsub], cent + (size_t)i * idx->dsub, sizeof(float) * idx->dsub);
-        std::memcpy(cent, renum.data(), sizeof(float) * sq);
-        if (perm_out_host) std::memcpy(perm_out_host + (size_t)j * kCentroids, pi, kCentroids);
-        if (loss_out_host) {
-            loss_out_host[2 * j] = before;
-            loss_out_host[2 * j + 1] = after;
-        }
+        pool.emplace_back([=] {
+            float *cent = &idx->cb_host[(size_t)j * sq];
+            std::vector<float> renum(sq);
+            uint8_t pi[kCentroids];
+            double before = 0.0, after = 0.0;
+            host_anneal(cent, idx->dsub, n_iter, t0, t_decay, alpha, seed + (uint64_t)j, pi, &before, &after);
+            for (int i = 0; i < kCentroids; ++i)
+                std::memcpy(&renum[(size_t)pi[i] * idx->dsub], cent + (size_t)i * idx->dsub,
+                            sizeof(float) * idx->dsub);
+            std::memcpy(cent, renum.data(), sizeof(float) * sq);
+            if (perm_out_host) std::memcpy(perm_out_host + (size_t)j * kCentroids, pi, kCentroids);
+            if (loss_out_host) {
+                loss_out_host[2 * j] = before;
+                loss_out_host[2 * j + 1] = after;
+            }
+        });
     }
+    for (auto &t : pool) t.join();
     return mark_codebook_changed(idx);
 }
 
