@@ -4,13 +4,14 @@
 //   * the TQ ADC tables (TQ * m * 256 float32) and the TQ running top-k lists live in LDS for
 //     the lifetime of the workgroup;
 //   * the TQ query codes live in scalar registers;
-//   * every wave streams blocks of 64 x C codes from memory into vector registers (one 16-byte
-//     load per lane, the next block prefetched) and compares each code with all TQ query codes:
-//     xor + popcount-accumulate per 32-bit word, then one funnel shift that appends the
-//     "too far" bit to a per-lane mask: 5 integer instructions per (query, 64-bit code) pair;
-//   * lanes that hold survivors append (query slot, code position) entries to a per-wave ring
-//     in LDS, positions assigned with ballot + prefix popcount, so that the expensive step runs
-//     on full wavefronts;
+//   * every wave streams blocks of 64 x CB codes from memory into vector registers (16-byte
+//     loads, the next block prefetched; CB = 32 / TQ codes per lane) and compares each code with
+//     all TQ query codes: xor + popcount-accumulate per 32-bit word, then one funnel shift that
+//     appends the "too far" bit to a 32-bit per-lane mask (one bit per (code, query)):
+//     5 integer instructions per (query, 64-bit code) pair;
+//   * lanes that hold survivors append one (bit number, code position) entry per turn to a
+//     per-wave ring in LDS, positions assigned with ballot + prefix popcount, so that the
+//     expensive step runs on full wavefronts;
 //   * whenever the ring holds 64 entries the wave drains them: re-reads the 64 codes, gathers
 //     m table entries each from LDS, sums them in float32 (j ascending) and compares with the
 //     query's current k-th best distance;
@@ -25,7 +26,7 @@ namespace psc {
 namespace {
 
 constexpr int kQueueCap = 128;        // ring entries per wave (power of two, >= 2*64)
-constexpr int kRelBits = 28;          // bits of a ring entry holding the position inside the slice
+constexpr int kRelBits = 27;          // bits of a ring entry holding the position inside the slice
 constexpr uint32_t kRelMask = (1u << kRelBits) - 1;
 constexpr int64_t kMaxSliceLen = (int64_t)1 << kRelBits;
 constexpr int kSpinLimit = 1 << 22;   // bounded wait on a list lock (each turn sleeps)
@@ -182,11 +183,11 @@ __device__ __forceinline__ void insert_candidates(const Lds<M, TQ> &s, const Sca
         __hip_atomic_store(&s.lock[q], 0, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
-// Score `nvalid` ring entries starting at `head` and feed the ones that beat the current
-// threshold to the lists.
+// Score the first `nvalid` (<= 64) entries of the wave's queue and feed the ones that beat the
+// current threshold to the lists.
 template <int M, int TQ>
-__device__ __forceinline__ void drain(const Lds<M, TQ> &s, const ScanArgs &a, lds_vu32 *ring, int head,
-                      int nvalid, int64_t slice_begin, int64_t q0)
+__device__ __forceinline__ void drain(const Lds<M, TQ> &s, const ScanArgs &a, lds_vu32 *ring,
+                                      int nvalid, int64_t slice_begin, int64_t q0)
 {
     const int lane = lane_id();
     const bool act = lane < nvalid;
@@ -194,9 +195,11 @@ __device__ __forceinline__ void drain(const Lds<M, TQ> &s, const ScanArgs &a, ld
     uint32_t rel = 0;
     int q = 0;
     if (act) {
-        const uint32_t e = ring[(head + lane) & (kQueueCap - 1)];
-        q = (int)(e >> kRelBits);
-        rel = e & kRelMask;
+        // entry = (b << kRelBits) | position of the lane's first code; b = c * TQ + (TQ - 1 - q)
+        const uint32_t e = ring[lane];
+        const uint32_t b = e >> kRelBits;
+        q = (int)((TQ - 1) - (b & (TQ - 1)));
+        rel = (e & kRelMask) + b / TQ;
         const uint32_t *cw = (const uint32_t *)(a.codes + (slice_begin + rel) * M);
         uint32_t w[M / 4];
         if constexpr (M == 8) {
@@ -239,7 +242,10 @@ scan_kernel(ScanArgs a)
     extern __shared__ __align__(16) unsigned char smem[];
     const Lds<M, TQ> s((PSC_LDS unsigned char *)smem, a.kpad);
     constexpr int WPC = M / 4;       // 32-bit words per code
-    constexpr int C = 4 / WPC;       // codes per 16-byte load: 2 (64-bit) or 1 (128-bit)
+    constexpr int CB = 32 / TQ;      // codes per lane and block: one survivor bit per (code, query)
+    constexpr int NLD = CB * M / 16; // 16-byte loads per lane and block
+    constexpr int CPL = 16 / M;      // codes per 16-byte load
+    static_assert(CB * TQ == 32 && NLD >= 1, "tile shape");
     const int tid = (int)threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -282,80 +288,115 @@ scan_kernel(ScanArgs a)
     }
     __syncthreads();
 
-    // bit b of a per-lane mask <-> query slot TQ-1-b; only the first nvq slots are real
-    const uint32_t qmask = (nvq == TQ) ? ((TQ == 32) ? 0xffffffffu : ((1u << TQ) - 1u))
-                                       : (((1u << TQ) - 1u) & ~((1u << (TQ - nvq)) - 1u));
+    // bit TQ-1-q of a code's TQ-bit field <-> query slot q; only the first nvq slots are real
+    const uint32_t qmask = ((1u << TQ) - 1u) & ~((1u << (TQ - nvq)) - 1u);
+    uint32_t qmask_all = 0u;
+#pragma unroll
+    for (int c = 0; c < CB; ++c) qmask_all |= qmask << (c * TQ);
     lds_vu32 *ring = s.queue + wave * kQueueCap;
-    int head = 0, tail = 0;  // wave-uniform ring cursors (tail - head < 64 between steps)
+    const uint32_t ring_base = (uint32_t)(uintptr_t)ring;  // LDS byte address of the wave's queue
+    int fill = 0;  // wave-uniform: entries waiting in the queue (< 64 between turns)
 
     const uint32_t bias = a.bias;
-    const int64_t stride = (int64_t)NW * 64 * C;
-    int64_t pos = slice_begin + (int64_t)wave * 64 * C + (int64_t)lane * C;
+    const int64_t stride = (int64_t)NW * 64 * CB;
+    const int64_t wave_first = slice_begin + (int64_t)wave * 64 * CB;
+    const uint8_t *lane_ptr = a.codes + (wave_first + (int64_t)lane * CB) * M;  // lane's first code
 
-    auto load_block = [&](int64_t p, uint32_t (&w)[4]) {
-        w[0] = w[1] = w[2] = w[3] = 0u;
-        if (p + C <= slice_end) {
-            const uint4 v = *(const uint4 *)(a.codes + p * M);
-            w[0] = v.x;
-            w[1] = v.y;
-            w[2] = v.z;
-            w[3] = v.w;
-        } else if (p < slice_end) {  // only when C == 2: the last, odd code
-            const uint2 v = *(const uint2 *)(a.codes + p * M);
-            w[0] = v.x;
-            w[1] = v.y;
+    // The lane's CB consecutive codes as NLD 16-byte loads.  `whole` (wave-uniform) says the
+    // wave's block lies entirely inside the slice; otherwise codes past the end read as zero
+    // (their survivor bits are masked off below).
+    auto load_block = [&](const uint8_t *ptr, int64_t first, bool whole, uint32_t (&w)[CB * WPC]) {
+        if (whole) {
+#pragma unroll
+            for (int l = 0; l < NLD; ++l) {
+                const uint4 v = *(const uint4 *)(ptr + l * 16);
+                w[l * 4 + 0] = v.x;
+                w[l * 4 + 1] = v.y;
+                w[l * 4 + 2] = v.z;
+                w[l * 4 + 3] = v.w;
+            }
+        } else {
+            const int64_t p = first + (int64_t)lane * CB;
+#pragma unroll
+            for (int l = 0; l < NLD; ++l) {
+                const int64_t pl = p + l * CPL;
+                uint32_t *o = &w[l * 4];
+                o[0] = o[1] = o[2] = o[3] = 0u;
+                if (pl + CPL <= slice_end) {
+                    const uint4 v = *(const uint4 *)(ptr + l * 16);
+                    o[0] = v.x;
+                    o[1] = v.y;
+                    o[2] = v.z;
+                    o[3] = v.w;
+                } else if (CPL == 2 && pl < slice_end) {  // the last, odd 64-bit code
+                    const uint2 v = *(const uint2 *)(ptr + l * 16);
+                    o[0] = v.x;
+                    o[1] = v.y;
+                }
+            }
         }
     };
 
-    uint32_t cur[4];
-    load_block(pos, cur);
-    for (int64_t blk = slice_begin + (int64_t)wave * 64 * C; blk < slice_end; blk += stride, pos += stride) {
-        uint32_t nxt[4];
-        load_block(pos + stride, nxt);
+    uint32_t cur[CB * WPC];
+    if (wave_first < slice_end) load_block(lane_ptr, wave_first, wave_first + 64 * CB <= slice_end, cur);
+    for (int64_t blk = wave_first; blk < slice_end; blk += stride) {
+        const bool whole = blk + 64 * CB <= slice_end;
+        uint32_t nxt[CB * WPC];
+        lane_ptr += stride * M;
+        if (blk + stride < slice_end)
+            load_block(lane_ptr, blk + stride, blk + stride + 64 * CB <= slice_end, nxt);
 
-        // ---- Hamming filter: per code, one "too far" bit per query
-        uint32_t far[C];
+        // ---- Hamming filter: bit c*TQ + (TQ-1-q) of `far` <=> code c is too far from query q
+        uint32_t far = 0u;
 #pragma unroll
-        for (int c = 0; c < C; ++c) far[c] = 0u;
+        for (int c = CB - 1; c >= 0; --c) {
 #pragma unroll
-        for (int q = 0; q < TQ; ++q) {
-#pragma unroll
-            for (int c = 0; c < C; ++c) {
+            for (int q = 0; q < TQ; ++q) {
                 uint32_t acc = bias;
 #pragma unroll
                 for (int w = 0; w < WPC; ++w) acc += (uint32_t)__popc(cur[c * WPC + w] ^ qw[q][w]);
-                far[c] = __builtin_amdgcn_alignbit(far[c], acc, 31);
+                far = __builtin_amdgcn_alignbit(far, acc, 31);
             }
         }
-        // ---- survivors -> ring, full wavefronts -> ADC
+        // ---- survivors -> queue (one entry per lane and turn), full wavefronts -> ADC
+        uint32_t valid = qmask_all;
+        if (!whole) {
+            valid = 0u;
 #pragma unroll
-        for (int c = 0; c < C; ++c) {
-            uint32_t sv = (pos + c < slice_end) ? (~far[c] & qmask) : 0u;
-            const uint32_t rel = (uint32_t)(pos + c - slice_begin);
-            while (true) {
-                const bool has = sv != 0u;
-                const uint64_t bal = ballot64(has);
-                if (bal == 0) break;
-                if (has) {
-                    const int b = __builtin_ctz(sv);
-                    sv &= sv - 1u;
-                    const uint32_t q = (uint32_t)(TQ - 1 - b);
-                    ring[(tail + prefix_count(bal)) & (kQueueCap - 1)] = (q << kRelBits) | rel;
-                }
-                tail += __builtin_popcountll(bal);
-                if (tail - head >= 64) {
-                    __builtin_amdgcn_wave_barrier();
-                    drain<M, TQ>(s, a, ring, head, 64, slice_begin, q0);
-                    head += 64;
-                }
+            for (int c = 0; c < CB; ++c)
+                valid |= (blk + (int64_t)lane * CB + c < slice_end) ? (qmask << (c * TQ)) : 0u;
+        }
+        uint32_t sv = ~far & valid;
+        const uint32_t rel0 = (uint32_t)(blk - slice_begin) + (uint32_t)lane * CB;
+        while (true) {
+            const bool has = sv != 0u;
+            const uint64_t bal = ballot64(has);
+            if (bal == 0) break;
+            if (has) {
+                const uint32_t b = (uint32_t)__builtin_ctz(sv);
+                sv &= sv - 1u;
+                const uint32_t at = ring_base + 4u * (uint32_t)fill;  // scalar
+                *(lds_vu32 *)(uintptr_t)(at + 4u * (uint32_t)prefix_count(bal)) = (b << kRelBits) | rel0;
+            }
+            fill += __builtin_popcountll(bal);
+            if (fill >= 64) {
+                __builtin_amdgcn_wave_barrier();
+                drain<M, TQ>(s, a, ring, 64, slice_begin, q0);
+                // entries 64..fill-1 move to the front
+                fill -= 64;
+                uint32_t e = 0u;
+                if (lane < fill) e = ring[64 + lane];
+                __builtin_amdgcn_wave_barrier();
+                if (lane < fill) ring[lane] = e;
+                __builtin_amdgcn_wave_barrier();
             }
         }
 #pragma unroll
-        for (int e = 0; e < 4; ++e) cur[e] = nxt[e];
+        for (int e = 0; e < CB * WPC; ++e) cur[e] = nxt[e];
     }
-    if (tail - head > 0) {
+    if (fill > 0) {
         __builtin_amdgcn_wave_barrier();
-        drain<M, TQ>(s, a, ring, head, tail - head, slice_begin, q0);
+        drain<M, TQ>(s, a, ring, fill, slice_begin, q0);
     }
     __syncthreads();
 
@@ -525,8 +566,8 @@ int plan_scan(int m, int64_t nq, int64_t n, int k, ScanPlan *plan)
     }
     const int64_t nqt = (nq + p.tq - 1) / p.tq;
     // Slices: enough workgroups to fill 256 compute units a few times over, a whole number of
-    // 128-code blocks each, and short enough for the 28-bit position field.
-    const int64_t block = 128;
+    // blocks each, and short enough for the position field of a ring entry.
+    const int64_t block = 512;  // codes per wave and step, at most (64 lanes x 8 codes)
     int64_t want = 1;
     if (nqt > 0) {
         const int64_t target_wg = 1024;
