@@ -20,6 +20,8 @@
 // Partial lists (one per query and slice) go to the workspace; a second kernel merges them.
 //
 // Ordering everywhere: (distance, id) ascending, lower id first on equal distance.
+#include <cstdlib>
+
 #include "common.h"
 
 namespace psc {
@@ -72,27 +74,45 @@ __device__ __forceinline__ uint32_t bcast_u(uint32_t v, int lane)
 typedef PSC_LDS float lds_f32;
 typedef PSC_LDS volatile float lds_vf32;
 typedef PSC_LDS volatile uint32_t lds_vu32;
+typedef PSC_LDS uint32_t lds_u32;
 typedef PSC_LDS volatile int lds_vi32;
 typedef PSC_LDS int lds_i32;
+
+typedef PSC_LDS volatile uint64_t lds_vu64;
+
+// One list entry = (sortable distance key, id) packed in 64 bits, key in the high word, so that
+// the unsigned 64-bit order is the (distance, id) order.  The key is the usual order-preserving
+// map of float bits to unsigned (negative values flip all bits, others flip the sign bit);
+// -0 is folded into +0 first so that equal distances get equal keys.
+__device__ __forceinline__ uint64_t pack_entry(float d, uint32_t id)
+{
+    const uint32_t u = __float_as_uint(d + 0.0f);
+    const uint32_t key = u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
+    return ((uint64_t)key << 32) | id;
+}
+__device__ __forceinline__ float entry_dist(uint64_t e)
+{
+    const uint32_t key = (uint32_t)(e >> 32);
+    return __uint_as_float(key ^ ((key >> 31) ? 0x80000000u : 0xffffffffu));
+}
+__device__ __forceinline__ uint32_t entry_id(uint64_t e) { return (uint32_t)e; }
 
 template <int M, int TQ>
 struct Lds {
     lds_f32 *lut;    // [TQ][M][256]
-    lds_vf32 *topd;  // [TQ][kpad]
-    lds_vu32 *topi;  // [TQ][kpad]
+    lds_vu64 *top;   // [TQ][kpad] sorted ascending
     lds_vf32 *thr;   // [TQ] current k-th best distance (+inf until the list is full)
     lds_vi32 *cnt;   // [TQ] entries in the list
     lds_i32 *lock;   // [TQ]
-    lds_vu32 *queue; // [nwaves][kQueueCap]
+    lds_u32 *queue;  // [nwaves][kQueueCap]; private to a wave: LDS keeps a wave's accesses in order
     __device__ __forceinline__ Lds(PSC_LDS unsigned char *base, int kpad)
     {
         lut = (lds_f32 *)base;
-        topd = (lds_vf32 *)(lut + TQ * M * 256);
-        topi = (lds_vu32 *)(topd + TQ * kpad);
-        thr = (lds_vf32 *)(topi + TQ * kpad);
+        top = (lds_vu64 *)(lut + TQ * M * 256);
+        thr = (lds_vf32 *)(top + TQ * kpad);
         cnt = (lds_vi32 *)(thr + TQ);
         lock = (lds_i32 *)(cnt + TQ);
-        queue = (lds_vu32 *)(lock + TQ);
+        queue = (lds_u32 *)(lock + TQ);
     }
 };
 
@@ -121,62 +141,52 @@ __device__ __forceinline__ void insert_candidates(const Lds<M, TQ> &s, const Sca
         return;
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    lds_vf32 *ld = s.topd + q * a.kpad;
-    lds_vu32 *li = s.topi + q * a.kpad;
+    lds_vu64 *list = s.top + q * a.kpad;
     int cnt = s.cnt[q];
     const int k = a.k;
     while (mine) {
         const int src = __builtin_ctzll(mine);
         mine &= mine - 1;
-        const float cd = bcast_f(d, src);
-        const uint32_t ci = bcast_u(id, src);
-        if (cnt == k) {
-            const float wd = ld[k - 1];
-            const uint32_t wi = li[k - 1];
-            if (!(cd < wd || (cd == wd && ci < wi))) continue;
-        }
-        // rank of the candidate = number of list entries ordered before it
-        int pos = 0;
-        for (int base = 0; base < cnt; base += 64) {
-            const int p = base + lane;
-            bool before = false;
-            if (p < cnt) {
-                const float pd = ld[p];
-                const uint32_t pi = li[p];
-                before = pd < cd || (pd == cd && pi < ci);
-            }
-            pos += __builtin_popcountll(ballot64(before));
-        }
+        const uint64_t cand = pack_entry(bcast_f(d, src), bcast_u(id, src));
+        if (cnt == k && !(cand < list[k - 1])) continue;
         // entries pos..last-1 move one place down the list (the k-th falls off when full)
         const int last = cnt < k ? cnt : k - 1;
-        if (last > pos) {
-            for (int base = ((last - 1) >> 6) << 6; base >= ((pos >> 6) << 6); base -= 64) {
+        int pos = 0;
+        if (k <= 128) {
+            // whole list in two registers per lane: rank and shift in one pass
+            const int p0 = lane, p1 = 64 + lane;
+            uint64_t e0 = ~0ull, e1 = ~0ull;
+            if (p0 < cnt) e0 = list[p0];
+            if (p1 < cnt) e1 = list[p1];
+            const bool b0 = e0 < cand, b1 = e1 < cand;
+            pos = __builtin_popcountll(ballot64(b0)) + __builtin_popcountll(ballot64(b1));
+            if (!b0 && p0 < last) list[p0 + 1] = e0;
+            if (!b1 && p1 < last) list[p1 + 1] = e1;
+        } else {
+            for (int base = 0; base < cnt; base += 64) {
                 const int p = base + lane;
-                const bool mv = p >= pos && p < last;
-                float pd = 0.f;
-                uint32_t pi = 0;
-                if (mv) {
-                    pd = ld[p];
-                    pi = li[p];
+                const bool before = p < cnt && list[p] < cand;
+                pos += __builtin_popcountll(ballot64(before));
+            }
+            if (last > pos) {
+                for (int base = ((last - 1) >> 6) << 6; base >= ((pos >> 6) << 6); base -= 64) {
+                    const int p = base + lane;
+                    const bool mv = p >= pos && p < last;
+                    uint64_t e = 0;
+                    if (mv) e = list[p];
+                    __builtin_amdgcn_wave_barrier();
+                    if (mv) list[p + 1] = e;
+                    __builtin_amdgcn_wave_barrier();
                 }
-                __builtin_amdgcn_wave_barrier();
-                if (mv) {
-                    ld[p + 1] = pd;
-                    li[p + 1] = pi;
-                }
-                __builtin_amdgcn_wave_barrier();
             }
         }
-        if (lane == 0) {
-            ld[pos] = cd;
-            li[pos] = ci;
-        }
+        if (lane == 0) list[pos] = cand;
         if (cnt < k) ++cnt;
         __builtin_amdgcn_wave_barrier();
     }
     if (lane == 0) {
         s.cnt[q] = cnt;
-        if (cnt == k) s.thr[q] = ld[k - 1];
+        if (cnt == k) s.thr[q] = entry_dist(list[k - 1]);
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     if (lane == 0)
@@ -186,7 +196,7 @@ __device__ __forceinline__ void insert_candidates(const Lds<M, TQ> &s, const Sca
 // Score the first `nvalid` (<= 64) entries of the wave's queue and feed the ones that beat the
 // current threshold to the lists.
 template <int M, int TQ>
-__device__ __forceinline__ void drain(const Lds<M, TQ> &s, const ScanArgs &a, lds_vu32 *ring,
+__device__ __forceinline__ void drain(const Lds<M, TQ> &s, const ScanArgs &a, const lds_u32 *ring,
                                       int nvalid, int64_t slice_begin, int64_t q0)
 {
     const int lane = lane_id();
@@ -293,7 +303,7 @@ scan_kernel(ScanArgs a)
     uint32_t qmask_all = 0u;
 #pragma unroll
     for (int c = 0; c < CB; ++c) qmask_all |= qmask << (c * TQ);
-    lds_vu32 *ring = s.queue + wave * kQueueCap;
+    lds_u32 *ring = s.queue + wave * kQueueCap;
     const uint32_t ring_base = (uint32_t)(uintptr_t)ring;  // LDS byte address of the wave's queue
     int fill = 0;  // wave-uniform: entries waiting in the queue (< 64 between turns)
 
@@ -374,10 +384,10 @@ scan_kernel(ScanArgs a)
             if (bal == 0) break;
             if (has) {
                 const uint32_t b = (uint32_t)__builtin_ctz(sv);
-                sv &= sv - 1u;
-                const uint32_t at = ring_base + 4u * (uint32_t)fill;  // scalar
-                *(lds_vu32 *)(uintptr_t)(at + 4u * (uint32_t)prefix_count(bal)) = (b << kRelBits) | rel0;
+                const uint32_t at = (uint32_t)__builtin_amdgcn_readfirstlane((int)(ring_base + 4u * (uint32_t)fill));
+                *(lds_u32 *)(uintptr_t)(at + 4u * (uint32_t)prefix_count(bal)) = (b << kRelBits) | rel0;
             }
+            sv &= sv - 1u;  // drops the bit just queued (zero stays zero)
             fill += __builtin_popcountll(bal);
             if (fill >= 64) {
                 __builtin_amdgcn_wave_barrier();
@@ -405,8 +415,9 @@ scan_kernel(ScanArgs a)
         const int q = e / a.k, r = e - q * a.k;
         const int64_t o = ((q0 + q) * a.nslice + slice) * a.k + r;
         const bool have = r < s.cnt[q];
-        a.part_d[o] = have ? s.topd[q * a.kpad + r] : __builtin_inff();
-        a.part_i[o] = have ? (slice_begin + (int64_t)s.topi[q * a.kpad + r]) : (int64_t)-1;
+        const uint64_t ent = s.top[q * a.kpad + r];
+        a.part_d[o] = have ? entry_dist(ent) : __builtin_inff();
+        a.part_i[o] = have ? (slice_begin + (int64_t)entry_id(ent)) : (int64_t)-1;
     }
 }
 
@@ -546,11 +557,14 @@ int plan_scan(int m, int64_t nq, int64_t n, int k, ScanPlan *plan)
         return PSC_EINVAL;
     }
     ScanPlan p;
-    p.kpad = (k + 63) / 64 * 64;
+    p.kpad = (k + 3) / 4 * 4;
     p.nwaves = 16;
     const int tq_options[3] = {16, 8, 4};
     p.tq = 0;
+    int tq_cap = 16;
+    if (const char *e = getenv("PSC_TQ")) tq_cap = atoi(e);  // experiment knob
     for (int t : tq_options) {
+        if (t > tq_cap) continue;
         if (m == 16 && t == 16) continue;  // 16 tables of 16 KiB do not fit
         size_t need = (size_t)t * m * 256 * 4 + (size_t)t * p.kpad * 8 + (size_t)t * 12 +
                       (size_t)p.nwaves * kQueueCap * 4;
