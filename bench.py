@@ -47,6 +47,9 @@ def main():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cpu-queries", type=int, default=192)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (known traffic, for scaling the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build measures one GPU only (the path shards without any exchange, "
@@ -129,6 +132,14 @@ def main():
         scan_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
         psc.workspace_status(scan_ws)
         return wall * 1e3, scan_ms
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     ms_step, scan_ms = run(args.ht, args.steps, args.warmup)
     pairs = float(nq) * float(n_db)

@@ -131,6 +131,16 @@ int psc_search(const psc_index *idx, const float *q_dev, int64_t nq, const uint8
                int64_t n, int ht, int k, int64_t *ids_dev, float *dists_dev, void *workspace_dev,
                size_t workspace_bytes, psc_stream stream);
 
+/* k-NN graph (Section 5): for every row i of x_dev [n][dim] the k nearest other rows:
+ * tables from the raw vector x_i, bit string = its stored code codes_dev[i], database = all n
+ * codes, row i itself never returned (rows with identical codes but another number stay
+ * eligible).  Same filter, scoring, order and padding as psc_scan; ids_dev / dists_dev [n][k].
+ * Queries are processed in chunks of 32768.  Workspace: psc_knn_graph_workspace_bytes. */
+size_t psc_knn_graph_workspace_bytes(const psc_index *idx, int64_t n, int k);
+int psc_knn_graph(const psc_index *idx, const float *x_dev, const uint8_t *codes_dev, int64_t n,
+                  int ht, int k, int64_t *ids_dev, float *dists_dev, void *workspace_dev,
+                  size_t workspace_bytes, psc_stream stream);
+
 /* Synchronise `stream` and report whether any scan that used this workspace since
  * the last call gave up on an internal wait (never expected; results of such a
  * scan are marked with id -2).  Returns 0 if clean, PSC_EHIP otherwise. */

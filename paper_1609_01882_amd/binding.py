@@ -51,6 +51,8 @@ def _load():
         "psc_scan": (i32, [i32, vp, vp, i64, vp, i64, i32, i32, vp, vp, vp, sz, vp]),
         "psc_search_workspace_bytes": (sz, [vp, i64, i64, i32]),
         "psc_search": (i32, [vp, vp, i64, vp, i64, i32, i32, vp, vp, vp, sz, vp]),
+        "psc_knn_graph_workspace_bytes": (sz, [vp, i64, i32]),
+        "psc_knn_graph": (i32, [vp, vp, vp, i64, i32, i32, vp, vp, vp, sz, vp]),
         "psc_workspace_status": (i32, [vp, vp]),
     }
     for name, (res, args) in sigs.items():
@@ -67,7 +69,8 @@ def exported_symbols():
     return ["psc_version", "psc_last_error", "psc_create", "psc_destroy", "psc_train_pq",
             "psc_optimize_index_assignment", "psc_set_codebook", "psc_get_codebook", "psc_encode",
             "psc_build_lut", "psc_hamming_filter", "psc_scan_workspace_bytes", "psc_scan",
-            "psc_search_workspace_bytes", "psc_search", "psc_workspace_status"]
+            "psc_search_workspace_bytes", "psc_search", "psc_knn_graph_workspace_bytes",
+            "psc_knn_graph", "psc_workspace_status"]
 
 
 def _check(rc: int):
@@ -166,6 +169,25 @@ class Index:
                               ht, k, _dev(ids, torch.int64, "ids"), _dev(dists, torch.float32, "dists"),
                               _dev(ws, torch.uint8, "workspace"), ws.numel(), _stream()))
         return ids, dists
+
+    def knn_graph(self, x: torch.Tensor, codes: torch.Tensor, ht: int, k: int, workspace=None, out=None):
+        """k nearest other rows for every row of x (ids [n,k] int64, dists [n,k] float32)."""
+        n = x.shape[0]
+        lib = _load()
+        need = lib.psc_knn_graph_workspace_bytes(self._h, n, k)
+        if need == 0:
+            _check(-1)
+        ws = workspace if workspace is not None else _workspace(need, x.device)
+        ids, dists = out if out is not None else (
+            torch.empty((n, k), dtype=torch.int64, device=x.device),
+            torch.empty((n, k), dtype=torch.float32, device=x.device))
+        _check(lib.psc_knn_graph(self._h, _dev(x, torch.float32, "x"), _dev(codes, torch.uint8, "codes"), n,
+                                 ht, k, _dev(ids, torch.int64, "ids"), _dev(dists, torch.float32, "dists"),
+                                 _dev(ws, torch.uint8, "workspace"), ws.numel(), _stream()))
+        return ids, dists
+
+    def knn_graph_workspace_bytes(self, n: int, k: int) -> int:
+        return int(_load().psc_knn_graph_workspace_bytes(self._h, n, k))
 
     def search_workspace_bytes(self, nq: int, n: int, k: int) -> int:
         return int(_load().psc_search_workspace_bytes(self._h, nq, n, k))

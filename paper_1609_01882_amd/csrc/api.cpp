@@ -210,7 +210,7 @@ int psc_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t nq,
              const uint8_t *codes_dev, int64_t n, int ht, int k, int64_t *ids_dev,
              float *dists_dev, void *workspace_dev, size_t workspace_bytes, psc_stream stream)
 {
-    return launch_scan(m, lut_dev, qcodes_dev, nq, codes_dev, n, ht, k, nullptr, 0, ids_dev, dists_dev,
+    return launch_scan(m, lut_dev, qcodes_dev, nq, codes_dev, n, ht, k, -1, true, ids_dev, dists_dev,
                        workspace_dev, workspace_bytes, (hipStream_t)stream);
 }
 
@@ -221,8 +221,8 @@ size_t psc_search_workspace_bytes(const psc_index *idx, int64_t nq, int64_t n, i
     if (!idx) return 0;
     ScanPlan p;
     if (plan_scan(idx->m, nq, n, k, &p) != PSC_OK) return 0;
-    return round256((size_t)nq * idx->m * kCentroids * sizeof(float)) + round256((size_t)nq * idx->m) +
-           p.total_bytes;
+    return round256(p.total_bytes) + round256((size_t)nq * idx->m * kCentroids * sizeof(float)) +
+           round256((size_t)nq * idx->m);
 }
 
 int psc_search(const psc_index *idx, const float *q_dev, int64_t nq, const uint8_t *codes_dev,
@@ -237,15 +237,69 @@ int psc_search(const psc_index *idx, const float *q_dev, int64_t nq, const uint8
     PSC_REQUIRE(workspace_dev && workspace_bytes >= need, "workspace too small: need %zu bytes, got %zu",
                 need, workspace_bytes);
     PSC_REQUIRE(((uintptr_t)workspace_dev & 255) == 0, "workspace must be 256-byte aligned");
-    char *w = (char *)workspace_dev;
+    // layout: [scan workspace (status word first)] [tables] [query codes]
+    ScanPlan p;
+    rc = plan_scan(idx->m, nq, n, k, &p);
+    if (rc != PSC_OK) return rc;
+    char *w = (char *)workspace_dev + round256(p.total_bytes);
     float *lut = (float *)w;
     w += round256((size_t)nq * idx->m * kCentroids * sizeof(float));
     uint8_t *qcodes = (uint8_t *)w;
-    w += round256((size_t)nq * idx->m);
     rc = psc_build_lut(idx, q_dev, nq, lut, qcodes, stream);
     if (rc != PSC_OK) return rc;
-    return launch_scan(idx->m, lut, qcodes, nq, codes_dev, n, ht, k, nullptr, 0, ids_dev, dists_dev, w,
-                       workspace_bytes - (size_t)(w - (char *)workspace_dev), (hipStream_t)stream);
+    return launch_scan(idx->m, lut, qcodes, nq, codes_dev, n, ht, k, -1, true, ids_dev, dists_dev,
+                       workspace_dev, round256(p.total_bytes), (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// k-NN graph (Section 5): every database vector in turn is the query.  Queries are processed in
+// chunks so that one chunk's tables fit the workspace; each chunk is a flat scan whose query
+// codes are the stored codes of the chunk's rows and which never returns a row to itself.
+// ---------------------------------------------------------------------------------------------
+static const int64_t kGraphChunk = 32768;
+
+size_t psc_knn_graph_workspace_bytes(const psc_index *idx, int64_t n, int k)
+{
+    if (!idx) return 0;
+    const int64_t qc = n < kGraphChunk ? n : kGraphChunk;
+    ScanPlan p;
+    if (plan_scan(idx->m, qc, n, k, &p) != PSC_OK) return 0;
+    return round256(p.total_bytes) + round256((size_t)qc * idx->m * kCentroids * sizeof(float));
+}
+
+int psc_knn_graph(const psc_index *idx, const float *x_dev, const uint8_t *codes_dev, int64_t n,
+                  int ht, int k, int64_t *ids_dev, float *dists_dev, void *workspace_dev,
+                  size_t workspace_bytes, psc_stream stream)
+{
+    int rc = need_codebook(idx);
+    if (rc != PSC_OK) return rc;
+    PSC_REQUIRE(n >= 0, "negative n");
+    const size_t need = psc_knn_graph_workspace_bytes(idx, n, k);
+    PSC_REQUIRE(need != 0, "%s", psc_last_error());
+    if (n == 0) return PSC_OK;
+    PSC_REQUIRE(x_dev && codes_dev && ids_dev && dists_dev, "null pointer");
+    PSC_REQUIRE(workspace_dev && workspace_bytes >= need, "workspace too small: need %zu bytes, got %zu",
+                need, workspace_bytes);
+    PSC_REQUIRE(((uintptr_t)workspace_dev & 255) == 0, "workspace must be 256-byte aligned");
+    // layout: [scan workspace for a full chunk (status word first)] [one chunk of tables]
+    const int64_t qc_max = n < kGraphChunk ? n : kGraphChunk;
+    ScanPlan p;
+    rc = plan_scan(idx->m, qc_max, n, k, &p);
+    if (rc != PSC_OK) return rc;
+    const size_t scan_ws_bytes = round256(p.total_bytes);
+    char *scan_ws = (char *)workspace_dev;
+    float *lut = (float *)((char *)workspace_dev + scan_ws_bytes);
+    for (int64_t c0 = 0; c0 < n; c0 += kGraphChunk) {
+        const int64_t qc = (n - c0) < kGraphChunk ? (n - c0) : kGraphChunk;
+        rc = launch_lut(idx->cb_dev, idx->dim, idx->m, x_dev + (size_t)c0 * idx->dim, qc, RowMap{}, lut,
+                        (hipStream_t)stream);
+        if (rc != PSC_OK) return rc;
+        rc = launch_scan(idx->m, lut, codes_dev + (size_t)c0 * idx->m, qc, codes_dev, n, ht, k, c0, c0 == 0,
+                         ids_dev + (size_t)c0 * k, dists_dev + (size_t)c0 * k, scan_ws, scan_ws_bytes,
+                         (hipStream_t)stream);
+        if (rc != PSC_OK) return rc;
+    }
+    return PSC_OK;
 }
 
 int psc_workspace_status(void *workspace_dev, psc_stream stream)

@@ -67,9 +67,11 @@ struct ScanPlan {
     size_t total_bytes = 0; // whole workspace
 };
 int plan_scan(int m, int64_t nq, int64_t n, int k, ScanPlan *plan);
+// skip_first >= 0: query q never returns database row skip_first + q (k-NN-graph mode).
+// clear_status: reset the workspace's status word first (false for follow-up chunks of one call).
 int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t nq,
-                const uint8_t *codes_dev, int64_t n, int ht, int k, const int64_t *skip_id_dev,
-                int64_t skip_base, int64_t *ids_dev, float *dists_dev, void *ws, size_t ws_bytes,
+                const uint8_t *codes_dev, int64_t n, int ht, int k, int64_t skip_first,
+                bool clear_status, int64_t *ids_dev, float *dists_dev, void *ws, size_t ws_bytes,
                 hipStream_t s);
 int launch_hamming_filter(int m, const uint8_t *qcodes_dev, int64_t nq, const uint8_t *codes_dev,
                           int64_t n, int ht, int64_t *nsurv_dev, uint8_t *hdist_dev, hipStream_t s);

@@ -37,8 +37,7 @@ struct ScanArgs {
     const float *lut;         // [nq][M][256]
     const uint8_t *qcodes;    // [nq][M]
     const uint8_t *codes;     // [n][M]
-    const int64_t *skip_id;   // optional [nq]: id never returned for that query
-    int64_t skip_base;        //   ... ids of this database are skip_base + position
+    int64_t skip_first;       // >= 0: query q never returns database row skip_first + q (graph mode)
     int64_t nq, n;
     int64_t slice_len;
     int nslice;
@@ -233,8 +232,8 @@ __device__ __forceinline__ void drain(const Lds<M, TQ> &s, const ScanArgs &a, co
         d = acc;
     }
     bool pass = act && d <= s.thr[q];
-    if (pass && a.skip_id != nullptr)
-        pass = (a.skip_base + slice_begin + (int64_t)rel) != a.skip_id[q0 + q];
+    if (a.skip_first >= 0)  // a vector is not its own neighbour
+        pass = pass && (slice_begin + (int64_t)rel) != a.skip_first + q0 + q;
     uint64_t pm = ballot64(pass);
     while (pm) {
         const int leader = __builtin_ctzll(pm);
@@ -624,8 +623,8 @@ int plan_scan(int m, int64_t nq, int64_t n, int k, ScanPlan *plan)
 }
 
 int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t nq,
-                const uint8_t *codes_dev, int64_t n, int ht, int k, const int64_t *skip_id_dev,
-                int64_t skip_base, int64_t *ids_dev, float *dists_dev, void *ws, size_t ws_bytes,
+                const uint8_t *codes_dev, int64_t n, int ht, int k, int64_t skip_first,
+                bool clear_status, int64_t *ids_dev, float *dists_dev, void *ws, size_t ws_bytes,
                 hipStream_t s)
 {
     ScanPlan p;
@@ -654,8 +653,7 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
     a.lut = lut_dev;
     a.qcodes = qcodes_dev;
     a.codes = codes_dev;
-    a.skip_id = skip_id_dev;
-    a.skip_base = skip_base;
+    a.skip_first = skip_first;
     a.nq = nq;
     a.n = n;
     a.slice_len = p.slice_len;
@@ -669,7 +667,7 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
     a.part_d = (float *)((char *)ws + 256);
     a.part_i = (int64_t *)((char *)ws + 256 + (((size_t)nq * p.nslice * k * sizeof(float) + 255) / 256 * 256));
 
-    hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, s, a.status);
+    if (clear_status) hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, s, a.status);
     if (m == 8) {
         if (p.tq == 16) rc = run_scan<8, 16, 16>(a, p.ntiles, p.lds_bytes, s);
         else if (p.tq == 8) rc = run_scan<8, 8, 16>(a, p.ntiles, p.lds_bytes, s);
