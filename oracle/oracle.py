@@ -151,7 +151,10 @@ def search_flat(queries, codebook, codes, ht: int, k: int, **kw):
     return scan(lut, query_codes(lut), codes, ht, k, **kw)
 
 
-def ivf_search(queries, codebook, coarse, offsets, codes, list_ids, nprobe: int, ht: int, k: int):
+def ivf_search(queries, codebook, coarse, offsets, codes, list_ids, nprobe: int, ht: int, k: int,
+               probed_in=None, qcodes_in=None, want_coarse=False):
+    """Inverted-file search with residual codes.  probed_in [nq,nprobe] / qcodes_in
+    [nq,nprobe,m] replace the oracle's own coarse ranking / per-list query codes."""
     q, cb, cc = _f64(queries), _f64(codebook), _f64(coarse)
     m, _, dsub = cb.shape
     D = m * dsub
@@ -165,12 +168,23 @@ def ivf_search(queries, codebook, coarse, offsets, codes, list_ids, nprobe: int,
     dists = np.empty((nq, k), dtype=np.float64)
     nsurv = np.zeros(nq, dtype=np.int64)
     probed = np.empty((nq, npb), dtype=np.int32)
+    pin = np.ascontiguousarray(probed_in, dtype=np.int32) if probed_in is not None else None
+    qin = _u8(qcodes_in) if qcodes_in is not None else None
+    if pin is not None:
+        assert pin.shape == (nq, npb)
+    if qin is not None:
+        assert qin.shape == (nq, npb, m)
+    cd = np.empty((nq, nlist), dtype=np.float64) if want_coarse else None
     rc = _L().orc_ivf_search(C.c_int(D), C.c_int(m), _p(cb), _p(cc), C.c_int(nlist), _p(offsets),
                              _p(codes), _p(list_ids), _p(q), C.c_int64(nq), C.c_int(nprobe),
-                             C.c_int(ht), C.c_int(k), _p(ids), _p(dists), _p(nsurv), _p(probed))
+                             C.c_int(ht), C.c_int(k), _p(pin), _p(qin), _p(ids), _p(dists), _p(nsurv),
+                             _p(probed), _p(cd))
     if rc != 0:
         raise MemoryError("oracle ivf search")
-    return dict(ids=ids, dists=dists, nsurv=nsurv, probed=probed)
+    out = dict(ids=ids, dists=dists, nsurv=nsurv, probed=probed)
+    if want_coarse:
+        out["coarse_d"] = cd
+    return out
 
 
 def knn_graph(x, codebook, codes, ht: int, k: int, rows=None, chunk: int = 1024):

@@ -276,10 +276,15 @@ static int coarse_cmp(const void *pa, const void *pb)
     return (a->list > b->list) - (a->list < b->list);
 }
 
+/* probed_in (may be NULL) [nq][nprobe]: take these lists instead of ranking the coarse        */
+/* centroids; qcodes_in (may be NULL) [nq][nprobe][m]: take these bit strings for the filter   */
+/* instead of the arg-min of the residual tables.  Both exist so that a float32 implementation  */
+/* whose near-ties fall the other way can be checked on identical decisions.                   */
 int orc_ivf_search(int D, int m, const double *cb, const double *coarse, int nlist,
                    const int64_t *offsets, const uint8_t *codes, const int32_t *list_ids,
                    const double *queries, int64_t nq, int nprobe, int ht, int k,
-                   int64_t *ids, double *dists, int64_t *nsurv, int32_t *probed)
+                   const int32_t *probed_in, const uint8_t *qcodes_in,
+                   int64_t *ids, double *dists, int64_t *nsurv, int32_t *probed, double *coarse_d)
 {
     int dsub = D / m;
     if (nprobe > nlist)
@@ -293,16 +298,20 @@ int orc_ivf_search(int D, int m, const double *cb, const double *coarse, int nli
         double *tab = (double *)malloc(sizeof(double) * (size_t)m * 256);
         uint8_t *qc = (uint8_t *)malloc((size_t)m);
         int64_t total = 0;
-        if (cl)
+        if (cl) {
             for (int l = 0; l < nlist; ++l) {
                 cl[l].dist = sqdist(qv, coarse + (int64_t)l * D, D);
                 cl[l].list = l;
+                if (coarse_d)
+                    coarse_d[q * nlist + l] = cl[l].dist;
             }
-        if (cl)
             qsort(cl, (size_t)nlist, sizeof(coarse_t), coarse_cmp);
-        if (cl)
+            if (probed_in)
+                for (int p = 0; p < nprobe; ++p)
+                    cl[p].list = probed_in[q * nprobe + p];
             for (int p = 0; p < nprobe; ++p)
                 total += offsets[cl[p].list + 1] - offsets[cl[p].list];
+        }
         cand_t *cand = (cand_t *)malloc(sizeof(cand_t) * (size_t)(total > 0 ? total : 1));
         if (!cl || !res || !tab || !qc || !cand) {
 #pragma omp atomic write
@@ -325,7 +334,7 @@ int orc_ivf_search(int D, int m, const double *cb, const double *coarse, int nli
                     if (tab[j * 256 + c] < tab[j * 256 + best])
                         best = c;
                 }
-                qc[j] = (uint8_t)best;
+                qc[j] = qcodes_in ? qcodes_in[(q * nprobe + p) * m + j] : (uint8_t)best;
             }
             for (int64_t i = offsets[l]; i < offsets[l + 1]; ++i) {
                 const uint8_t *code = codes + i * m;

@@ -258,13 +258,29 @@ int psc_search(const psc_index *idx, const float *q_dev, int64_t nq, const uint8
 // ---------------------------------------------------------------------------------------------
 static const int64_t kGraphChunk = 32768;
 
+// Scan workspace that serves both the full chunks and the shorter last chunk (whose plan may
+// cut the database into more slices).
+static size_t graph_scan_workspace(const psc_index *idx, int64_t n, int k)
+{
+    const int64_t qc = n < kGraphChunk ? n : kGraphChunk;
+    const int64_t tail = n % kGraphChunk;
+    ScanPlan p, pt;
+    if (plan_scan(idx->m, qc, n, k, &p) != PSC_OK) return 0;
+    size_t bytes = p.total_bytes;
+    if (n > kGraphChunk && tail != 0) {
+        if (plan_scan(idx->m, tail, n, k, &pt) != PSC_OK) return 0;
+        if (pt.total_bytes > bytes) bytes = pt.total_bytes;
+    }
+    return round256(bytes);
+}
+
 size_t psc_knn_graph_workspace_bytes(const psc_index *idx, int64_t n, int k)
 {
     if (!idx) return 0;
     const int64_t qc = n < kGraphChunk ? n : kGraphChunk;
-    ScanPlan p;
-    if (plan_scan(idx->m, qc, n, k, &p) != PSC_OK) return 0;
-    return round256(p.total_bytes) + round256((size_t)qc * idx->m * kCentroids * sizeof(float));
+    const size_t scan_bytes = graph_scan_workspace(idx, n, k);
+    if (scan_bytes == 0) return 0;
+    return scan_bytes + round256((size_t)qc * idx->m * kCentroids * sizeof(float));
 }
 
 int psc_knn_graph(const psc_index *idx, const float *x_dev, const uint8_t *codes_dev, int64_t n,
@@ -283,10 +299,7 @@ int psc_knn_graph(const psc_index *idx, const float *x_dev, const uint8_t *codes
     PSC_REQUIRE(((uintptr_t)workspace_dev & 255) == 0, "workspace must be 256-byte aligned");
     // layout: [scan workspace for a full chunk (status word first)] [one chunk of tables]
     const int64_t qc_max = n < kGraphChunk ? n : kGraphChunk;
-    ScanPlan p;
-    rc = plan_scan(idx->m, qc_max, n, k, &p);
-    if (rc != PSC_OK) return rc;
-    const size_t scan_ws_bytes = round256(p.total_bytes);
+    const size_t scan_ws_bytes = graph_scan_workspace(idx, n, k);
     char *scan_ws = (char *)workspace_dev;
     float *lut = (float *)((char *)workspace_dev + scan_ws_bytes);
     for (int64_t c0 = 0; c0 < n; c0 += kGraphChunk) {
