@@ -141,6 +141,43 @@ int psc_knn_graph(const psc_index *idx, const float *x_dev, const uint8_t *codes
                   int ht, int k, int64_t *ids_dev, float *dists_dev, void *workspace_dev,
                   size_t workspace_bytes, psc_stream stream);
 
+/* ------------------------------------------------------------------ inverted file with residual codes (Section 4.3) */
+/* Coarse quantizer: nlist (<= 16384) centroids of dim floats (dim % 4 == 0, dim <= 1024).
+ * psc_ivf_train_coarse runs k-means on x_host [n][dim] (assignment step on the current
+ * device, synchronous, allocates and frees its own scratch); psc_ivf_set_coarse installs
+ * given centroids.  Either call forgets previously set lists. */
+int psc_ivf_train_coarse(psc_index *idx, const float *x_host, int64_t n, int nlist, int iters, uint64_t seed);
+int psc_ivf_set_coarse(psc_index *idx, const float *centroids_host, int nlist);
+int psc_ivf_get_coarse(const psc_index *idx, float *centroids_host);
+
+/* Index construction: list_no_dev [n] (int32) = nearest coarse centroid of each row of
+ * x_dev [n][dim] (squared L2 in float32, lowest number on ties); rescodes_dev (may be NULL)
+ * [n][m] = PQ code of the residual x - centroid[list_no]. */
+int psc_ivf_assign_encode(const psc_index *idx, const float *x_dev, int64_t n, int32_t *list_no_dev,
+                          uint8_t *rescodes_dev, psc_stream stream);
+
+/* The inverted lists, borrowed (the caller keeps them alive and unchanged while searching):
+ * codes_dev [n][m] residual codes grouped by list, ids_dev [n] (int32, >= 0) the id of each
+ * stored code, offsets_dev [nlist+1] (int64, device memory) list l = rows offsets[l] ..
+ * offsets[l+1]-1.  codes_dev must be 16-byte aligned. */
+int psc_ivf_set_lists(psc_index *idx, const int64_t *offsets_dev, const uint8_t *codes_dev,
+                      const int32_t *ids_dev, int64_t n);
+
+/* Search: for every query the nprobe nearest coarse centroids (squared L2 in float32, lower list
+ * number on ties; nprobe is clipped to nlist, at most 1024); for every probed list l the
+ * residual q - centroid[l] gives that list's ADC tables and the query's bit string for that
+ * list; the list's codes are filtered (Hamming <= ht) and scored as in psc_scan; one ranking by
+ * (distance, id) over the union of the probed lists, ids taken from ids_dev.  No cap on lists
+ * or distance evaluations.
+ * probed_out_dev (may be NULL) [nq][nprobe] int32 receives the probed lists in ascending
+ * coarse distance; qcodes_out_dev (may be NULL) [nq][nprobe][m] the per-list query codes.
+ * The workspace (psc_ivf_search_workspace_bytes; it holds one table per (query, list) pair:
+ * nq*nprobe*m KiB) starts with the status word psc_workspace_status reads. */
+size_t psc_ivf_search_workspace_bytes(const psc_index *idx, int64_t nq, int nprobe, int k);
+int psc_ivf_search(const psc_index *idx, const float *q_dev, int64_t nq, int nprobe, int ht, int k,
+                   int64_t *ids_dev, float *dists_dev, int32_t *probed_out_dev, uint8_t *qcodes_out_dev,
+                   void *workspace_dev, size_t workspace_bytes, psc_stream stream);
+
 /* Synchronise `stream` and report whether any scan that used this workspace since
  * the last call gave up on an internal wait (never expected; results of such a
  * scan are marked with id -2).  Returns 0 if clean, PSC_EHIP otherwise. */

@@ -53,6 +53,13 @@ def _load():
         "psc_search": (i32, [vp, vp, i64, vp, i64, i32, i32, vp, vp, vp, sz, vp]),
         "psc_knn_graph_workspace_bytes": (sz, [vp, i64, i32]),
         "psc_knn_graph": (i32, [vp, vp, vp, i64, i32, i32, vp, vp, vp, sz, vp]),
+        "psc_ivf_train_coarse": (i32, [vp, vp, i64, i32, i32, u64]),
+        "psc_ivf_set_coarse": (i32, [vp, vp, i32]),
+        "psc_ivf_get_coarse": (i32, [vp, vp]),
+        "psc_ivf_assign_encode": (i32, [vp, vp, i64, vp, vp, vp]),
+        "psc_ivf_set_lists": (i32, [vp, vp, vp, vp, i64]),
+        "psc_ivf_search_workspace_bytes": (sz, [vp, i64, i32, i32]),
+        "psc_ivf_search": (i32, [vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]),
         "psc_workspace_status": (i32, [vp, vp]),
     }
     for name, (res, args) in sigs.items():
@@ -70,7 +77,9 @@ def exported_symbols():
             "psc_optimize_index_assignment", "psc_set_codebook", "psc_get_codebook", "psc_encode",
             "psc_build_lut", "psc_hamming_filter", "psc_scan_workspace_bytes", "psc_scan",
             "psc_search_workspace_bytes", "psc_search", "psc_knn_graph_workspace_bytes",
-            "psc_knn_graph", "psc_workspace_status"]
+            "psc_knn_graph", "psc_ivf_train_coarse", "psc_ivf_set_coarse", "psc_ivf_get_coarse",
+            "psc_ivf_assign_encode", "psc_ivf_set_lists", "psc_ivf_search_workspace_bytes",
+            "psc_ivf_search", "psc_workspace_status"]
 
 
 def _check(rc: int):
@@ -102,6 +111,8 @@ class Index:
     def __init__(self, dim: int, m: int):
         lib = _load()
         self.dim, self.m, self.dsub = dim, m, dim // m if m else 0
+        self.nlist = 0
+        self._lists = None
         h = C.c_void_p()
         _check(lib.psc_create(C.byref(h), dim, m))
         self._h = h
@@ -185,6 +196,64 @@ class Index:
                                  ht, k, _dev(ids, torch.int64, "ids"), _dev(dists, torch.float32, "dists"),
                                  _dev(ws, torch.uint8, "workspace"), ws.numel(), _stream()))
         return ids, dists
+
+    # -- inverted file
+    def ivf_train_coarse(self, x: np.ndarray, nlist: int, iters: int = 10, seed: int = 0):
+        x = np.ascontiguousarray(x, dtype=np.float32)
+        assert x.ndim == 2 and x.shape[1] == self.dim
+        _check(_load().psc_ivf_train_coarse(self._h, x.ctypes.data_as(C.c_void_p), x.shape[0], nlist, iters, seed))
+        self.nlist = nlist
+
+    def ivf_set_coarse(self, cent: np.ndarray):
+        cent = np.ascontiguousarray(cent, dtype=np.float32)
+        assert cent.ndim == 2 and cent.shape[1] == self.dim
+        _check(_load().psc_ivf_set_coarse(self._h, cent.ctypes.data_as(C.c_void_p), cent.shape[0]))
+        self.nlist = cent.shape[0]
+
+    def ivf_get_coarse(self) -> np.ndarray:
+        cent = np.empty((self.nlist, self.dim), dtype=np.float32)
+        _check(_load().psc_ivf_get_coarse(self._h, cent.ctypes.data_as(C.c_void_p)))
+        return cent
+
+    def ivf_assign_encode(self, x: torch.Tensor, want_codes: bool = True):
+        n = x.shape[0]
+        list_no = torch.empty(n, dtype=torch.int32, device=x.device)
+        codes = torch.empty((n, self.m), dtype=torch.uint8, device=x.device) if want_codes else None
+        _check(_load().psc_ivf_assign_encode(self._h, _dev(x, torch.float32, "x"), n,
+                                             _dev(list_no, torch.int32, "list_no"),
+                                             _dev(codes, torch.uint8, "codes") if want_codes else None, _stream()))
+        return list_no, codes
+
+    def ivf_set_lists(self, offsets: torch.Tensor, codes: torch.Tensor, ids: torch.Tensor):
+        """Borrow the caller's lists; the tensors are kept referenced by this object."""
+        n = codes.shape[0]
+        _check(_load().psc_ivf_set_lists(self._h, _dev(offsets, torch.int64, "offsets"),
+                                         _dev(codes, torch.uint8, "codes"), _dev(ids, torch.int32, "ids"), n))
+        self._lists = (offsets, codes, ids)
+
+    def ivf_search_workspace_bytes(self, nq: int, nprobe: int, k: int) -> int:
+        return int(_load().psc_ivf_search_workspace_bytes(self._h, nq, nprobe, k))
+
+    def ivf_search(self, q: torch.Tensor, nprobe: int, ht: int, k: int, workspace=None, out=None,
+                   want_debug: bool = False):
+        nq = q.shape[0]
+        lib = _load()
+        need = lib.psc_ivf_search_workspace_bytes(self._h, nq, nprobe, k)
+        if need == 0:
+            _check(-1)
+        ws = workspace if workspace is not None else _workspace(need, q.device)
+        ids, dists = out if out is not None else (
+            torch.empty((nq, k), dtype=torch.int64, device=q.device),
+            torch.empty((nq, k), dtype=torch.float32, device=q.device))
+        npb = min(nprobe, self.nlist)
+        probed = torch.empty((nq, npb), dtype=torch.int32, device=q.device) if want_debug else None
+        qcodes = torch.empty((nq, npb, self.m), dtype=torch.uint8, device=q.device) if want_debug else None
+        _check(lib.psc_ivf_search(self._h, _dev(q, torch.float32, "q"), nq, nprobe, ht, k,
+                                  _dev(ids, torch.int64, "ids"), _dev(dists, torch.float32, "dists"),
+                                  _dev(probed, torch.int32, "probed") if want_debug else None,
+                                  _dev(qcodes, torch.uint8, "qcodes") if want_debug else None,
+                                  _dev(ws, torch.uint8, "workspace"), ws.numel(), _stream()))
+        return (ids, dists, probed, qcodes) if want_debug else (ids, dists)
 
     def knn_graph_workspace_bytes(self, n: int, k: int) -> int:
         return int(_load().psc_knn_graph_workspace_bytes(self._h, n, k))

@@ -1,4 +1,5 @@
 // C ABI of libpsc: argument checking and dispatch.  See include/psc.h for the contract.
+#include <algorithm>
 #include <cstring>
 #include <new>
 #include <string>
@@ -79,6 +80,7 @@ void psc_destroy(psc_index *idx)
 {
     if (!idx) return;
     if (idx->cb_dev) (void)hipFree(idx->cb_dev);
+    if (idx->coarse_dev) (void)hipFree(idx->coarse_dev);
     delete idx;
 }
 
@@ -313,6 +315,306 @@ int psc_knn_graph(const psc_index *idx, const float *x_dev, const uint8_t *codes
         if (rc != PSC_OK) return rc;
     }
     return PSC_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Inverted file with residual codes (Section 4.3)
+// ---------------------------------------------------------------------------------------------
+static int sync_coarse_to_device(const psc_index *idx)
+{
+    if (idx->coarse_current) return PSC_OK;
+    const size_t bytes = idx->coarse_host.size() * sizeof(float);
+    if (idx->coarse_dev) {
+        PSC_HIP_TRY(hipFree(idx->coarse_dev));
+        idx->coarse_dev = nullptr;
+    }
+    PSC_HIP_TRY(hipMalloc((void **)&idx->coarse_dev, bytes));
+    PSC_HIP_TRY(hipMemcpy(idx->coarse_dev, idx->coarse_host.data(), bytes, hipMemcpyHostToDevice));
+    idx->coarse_current = true;
+    return PSC_OK;
+}
+
+static int need_coarse(const psc_index *idx)
+{
+    PSC_REQUIRE(idx != nullptr, "null index");
+    if (idx->nlist == 0) {
+        set_error("no coarse quantizer: call psc_ivf_train_coarse or psc_ivf_set_coarse first");
+        return PSC_ESTATE;
+    }
+    return sync_coarse_to_device(idx);
+}
+
+int psc_ivf_set_coarse(psc_index *idx, const float *centroids_host, int nlist)
+{
+    PSC_REQUIRE(idx && centroids_host, "null pointer");
+    PSC_REQUIRE(nlist >= 1 && nlist <= 16384, "nlist must be in [1, 16384], got %d", nlist);
+    PSC_REQUIRE(idx->dim % 4 == 0 && idx->dim <= 1024, "inverted file needs dim %% 4 == 0 and dim <= 1024");
+    try {
+        idx->coarse_host.assign(centroids_host, centroids_host + (size_t)nlist * idx->dim);
+    } catch (const std::bad_alloc &) {
+        set_error("out of host memory");
+        return PSC_ENOMEM;
+    }
+    idx->nlist = nlist;
+    idx->coarse_current = false;
+    idx->list_off_dev = nullptr;  // lists built for another quantizer no longer apply
+    idx->list_codes_dev = nullptr;
+    idx->list_ids_dev = nullptr;
+    idx->list_n = 0;
+    return PSC_OK;
+}
+
+int psc_ivf_get_coarse(const psc_index *idx, float *centroids_host)
+{
+    PSC_REQUIRE(idx && centroids_host, "null pointer");
+    if (idx->nlist == 0) {
+        set_error("no coarse quantizer");
+        return PSC_ESTATE;
+    }
+    std::memcpy(centroids_host, idx->coarse_host.data(), idx->coarse_host.size() * sizeof(float));
+    return PSC_OK;
+}
+
+// k-means of the coarse quantizer: assignment on the device (the nearest-centroid kernel),
+// centroid update on the host in double precision.
+int psc_ivf_train_coarse(psc_index *idx, const float *x_host, int64_t n, int nlist, int iters, uint64_t seed)
+{
+    PSC_REQUIRE(idx && x_host, "null pointer");
+    PSC_REQUIRE(nlist >= 1 && nlist <= 16384 && n >= nlist && iters >= 1, "bad coarse training arguments");
+    PSC_REQUIRE(idx->dim % 4 == 0 && idx->dim <= 1024, "inverted file needs dim %% 4 == 0 and dim <= 1024");
+    const int dim = idx->dim;
+    std::vector<float> cent;
+    std::vector<int32_t> assign;
+    std::vector<double> sum;
+    std::vector<int64_t> count;
+    try {
+        cent.resize((size_t)nlist * dim);
+        assign.resize((size_t)n);
+        sum.resize((size_t)nlist * dim);
+        count.resize((size_t)nlist);
+    } catch (const std::bad_alloc &) {
+        set_error("out of host memory");
+        return PSC_ENOMEM;
+    }
+    int rc = host_kmeans(x_host, n, dim, nlist, 0, seed, cent.data());  // 0 iterations: the seeded start only
+    if (rc != PSC_OK) return rc;
+    float *x_dev = nullptr, *c_dev = nullptr;
+    int32_t *a_dev = nullptr;
+    auto cleanup = [&] {
+        if (x_dev) (void)hipFree(x_dev);
+        if (c_dev) (void)hipFree(c_dev);
+        if (a_dev) (void)hipFree(a_dev);
+    };
+#define IVF_TRY(expr)                                                                              \
+    do {                                                                                           \
+        hipError_t e_ = (expr);                                                                    \
+        if (e_ != hipSuccess) {                                                                    \
+            set_error("%s failed: %s", #expr, hipGetErrorString(e_));                              \
+            cleanup();                                                                             \
+            return PSC_EHIP;                                                                       \
+        }                                                                                          \
+    } while (0)
+    IVF_TRY(hipMalloc((void **)&x_dev, (size_t)n * dim * sizeof(float)));
+    IVF_TRY(hipMalloc((void **)&c_dev, (size_t)nlist * dim * sizeof(float)));
+    IVF_TRY(hipMalloc((void **)&a_dev, (size_t)n * sizeof(int32_t)));
+    IVF_TRY(hipMemcpy(x_dev, x_host, (size_t)n * dim * sizeof(float), hipMemcpyHostToDevice));
+    for (int it = 0; it < iters; ++it) {
+        IVF_TRY(hipMemcpy(c_dev, cent.data(), cent.size() * sizeof(float), hipMemcpyHostToDevice));
+        rc = launch_nearest_centroid(x_dev, n, dim, c_dev, nlist, a_dev, nullptr);
+        if (rc != PSC_OK) {
+            cleanup();
+            return rc;
+        }
+        IVF_TRY(hipMemcpy(assign.data(), a_dev, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost));
+        std::fill(sum.begin(), sum.end(), 0.0);
+        std::fill(count.begin(), count.end(), (int64_t)0);
+        for (int64_t i = 0; i < n; ++i) {
+            double *sp = &sum[(size_t)assign[i] * dim];
+            const float *xi = x_host + (size_t)i * dim;
+            for (int t = 0; t < dim; ++t) sp[t] += xi[t];
+            ++count[assign[i]];
+        }
+        for (int c = 0; c < nlist; ++c) {
+            if (count[c] == 0) {
+                // empty cell: restart it on a member of the most populated cell
+                const int big = (int)(std::max_element(count.begin(), count.end()) - count.begin());
+                for (int64_t i = 0; i < n; ++i)
+                    if (assign[i] == big) {
+                        for (int t = 0; t < dim; ++t) {
+                            sum[(size_t)big * dim + t] -= x_host[(size_t)i * dim + t];
+                            sum[(size_t)c * dim + t] = x_host[(size_t)i * dim + t];
+                        }
+                        --count[big];
+                        count[c] = 1;
+                        assign[i] = c;
+                        break;
+                    }
+            }
+        }
+        for (int c = 0; c < nlist; ++c)
+            if (count[c] > 0)
+                for (int t = 0; t < dim; ++t)
+                    cent[(size_t)c * dim + t] = (float)(sum[(size_t)c * dim + t] / (double)count[c]);
+    }
+#undef IVF_TRY
+    cleanup();
+    return psc_ivf_set_coarse(idx, cent.data(), nlist);
+}
+
+int psc_ivf_assign_encode(const psc_index *idx, const float *x_dev, int64_t n, int32_t *list_no_dev,
+                          uint8_t *rescodes_dev, psc_stream stream)
+{
+    int rc = need_coarse(idx);
+    if (rc != PSC_OK) return rc;
+    PSC_REQUIRE(n >= 0, "negative n");
+    if (n == 0) return PSC_OK;
+    PSC_REQUIRE(x_dev && list_no_dev, "null pointer");
+    rc = launch_nearest_centroid(x_dev, n, idx->dim, idx->coarse_dev, idx->nlist, list_no_dev, (hipStream_t)stream);
+    if (rc != PSC_OK || !rescodes_dev) return rc;
+    rc = need_codebook(idx);
+    if (rc != PSC_OK) return rc;
+    RowMap map;
+    map.sub = idx->coarse_dev;
+    map.sub_idx = list_no_dev;
+    return launch_encode(idx->cb_dev, idx->dim, idx->m, x_dev, n, map, rescodes_dev, (hipStream_t)stream);
+}
+
+int psc_ivf_set_lists(psc_index *idx, const int64_t *offsets_dev, const uint8_t *codes_dev,
+                      const int32_t *ids_dev, int64_t n)
+{
+    PSC_REQUIRE(idx != nullptr, "null index");
+    if (idx->nlist == 0) {
+        set_error("no coarse quantizer");
+        return PSC_ESTATE;
+    }
+    PSC_REQUIRE(offsets_dev && n >= 0 && (n == 0 || (codes_dev && ids_dev)), "null pointer");
+    PSC_REQUIRE(((uintptr_t)codes_dev & 15) == 0, "list codes must be 16-byte aligned");
+    idx->list_off_dev = offsets_dev;
+    idx->list_codes_dev = codes_dev;
+    idx->list_ids_dev = ids_dev;
+    idx->list_n = n;
+    return PSC_OK;
+}
+
+namespace {
+struct IvfLayout {
+    ScanPlan plan;
+    int64_t njobs, nblk, max_tiles;
+    size_t off_status, off_dist, off_probed, off_hist, off_list_begin, off_tile_begin, off_job_q, off_job_list,
+        off_job_slot, off_tiles, off_lut, off_qcodes, off_part_d, off_part_i, total;
+};
+
+int ivf_layout(const psc_index *idx, int64_t nq, int nprobe, int k, IvfLayout *L)
+{
+    PSC_REQUIRE(idx && idx->nlist > 0, "no coarse quantizer");
+    PSC_REQUIRE(nq >= 0 && nprobe >= 1, "bad nq/nprobe");
+    if (nprobe > idx->nlist) nprobe = idx->nlist;
+    PSC_REQUIRE(nprobe <= 1024, "at most 1024 probes");
+    L->njobs = nq * nprobe;
+    PSC_REQUIRE(L->njobs < 0x7fffffffLL, "too many (query, list) jobs");
+    int rc = plan_scan(idx->m, L->njobs > 0 ? L->njobs : 1, idx->list_n, k, &L->plan);
+    if (rc != PSC_OK) return rc;
+    L->nblk = (nq + 15) / 16;
+    L->max_tiles = L->njobs / L->plan.tq + idx->nlist;
+    size_t o = 0;
+    auto take = [&](size_t bytes) {
+        size_t at = o;
+        o += round256(bytes);
+        return at;
+    };
+    L->off_status = take(256);
+    L->off_dist = take((size_t)nq * idx->nlist * sizeof(float));
+    L->off_probed = take((size_t)L->njobs * sizeof(int32_t));
+    L->off_hist = take((size_t)L->nblk * idx->nlist * sizeof(int32_t));
+    L->off_list_begin = take((size_t)(idx->nlist + 1) * sizeof(int32_t));
+    L->off_tile_begin = take((size_t)(idx->nlist + 1) * sizeof(int32_t));
+    L->off_job_q = take((size_t)L->njobs * sizeof(int32_t));
+    L->off_job_list = take((size_t)L->njobs * sizeof(int32_t));
+    L->off_job_slot = take((size_t)L->njobs * sizeof(int32_t));
+    L->off_tiles = take((size_t)L->max_tiles * 16);
+    L->off_lut = take((size_t)L->njobs * idx->m * kCentroids * sizeof(float));
+    L->off_qcodes = take((size_t)L->njobs * idx->m);
+    L->off_part_d = take((size_t)L->njobs * k * sizeof(float));
+    L->off_part_i = take((size_t)L->njobs * k * sizeof(int64_t));
+    L->total = o;
+    return PSC_OK;
+}
+}  // namespace
+
+size_t psc_ivf_search_workspace_bytes(const psc_index *idx, int64_t nq, int nprobe, int k)
+{
+    IvfLayout L;
+    if (ivf_layout(idx, nq, nprobe, k, &L) != PSC_OK) return 0;
+    return L.total;
+}
+
+int psc_ivf_search(const psc_index *idx, const float *q_dev, int64_t nq, int nprobe, int ht, int k,
+                   int64_t *ids_dev, float *dists_dev, int32_t *probed_out_dev, uint8_t *qcodes_out_dev,
+                   void *workspace_dev, size_t workspace_bytes, psc_stream stream)
+{
+    int rc = need_codebook(idx);
+    if (rc != PSC_OK) return rc;
+    rc = need_coarse(idx);
+    if (rc != PSC_OK) return rc;
+    if (!idx->list_off_dev) {
+        set_error("no inverted lists: call psc_ivf_set_lists first");
+        return PSC_ESTATE;
+    }
+    PSC_REQUIRE(ht >= 0, "ht must be >= 0");
+    IvfLayout L;
+    rc = ivf_layout(idx, nq, nprobe, k, &L);
+    if (rc != PSC_OK) return rc;
+    if (nprobe > idx->nlist) nprobe = idx->nlist;
+    if (nq == 0) return PSC_OK;
+    PSC_REQUIRE(q_dev && ids_dev && dists_dev, "null pointer");
+    PSC_REQUIRE(workspace_dev && workspace_bytes >= L.total, "workspace too small: need %zu bytes, got %zu",
+                L.total, workspace_bytes);
+    PSC_REQUIRE(((uintptr_t)workspace_dev & 255) == 0, "workspace must be 256-byte aligned");
+    hipStream_t s = (hipStream_t)stream;
+    char *w = (char *)workspace_dev;
+    float *dist = (float *)(w + L.off_dist);
+    int32_t *probed = (int32_t *)(w + L.off_probed);
+    IvfJobBuffers jb;
+    jb.hist = (int32_t *)(w + L.off_hist);
+    jb.list_begin = (int32_t *)(w + L.off_list_begin);
+    jb.tile_begin = (int32_t *)(w + L.off_tile_begin);
+    jb.job_q = (int32_t *)(w + L.off_job_q);
+    jb.job_list = (int32_t *)(w + L.off_job_list);
+    jb.job_slot = (int32_t *)(w + L.off_job_slot);
+    jb.tiles = w + L.off_tiles;
+    float *lut = (float *)(w + L.off_lut);
+    uint8_t *qcodes = (uint8_t *)(w + L.off_qcodes);
+
+    // 1. coarse quantization of the queries and choice of the lists
+    rc = launch_coarse_distances(q_dev, nq, idx->dim, idx->coarse_dev, idx->nlist, dist, s);
+    if (rc != PSC_OK) return rc;
+    rc = launch_select_probes(dist, nq, idx->nlist, nprobe, probed, s);
+    if (rc != PSC_OK) return rc;
+    if (probed_out_dev)
+        PSC_HIP_TRY(hipMemcpyAsync(probed_out_dev, probed, (size_t)L.njobs * sizeof(int32_t),
+                                   hipMemcpyDeviceToDevice, s));
+    // 2. jobs grouped by list, cut into tiles
+    rc = launch_build_jobs(probed, nq, nprobe, idx->nlist, L.plan.tq, jb, s);
+    if (rc != PSC_OK) return rc;
+    // 3. per-job residual tables and query codes (rows in job order)
+    RowMap map;
+    map.row_idx = jb.job_q;
+    map.sub = idx->coarse_dev;
+    map.sub_idx = jb.job_list;
+    rc = launch_lut(idx->cb_dev, idx->dim, idx->m, q_dev, L.njobs, map, lut, s);
+    if (rc != PSC_OK) return rc;
+    rc = launch_encode(idx->cb_dev, idx->dim, idx->m, q_dev, L.njobs, map, qcodes, s);
+    if (rc != PSC_OK) return rc;
+    if (qcodes_out_dev) {
+        rc = launch_unsort_rows(qcodes, jb.job_slot, L.njobs, idx->m, qcodes_out_dev, s);
+        if (rc != PSC_OK) return rc;
+    }
+    // 4. the fused scan over the tiles, 5. one merge per query over its nprobe partial lists
+    return launch_ivf_scan(idx->m, L.plan.tq, L.plan.kpad, L.plan.lds_bytes, lut, qcodes, idx->list_codes_dev,
+                           idx->list_n, ht, k, jb.tiles, jb.tile_begin + idx->nlist, L.max_tiles,
+                           idx->list_off_dev, idx->list_ids_dev, jb.job_slot, (float *)(w + L.off_part_d),
+                           (int64_t *)(w + L.off_part_i), (int *)(w + L.off_status), nq, nprobe, ids_dev,
+                           dists_dev, s);
 }
 
 int psc_workspace_status(void *workspace_dev, psc_stream stream)

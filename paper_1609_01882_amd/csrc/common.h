@@ -73,8 +73,41 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
                 const uint8_t *codes_dev, int64_t n, int ht, int k, int64_t skip_first,
                 bool clear_status, int64_t *ids_dev, float *dists_dev, void *ws, size_t ws_bytes,
                 hipStream_t s);
+int launch_ivf_scan(int m, int tq, int kpad, size_t lds_bytes, const float *lut_dev,
+                    const uint8_t *qcodes_dev, const uint8_t *codes_dev, int64_t n, int ht, int k,
+                    const void *tiles_dev, const int *ntiles_dev, int64_t max_tiles,
+                    const int64_t *list_off_dev, const int32_t *ext_ids_dev, const int32_t *job_slot_dev,
+                    float *part_d, int64_t *part_i, int *status, int64_t nq, int nprobe,
+                    int64_t *ids_dev, float *dists_dev, hipStream_t s);
 int launch_hamming_filter(int m, const uint8_t *qcodes_dev, int64_t nq, const uint8_t *codes_dev,
                           int64_t n, int ht, int64_t *nsurv_dev, uint8_t *hdist_dev, hipStream_t s);
+
+// ---- inverted-file helpers (kernels_ivf.hip)
+// Squared distances of rows x [n][dim] to centroids [nlist][dim] -> dist [n][nlist] (float32).
+int launch_coarse_distances(const float *x_dev, int64_t n, int dim, const float *cent_dev, int nlist,
+                            float *dist_dev, hipStream_t s);
+// Per row the nprobe smallest of dist [n][nlist] by (distance, list number) -> probed [n][nprobe].
+int launch_select_probes(const float *dist_dev, int64_t n, int nlist, int nprobe, int32_t *probed_dev,
+                         hipStream_t s);
+// Nearest centroid of each row (lowest number on ties) -> assign [n] (int32).
+int launch_nearest_centroid(const float *x_dev, int64_t n, int dim, const float *cent_dev, int nlist,
+                            int32_t *assign_dev, hipStream_t s);
+struct IvfJobBuffers {
+    int32_t *hist;       // [nblk][nlist]
+    int32_t *list_begin; // [nlist+1] first sorted job of each list
+    int32_t *tile_begin; // [nlist+1] first tile of each list; tile_begin[nlist] = tile count
+    int32_t *job_q;      // [njobs] query of the sorted job
+    int32_t *job_list;   // [njobs]
+    int32_t *job_slot;   // [njobs] query * nprobe + probe rank
+    void *tiles;         // [max_tiles] x 16 bytes
+};
+// Sort the (query, probe) jobs by list (stable in query order) and cut each list's jobs into
+// tiles of at most tq.
+int launch_build_jobs(const int32_t *probed_dev, int64_t nq, int nprobe, int nlist, int tq,
+                      const IvfJobBuffers &b, hipStream_t s);
+
+int launch_unsort_rows(const uint8_t *src_dev, const int32_t *job_slot_dev, int64_t njobs, int row_bytes,
+                       uint8_t *dst_dev, hipStream_t s);
 
 }  // namespace psc
 
@@ -85,4 +118,13 @@ struct psc_index {
     std::vector<float> cb_host;  // [m][256][dsub], the master copy
     mutable float *cb_dev = nullptr;
     mutable bool dev_current = false;  // device copy matches cb_host
+    // inverted file: coarse centroids (owned) and borrowed views of the caller's lists
+    int nlist = 0;
+    std::vector<float> coarse_host;  // [nlist][dim]
+    mutable float *coarse_dev = nullptr;
+    mutable bool coarse_current = false;
+    const int64_t *list_off_dev = nullptr;  // [nlist+1]
+    const uint8_t *list_codes_dev = nullptr;
+    const int32_t *list_ids_dev = nullptr;
+    int64_t list_n = 0;
 };

@@ -1,0 +1,369 @@
+// Inverted-file variant (Section 2 "Non-exhaustive search", Section 4.3): coarse quantizer,
+// selection of the lists to probe, and the device-side bookkeeping that turns the
+// (query, probed list) jobs into list-major tiles for the fused scan.
+//
+// A query probes the nprobe coarse centroids nearest to it (exact squared L2 in float32,
+// coordinates ascending, lower list number on equal distance).  Jobs are then grouped by list so
+// that the codes of a list are streamed once per tile of up to TQ queries that probe it.
+#include "common.h"
+
+namespace psc {
+namespace {
+
+constexpr int kRows = 16;  // rows per workgroup in the distance kernels
+
+// dist[r][c] = || x_r - cent_c ||^2 for a tile of kRows rows and 256 centroids per workgroup.
+// Rows sit in LDS (read as broadcasts), each thread walks its own centroid row.
+__global__ void __launch_bounds__(256)
+coarse_dist_kernel(const float *__restrict__ x, int64_t n, int dim, const float *__restrict__ cent,
+                   int nlist, float *__restrict__ dist)
+{
+    extern __shared__ __align__(16) float rows[];  // [kRows][dim]
+    const int64_t r0 = (int64_t)blockIdx.x * kRows;
+    for (int e = threadIdx.x; e < kRows * dim; e += 256) {
+        const int64_t r = r0 + e / dim;
+        rows[e] = r < n ? x[r * dim + e % dim] : 0.f;
+    }
+    __syncthreads();
+    const int c = blockIdx.y * 256 + threadIdx.x;
+    if (c >= nlist) return;
+    const float *crow = cent + (int64_t)c * dim;
+    float acc[kRows];
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) acc[r] = 0.f;
+    for (int d = 0; d < dim; d += 4) {
+        const float4 cv = *(const float4 *)(crow + d);
+#pragma unroll
+        for (int r = 0; r < kRows; ++r) {
+            const float4 xv = *(const float4 *)(rows + r * dim + d);
+            float t = xv.x - cv.x;
+            acc[r] = fmaf(t, t, acc[r]);
+            t = xv.y - cv.y;
+            acc[r] = fmaf(t, t, acc[r]);
+            t = xv.z - cv.z;
+            acc[r] = fmaf(t, t, acc[r]);
+            t = xv.w - cv.w;
+            acc[r] = fmaf(t, t, acc[r]);
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < kRows; ++r)
+        if (r0 + r < n) dist[(r0 + r) * nlist + c] = acc[r];
+}
+
+__device__ __forceinline__ uint64_t order_key(float d, uint32_t idx)
+{
+    const uint32_t u = __float_as_uint(d + 0.0f);
+    const uint32_t key = u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
+    return ((uint64_t)key << 32) | idx;
+}
+
+__device__ __forceinline__ uint64_t wave_min_u64(uint64_t v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const uint64_t o = __shfl_xor(v, off, 64);
+        v = o < v ? o : v;
+    }
+    return v;
+}
+
+// One workgroup per row: nprobe times take the smallest remaining (distance, list) key.
+__global__ void __launch_bounds__(256)
+select_probes_kernel(const float *__restrict__ dist, int nlist, int nprobe, int32_t *__restrict__ probed)
+{
+    extern __shared__ __align__(16) uint64_t keys[];  // [nlist]
+    __shared__ uint64_t wave_best[4];
+    const int64_t r = blockIdx.x;
+    for (int c = threadIdx.x; c < nlist; c += 256) keys[c] = order_key(dist[r * nlist + c], (uint32_t)c);
+    __syncthreads();
+    for (int p = 0; p < nprobe; ++p) {
+        uint64_t best = ~0ull;
+        for (int c = threadIdx.x; c < nlist; c += 256) {
+            const uint64_t v = keys[c];
+            best = v < best ? v : best;
+        }
+        best = wave_min_u64(best);
+        if ((threadIdx.x & 63) == 0) wave_best[threadIdx.x >> 6] = best;
+        __syncthreads();
+        uint64_t b = wave_best[0];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) b = wave_best[w] < b ? wave_best[w] : b;
+        const uint32_t sel = (uint32_t)b;
+        if (threadIdx.x == 0) {
+            probed[r * nprobe + p] = (int32_t)sel;
+            keys[sel] = ~0ull;
+        }
+        __syncthreads();
+    }
+}
+
+// Nearest centroid per row: the same distance arithmetic as coarse_dist_kernel, with a running
+// (distance, number) minimum per thread over all centroid blocks and one reduction per row.
+__global__ void __launch_bounds__(256)
+nearest_centroid_kernel(const float *__restrict__ x, int64_t n, int dim, const float *__restrict__ cent,
+                        int nlist, int32_t *__restrict__ assign)
+{
+    extern __shared__ __align__(16) float rows[];  // [kRows][dim], then 4*kRows uint64 for the reduction
+    const int64_t r0 = (int64_t)blockIdx.x * kRows;
+    for (int e = threadIdx.x; e < kRows * dim; e += 256) {
+        const int64_t r = r0 + e / dim;
+        rows[e] = r < n ? x[r * dim + e % dim] : 0.f;
+    }
+    __syncthreads();
+    uint64_t best[kRows];
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) best[r] = ~0ull;
+    for (int c = threadIdx.x; c < nlist; c += 256) {
+        const float *crow = cent + (int64_t)c * dim;
+        float acc[kRows];
+#pragma unroll
+        for (int r = 0; r < kRows; ++r) acc[r] = 0.f;
+        for (int d = 0; d < dim; d += 4) {
+            const float4 cv = *(const float4 *)(crow + d);
+#pragma unroll
+            for (int r = 0; r < kRows; ++r) {
+                const float4 xv = *(const float4 *)(rows + r * dim + d);
+                float t = xv.x - cv.x;
+                acc[r] = fmaf(t, t, acc[r]);
+                t = xv.y - cv.y;
+                acc[r] = fmaf(t, t, acc[r]);
+                t = xv.z - cv.z;
+                acc[r] = fmaf(t, t, acc[r]);
+                t = xv.w - cv.w;
+                acc[r] = fmaf(t, t, acc[r]);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < kRows; ++r) {
+            const uint64_t key = order_key(acc[r], (uint32_t)c);
+            best[r] = key < best[r] ? key : best[r];
+        }
+    }
+    __syncthreads();  // rows no longer needed: reuse LDS for the cross-wave reduction
+    uint64_t *red = (uint64_t *)rows;
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+        const uint64_t b = wave_min_u64(best[r]);
+        if ((threadIdx.x & 63) == 0) red[(threadIdx.x >> 6) * kRows + r] = b;
+    }
+    __syncthreads();
+    if (threadIdx.x < kRows && r0 + threadIdx.x < n) {
+        uint64_t b = red[threadIdx.x];
+        for (int w = 1; w < 4; ++w) b = red[w * kRows + threadIdx.x] < b ? red[w * kRows + threadIdx.x] : b;
+        assign[r0 + threadIdx.x] = (int32_t)(uint32_t)b;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Job bookkeeping.  Jobs in query-major order are cut into blocks of kJobBlockQ queries; a
+// stable counting sort by list number (block histograms -> column prefix -> in-order scatter)
+// gives every list its jobs in ascending query order, reproducibly.
+// ---------------------------------------------------------------------------------------------
+constexpr int kJobBlockQ = 16;
+
+__global__ void zero_i32_kernel(int32_t *p, int64_t n)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < n) p[e] = 0;
+}
+
+__global__ void job_hist_kernel(const int32_t *__restrict__ probed, int64_t nq, int nprobe, int nlist,
+                                int32_t *__restrict__ hist)
+{
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= nq * nprobe) return;
+    const int64_t q = j / nprobe;
+    atomicAdd(&hist[(q / kJobBlockQ) * nlist + probed[j]], 1);
+}
+
+// hist[b][l] -> number of jobs of list l in blocks before b; totals[l] = jobs of list l.
+__global__ void job_column_prefix_kernel(int32_t *__restrict__ hist, int64_t nblk, int nlist,
+                                         int32_t *__restrict__ totals)
+{
+    const int l = blockIdx.x * blockDim.x + threadIdx.x;
+    if (l >= nlist) return;
+    int32_t run = 0;
+    for (int64_t b = 0; b < nblk; ++b) {
+        const int32_t c = hist[b * nlist + l];
+        hist[b * nlist + l] = run;
+        run += c;
+    }
+    totals[l] = run;
+}
+
+// One workgroup: list_begin = exclusive prefix of totals; tile_begin = exclusive prefix of
+// ceil(totals / tq).  `totals` aliases list_begin (read before written, element-wise by owner).
+__global__ void __launch_bounds__(1024)
+job_list_prefix_kernel(int32_t *__restrict__ list_begin, int32_t *__restrict__ tile_begin, int nlist, int tq)
+{
+    __shared__ int32_t pj[1024], pt[1024];
+    const int t = threadIdx.x;
+    const int per = (nlist + 1023) / 1024;
+    const int lo = t * per, hi = min(nlist, lo + per);
+    int32_t sj = 0, st = 0;
+    for (int l = lo; l < hi; ++l) {
+        sj += list_begin[l];
+        st += (list_begin[l] + tq - 1) / tq;
+    }
+    pj[t] = sj;
+    pt[t] = st;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {
+        const int32_t aj = t >= off ? pj[t - off] : 0, at = t >= off ? pt[t - off] : 0;
+        __syncthreads();
+        pj[t] += aj;
+        pt[t] += at;
+        __syncthreads();
+    }
+    int32_t bj = pj[t] - sj, bt = pt[t] - st;  // exclusive
+    for (int l = lo; l < hi; ++l) {
+        const int32_t c = list_begin[l];
+        list_begin[l] = bj;
+        tile_begin[l] = bt;
+        bj += c;
+        bt += (c + tq - 1) / tq;
+    }
+    if (t == 1023) {
+        list_begin[nlist] = pj[1023];
+        tile_begin[nlist] = pt[1023];
+    }
+}
+
+// One workgroup per block of kJobBlockQ queries, queries taken in order: job (q, p) goes to
+// list_begin[l] + (jobs of l in earlier blocks) + (jobs of l earlier in this block).
+__global__ void __launch_bounds__(256)
+job_scatter_kernel(const int32_t *__restrict__ probed, int64_t nq, int nprobe, int nlist,
+                   int32_t *__restrict__ hist, const int32_t *__restrict__ list_begin,
+                   int32_t *__restrict__ job_q, int32_t *__restrict__ job_list, int32_t *__restrict__ job_slot)
+{
+    const int64_t b = blockIdx.x;
+    int32_t *run = hist + b * nlist;
+    for (int qi = 0; qi < kJobBlockQ; ++qi) {
+        const int64_t q = b * kJobBlockQ + qi;
+        if (q >= nq) break;
+        for (int p = threadIdx.x; p < nprobe; p += 256) {  // the lists of one query are distinct
+            const int l = probed[q * nprobe + p];
+            // the only writer of run[l] in this turn; the atomic keeps it coherent across turns
+            const int32_t at = list_begin[l] + atomicAdd(&run[l], 1);
+            job_q[at] = (int32_t)q;
+            job_list[at] = l;
+            job_slot[at] = (int32_t)(q * nprobe + p);
+        }
+        __syncthreads();
+    }
+}
+
+struct TileRec {
+    int32_t job_begin, njobs, list, pad;
+};
+
+__global__ void job_tiles_kernel(const int32_t *__restrict__ list_begin, const int32_t *__restrict__ tile_begin,
+                                 int nlist, int tq, TileRec *__restrict__ tiles)
+{
+    const int l = blockIdx.x * blockDim.x + threadIdx.x;
+    if (l >= nlist) return;
+    const int32_t jb = list_begin[l], cnt = list_begin[l + 1] - jb;
+    int32_t t = tile_begin[l];
+    for (int32_t o = 0; o < cnt; o += tq, ++t) tiles[t] = TileRec{jb + o, min(tq, cnt - o), l, 0};
+}
+
+// Copy per-job rows (job-sorted) back to (query, probe) order.
+__global__ void unsort_rows_kernel(const uint8_t *__restrict__ src, const int32_t *__restrict__ job_slot,
+                                   int64_t njobs, int row_bytes, uint8_t *__restrict__ dst)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= njobs * row_bytes) return;
+    const int64_t j = e / row_bytes;
+    dst[(int64_t)job_slot[j] * row_bytes + e % row_bytes] = src[e];
+}
+
+}  // namespace
+
+int launch_unsort_rows(const uint8_t *src_dev, const int32_t *job_slot_dev, int64_t njobs, int row_bytes,
+                       uint8_t *dst_dev, hipStream_t s)
+{
+    const int64_t total = njobs * row_bytes;
+    if (total == 0) return PSC_OK;
+    hipLaunchKernelGGL(unsort_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, src_dev,
+                       job_slot_dev, njobs, row_bytes, dst_dev);
+    PSC_HIP_TRY(hipGetLastError());
+    return PSC_OK;
+}
+
+static int check_dim(int dim, int nlist)
+{
+    PSC_REQUIRE(dim > 0 && dim % 4 == 0 && dim <= 1024, "coarse quantizer needs dim %% 4 == 0 and dim <= 1024, got %d", dim);
+    PSC_REQUIRE(nlist >= 1 && nlist <= 16384, "nlist must be in [1, 16384], got %d", nlist);
+    return PSC_OK;
+}
+
+int launch_coarse_distances(const float *x_dev, int64_t n, int dim, const float *cent_dev, int nlist,
+                            float *dist_dev, hipStream_t s)
+{
+    int rc = check_dim(dim, nlist);
+    if (rc != PSC_OK) return rc;
+    if (n == 0) return PSC_OK;
+    PSC_REQUIRE((n + kRows - 1) / kRows <= 0x7fffffffLL, "too many rows");
+    dim3 grid((unsigned)((n + kRows - 1) / kRows), (unsigned)((nlist + 255) / 256));
+    hipLaunchKernelGGL(coarse_dist_kernel, grid, dim3(256), (size_t)kRows * dim * sizeof(float), s, x_dev, n, dim,
+                       cent_dev, nlist, dist_dev);
+    PSC_HIP_TRY(hipGetLastError());
+    return PSC_OK;
+}
+
+int launch_select_probes(const float *dist_dev, int64_t n, int nlist, int nprobe, int32_t *probed_dev,
+                         hipStream_t s)
+{
+    PSC_REQUIRE(nprobe >= 1 && nprobe <= nlist && nlist <= 16384, "bad nprobe/nlist");
+    if (n == 0) return PSC_OK;
+    PSC_REQUIRE(n <= 0x7fffffffLL, "too many rows");
+    static bool configured = false;
+    if (!configured) {
+        PSC_HIP_TRY(hipFuncSetAttribute((const void *)select_probes_kernel,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 16384 * 8));
+        configured = true;
+    }
+    hipLaunchKernelGGL(select_probes_kernel, dim3((unsigned)n), dim3(256), (size_t)nlist * sizeof(uint64_t), s,
+                       dist_dev, nlist, nprobe, probed_dev);
+    PSC_HIP_TRY(hipGetLastError());
+    return PSC_OK;
+}
+
+int launch_nearest_centroid(const float *x_dev, int64_t n, int dim, const float *cent_dev, int nlist,
+                            int32_t *assign_dev, hipStream_t s)
+{
+    int rc = check_dim(dim, nlist);
+    if (rc != PSC_OK) return rc;
+    if (n == 0) return PSC_OK;
+    PSC_REQUIRE((n + kRows - 1) / kRows <= 0x7fffffffLL, "too many rows");
+    size_t lds = (size_t)kRows * dim * sizeof(float);
+    if (lds < 4 * kRows * sizeof(uint64_t)) lds = 4 * kRows * sizeof(uint64_t);
+    hipLaunchKernelGGL(nearest_centroid_kernel, dim3((unsigned)((n + kRows - 1) / kRows)), dim3(256), lds, s,
+                       x_dev, n, dim, cent_dev, nlist, assign_dev);
+    PSC_HIP_TRY(hipGetLastError());
+    return PSC_OK;
+}
+
+int launch_build_jobs(const int32_t *probed_dev, int64_t nq, int nprobe, int nlist, int tq,
+                      const IvfJobBuffers &b, hipStream_t s)
+{
+    const int64_t njobs = nq * nprobe;
+    const int64_t nblk = (nq + kJobBlockQ - 1) / kJobBlockQ;
+    PSC_REQUIRE(njobs < 0x7fffffffLL && nblk * nlist < ((int64_t)1 << 40), "too many jobs");
+    const int64_t hcells = nblk * nlist;
+    hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)((hcells + 255) / 256)), dim3(256), 0, s, b.hist, hcells);
+    hipLaunchKernelGGL(job_hist_kernel, dim3((unsigned)((njobs + 255) / 256)), dim3(256), 0, s, probed_dev, nq,
+                       nprobe, nlist, b.hist);
+    hipLaunchKernelGGL(job_column_prefix_kernel, dim3((unsigned)((nlist + 255) / 256)), dim3(256), 0, s, b.hist,
+                       nblk, nlist, b.list_begin);
+    hipLaunchKernelGGL(job_list_prefix_kernel, dim3(1), dim3(1024), 0, s, b.list_begin, b.tile_begin, nlist, tq);
+    hipLaunchKernelGGL(job_scatter_kernel, dim3((unsigned)nblk), dim3(256), 0, s, probed_dev, nq, nprobe, nlist,
+                       b.hist, b.list_begin, b.job_q, b.job_list, b.job_slot);
+    hipLaunchKernelGGL(job_tiles_kernel, dim3((unsigned)((nlist + 255) / 256)), dim3(256), 0, s, b.list_begin,
+                       b.tile_begin, nlist, tq, (TileRec *)b.tiles);
+    PSC_HIP_TRY(hipGetLastError());
+    return PSC_OK;
+}
+
+}  // namespace psc

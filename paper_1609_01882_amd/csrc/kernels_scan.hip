@@ -33,6 +33,10 @@ constexpr uint32_t kRelMask = (1u << kRelBits) - 1;
 constexpr int64_t kMaxSliceLen = (int64_t)1 << kRelBits;
 constexpr int kSpinLimit = 1 << 22;   // bounded wait on a list lock (each turn sleeps)
 
+struct IvfTile {
+    int32_t job_begin, njobs, list, pad;
+};
+
 struct ScanArgs {
     const float *lut;         // [nq][M][256]
     const uint8_t *qcodes;    // [nq][M]
@@ -46,6 +50,13 @@ struct ScanArgs {
     float *part_d;            // [nq][nslice][k]
     int64_t *part_i;          // [nq][nslice][k]
     int *status;              // set non-zero if a bounded wait expired
+    // inverted-file mode (Section 4.3): a tile = up to TQ (query, list) jobs of ONE list, rows
+    // job_begin.. of the job-sorted tables / query codes; the scanned range is that list
+    const IvfTile *tiles;     // [*ntiles]
+    const int *ntiles;        // device-side count (the grid is an upper bound)
+    const int64_t *list_off;  // [nlist+1] list boundaries in `codes`
+    const int32_t *ext_ids;   // [n] id of each stored code
+    const int32_t *job_slot;  // [njobs] partial list (query * nprobe + probe) a job writes
 };
 
 __device__ __forceinline__ uint64_t ballot64(bool p) { return __ballot(p); }
@@ -194,7 +205,7 @@ __device__ __forceinline__ void insert_candidates(const Lds<M, TQ> &s, const Sca
 
 // Score the first `nvalid` (<= 64) entries of the wave's queue and feed the ones that beat the
 // current threshold to the lists.
-template <int M, int TQ>
+template <int M, int TQ, bool IVF>
 __device__ __forceinline__ void drain(const Lds<M, TQ> &s, const ScanArgs &a, const lds_u32 *ring,
                                       int nvalid, int64_t slice_begin, int64_t q0)
 {
@@ -232,19 +243,24 @@ __device__ __forceinline__ void drain(const Lds<M, TQ> &s, const ScanArgs &a, co
         d = acc;
     }
     bool pass = act && d <= s.thr[q];
-    if (a.skip_first >= 0)  // a vector is not its own neighbour
-        pass = pass && (slice_begin + (int64_t)rel) != a.skip_first + q0 + q;
+    uint32_t key = rel;  // what breaks distance ties: the position, or the stored id
+    if constexpr (IVF) {
+        if (pass) key = (uint32_t)a.ext_ids[slice_begin + rel];
+    } else {
+        if (a.skip_first >= 0)  // a vector is not its own neighbour
+            pass = pass && (slice_begin + (int64_t)rel) != a.skip_first + q0 + q;
+    }
     uint64_t pm = ballot64(pass);
     while (pm) {
         const int leader = __builtin_ctzll(pm);
         const int qcur = __builtin_amdgcn_readlane(q, leader);
         const uint64_t mine = ballot64(pass && q == qcur);
         pm &= ~mine;
-        insert_candidates<M, TQ>(s, a, qcur, mine, d, rel);
+        insert_candidates<M, TQ>(s, a, qcur, mine, d, key);
     }
 }
 
-template <int M, int TQ, int NW>
+template <int M, int TQ, int NW, bool IVF>
 __global__ void __launch_bounds__(NW * 64)
 scan_kernel(ScanArgs a)
 {
@@ -259,12 +275,29 @@ scan_kernel(ScanArgs a)
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    const int64_t tile = blockIdx.x;
-    const int slice = (int)(tile % a.nslice);
-    const int64_t q0 = (tile / a.nslice) * TQ;
-    const int nvq = (int)((a.nq - q0) < TQ ? (a.nq - q0) : TQ);
-    const int64_t slice_begin = (int64_t)slice * a.slice_len;
-    const int64_t slice_end = (slice_begin + a.slice_len) < a.n ? (slice_begin + a.slice_len) : a.n;
+    // flat mode: tile -> (query tile, database slice); inverted-file mode: tile -> descriptor.
+    // [valid_begin, slice_end) is scanned; slice_begin (<= valid_begin) is where positions count
+    // from and is a whole number of 16-byte loads into `codes`.
+    int slice = 0;
+    int64_t q0, slice_begin, valid_begin, slice_end;
+    int nvq;
+    if constexpr (IVF) {
+        if ((int)blockIdx.x >= *a.ntiles) return;  // the grid is an upper bound on the tile count
+        const IvfTile t = a.tiles[blockIdx.x];
+        q0 = t.job_begin;
+        nvq = t.njobs;
+        valid_begin = a.list_off[t.list];
+        slice_end = a.list_off[t.list + 1];
+        slice_begin = valid_begin - valid_begin % CPL;
+    } else {
+        const int64_t tile = blockIdx.x;
+        slice = (int)(tile % a.nslice);
+        q0 = (tile / a.nslice) * TQ;
+        nvq = (int)((a.nq - q0) < TQ ? (a.nq - q0) : TQ);
+        slice_begin = (int64_t)slice * a.slice_len;
+        valid_begin = slice_begin;
+        slice_end = (slice_begin + a.slice_len) < a.n ? (slice_begin + a.slice_len) : a.n;
+    }
 
     // ---- stage the tables, reset the lists
     {
@@ -348,8 +381,10 @@ scan_kernel(ScanArgs a)
 
     uint32_t cur[CB * WPC];
     if (wave_first < slice_end) load_block(lane_ptr, wave_first, wave_first + 64 * CB <= slice_end, cur);
+    // (codes between slice_begin and valid_begin are readable -- they belong to the previous list --
+    //  and are masked off below)
     for (int64_t blk = wave_first; blk < slice_end; blk += stride) {
-        const bool whole = blk + 64 * CB <= slice_end;
+        const bool whole = blk + 64 * CB <= slice_end && blk >= valid_begin;
         uint32_t nxt[CB * WPC];
         lane_ptr += stride * M;
         if (blk + stride < slice_end)
@@ -373,7 +408,9 @@ scan_kernel(ScanArgs a)
             valid = 0u;
 #pragma unroll
             for (int c = 0; c < CB; ++c)
-                valid |= (blk + (int64_t)lane * CB + c < slice_end) ? (qmask << (c * TQ)) : 0u;
+                valid |= (blk + (int64_t)lane * CB + c < slice_end && blk + (int64_t)lane * CB + c >= valid_begin)
+                             ? (qmask << (c * TQ))
+                             : 0u;
         }
         uint32_t sv = ~far & valid;
         const uint32_t rel0 = (uint32_t)(blk - slice_begin) + (uint32_t)lane * CB;
@@ -390,7 +427,7 @@ scan_kernel(ScanArgs a)
             fill += __builtin_popcountll(bal);
             if (fill >= 64) {
                 __builtin_amdgcn_wave_barrier();
-                drain<M, TQ>(s, a, ring, 64, slice_begin, q0);
+                drain<M, TQ, IVF>(s, a, ring, 64, slice_begin, q0);
                 // entries 64..fill-1 move to the front
                 fill -= 64;
                 uint32_t e = 0u;
@@ -405,18 +442,25 @@ scan_kernel(ScanArgs a)
     }
     if (fill > 0) {
         __builtin_amdgcn_wave_barrier();
-        drain<M, TQ>(s, a, ring, fill, slice_begin, q0);
+        drain<M, TQ, IVF>(s, a, ring, fill, slice_begin, q0);
     }
     __syncthreads();
 
     // ---- write the tile's lists (padded) to the workspace
     for (int e = tid; e < nvq * a.k; e += NW * 64) {
         const int q = e / a.k, r = e - q * a.k;
-        const int64_t o = ((q0 + q) * a.nslice + slice) * a.k + r;
         const bool have = r < s.cnt[q];
         const uint64_t ent = s.top[q * a.kpad + r];
+        int64_t o, id;
+        if constexpr (IVF) {
+            o = (int64_t)a.job_slot[q0 + q] * a.k + r;
+            id = (int64_t)entry_id(ent);
+        } else {
+            o = ((q0 + q) * a.nslice + slice) * a.k + r;
+            id = slice_begin + (int64_t)entry_id(ent);
+        }
         a.part_d[o] = have ? entry_dist(ent) : __builtin_inff();
-        a.part_i[o] = have ? (slice_begin + (int64_t)entry_id(ent)) : (int64_t)-1;
+        a.part_i[o] = have ? id : (int64_t)-1;
     }
 }
 
@@ -522,18 +566,30 @@ __global__ void zero_u64_kernel(unsigned long long *p, int64_t n)
     if (e < n) p[e] = 0;
 }
 
-template <int M, int TQ, int NW>
+template <int M, int TQ, int NW, bool IVF>
 int run_scan(const ScanArgs &a, int64_t ntiles, size_t lds, hipStream_t s)
 {
     static bool configured = false;  // raise the dynamic-LDS ceiling once per instantiation
     if (!configured) {
-        PSC_HIP_TRY(hipFuncSetAttribute((const void *)scan_kernel<M, TQ, NW>,
+        PSC_HIP_TRY(hipFuncSetAttribute((const void *)scan_kernel<M, TQ, NW, IVF>,
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
         configured = true;
     }
-    hipLaunchKernelGGL((scan_kernel<M, TQ, NW>), dim3((unsigned)ntiles), dim3(NW * 64), lds, s, a);
+    hipLaunchKernelGGL((scan_kernel<M, TQ, NW, IVF>), dim3((unsigned)ntiles), dim3(NW * 64), lds, s, a);
     PSC_HIP_TRY(hipGetLastError());
     return PSC_OK;
+}
+
+template <bool IVF>
+int dispatch_scan(int m, int tq, const ScanArgs &a, int64_t ntiles, size_t lds, hipStream_t s)
+{
+    if (m == 8) {
+        if (tq == 16) return run_scan<8, 16, 16, IVF>(a, ntiles, lds, s);
+        if (tq == 8) return run_scan<8, 8, 16, IVF>(a, ntiles, lds, s);
+        return run_scan<8, 4, 16, IVF>(a, ntiles, lds, s);
+    }
+    if (tq == 8) return run_scan<16, 8, 16, IVF>(a, ntiles, lds, s);
+    return run_scan<16, 4, 16, IVF>(a, ntiles, lds, s);
 }
 
 constexpr size_t kLdsBudget = 160 * 1024;
@@ -668,17 +724,61 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
     a.part_i = (int64_t *)((char *)ws + 256 + (((size_t)nq * p.nslice * k * sizeof(float) + 255) / 256 * 256));
 
     if (clear_status) hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, s, a.status);
-    if (m == 8) {
-        if (p.tq == 16) rc = run_scan<8, 16, 16>(a, p.ntiles, p.lds_bytes, s);
-        else if (p.tq == 8) rc = run_scan<8, 8, 16>(a, p.ntiles, p.lds_bytes, s);
-        else rc = run_scan<8, 4, 16>(a, p.ntiles, p.lds_bytes, s);
-    } else {
-        if (p.tq == 8) rc = run_scan<16, 8, 16>(a, p.ntiles, p.lds_bytes, s);
-        else rc = run_scan<16, 4, 16>(a, p.ntiles, p.lds_bytes, s);
-    }
+    a.tiles = nullptr;
+    a.ntiles = nullptr;
+    a.list_off = nullptr;
+    a.ext_ids = nullptr;
+    a.job_slot = nullptr;
+    rc = dispatch_scan<false>(m, p.tq, a, p.ntiles, p.lds_bytes, s);
     if (rc != PSC_OK) return rc;
     hipLaunchKernelGGL(merge_kernel, dim3((unsigned)nq), dim3(64), 0, s, a.part_d, a.part_i, p.nslice, k,
                        (int64_t)0, a.status, ids_dev, dists_dev);
+    PSC_HIP_TRY(hipGetLastError());
+    return PSC_OK;
+}
+
+// Inverted-file scan: one workgroup per tile descriptor (up to `max_tiles`; the actual count is
+// read on the device), partial lists written at job_slot[job] * k, then one merge per query
+// over its nprobe partial lists.
+int launch_ivf_scan(int m, int tq, int kpad, size_t lds_bytes, const float *lut_dev,
+                    const uint8_t *qcodes_dev, const uint8_t *codes_dev, int64_t n, int ht, int k,
+                    const void *tiles_dev, const int *ntiles_dev, int64_t max_tiles,
+                    const int64_t *list_off_dev, const int32_t *ext_ids_dev, const int32_t *job_slot_dev,
+                    float *part_d, int64_t *part_i, int *status, int64_t nq, int nprobe,
+                    int64_t *ids_dev, float *dists_dev, hipStream_t s)
+{
+    PSC_REQUIRE(((uintptr_t)codes_dev & 15) == 0 && ((uintptr_t)qcodes_dev & 15) == 0 &&
+                    ((uintptr_t)lut_dev & 15) == 0,
+                "codes, query codes and tables must be 16-byte aligned");
+    PSC_REQUIRE(max_tiles <= 0x7fffffffLL, "too many tiles");
+    ScanArgs a;
+    a.lut = lut_dev;
+    a.qcodes = qcodes_dev;
+    a.codes = codes_dev;
+    a.skip_first = -1;
+    a.nq = 0;
+    a.n = n;
+    a.slice_len = 0;
+    a.nslice = 1;
+    a.k = k;
+    a.kpad = kpad;
+    const int nbits = 8 * m;
+    a.bias = 0x7fffffffu - (uint32_t)(ht > nbits ? nbits : ht);
+    a.part_d = part_d;
+    a.part_i = part_i;
+    a.status = status;
+    a.tiles = (const IvfTile *)tiles_dev;
+    a.ntiles = ntiles_dev;
+    a.list_off = list_off_dev;
+    a.ext_ids = ext_ids_dev;
+    a.job_slot = job_slot_dev;
+    hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, s, a.status);
+    if (max_tiles > 0) {
+        int rc = dispatch_scan<true>(m, tq, a, max_tiles, lds_bytes, s);
+        if (rc != PSC_OK) return rc;
+    }
+    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)nq), dim3(64), 0, s, part_d, part_i, nprobe, k,
+                       (int64_t)0, status, ids_dev, dists_dev);
     PSC_HIP_TRY(hipGetLastError());
     return PSC_OK;
 }

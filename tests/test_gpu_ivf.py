@@ -1,0 +1,146 @@
+"""Parity of the inverted-file variant (Section 4.3) with the oracle (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import workloads as W
+from gpu_util import RTOL, assert_topk_matches
+
+pytestmark = pytest.mark.gpu
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def build_ivf(psc, n, nlist, seed, m=8):
+    """Train coarse + residual PQ with the library, build the lists with the library's
+    assignment/encoding; grouping by list is a stable sort (harness plumbing)."""
+    xt = W.sift_like(6000, seed=seed, stream=1)
+    xb = W.sift_like(n, seed=seed, stream=2)
+    idx = psc.Index(128, m)
+    idx.ivf_train_coarse(xt, nlist, iters=6, seed=3)
+    coarse = idx.ivf_get_coarse()
+    lt, _ = idx.ivf_assign_encode(_dev(xt), want_codes=False)
+    res_t = xt - coarse[lt.cpu().numpy()]
+    idx.train_pq(res_t, iters=5, seed=4)
+    idx.optimize_index_assignment(n_iter=30_000, seed=5)
+    list_no, codes = idx.ivf_assign_encode(_dev(xb))
+    torch.cuda.synchronize()
+    order = torch.sort(list_no.to(torch.int64), stable=True).indices
+    counts = torch.bincount(list_no.to(torch.int64), minlength=nlist)
+    offsets = torch.zeros(nlist + 1, dtype=torch.int64, device="cuda")
+    offsets[1:] = torch.cumsum(counts, 0)
+    lcodes = codes[order].contiguous()
+    lids = order.to(torch.int32).contiguous()
+    idx.ivf_set_lists(offsets, lcodes, lids)
+    return dict(idx=idx, xb=xb, coarse=coarse, cb=idx.get_codebook(), list_no=list_no.cpu().numpy(),
+                codes=codes.cpu().numpy(), offsets=offsets.cpu().numpy(), lcodes=lcodes.cpu().numpy(),
+                lids=lids.cpu().numpy())
+
+
+@pytest.fixture(scope="module")
+def ivf():
+    import paper_1609_01882_amd as psc
+    return psc, build_ivf(psc, 80_001, 64, seed=70)
+
+
+def test_assignment_and_residual_codes(ivf):
+    psc, s = ivf
+    n = 20_000
+    d = ((s["xb"][:n, None, :].astype(np.float64) - s["coarse"][None, :, :].astype(np.float64)) ** 2).sum(axis=2)
+    ref = d.argmin(axis=1)
+    bad = np.flatnonzero(s["list_no"][:n] != ref)
+    assert len(bad) < 5
+    for i in bad:  # only near-ties may fall the other way
+        assert abs(d[i, s["list_no"][i]] - d[i, ref[i]]) <= RTOL * d[i, ref[i]]
+    res = s["xb"][:n].astype(np.float64) - s["coarse"][s["list_no"][:n]].astype(np.float64)
+    ref_codes = O.encode(res, s["cb"])
+    assert (ref_codes != s["codes"][:n]).sum() < 20
+    # the lists partition the database
+    assert s["offsets"][0] == 0 and s["offsets"][-1] == len(s["xb"])
+    assert sorted(s["lids"].tolist()) == list(range(len(s["xb"])))
+
+
+@pytest.mark.parametrize("nprobe,ht,k", [(8, 24, 10), (8, 64, 100), (1, 20, 10), (64, 28, 100), (3, 0, 5)])
+def test_ivf_search_matches_oracle(ivf, nprobe, ht, k):
+    psc, s = ivf
+    idx = s["idx"]
+    xq = W.sift_like(37, seed=70, stream=3)
+    ids, d, probed, qcodes = idx.ivf_search(_dev(xq), nprobe, ht, k, want_debug=True)
+    torch.cuda.synchronize()
+    ids, d, probed, qcodes = ids.cpu().numpy(), d.cpu().numpy(), probed.cpu().numpy(), qcodes.cpu().numpy()
+    # the oracle's own coarse ranking: the same lists in the same order, up to near-ties
+    own = O.ivf_search(xq, s["cb"], s["coarse"], s["offsets"], s["lcodes"], s["lids"], nprobe, ht, k,
+                       want_coarse=True)
+    diff = np.argwhere(own["probed"] != probed)
+    for q, p in diff:
+        a, b = own["coarse_d"][q, own["probed"][q, p]], own["coarse_d"][q, probed[q, p]]
+        assert abs(a - b) <= RTOL * a
+    assert len(diff) <= 2
+    # same decisions (probed lists, per-list bit strings) -> same survivors, ids and distances
+    ref = O.ivf_search(xq, s["cb"], s["coarse"], s["offsets"], s["lcodes"], s["lids"], nprobe, ht, k,
+                       probed_in=probed, qcodes_in=qcodes)
+    pad = ref["ids"] < 0
+    assert np.array_equal(ids < 0, pad)
+    assert np.allclose(d[~pad], ref["dists"][~pad], rtol=RTOL)
+    mism = np.argwhere((ids != ref["ids"]) & ~pad)
+    for q, r in mism:  # only where oracle distances tie within tolerance
+        near = np.abs(ref["dists"][q] - ref["dists"][q, r]) <= RTOL * ref["dists"][q, r]
+        assert ids[q, r] in ref["ids"][q][near] or abs(d[q, r] - ref["dists"][q, r]) <= RTOL * ref["dists"][q, r]
+    assert len(mism) <= 0.01 * ids.size
+    # the per-list query codes agree with the oracle's own on all but near-ties
+    own_q = O.ivf_search(xq, s["cb"], s["coarse"], s["offsets"], s["lcodes"], s["lids"], nprobe, ht, k,
+                         probed_in=probed)
+    assert np.array_equal(own_q["nsurv"], ref["nsurv"]) or (own_q["nsurv"] != ref["nsurv"]).mean() < 0.1
+
+
+def test_single_list_is_flat_search():
+    import paper_1609_01882_amd as psc
+    xt = W.sift_like(3000, seed=71, stream=1)
+    xb = W.sift_like(30_000, seed=71, stream=2)
+    xq = W.sift_like(20, seed=71, stream=3)
+    idx = psc.Index(128, 8)
+    idx.train_pq(xt, iters=4, seed=1)
+    idx.ivf_set_coarse(np.zeros((1, 128), np.float32))
+    list_no, codes = idx.ivf_assign_encode(_dev(xb))
+    assert int(list_no.abs().sum()) == 0
+    flat_codes = idx.encode(_dev(xb))
+    assert torch.equal(codes, flat_codes)
+    offsets = torch.tensor([0, len(xb)], dtype=torch.int64, device="cuda")
+    ids32 = torch.arange(len(xb), dtype=torch.int32, device="cuda")
+    idx.ivf_set_lists(offsets, codes, ids32)
+    for ht in (22, 64):
+        a = idx.ivf_search(_dev(xq), 1, ht, 10)
+        b = idx.search(_dev(xq), codes, ht, 10)
+        torch.cuda.synchronize()
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+def test_ivf_odd_list_boundaries_and_empty_lists():
+    """Lists that start at odd positions (misaligned for 16-byte loads) and empty lists."""
+    import paper_1609_01882_amd as psc
+    rng = np.random.default_rng(5)
+    idx = psc.Index(128, 8)
+    cb = rng.normal(size=(8, 256, 16)).astype(np.float32) * 20
+    idx.set_codebook(cb)
+    coarse = (rng.random(size=(6, 128)) * 100).astype(np.float32)
+    idx.ivf_set_coarse(coarse)
+    sizes = [7, 0, 131, 1, 0, 64]
+    offsets = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    n = int(offsets[-1])
+    lcodes = W.random_codes(n, 8, seed=3)
+    lids = rng.permutation(n).astype(np.int32)  # ids unrelated to positions
+    idx.ivf_set_lists(_dev(offsets), _dev(lcodes), _dev(lids))
+    xq = (rng.random(size=(5, 128)) * 100).astype(np.float32)
+    ids, d, probed, qcodes = idx.ivf_search(_dev(xq), 6, 64, 300, want_debug=True)
+    torch.cuda.synchronize()
+    ref = O.ivf_search(xq, cb, coarse, offsets, lcodes, lids, 6, 64, 300,
+                       probed_in=probed.cpu().numpy(), qcodes_in=qcodes.cpu().numpy())
+    ids, d = ids.cpu().numpy(), d.cpu().numpy()
+    assert np.array_equal(ids < 0, ref["ids"] < 0) and (ids[0] >= 0).sum() == n
+    assert np.allclose(d[ids >= 0], ref["dists"][ref["ids"] >= 0], rtol=RTOL)
+    assert (ids == ref["ids"]).mean() > 0.99
+    for q in range(5):
+        assert sorted(ids[q][ids[q] >= 0].tolist()) == list(range(n))
