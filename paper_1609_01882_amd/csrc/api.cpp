@@ -500,7 +500,7 @@ namespace {
 struct IvfLayout {
     ScanPlan plan;
     int64_t njobs, nblk, max_tiles;
-    size_t off_status, off_dist, off_probed, off_hist, off_list_begin, off_tile_begin, off_job_q, off_job_list,
+    size_t off_status, off_gthr, off_dist, off_probed, off_hist, off_list_begin, off_tile_begin, off_job_q, off_job_list,
         off_job_slot, off_tiles, off_lut, off_qcodes, off_part_d, off_part_i, total;
 };
 
@@ -523,6 +523,7 @@ int ivf_layout(const psc_index *idx, int64_t nq, int nprobe, int k, IvfLayout *L
         return at;
     };
     L->off_status = take(256);
+    L->off_gthr = take((size_t)nq * sizeof(uint32_t));
     L->off_dist = take((size_t)nq * idx->nlist * sizeof(float));
     L->off_probed = take((size_t)L->njobs * sizeof(int32_t));
     L->off_hist = take((size_t)L->nblk * idx->nlist * sizeof(int32_t));
@@ -612,7 +613,8 @@ int psc_ivf_search(const psc_index *idx, const float *q_dev, int64_t nq, int npr
     // 4. the fused scan over the tiles, 5. one merge per query over its nprobe partial lists
     return launch_ivf_scan(idx->m, L.plan.tq, L.plan.kpad, L.plan.lds_bytes, lut, qcodes, idx->list_codes_dev,
                            idx->list_n, ht, k, jb.tiles, jb.tile_begin + idx->nlist, L.max_tiles,
-                           idx->list_off_dev, idx->list_ids_dev, jb.job_slot, (float *)(w + L.off_part_d),
+                           idx->list_off_dev, idx->list_ids_dev, jb.job_slot, jb.job_q,
+                           (uint32_t *)(w + L.off_gthr), (float *)(w + L.off_part_d),
                            (int64_t *)(w + L.off_part_i), (int *)(w + L.off_status), nq, nprobe, ids_dev,
                            dists_dev, s);
 }

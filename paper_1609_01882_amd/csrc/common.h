@@ -63,6 +63,7 @@ struct ScanPlan {
     int64_t slice_len = 0;
     int64_t ntiles = 0;
     size_t lds_bytes = 0;
+    size_t gthr_bytes = 0;  // per-query shared thresholds
     size_t part_bytes = 0;  // partial result lists
     size_t total_bytes = 0; // whole workspace
 };
@@ -77,8 +78,8 @@ int launch_ivf_scan(int m, int tq, int kpad, size_t lds_bytes, const float *lut_
                     const uint8_t *qcodes_dev, const uint8_t *codes_dev, int64_t n, int ht, int k,
                     const void *tiles_dev, const int *ntiles_dev, int64_t max_tiles,
                     const int64_t *list_off_dev, const int32_t *ext_ids_dev, const int32_t *job_slot_dev,
-                    float *part_d, int64_t *part_i, int *status, int64_t nq, int nprobe,
-                    int64_t *ids_dev, float *dists_dev, hipStream_t s);
+                    const int32_t *job_q_dev, uint32_t *gthr_dev, float *part_d, int64_t *part_i, int *status,
+                    int64_t nq, int nprobe, int64_t *ids_dev, float *dists_dev, hipStream_t s);
 int launch_hamming_filter(int m, const uint8_t *qcodes_dev, int64_t nq, const uint8_t *codes_dev,
                           int64_t n, int ht, int64_t *nsurv_dev, uint8_t *hdist_dev, hipStream_t s);
 

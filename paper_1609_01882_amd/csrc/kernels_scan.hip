@@ -50,6 +50,12 @@ struct ScanArgs {
     float *part_d;            // [nq][nslice][k]
     int64_t *part_i;          // [nq][nslice][k]
     int *status;              // set non-zero if a bounded wait expired
+    // Per query, the smallest k-th-best distance any workgroup working for that query has
+    // reached so far, as a sortable key (see dist_key).  Nothing farther than it can be in the
+    // query's final top-k, so every workgroup of the query prunes with it: the partial lists
+    // of one query behave like one stream instead of one warm-up per slice or list.
+    uint32_t *gthr;           // [number of queries]
+    const int32_t *job_q;     // inverted-file mode: query of each job (index into gthr)
     // inverted-file mode (Section 4.3): a tile = up to TQ (query, list) jobs of ONE list, rows
     // job_begin.. of the job-sorted tables / query codes; the scanned range is that list
     const IvfTile *tiles;     // [*ntiles]
@@ -94,17 +100,21 @@ typedef PSC_LDS volatile uint64_t lds_vu64;
 // the unsigned 64-bit order is the (distance, id) order.  The key is the usual order-preserving
 // map of float bits to unsigned (negative values flip all bits, others flip the sign bit);
 // -0 is folded into +0 first so that equal distances get equal keys.
-__device__ __forceinline__ uint64_t pack_entry(float d, uint32_t id)
+__device__ __forceinline__ uint32_t dist_key(float d)
 {
     const uint32_t u = __float_as_uint(d + 0.0f);
-    const uint32_t key = u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
-    return ((uint64_t)key << 32) | id;
+    return u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
 }
-__device__ __forceinline__ float entry_dist(uint64_t e)
+__device__ __forceinline__ float key_dist(uint32_t key)
 {
-    const uint32_t key = (uint32_t)(e >> 32);
     return __uint_as_float(key ^ ((key >> 31) ? 0x80000000u : 0xffffffffu));
 }
+constexpr uint32_t kKeyInf = 0xff800000u;  // dist_key(+infinity)
+__device__ __forceinline__ uint64_t pack_entry(float d, uint32_t id)
+{
+    return ((uint64_t)dist_key(d) << 32) | id;
+}
+__device__ __forceinline__ float entry_dist(uint64_t e) { return key_dist((uint32_t)(e >> 32)); }
 __device__ __forceinline__ uint32_t entry_id(uint64_t e) { return (uint32_t)e; }
 
 template <int M, int TQ>
@@ -128,11 +138,17 @@ struct Lds {
 
 // Insert the candidates held by the lanes in `mine` (all for query slot q) into q's list.
 // Executed by the whole wave; mine is wave-uniform.
-template <int M, int TQ>
-__device__ __forceinline__ void insert_candidates(const Lds<M, TQ> &s, const ScanArgs &a, int q, uint64_t mine,
-                                  float d, uint32_t id)
+template <int M, int TQ, bool SHARE>
+__device__ __forceinline__ void insert_candidates(const Lds<M, TQ> &s, const ScanArgs &a, int q, int64_t qid,
+                                                  uint64_t mine, float d, uint32_t id)
 {
     const int lane = lane_id();
+    // What other workgroups of this query have reached so far; asked for now, used at the end,
+    // so that the trip to memory overlaps the work on the list.
+    uint32_t seen = kKeyInf;
+    if constexpr (SHARE) {
+        if (lane == 0) seen = __hip_atomic_load(&a.gthr[qid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     int got = 0;
     if (lane == 0) {
         int spins = 0;
@@ -194,18 +210,33 @@ __device__ __forceinline__ void insert_candidates(const Lds<M, TQ> &s, const Sca
         if (cnt < k) ++cnt;
         __builtin_amdgcn_wave_barrier();
     }
+    uint32_t own_key = kKeyInf;
     if (lane == 0) {
         s.cnt[q] = cnt;
-        if (cnt == k) s.thr[q] = entry_dist(list[k - 1]);
+        if (cnt == k) {
+            own_key = (uint32_t)(list[k - 1] >> 32);
+            const float own = key_dist(own_key);
+            if (own < s.thr[q]) s.thr[q] = own;
+        }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    if (lane == 0)
+    if (lane == 0) {
         __hip_atomic_store(&s.lock[q], 0, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        // Outside the lock: publish this list's k-th best (no reply awaited) and adopt what the
+        // other workgroups of the query had reached.  A concurrent, lower local threshold may be
+        // overwritten by a slightly higher one here; that only admits a few more candidates.
+        if constexpr (SHARE) {
+            const float other = key_dist(seen);
+            if (other < s.thr[q]) s.thr[q] = other;
+            if (own_key < seen)  // last, so that nothing here waits for it
+                (void)__hip_atomic_fetch_min(&a.gthr[qid], own_key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
 }
 
 // Score the first `nvalid` (<= 64) entries of the wave's queue and feed the ones that beat the
 // current threshold to the lists.
-template <int M, int TQ, bool IVF>
+template <int M, int TQ, bool IVF, bool SHARE>
 __device__ __forceinline__ void drain(const Lds<M, TQ> &s, const ScanArgs &a, const lds_u32 *ring,
                                       int nvalid, int64_t slice_begin, int64_t q0)
 {
@@ -256,11 +287,14 @@ __device__ __forceinline__ void drain(const Lds<M, TQ> &s, const ScanArgs &a, co
         const int qcur = __builtin_amdgcn_readlane(q, leader);
         const uint64_t mine = ballot64(pass && q == qcur);
         pm &= ~mine;
-        insert_candidates<M, TQ>(s, a, qcur, mine, d, key);
+        insert_candidates<M, TQ, SHARE>(s, a, qcur, IVF ? (int64_t)a.job_q[q0 + qcur] : q0 + qcur, mine, d, key);
     }
 }
 
-template <int M, int TQ, int NW, bool IVF>
+// SHARE: the workgroups of one query exchange their k-th-best distance through `gthr`.  Worth
+// a trip to memory per insertion when a query is served by many workgroups (inverted lists,
+// many slices), not when there are two.
+template <int M, int TQ, int NW, bool IVF, bool SHARE>
 __global__ void __launch_bounds__(NW * 64)
 scan_kernel(ScanArgs a)
 {
@@ -311,7 +345,13 @@ scan_kernel(ScanArgs a)
             dst[e] = v;
         }
         if (tid < TQ) {
-            s.thr[tid] = __builtin_inff();
+            float t0 = __builtin_inff();
+            if constexpr (SHARE) {
+                if (tid < nvq)
+                    t0 = key_dist(__hip_atomic_load(&a.gthr[IVF ? (int64_t)a.job_q[q0 + tid] : q0 + tid],
+                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            }
+            s.thr[tid] = t0;
             s.cnt[tid] = 0;
             s.lock[tid] = 0;
         }
@@ -427,7 +467,7 @@ scan_kernel(ScanArgs a)
             fill += __builtin_popcountll(bal);
             if (fill >= 64) {
                 __builtin_amdgcn_wave_barrier();
-                drain<M, TQ, IVF>(s, a, ring, 64, slice_begin, q0);
+                drain<M, TQ, IVF, SHARE>(s, a, ring, 64, slice_begin, q0);
                 // entries 64..fill-1 move to the front
                 fill -= 64;
                 uint32_t e = 0u;
@@ -442,7 +482,7 @@ scan_kernel(ScanArgs a)
     }
     if (fill > 0) {
         __builtin_amdgcn_wave_barrier();
-        drain<M, TQ, IVF>(s, a, ring, fill, slice_begin, q0);
+        drain<M, TQ, IVF, SHARE>(s, a, ring, fill, slice_begin, q0);
     }
     __syncthreads();
 
@@ -534,6 +574,12 @@ __global__ void fill_padding_kernel(int64_t *ids, float *dists, int64_t total)
 
 __global__ void clear_status_kernel(int *status) { *status = 0; }
 
+__global__ void fill_u32_kernel(uint32_t *p, int64_t n, uint32_t v)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < n) p[e] = v;
+}
+
 // Hamming filter alone: per query the number of codes within ht (and optionally every distance).
 template <int M>
 __global__ void __launch_bounds__(256)
@@ -566,30 +612,30 @@ __global__ void zero_u64_kernel(unsigned long long *p, int64_t n)
     if (e < n) p[e] = 0;
 }
 
-template <int M, int TQ, int NW, bool IVF>
+template <int M, int TQ, int NW, bool IVF, bool SHARE>
 int run_scan(const ScanArgs &a, int64_t ntiles, size_t lds, hipStream_t s)
 {
     static bool configured = false;  // raise the dynamic-LDS ceiling once per instantiation
     if (!configured) {
-        PSC_HIP_TRY(hipFuncSetAttribute((const void *)scan_kernel<M, TQ, NW, IVF>,
+        PSC_HIP_TRY(hipFuncSetAttribute((const void *)scan_kernel<M, TQ, NW, IVF, SHARE>,
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
         configured = true;
     }
-    hipLaunchKernelGGL((scan_kernel<M, TQ, NW, IVF>), dim3((unsigned)ntiles), dim3(NW * 64), lds, s, a);
+    hipLaunchKernelGGL((scan_kernel<M, TQ, NW, IVF, SHARE>), dim3((unsigned)ntiles), dim3(NW * 64), lds, s, a);
     PSC_HIP_TRY(hipGetLastError());
     return PSC_OK;
 }
 
-template <bool IVF>
+template <bool IVF, bool SHARE>
 int dispatch_scan(int m, int tq, const ScanArgs &a, int64_t ntiles, size_t lds, hipStream_t s)
 {
     if (m == 8) {
-        if (tq == 16) return run_scan<8, 16, 16, IVF>(a, ntiles, lds, s);
-        if (tq == 8) return run_scan<8, 8, 16, IVF>(a, ntiles, lds, s);
-        return run_scan<8, 4, 16, IVF>(a, ntiles, lds, s);
+        if (tq == 16) return run_scan<8, 16, 16, IVF, SHARE>(a, ntiles, lds, s);
+        if (tq == 8) return run_scan<8, 8, 16, IVF, SHARE>(a, ntiles, lds, s);
+        return run_scan<8, 4, 16, IVF, SHARE>(a, ntiles, lds, s);
     }
-    if (tq == 8) return run_scan<16, 8, 16, IVF>(a, ntiles, lds, s);
-    return run_scan<16, 4, 16, IVF>(a, ntiles, lds, s);
+    if (tq == 8) return run_scan<16, 8, 16, IVF, SHARE>(a, ntiles, lds, s);
+    return run_scan<16, 4, 16, IVF, SHARE>(a, ntiles, lds, s);
 }
 
 constexpr size_t kLdsBudget = 160 * 1024;
@@ -673,7 +719,8 @@ int plan_scan(int m, int64_t nq, int64_t n, int k, ScanPlan *plan)
     p.ntiles = nqt * nslice;
     const size_t dist_bytes = ((size_t)nq * nslice * k * sizeof(float) + 255) / 256 * 256;
     p.part_bytes = dist_bytes + (size_t)nq * nslice * k * sizeof(int64_t);
-    p.total_bytes = 256 + p.part_bytes;
+    p.gthr_bytes = ((size_t)nq * sizeof(uint32_t) + 255) / 256 * 256;
+    p.total_bytes = 256 + p.gthr_bytes + p.part_bytes;
     *plan = p;
     return PSC_OK;
 }
@@ -720,8 +767,11 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
     const int ht_eff = ht > nbits ? nbits : ht;
     a.bias = 0x7fffffffu - (uint32_t)ht_eff;
     a.status = (int *)ws;
-    a.part_d = (float *)((char *)ws + 256);
-    a.part_i = (int64_t *)((char *)ws + 256 + (((size_t)nq * p.nslice * k * sizeof(float) + 255) / 256 * 256));
+    a.gthr = (uint32_t *)((char *)ws + 256);
+    a.job_q = nullptr;
+    a.part_d = (float *)((char *)ws + 256 + p.gthr_bytes);
+    a.part_i = (int64_t *)((char *)a.part_d + (((size_t)nq * p.nslice * k * sizeof(float) + 255) / 256 * 256));
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((nq + 255) / 256)), dim3(256), 0, s, a.gthr, nq, kKeyInf);
 
     if (clear_status) hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, s, a.status);
     a.tiles = nullptr;
@@ -729,7 +779,8 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
     a.list_off = nullptr;
     a.ext_ids = nullptr;
     a.job_slot = nullptr;
-    rc = dispatch_scan<false>(m, p.tq, a, p.ntiles, p.lds_bytes, s);
+    rc = p.nslice >= 4 ? dispatch_scan<false, true>(m, p.tq, a, p.ntiles, p.lds_bytes, s)
+                       : dispatch_scan<false, false>(m, p.tq, a, p.ntiles, p.lds_bytes, s);
     if (rc != PSC_OK) return rc;
     hipLaunchKernelGGL(merge_kernel, dim3((unsigned)nq), dim3(64), 0, s, a.part_d, a.part_i, p.nslice, k,
                        (int64_t)0, a.status, ids_dev, dists_dev);
@@ -744,8 +795,8 @@ int launch_ivf_scan(int m, int tq, int kpad, size_t lds_bytes, const float *lut_
                     const uint8_t *qcodes_dev, const uint8_t *codes_dev, int64_t n, int ht, int k,
                     const void *tiles_dev, const int *ntiles_dev, int64_t max_tiles,
                     const int64_t *list_off_dev, const int32_t *ext_ids_dev, const int32_t *job_slot_dev,
-                    float *part_d, int64_t *part_i, int *status, int64_t nq, int nprobe,
-                    int64_t *ids_dev, float *dists_dev, hipStream_t s)
+                    const int32_t *job_q_dev, uint32_t *gthr_dev, float *part_d, int64_t *part_i, int *status,
+                    int64_t nq, int nprobe, int64_t *ids_dev, float *dists_dev, hipStream_t s)
 {
     PSC_REQUIRE(((uintptr_t)codes_dev & 15) == 0 && ((uintptr_t)qcodes_dev & 15) == 0 &&
                     ((uintptr_t)lut_dev & 15) == 0,
@@ -772,9 +823,12 @@ int launch_ivf_scan(int m, int tq, int kpad, size_t lds_bytes, const float *lut_
     a.list_off = list_off_dev;
     a.ext_ids = ext_ids_dev;
     a.job_slot = job_slot_dev;
+    a.job_q = job_q_dev;
+    a.gthr = gthr_dev;
     hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, s, a.status);
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((nq + 255) / 256)), dim3(256), 0, s, gthr_dev, nq, kKeyInf);
     if (max_tiles > 0) {
-        int rc = dispatch_scan<true>(m, tq, a, max_tiles, lds_bytes, s);
+        int rc = dispatch_scan<true, true>(m, tq, a, max_tiles, lds_bytes, s);
         if (rc != PSC_OK) return rc;
     }
     hipLaunchKernelGGL(merge_kernel, dim3((unsigned)nq), dim3(64), 0, s, part_d, part_i, nprobe, k,

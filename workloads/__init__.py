@@ -11,6 +11,7 @@ from .generators import (  # noqa: F401
     WorkloadConfig,
     mixture_centres,
     sift_like,
+    sift_like_torch,
     relu_like,
     random_codes,
     get_config,

@@ -112,6 +112,25 @@ def relu_like(n: int, seed: int, stream: int, start: int = 0, dim: int = 256,
     return out
 
 
+def sift_like_torch(n: int, seed: int, stream: int, start: int = 0, dim: int = 128, n_centres: int = 100,
+                    sigma: float = 15.0, device="cuda"):
+    """Same recipe as `sift_like`, drawn on `device` with torch's generator (one generator per
+    chunk, seeded from (seed, stream, chunk)); for databases too large to generate on the host.
+    The draws differ from the numpy stream of `sift_like`; centres are the same."""
+    import torch
+
+    centres = torch.from_numpy(mixture_centres(seed, n_centres, dim, "uniform100").astype(np.float32)).to(device)
+    out = torch.empty((n, dim), dtype=torch.float32, device=device)
+    for c, lo, take, off in _chunks(start, n):
+        g = torch.Generator(device=device)
+        g.manual_seed((seed * 1_000_003 + stream) * 1_000_003 + c)
+        comp = torch.randint(0, n_centres, (CHUNK,), generator=g, device=device)
+        noise = torch.randn((CHUNK, dim), generator=g, device=device, dtype=torch.float32)
+        v = centres[comp[lo:lo + take]] + sigma * noise[lo:lo + take]
+        out[off:off + take] = v.clamp_(0.0, 255.0).round_()
+    return out
+
+
 def random_codes(n: int, nbytes: int, seed: int, start: int = 0) -> np.ndarray:
     """Uniformly random byte codes, uint8 [n, nbytes] (every bit fair and independent)."""
     out = np.empty((n, nbytes), dtype=np.uint8)
