@@ -28,9 +28,10 @@ PEAK_INT_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # popcount-accumulate, plus one compare against the threshold.
 OPS_PER_PAIR = {8: 5, 16: 9}
 
-# HBM traffic per scan launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see
-# profiles/), keyed by (workload, ht); None until measured.
-MEASURED_TRAFFIC_BYTES = {}
+# Bytes per scan launch between L2 and the memory fabric, measured with rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE (two runs, scaled by what the same counters read for a 1 GiB copy:
+# x2.0 and x1.0), see profiles/scan_kernel_flat64_ht24.md; keyed by (workload, ht).
+MEASURED_TRAFFIC_BYTES = {("flat64", 24): 7.353e9 + 24.3e6}
 
 
 def log(*a):
@@ -203,7 +204,7 @@ def main():
         "roofline": {"bound": "alu", "kernel": "scan_kernel<8,16,16>", "achieved": achieved,
                      "peak": PEAK_INT_TOPS, "unit": "TOP/s (int32 lane-ops)", "frac": achieved / PEAK_INT_TOPS,
                      "ops_per_pair": OPS_PER_PAIR[m], "kernel_ms": scan_ms,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(("flat64", args.ht))},
+                     "traffic": None if args.small else MEASURED_TRAFFIC_BYTES.get(("flat64", args.ht))},
         "cpu_baseline": cpu,
         "sweep": sweep,
         "paper_context": {"adc_evals_per_s_per_core": 222e6, "hamming_evals_per_s_per_core": 1.19e9,
