@@ -13,7 +13,7 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libpsc.so")
+_LIB_PATH = os.environ.get("PSC_LIB_PATH") or os.path.join(_HERE, "libpsc.so")
 _lib = None
 
 PSC_MAX_K = 1024

@@ -32,15 +32,17 @@ def is_stale() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(force: bool = True, extra=()) -> str:
-    if not force and not is_stale():
+def build(force: bool = True, extra=(), out: str = LIB, replace: dict | None = None) -> str:
+    """Compile every source in csrc/ into one shared library.  `out` / `replace` (source file
+    name -> other path) build a variant next to the product library, for A/B experiments."""
+    if not force and out == LIB and not is_stale():
         return LIB
     cmd = [HIPCC] + FLAGS + list(extra)
     for s in sources():
-        cmd += ["-x", "hip", s]
-    cmd += ["-o", LIB, "-lpthread"]
+        cmd += ["-x", "hip", (replace or {}).get(os.path.basename(s), s)]
+    cmd += ["-o", out, "-lpthread"]
     subprocess.run(cmd, check=True)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

@@ -125,7 +125,8 @@ struct Lds {
     lds_vi32 *cnt;   // [TQ] entries in the list
     lds_i32 *lock;   // [TQ]
     lds_u32 *queue;  // [nwaves][kQueueCap]; private to a wave: LDS keeps a wave's accesses in order
-    __device__ __forceinline__ Lds(PSC_LDS unsigned char *base, int kpad)
+    lds_u32 *dump;   // [nwaves][64] where lanes with nothing to queue write
+    __device__ __forceinline__ Lds(PSC_LDS unsigned char *base, int kpad, int nwaves)
     {
         lut = (lds_f32 *)base;
         top = (lds_vu64 *)(lut + TQ * M * 256);
@@ -133,6 +134,7 @@ struct Lds {
         cnt = (lds_vi32 *)(thr + TQ);
         lock = (lds_i32 *)(cnt + TQ);
         queue = (lds_u32 *)(lock + TQ);
+        dump = queue + nwaves * kQueueCap;
     }
 };
 
@@ -299,7 +301,7 @@ __global__ void __launch_bounds__(NW * 64)
 scan_kernel(ScanArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    const Lds<M, TQ> s((PSC_LDS unsigned char *)smem, a.kpad);
+    const Lds<M, TQ> s((PSC_LDS unsigned char *)smem, a.kpad, NW);
     constexpr int WPC = M / 4;       // 32-bit words per code
     constexpr int CB = 32 / TQ;      // codes per lane and block: one survivor bit per (code, query)
     constexpr int NLD = CB * M / 16; // 16-byte loads per lane and block
@@ -419,53 +421,96 @@ scan_kernel(ScanArgs a)
         }
     };
 
-    uint32_t cur[CB * WPC];
-    if (wave_first < slice_end) load_block(lane_ptr, wave_first, wave_first + 64 * CB <= slice_end, cur);
-    // (codes between slice_begin and valid_begin are readable -- they belong to the previous list --
-    //  and are masked off below)
-    for (int64_t blk = wave_first; blk < slice_end; blk += stride) {
-        const bool whole = blk + 64 * CB <= slice_end && blk >= valid_begin;
-        uint32_t nxt[CB * WPC];
-        lane_ptr += stride * M;
-        if (blk + stride < slice_end)
-            load_block(lane_ptr, blk + stride, blk + stride + 64 * CB <= slice_end, nxt);
-
-        // ---- Hamming filter: bit c*TQ + (TQ-1-q) of `far` <=> code c is too far from query q
-        uint32_t far = 0u;
+    // A wave works on U of its blocks per turn of the main loop ("super-block"): all U filters run
+    // back to back (pure VALU) with the U next blocks already asked for, and only then are the U
+    // survivor masks queued one after the other -- so a wave waits for memory once per U blocks.
+    // (Codes between slice_begin and valid_begin are readable -- they belong to the previous list
+    //  -- and are masked off.)
+    constexpr int U = (CB * WPC <= 4) ? 4 : (CB * WPC <= 16 ? 2 : 1);
+    const int64_t sstride = stride * U;
+    uint32_t cur[U][CB * WPC];
 #pragma unroll
-        for (int c = CB - 1; c >= 0; --c) {
+    for (int u = 0; u < U; ++u) {
+        const int64_t b = wave_first + u * stride;
+        if (b < slice_end) load_block(lane_ptr + u * stride * M, b, b + 64 * CB <= slice_end, cur[u]);
+    }
+    // Lanes without a survivor in a turn write to a private dump word instead of being masked
+    // off: cheaper than switching the execution mask twice per turn.
+    const uint32_t dump_addr = (uint32_t)(uintptr_t)(s.dump + wave * 64 + lane);
+    for (int64_t sb = wave_first; sb < slice_end; sb += sstride) {
+        // ---- Hamming filter: bit c*TQ + (TQ-1-q) of a mask <=> code c is within ht of query q
+        uint32_t svs[U];
 #pragma unroll
-            for (int q = 0; q < TQ; ++q) {
-                uint32_t acc = bias;
+        for (int u = 0; u < U; ++u) {
+            const int64_t blk = sb + u * stride;
+            uint32_t far = 0u;
 #pragma unroll
-                for (int w = 0; w < WPC; ++w) acc += (uint32_t)__popc(cur[c * WPC + w] ^ qw[q][w]);
-                far = __builtin_amdgcn_alignbit(far, acc, 31);
+            for (int c = CB - 1; c >= 0; --c) {
+#pragma unroll
+                for (int q = 0; q < TQ; ++q) {
+                    uint32_t acc = bias;
+#pragma unroll
+                    for (int w = 0; w < WPC; ++w) acc += (uint32_t)__popc(cur[u][c * WPC + w] ^ qw[q][w]);
+                    far = __builtin_amdgcn_alignbit(far, acc, 31);
+                }
             }
+            uint32_t valid = qmask_all;
+            if (!(blk + 64 * CB <= slice_end && blk >= valid_begin)) {  // ragged or absent block
+                valid = 0u;
+#pragma unroll
+                for (int c = 0; c < CB; ++c) {
+                    const int64_t p = blk + (int64_t)lane * CB + c;
+                    valid |= (p < slice_end && p >= valid_begin) ? (qmask << (c * TQ)) : 0u;
+                }
+            }
+            svs[u] = ~far & valid;
+        }
+        // ---- ask for the next super-block
+        lane_ptr += sstride * M;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t b = sb + sstride + u * stride;
+            if (b < slice_end) load_block(lane_ptr + u * stride * M, b, b + 64 * CB <= slice_end, cur[u]);
         }
         // ---- survivors -> queue (one entry per lane and turn), full wavefronts -> ADC
-        uint32_t valid = qmask_all;
-        if (!whole) {
-            valid = 0u;
-#pragma unroll
-            for (int c = 0; c < CB; ++c)
-                valid |= (blk + (int64_t)lane * CB + c < slice_end && blk + (int64_t)lane * CB + c >= valid_begin)
-                             ? (qmask << (c * TQ))
-                             : 0u;
-        }
-        uint32_t sv = ~far & valid;
-        const uint32_t rel0 = (uint32_t)(blk - slice_begin) + (uint32_t)lane * CB;
-        while (true) {
-            const bool has = sv != 0u;
-            const uint64_t bal = ballot64(has);
-            if (bal == 0) break;
-            if (has) {
-                const uint32_t b = (uint32_t)__builtin_ctz(sv);
-                const uint32_t at = (uint32_t)__builtin_amdgcn_readfirstlane((int)(ring_base + 4u * (uint32_t)fill));
-                *(lds_u32 *)(uintptr_t)(at + 4u * (uint32_t)prefix_count(bal)) = (b << kRelBits) | rel0;
-            }
-            sv &= sv - 1u;  // drops the bit just queued (zero stays zero)
-            fill += __builtin_popcountll(bal);
-            if (fill >= 64) {
+        uint32_t rel0 = (uint32_t)(sb - slice_begin) + (uint32_t)lane * CB;
+#pragma nounroll
+        for (int u = 0; u < U; ++u) {
+            uint32_t sv = svs[0];
+            while (true) {
+                // Queue one survivor bit per lane and turn until no lane has bits left or 64 entries
+                // wait.  Hand-scheduled: the compiler's version of this loop spends more scalar
+                // instructions on loop control than vector instructions on the work, and every
+                // instruction of a wave costs an issue slot.  Per turn: the lanes with a bit are
+                // counted (vcc), each takes slot fill + (number of such lanes below it), writes
+                // (bit number << kRelBits) | position, and clears that bit; lanes without a bit
+                // write to their dump word.  `base` = byte address of queue slot `fill`.
+                uint32_t base = ring_base + 4u * (uint32_t)fill, t0, t1, n;
+                asm volatile(
+                    "1:\n\t"
+                    "v_cmp_ne_u32_e32 vcc, 0, %[sv]\n\t"
+                    "s_cbranch_vccz 2f\n\t"
+                    "v_mbcnt_lo_u32_b32 %[t0], vcc_lo, 0\n\t"
+                    "v_mbcnt_hi_u32_b32 %[t0], vcc_hi, %[t0]\n\t"
+                    "v_ffbl_b32_e32 %[t1], %[sv]\n\t"
+                    "v_lshl_add_u32 %[t0], %[t0], 2, %[base]\n\t"
+                    "v_lshl_or_b32 %[t1], %[t1], 27, %[rel0]\n\t"
+                    "v_cndmask_b32_e32 %[t0], %[dump], %[t0], vcc\n\t"
+                    "ds_write_b32 %[t0], %[t1]\n\t"
+                    "s_bcnt1_i32_b64 %[n], vcc\n\t"
+                    "v_add_u32_e32 %[t0], -1, %[sv]\n\t"
+                    "s_lshl2_add_u32 %[base], %[n], %[base]\n\t"
+                    "v_and_b32_e32 %[sv], %[sv], %[t0]\n\t"
+                    "s_add_i32 %[fill], %[fill], %[n]\n\t"
+                    "s_cmp_lt_i32 %[fill], 64\n\t"
+                    "s_cbranch_scc1 1b\n\t"
+                    "2:"
+                    : [sv] "+v"(sv), [fill] "+s"(fill), [base] "+s"(base), [t0] "=&v"(t0), [t1] "=&v"(t1),
+                      [n] "=&s"(n)
+                    : [rel0] "v"(rel0), [dump] "v"(dump_addr)
+                    : "vcc", "scc", "memory");
+                static_assert(kRelBits == 27, "the shift in the queueing loop");
+                if (fill < 64) break;  // every lane is out of bits
                 __builtin_amdgcn_wave_barrier();
                 drain<M, TQ, IVF, SHARE>(s, a, ring, 64, slice_begin, q0);
                 // entries 64..fill-1 move to the front
@@ -476,9 +521,11 @@ scan_kernel(ScanArgs a)
                 if (lane < fill) ring[lane] = e;
                 __builtin_amdgcn_wave_barrier();
             }
-        }
+            // next mask of the super-block moves into place
 #pragma unroll
-        for (int e = 0; e < CB * WPC; ++e) cur[e] = nxt[e];
+            for (int v = 0; v + 1 < U; ++v) svs[v] = svs[v + 1];
+            rel0 += (uint32_t)stride;
+        }
     }
     if (fill > 0) {
         __builtin_amdgcn_wave_barrier();
@@ -668,7 +715,7 @@ int plan_scan(int m, int64_t nq, int64_t n, int k, ScanPlan *plan)
         if (t > tq_cap) continue;
         if (m == 16 && t == 16) continue;  // 16 tables of 16 KiB do not fit
         size_t need = (size_t)t * m * 256 * 4 + (size_t)t * p.kpad * 8 + (size_t)t * 12 +
-                      (size_t)p.nwaves * kQueueCap * 4;
+                      (size_t)p.nwaves * (kQueueCap + 64) * 4;
         if (need <= kLdsBudget) {
             p.tq = t;
             p.lds_bytes = need;
