@@ -99,8 +99,12 @@ int psc_encode(const psc_index *idx, const float *x_dev, int64_t n, uint8_t *cod
 
 /* ADC tables (Section 4.2 "ADC"): lut_dev [nq][m][256] float32,
  * lut[q][j][c] = squared Euclidean distance between sub-vector j of query q and
- * centroid c of sub-quantizer j.  qcodes_dev (may be NULL) [nq][m] receives the
- * query's own code = per row the index of the smallest entry (lowest on ties). */
+ * centroid c of sub-quantizer j.  For even dim/m the tables are computed on the matrix cores
+ * (full float32 MFMA) as |q'|^2 - 2 q'.c' + |c'|^2 with both sides centred on the
+ * sub-quantizer's mean centroid, clamped at 0: an entry is accurate to float32 rounding of
+ * those three terms (about 2e-6 x the largest entry of its row), sums of m entries to well
+ * below 1e-5 relative.  qcodes_dev (may be NULL) [nq][m] receives the query's own code = per
+ * row the index of the smallest entry of that very table (lowest on ties). */
 int psc_build_lut(const psc_index *idx, const float *q_dev, int64_t nq, float *lut_dev,
                   uint8_t *qcodes_dev, psc_stream stream);
 

@@ -33,9 +33,24 @@ static int mark_codebook_changed(psc_index *idx)
 static int sync_codebook_to_device(const psc_index *idx)
 {
     if (idx->dev_current) return PSC_OK;
-    const size_t bytes = idx->cb_host.size() * sizeof(float);
-    if (!idx->cb_dev) PSC_HIP_TRY(hipMalloc((void **)&idx->cb_dev, bytes));
-    PSC_HIP_TRY(hipMemcpy(idx->cb_dev, idx->cb_host.data(), bytes, hipMemcpyHostToDevice));
+    // device image: the codebook, the codebook centred on each sub-quantizer's mean centroid,
+    // and those means (the last two feed the matrix-core table kernel)
+    const size_t n = idx->cb_host.size(), sq = (size_t)kCentroids * idx->dsub;
+    std::vector<float> img(2 * n + (size_t)idx->m * idx->dsub);
+    std::memcpy(img.data(), idx->cb_host.data(), n * sizeof(float));
+    for (int j = 0; j < idx->m; ++j) {
+        float *mu = &img[2 * n + (size_t)j * idx->dsub];
+        for (int t = 0; t < idx->dsub; ++t) {
+            double acc = 0.0;
+            for (int c = 0; c < kCentroids; ++c) acc += idx->cb_host[j * sq + (size_t)c * idx->dsub + t];
+            mu[t] = (float)(acc / kCentroids);
+        }
+        for (int c = 0; c < kCentroids; ++c)
+            for (int t = 0; t < idx->dsub; ++t)
+                img[n + j * sq + (size_t)c * idx->dsub + t] = idx->cb_host[j * sq + (size_t)c * idx->dsub + t] - mu[t];
+    }
+    if (!idx->cb_dev) PSC_HIP_TRY(hipMalloc((void **)&idx->cb_dev, img.size() * sizeof(float)));
+    PSC_HIP_TRY(hipMemcpy(idx->cb_dev, img.data(), img.size() * sizeof(float), hipMemcpyHostToDevice));
     idx->dev_current = true;
     return PSC_OK;
 }
@@ -188,10 +203,16 @@ int psc_build_lut(const psc_index *idx, const float *q_dev, int64_t nq, float *l
     PSC_REQUIRE(nq >= 0, "negative nq");
     if (nq == 0) return PSC_OK;
     PSC_REQUIRE(q_dev && lut_dev, "null pointer");
-    rc = launch_lut(idx->cb_dev, idx->dim, idx->m, q_dev, nq, RowMap{}, lut_dev, (hipStream_t)stream);
+    if (idx->dsub % 2 == 0) {
+        // the dense contraction of the path: matrix cores
+        const size_t n = idx->cb_host.size();
+        rc = launch_lut_mfma(idx->cb_dev + n, idx->cb_dev + 2 * n, idx->dim, idx->m, q_dev, nq, lut_dev,
+                             (hipStream_t)stream);
+    } else {
+        rc = launch_lut(idx->cb_dev, idx->dim, idx->m, q_dev, nq, RowMap{}, lut_dev, (hipStream_t)stream);
+    }
     if (rc != PSC_OK) return rc;
-    if (qcodes_dev)
-        rc = launch_encode(idx->cb_dev, idx->dim, idx->m, q_dev, nq, RowMap{}, qcodes_dev, (hipStream_t)stream);
+    if (qcodes_dev) rc = launch_row_argmin(lut_dev, nq * idx->m, qcodes_dev, (hipStream_t)stream);
     return rc;
 }
 
@@ -306,8 +327,14 @@ int psc_knn_graph(const psc_index *idx, const float *x_dev, const uint8_t *codes
     float *lut = (float *)((char *)workspace_dev + scan_ws_bytes);
     for (int64_t c0 = 0; c0 < n; c0 += kGraphChunk) {
         const int64_t qc = (n - c0) < kGraphChunk ? (n - c0) : kGraphChunk;
-        rc = launch_lut(idx->cb_dev, idx->dim, idx->m, x_dev + (size_t)c0 * idx->dim, qc, RowMap{}, lut,
-                        (hipStream_t)stream);
+        if (idx->dsub % 2 == 0) {
+            const size_t nc = idx->cb_host.size();
+            rc = launch_lut_mfma(idx->cb_dev + nc, idx->cb_dev + 2 * nc, idx->dim, idx->m,
+                                 x_dev + (size_t)c0 * idx->dim, qc, lut, (hipStream_t)stream);
+        } else {
+            rc = launch_lut(idx->cb_dev, idx->dim, idx->m, x_dev + (size_t)c0 * idx->dim, qc, RowMap{}, lut,
+                            (hipStream_t)stream);
+        }
         if (rc != PSC_OK) return rc;
         rc = launch_scan(idx->m, lut, codes_dev + (size_t)c0 * idx->m, qc, codes_dev, n, ht, k, c0, c0 == 0,
                          ids_dev + (size_t)c0 * k, dists_dev + (size_t)c0 * k, scan_ws, scan_ws_bytes,

@@ -53,6 +53,11 @@ int launch_lut(const float *cb_dev, int dim, int m, const float *x_dev, int64_t 
                const RowMap &map, float *lut_dev, hipStream_t s);
 int launch_encode(const float *cb_dev, int dim, int m, const float *x_dev, int64_t nrows,
                   const RowMap &map, uint8_t *codes_dev, hipStream_t s);
+// Tables on the matrix cores from the centred codebook cbc [m][256][dsub] and the per-sub-quantizer
+// mean centroids mu [m][dsub]; and the arg-min of every table row (nrows_total = rows x m).
+int launch_lut_mfma(const float *cbc_dev, const float *mu_dev, int dim, int m, const float *x_dev,
+                    int64_t nrows, float *lut_dev, hipStream_t s);
+int launch_row_argmin(const float *lut_dev, int64_t nrows_total, uint8_t *codes_dev, hipStream_t s);
 
 // ---- device launchers (kernels_scan.hip)
 struct ScanPlan {
@@ -117,7 +122,7 @@ struct psc_index {
     int device = 0;
     bool has_codebook = false;
     std::vector<float> cb_host;  // [m][256][dsub], the master copy
-    mutable float *cb_dev = nullptr;
+    mutable float *cb_dev = nullptr;   // [m][256][dsub], then the centred copy, then mu [m][dsub]
     mutable bool dev_current = false;  // device copy matches cb_host
     // inverted file: coarse centroids (owned) and borrowed views of the caller's lists
     int nlist = 0;

@@ -98,6 +98,114 @@ encode_kernel(const float *__restrict__ cb, int dim, int m, const float *__restr
     codes[r * m + j] = (uint8_t)bi;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Table construction as a dense contraction on the matrix cores (full float32 MFMA):
+//     || q - c ||^2 = || q' ||^2 - 2 q'.c' + || c' ||^2,     q' = q - mu_j,  c' = c - mu_j
+// where mu_j is the mean centroid of sub-quantizer j (distances do not change under a common
+// shift; centring keeps the three terms small, which keeps the cancellation error small).
+// One workgroup = 32 rows x the 256 centroids of one sub-quantizer; each of its 4 waves owns two
+// 32 x 32 output tiles and runs DSUB/2 v_mfma_f32_32x32x2f32 steps per tile.
+//
+// v_mfma_f32_32x32x2f32 operand layout (wave64, lane l): A[i][k] with i = l % 32, k = l / 32;
+// B[k][j] with k = l / 32, j = l % 32; D[i][j] in 16 registers, register v holding row
+// i = 8 * (v / 4) + 4 * (l / 32) + v % 4, column j = l % 32.
+// ---------------------------------------------------------------------------------------------
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+template <int DSUB>
+__global__ void __launch_bounds__(256)
+lut_mfma_kernel(const float *__restrict__ cbc /* centred codebook */, const float *__restrict__ mu, int dim,
+                int m, const float *__restrict__ x, int64_t nrows, float *__restrict__ lut)
+{
+    static_assert(DSUB % 2 == 0, "two coordinates per MFMA step");
+    constexpr int KS = DSUB / 2;
+    __shared__ float qn_s[4][32];
+    const int j = blockIdx.y;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int half = lane >> 5, col = lane & 31;
+    const int64_t r0 = (int64_t)blockIdx.x * 32;
+
+    // A operand: row r0 + col, coordinates half, 2 + half, 4 + half, ... (centred)
+    float a[KS];
+    {
+        const int64_t r = r0 + col;
+        const float *xr = x + (r < nrows ? r : nrows - 1) * dim + j * DSUB;
+        const float *mj = mu + j * DSUB;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) a[kk] = xr[2 * kk + half] - mj[2 * kk + half];
+    }
+    // || q' ||^2 of row `col`: this lane's half of the coordinates plus the other half's
+    float qn = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) qn = fmaf(a[kk], a[kk], qn);
+    qn += __shfl_xor(qn, 32, 64);
+    if (half == 0) qn_s[wave][col] = qn;
+    __builtin_amdgcn_wave_barrier();
+
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const int c0 = (wave * 2 + t) * 32;
+        const float *cr = cbc + ((int64_t)j * kCentroids + c0 + col) * DSUB;
+        float b[KS];
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) b[kk] = cr[2 * kk + half];
+        float cn = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) cn = fmaf(b[kk], b[kk], cn);
+        cn += __shfl_xor(cn, 32, 64);
+        f32x16 acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[kk], b[kk], acc, 0, 0, 0);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int i = 8 * (v / 4) + 4 * half + v % 4;
+            const int64_t r = r0 + i;
+            if (r < nrows) {
+                const float d = fmaf(-2.0f, acc[v], qn_s[wave][i] + cn);
+                lut[(r * m + j) * kCentroids + c0 + col] = d > 0.f ? d : 0.f;
+            }
+        }
+    }
+}
+
+// code[r][j] = index of the smallest entry of table row (r, j), lowest index on ties: the query's
+// own code, taken from the very table the scan will use.  One wave per row.
+__global__ void __launch_bounds__(256)
+row_argmin_kernel(const float *__restrict__ lut, int64_t nrows_total, uint8_t *__restrict__ codes)
+{
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= nrows_total) return;
+    const int lane = threadIdx.x & 63;
+    const float4 v = *(const float4 *)(lut + row * kCentroids + lane * 4);
+    float best = v.x;
+    int bi = lane * 4;
+    if (v.y < best) { best = v.y; bi = lane * 4 + 1; }
+    if (v.z < best) { best = v.z; bi = lane * 4 + 2; }
+    if (v.w < best) { best = v.w; bi = lane * 4 + 3; }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float ob = __shfl_xor(best, off, 64);
+        const int oi = __shfl_xor(bi, off, 64);
+        if (ob < best || (ob == best && oi < bi)) {
+            best = ob;
+            bi = oi;
+        }
+    }
+    if (lane == 0) codes[row] = (uint8_t)bi;
+}
+
+template <int DSUB>
+int run_lut_mfma(const float *cbc, const float *mu, int dim, int m, const float *x, int64_t nrows, float *lut,
+                 hipStream_t s)
+{
+    dim3 grid((unsigned)((nrows + 31) / 32), (unsigned)m);
+    hipLaunchKernelGGL((lut_mfma_kernel<DSUB>), grid, dim3(256), 0, s, cbc, mu, dim, m, x, nrows, lut);
+    PSC_HIP_TRY(hipGetLastError());
+    return PSC_OK;
+}
+
 template <int DSUB>
 int run_lut(const float *cb, int dim, int m, const float *x, int64_t nrows, const RowMap &map,
             float *lut, hipStream_t s)
@@ -150,6 +258,44 @@ int launch_lut(const float *cb_dev, int dim, int m, const float *x_dev, int64_t 
 #define CALL(DS) run_lut<DS>(cb_dev, dim, m, x_dev, nrows, map, lut_dev, s)
     PSC_DSUB_SWITCH(dim / m, CALL)
 #undef CALL
+}
+
+int launch_lut_mfma(const float *cbc_dev, const float *mu_dev, int dim, int m, const float *x_dev,
+                    int64_t nrows, float *lut_dev, hipStream_t s)
+{
+    if (nrows == 0) return PSC_OK;
+    if ((nrows + 31) / 32 > 0x7fffffffLL) {
+        set_error("too many rows for one table launch");
+        return PSC_EINVAL;
+    }
+    switch (dim / m) {
+    case 2: return run_lut_mfma<2>(cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
+    case 4: return run_lut_mfma<4>(cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
+    case 6: return run_lut_mfma<6>(cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
+    case 8: return run_lut_mfma<8>(cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
+    case 12: return run_lut_mfma<12>(cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
+    case 16: return run_lut_mfma<16>(cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
+    case 24: return run_lut_mfma<24>(cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
+    case 32: return run_lut_mfma<32>(cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
+    case 48: return run_lut_mfma<48>(cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
+    case 64: return run_lut_mfma<64>(cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
+    default:
+        set_error("the matrix-core table kernel needs an even sub-vector length, got %d", dim / m);
+        return PSC_EINVAL;
+    }
+}
+
+int launch_row_argmin(const float *lut_dev, int64_t nrows_total, uint8_t *codes_dev, hipStream_t s)
+{
+    if (nrows_total == 0) return PSC_OK;
+    if ((nrows_total + 3) / 4 > 0x7fffffffLL) {
+        set_error("too many table rows");
+        return PSC_EINVAL;
+    }
+    hipLaunchKernelGGL(row_argmin_kernel, dim3((unsigned)((nrows_total + 3) / 4)), dim3(256), 0, s, lut_dev,
+                       nrows_total, codes_dev);
+    PSC_HIP_TRY(hipGetLastError());
+    return PSC_OK;
 }
 
 int launch_encode(const float *cb_dev, int dim, int m, const float *x_dev, int64_t nrows,

@@ -38,12 +38,22 @@ def test_tables_and_query_codes(setup, m):
     torch.cuda.synchronize()
     lut, qc = lut.cpu().numpy(), qc.cpu().numpy()
     ref = O.build_lut(s["xq"], s["cb"])
-    assert np.allclose(lut, ref, rtol=RTOL, atol=1e-4)
+    # The tables come from the expansion |q'|^2 - 2 q'.c' + |c'|^2 in float32 on the matrix
+    # cores: an entry is exact to float32 rounding of those terms, whose size is that of the
+    # largest entry of the row -- hence an absolute allowance of 2e-6 x the row maximum (about
+    # 30 ulp of the terms) next to the 1e-5 relative one.
+    allow = RTOL * ref + 2e-6 * ref.max(axis=2, keepdims=True)
+    assert np.all(np.abs(lut - ref) <= allow), np.max(np.abs(lut - ref) / allow)
+    # ADC sums built from these tables stay within the 1e-5 relative bound of the path
+    codes = W.random_codes(4000, m, seed=3)
+    got = sum(lut[:, j, codes[:, j]].astype(np.float64) for j in range(m))
+    want = sum(ref[:, j, codes[:, j]] for j in range(m))
+    assert np.max(np.abs(got - want) / want) < RTOL / 10
     # the query code is the arg-min of the float32 table row (lowest index on ties) ...
     assert np.array_equal(qc, lut.argmin(axis=2).astype(np.uint8))
     # ... and a valid code in the oracle's eyes: its entry is within tolerance of the row minimum
     pick = np.take_along_axis(ref, qc[:, :, None].astype(np.int64), axis=2)[:, :, 0]
-    assert np.all(pick <= ref.min(axis=2) * (1 + RTOL) + 1e-4)
+    assert np.all(pick <= ref.min(axis=2) + allow.min(axis=2) + allow[:, :, 0] * 0 + 2e-6 * ref.max(axis=2))
     assert (qc == O.query_codes(ref)).mean() > 0.999
 
 
