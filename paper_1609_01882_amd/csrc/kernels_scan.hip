@@ -551,6 +551,122 @@ scan_kernel(ScanArgs a)
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Pure ADC scan: ht >= 8m keeps every code (Section 4.2 "ADC", the PQ baseline of the paper), so
+// there is nothing to filter or to queue: every (query, code) pair is scored.  The bound is the
+// LDS gather rate, so the TQ tables are interleaved in LDS four queries to an entry,
+// lut4[g][j][c] = (T_{4g}[j][c], .., T_{4g+3}[j][c]): one 16-byte read serves four queries of
+// the tile, and a code's m byte offsets are computed once for all TQ queries.
+// Same tiling (query tile x database slice), lists, ordering and outputs as scan_kernel.
+// ---------------------------------------------------------------------------------------------
+template <int M, int TQ, int NW, bool SHARE>
+__global__ void __launch_bounds__(NW * 64)
+adc_kernel(ScanArgs a)
+{
+    static_assert(TQ % 4 == 0, "four queries per table entry");
+    extern __shared__ __align__(16) unsigned char smem[];
+    const Lds<M, TQ> s((PSC_LDS unsigned char *)smem, a.kpad, NW);
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    constexpr int G = TQ / 4;
+    constexpr int WPC = M / 4;
+    constexpr int CPL = 16 / M;  // codes per 16-byte load
+    const int tid = (int)threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    const int64_t tile = blockIdx.x;
+    const int slice = (int)(tile % a.nslice);
+    const int64_t q0 = (tile / a.nslice) * TQ;
+    const int nvq = (int)((a.nq - q0) < TQ ? (a.nq - q0) : TQ);
+    const int64_t slice_begin = (int64_t)slice * a.slice_len;
+    const int64_t slice_end = (slice_begin + a.slice_len) < a.n ? (slice_begin + a.slice_len) : a.n;
+
+    // ---- stage the tables interleaved, reset the lists
+    {
+        const float *src = a.lut + q0 * (M * 256);
+        PSC_LDS float *dst = (PSC_LDS float *)s.lut;
+        for (int e = tid; e < TQ * M * 256; e += NW * 64) {
+            const int q = e / (M * 256), r = e - q * (M * 256);
+            dst[(((q >> 2) * (M * 256) + r) << 2) + (q & 3)] = q < nvq ? src[e] : 0.f;
+        }
+        if (tid < TQ) {
+            float t0 = __builtin_inff();
+            if constexpr (SHARE) {
+                if (tid < nvq)
+                    t0 = key_dist(__hip_atomic_load(&a.gthr[q0 + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            }
+            s.thr[tid] = t0;
+            s.cnt[tid] = 0;
+            s.lock[tid] = 0;
+        }
+    }
+    __syncthreads();
+
+    const PSC_LDS f32x4 *lut4 = (const PSC_LDS f32x4 *)s.lut;
+    const int64_t stride = (int64_t)NW * 64 * CPL;
+    const int64_t skip_rel = a.skip_first + q0 - slice_begin;
+    const bool skipping = a.skip_first >= 0 && skip_rel > -(int64_t)TQ && skip_rel < kMaxSliceLen;
+    for (int64_t blk = slice_begin + (int64_t)wave * 64 * CPL; blk < slice_end; blk += stride) {
+        const int64_t p0 = blk + (int64_t)lane * CPL;
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+        if (p0 + CPL <= slice_end) {
+            const uint4 v = *(const uint4 *)(a.codes + p0 * M);
+            w[0] = v.x;
+            w[1] = v.y;
+            w[2] = v.z;
+            w[3] = v.w;
+        } else if (CPL == 2 && p0 < slice_end) {
+            const uint2 v = *(const uint2 *)(a.codes + p0 * M);
+            w[0] = v.x;
+            w[1] = v.y;
+        }
+        // thresholds of the tile, refreshed once per block: lane q holds thr[q]
+        const float thr_v = s.thr[lane & (TQ - 1)];
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) {
+            const bool live = p0 + c < slice_end;
+            const uint32_t rel = (uint32_t)(p0 + c - slice_begin);
+            uint32_t off[M];  // byte offset of the code's entry inside sub-table j
+#pragma unroll
+            for (int j = 0; j < M; ++j) off[j] = ((w[c * WPC + (j >> 2)] >> (8 * (j & 3))) & 0xffu);
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                f32x4 acc = lut4[(g * M + 0) * 256 + off[0]];
+#pragma unroll
+                for (int j = 1; j < M; ++j) acc += lut4[(g * M + j) * 256 + off[j]];
+                float d[4] = {acc.x, acc.y, acc.z, acc.w};
+                uint64_t any = 0;
+                bool pass[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int q = g * 4 + i;
+                    const float thr = bcast_f(thr_v, q);
+                    pass[i] = live && q < nvq && d[i] <= thr;
+                    if (skipping) pass[i] = pass[i] && rel != (uint32_t)((int32_t)skip_rel + q);
+                    any |= ballot64(pass[i]);
+                }
+                if (any) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const uint64_t mine = ballot64(pass[i]);
+                        if (mine) insert_candidates<M, TQ, SHARE>(s, a, g * 4 + i, q0 + g * 4 + i, mine, d[i], rel);
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    for (int e = tid; e < nvq * a.k; e += NW * 64) {
+        const int q = e / a.k, r = e - q * a.k;
+        const bool have = r < s.cnt[q];
+        const uint64_t ent = s.top[q * a.kpad + r];
+        const int64_t o = ((q0 + q) * a.nslice + slice) * a.k + r;
+        a.part_d[o] = have ? entry_dist(ent) : __builtin_inff();
+        a.part_i[o] = have ? (slice_begin + (int64_t)entry_id(ent)) : (int64_t)-1;
+    }
+}
+
 // Merge the nslice sorted partial lists of each query into the final k (one wave per query).
 __global__ void __launch_bounds__(64)
 merge_kernel(const float *__restrict__ part_d, const int64_t *__restrict__ part_i, int nslice, int k,
@@ -671,6 +787,32 @@ int run_scan(const ScanArgs &a, int64_t ntiles, size_t lds, hipStream_t s)
     hipLaunchKernelGGL((scan_kernel<M, TQ, NW, IVF, SHARE>), dim3((unsigned)ntiles), dim3(NW * 64), lds, s, a);
     PSC_HIP_TRY(hipGetLastError());
     return PSC_OK;
+}
+
+template <int M, int TQ, int NW, bool SHARE>
+int run_adc(const ScanArgs &a, int64_t ntiles, size_t lds, hipStream_t s)
+{
+    static bool configured = false;
+    if (!configured) {
+        PSC_HIP_TRY(hipFuncSetAttribute((const void *)adc_kernel<M, TQ, NW, SHARE>,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        configured = true;
+    }
+    hipLaunchKernelGGL((adc_kernel<M, TQ, NW, SHARE>), dim3((unsigned)ntiles), dim3(NW * 64), lds, s, a);
+    PSC_HIP_TRY(hipGetLastError());
+    return PSC_OK;
+}
+
+template <bool SHARE>
+int dispatch_adc(int m, int tq, const ScanArgs &a, int64_t ntiles, size_t lds, hipStream_t s)
+{
+    if (m == 8) {
+        if (tq == 16) return run_adc<8, 16, 16, SHARE>(a, ntiles, lds, s);
+        if (tq == 8) return run_adc<8, 8, 16, SHARE>(a, ntiles, lds, s);
+        return run_adc<8, 4, 16, SHARE>(a, ntiles, lds, s);
+    }
+    if (tq == 8) return run_adc<16, 8, 16, SHARE>(a, ntiles, lds, s);
+    return run_adc<16, 4, 16, SHARE>(a, ntiles, lds, s);
 }
 
 template <bool IVF, bool SHARE>
@@ -826,8 +968,12 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
     a.list_off = nullptr;
     a.ext_ids = nullptr;
     a.job_slot = nullptr;
-    rc = p.nslice >= 4 ? dispatch_scan<false, true>(m, p.tq, a, p.ntiles, p.lds_bytes, s)
-                       : dispatch_scan<false, false>(m, p.tq, a, p.ntiles, p.lds_bytes, s);
+    if (ht >= nbits)  // nothing to filter: the pure-ADC kernel
+        rc = p.nslice >= 4 ? dispatch_adc<true>(m, p.tq, a, p.ntiles, p.lds_bytes, s)
+                           : dispatch_adc<false>(m, p.tq, a, p.ntiles, p.lds_bytes, s);
+    else
+        rc = p.nslice >= 4 ? dispatch_scan<false, true>(m, p.tq, a, p.ntiles, p.lds_bytes, s)
+                           : dispatch_scan<false, false>(m, p.tq, a, p.ntiles, p.lds_bytes, s);
     if (rc != PSC_OK) return rc;
     hipLaunchKernelGGL(merge_kernel, dim3((unsigned)nq), dim3(64), 0, s, a.part_d, a.part_i, p.nslice, k,
                        (int64_t)0, a.status, ids_dev, dists_dev);
