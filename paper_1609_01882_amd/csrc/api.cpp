@@ -321,7 +321,6 @@ int psc_knn_graph(const psc_index *idx, const float *x_dev, const uint8_t *codes
                 need, workspace_bytes);
     PSC_REQUIRE(((uintptr_t)workspace_dev & 255) == 0, "workspace must be 256-byte aligned");
     // layout: [scan workspace for a full chunk (status word first)] [one chunk of tables]
-    const int64_t qc_max = n < kGraphChunk ? n : kGraphChunk;
     const size_t scan_ws_bytes = graph_scan_workspace(idx, n, k);
     char *scan_ws = (char *)workspace_dev;
     float *lut = (float *)((char *)workspace_dev + scan_ws_bytes);

@@ -626,7 +626,7 @@ adc_kernel(ScanArgs a)
         for (int c = 0; c < CPL; ++c) {
             const bool live = p0 + c < slice_end;
             const uint32_t rel = (uint32_t)(p0 + c - slice_begin);
-            uint32_t off[M];  // byte offset of the code's entry inside sub-table j
+            uint32_t off[M];  // the code's byte for sub-quantizer j = its entry in sub-table j
 #pragma unroll
             for (int j = 0; j < M; ++j) off[j] = ((w[c * WPC + (j >> 2)] >> (8 * (j & 3))) & 0xffu);
 #pragma unroll
@@ -851,8 +851,9 @@ int plan_scan(int m, int64_t nq, int64_t n, int k, ScanPlan *plan)
     p.nwaves = 16;
     const int tq_options[3] = {16, 8, 4};
     p.tq = 0;
-    int tq_cap = 16;
-    if (const char *e = getenv("PSC_TQ")) tq_cap = atoi(e);  // experiment knob
+    // small batches: no more query slots than queries (every slot costs filter work), which
+    // keeps a one-pass scan of few queries bound by memory bandwidth rather than by the ALUs
+    const int tq_cap = nq <= 4 ? 4 : (nq <= 8 ? 8 : 16);
     for (int t : tq_options) {
         if (t > tq_cap) continue;
         if (m == 16 && t == 16) continue;  // 16 tables of 16 KiB do not fit

@@ -50,6 +50,10 @@ def _run(psc, lut, qcodes, codes, ht, k):
     (16, 50_001, 19, 100, "int"),
     (8, 30_000, 3, 300, "int"),         # k > 128: smaller query tile
     (16, 20_000, 9, 1024, "float"),     # maximum k
+    (8, 60_001, 1, 100, "float"),       # small batches take narrower query tiles
+    (8, 45_003, 8, 10, "int"),
+    (16, 33_001, 2, 100, "int"),
+    (16, 40_001, 7, 10, "float"),
 ])
 def test_scan_random_codes(psc, m, n, nq, k, lut_kind):
     codes, qcodes, lut = _rand_problem(m, n, nq, seed=100 + m + k, lut_kind=lut_kind)
