@@ -558,8 +558,11 @@ scan_kernel(ScanArgs a)
 // lut4[g][j][c] = (T_{4g}[j][c], .., T_{4g+3}[j][c]): one 16-byte read serves four queries of
 // the tile, and a code's m byte offsets are computed once for all TQ queries.
 // Same tiling (query tile x database slice), lists, ordering and outputs as scan_kernel.
+// FILTER: the Hamming test of Section 3.1 is still applied, as one more condition on every pair.
+// This is the cheaper route when the threshold lets a large share of the codes through: scoring
+// everything from the interleaved tables then costs less than queueing the survivors one by one.
 // ---------------------------------------------------------------------------------------------
-template <int M, int TQ, int NW, bool SHARE>
+template <int M, int TQ, int NW, bool SHARE, bool FILTER>
 __global__ void __launch_bounds__(NW * 64)
 adc_kernel(ScanArgs a)
 {
@@ -598,6 +601,17 @@ adc_kernel(ScanArgs a)
             s.thr[tid] = t0;
             s.cnt[tid] = 0;
             s.lock[tid] = 0;
+        }
+    }
+    // ---- query codes -> scalar registers (only the filtering variant reads them)
+    uint32_t qw[TQ][WPC];
+    if constexpr (FILTER) {
+        const uint32_t *qc = (const uint32_t *)a.qcodes;
+#pragma unroll
+        for (int q = 0; q < TQ; ++q) {
+            const int64_t qq = (q < nvq) ? (q0 + q) : q0;
+#pragma unroll
+            for (int w = 0; w < WPC; ++w) qw[q][w] = __builtin_amdgcn_readfirstlane(qc[qq * WPC + w]);
         }
     }
     __syncthreads();
@@ -642,6 +656,12 @@ adc_kernel(ScanArgs a)
                     const int q = g * 4 + i;
                     const float thr = bcast_f(thr_v, q);
                     pass[i] = live && q < nvq && d[i] <= thr;
+                    if constexpr (FILTER) {  // bias + h overflows into the sign bit iff h > ht
+                        uint32_t acc = a.bias;
+#pragma unroll
+                        for (int ww = 0; ww < WPC; ++ww) acc += (uint32_t)__popc(w[c * WPC + ww] ^ qw[q][ww]);
+                        pass[i] = pass[i] && (int32_t)acc >= 0;
+                    }
                     if (skipping) pass[i] = pass[i] && rel != (uint32_t)((int32_t)skip_rel + q);
                     any |= ballot64(pass[i]);
                 }
@@ -789,30 +809,44 @@ int run_scan(const ScanArgs &a, int64_t ntiles, size_t lds, hipStream_t s)
     return PSC_OK;
 }
 
-template <int M, int TQ, int NW, bool SHARE>
+template <int M, int TQ, int NW, bool SHARE, bool FILTER>
 int run_adc(const ScanArgs &a, int64_t ntiles, size_t lds, hipStream_t s)
 {
     static bool configured = false;
     if (!configured) {
-        PSC_HIP_TRY(hipFuncSetAttribute((const void *)adc_kernel<M, TQ, NW, SHARE>,
+        PSC_HIP_TRY(hipFuncSetAttribute((const void *)adc_kernel<M, TQ, NW, SHARE, FILTER>,
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
         configured = true;
     }
-    hipLaunchKernelGGL((adc_kernel<M, TQ, NW, SHARE>), dim3((unsigned)ntiles), dim3(NW * 64), lds, s, a);
+    hipLaunchKernelGGL((adc_kernel<M, TQ, NW, SHARE, FILTER>), dim3((unsigned)ntiles), dim3(NW * 64), lds, s, a);
     PSC_HIP_TRY(hipGetLastError());
     return PSC_OK;
 }
 
-template <bool SHARE>
+template <bool SHARE, bool FILTER>
 int dispatch_adc(int m, int tq, const ScanArgs &a, int64_t ntiles, size_t lds, hipStream_t s)
 {
     if (m == 8) {
-        if (tq == 16) return run_adc<8, 16, 16, SHARE>(a, ntiles, lds, s);
-        if (tq == 8) return run_adc<8, 8, 16, SHARE>(a, ntiles, lds, s);
-        return run_adc<8, 4, 16, SHARE>(a, ntiles, lds, s);
+        if (tq == 16) return run_adc<8, 16, 16, SHARE, FILTER>(a, ntiles, lds, s);
+        if (tq == 8) return run_adc<8, 8, 16, SHARE, FILTER>(a, ntiles, lds, s);
+        return run_adc<8, 4, 16, SHARE, FILTER>(a, ntiles, lds, s);
     }
-    if (tq == 8) return run_adc<16, 8, 16, SHARE>(a, ntiles, lds, s);
-    return run_adc<16, 4, 16, SHARE>(a, ntiles, lds, s);
+    if (tq == 8) return run_adc<16, 8, 16, SHARE, FILTER>(a, ntiles, lds, s);
+    return run_adc<16, 4, 16, SHARE, FILTER>(a, ntiles, lds, s);
+}
+
+// Share of uniformly random b-bit codes within Hamming distance ht of a given one: what the
+// launcher goes by when it picks the kernel (real codes differ, but not by enough to matter for
+// a choice between two kernels that both give the same results).
+double random_code_survival(int nbits, int ht)
+{
+    double c = 1.0, sum = 0.0;  // c = C(nbits, i) / 2^nbits, built up stepwise
+    for (int i = 0; i < nbits; ++i) c *= 0.5;
+    for (int i = 0; i <= ht && i <= nbits; ++i) {
+        sum += c;
+        c = c * (double)(nbits - i) / (double)(i + 1);
+    }
+    return sum;
 }
 
 template <bool IVF, bool SHARE>
@@ -969,9 +1003,15 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
     a.list_off = nullptr;
     a.ext_ids = nullptr;
     a.job_slot = nullptr;
+    // survivor share from which scoring every pair is the faster route (measured at 10M x 10k:
+    // 64-bit codes cross between ht = 30 and 31, 128-bit codes between ht = 61 and 62)
+    const double dense_from = 0.36;
     if (ht >= nbits)  // nothing to filter: the pure-ADC kernel
-        rc = p.nslice >= 4 ? dispatch_adc<true>(m, p.tq, a, p.ntiles, p.lds_bytes, s)
-                           : dispatch_adc<false>(m, p.tq, a, p.ntiles, p.lds_bytes, s);
+        rc = p.nslice >= 4 ? dispatch_adc<true, false>(m, p.tq, a, p.ntiles, p.lds_bytes, s)
+                           : dispatch_adc<false, false>(m, p.tq, a, p.ntiles, p.lds_bytes, s);
+    else if (random_code_survival(nbits, ht) >= dense_from)
+        rc = p.nslice >= 4 ? dispatch_adc<true, true>(m, p.tq, a, p.ntiles, p.lds_bytes, s)
+                           : dispatch_adc<false, true>(m, p.tq, a, p.ntiles, p.lds_bytes, s);
     else
         rc = p.nslice >= 4 ? dispatch_scan<false, true>(m, p.tq, a, p.ntiles, p.lds_bytes, s)
                            : dispatch_scan<false, false>(m, p.tq, a, p.ntiles, p.lds_bytes, s);
