@@ -687,7 +687,28 @@ adc_kernel(ScanArgs a)
     }
 }
 
+// Smallest value of v over the wave, in every lane: four row-local steps on the data-parallel
+// path, then the four row results through scalar registers.
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v)
+{
+    auto step = [](uint32_t x, uint32_t y) { return y < x ? y : x; };
+    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xB1, 0xf, 0xf, false));   // lane ^ 1
+    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x4E, 0xf, 0xf, false));   // lane ^ 2
+    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x141, 0xf, 0xf, false));  // mirror in 8
+    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x140, 0xf, 0xf, false));  // mirror in 16
+    const uint32_t r0 = (uint32_t)__builtin_amdgcn_readlane((int)v, 0);
+    const uint32_t r1 = (uint32_t)__builtin_amdgcn_readlane((int)v, 16);
+    const uint32_t r2 = (uint32_t)__builtin_amdgcn_readlane((int)v, 32);
+    const uint32_t r3 = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+    return step(step(r0, r1), step(r2, r3));
+}
+
 // Merge the nslice sorted partial lists of each query into the final k (one wave per query).
+// Lane l owns lists l, l + 64, ...: it keeps the head of each in registers together with the
+// entry after it, so that a step of the merge (pick the smallest head of the wave, advance that
+// list) waits for memory only when one list wins several times in a row.  Padding entries
+// (id < 0) end a list.
+template <int OWN>
 __global__ void __launch_bounds__(64)
 merge_kernel(const float *__restrict__ part_d, const int64_t *__restrict__ part_i, int nslice, int k,
              int64_t id_base, const int *__restrict__ status, int64_t *__restrict__ ids,
@@ -698,52 +719,94 @@ merge_kernel(const float *__restrict__ part_d, const int64_t *__restrict__ part_
     const float *pd = part_d + q * nslice * k;
     const int64_t *pi = part_i + q * nslice * k;
     const bool poisoned = *status != 0;
-    // lane owns lists lane, lane+64, ...; head[] index into each (kept in a small loop instead of
-    // registers: nslice/64 is tiny)
-    constexpr int kMaxOwn = 16;  // up to 1024 slices
-    int hd[kMaxOwn];
+    uint32_t hk[OWN], nk[OWN];  // distance keys of the head and of the entry after it (kKeyNone: none)
+    int64_t hi[OWN], ni[OWN];   // their ids
+    int pos[OWN];               // index of the head in its list
+    constexpr uint32_t kKeyNone = 0xffffffffu;  // above every real key, +infinity included
+    auto fetch = [&](int l, int at, uint32_t &key, int64_t &id) {
+        key = kKeyNone;
+        id = -1;
+        if (l < nslice && at < k) {
+            const int64_t i = pi[(int64_t)l * k + at];
+            if (i >= 0) {
+                id = i;
+                key = dist_key(pd[(int64_t)l * k + at]);
+            }
+        }
+    };
 #pragma unroll
-    for (int t = 0; t < kMaxOwn; ++t) hd[t] = 0;
+    for (int t = 0; t < OWN; ++t) {
+        pos[t] = 0;
+        fetch(lane + 64 * t, 0, hk[t], hi[t]);
+        fetch(lane + 64 * t, 1, nk[t], ni[t]);
+    }
     for (int r = 0; r < k; ++r) {
-        float bd = __builtin_inff();
-        int64_t bi = INT64_MAX;
-        int bl = -1;
+        // the lane's best head
+        uint32_t bk = hk[0];
+        int64_t bi = hi[0];
+        int bt = 0;
 #pragma unroll
-        for (int t = 0; t < kMaxOwn; ++t) {
-            const int l = lane + 64 * t;
-            if (l < nslice && hd[t] < k) {
-                const float d = pd[l * k + hd[t]];
-                const int64_t i = pi[l * k + hd[t]];
-                if (i >= 0 && (d < bd || (d == bd && i < bi))) {
-                    bd = d;
-                    bi = i;
-                    bl = l;
+        for (int t = 1; t < OWN; ++t) {
+            if (hk[t] < bk || (hk[t] == bk && hk[t] != kKeyNone && hi[t] < bi)) {
+                bk = hk[t];
+                bi = hi[t];
+                bt = t;
+            }
+        }
+        // the wave's: smallest key, and the lowest id among the lanes that hold it
+        const uint32_t wk = wave_min_u32(bk);
+        uint64_t tied = ballot64(bk == wk);
+        int win = __builtin_ctzll(tied);
+        if (wk != kKeyNone && (tied & (tied - 1))) {
+            int64_t best = INT64_MAX;
+            while (tied) {
+                const int l = __builtin_ctzll(tied);
+                tied &= tied - 1;
+                const int64_t cand = ((int64_t)__builtin_amdgcn_readlane((int)(bi >> 32), l) << 32) |
+                                     (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)bi, l);
+                if (cand < best) {
+                    best = cand;
+                    win = l;
                 }
             }
         }
-        // wave-wide arg-min of (bd, bi)
+        const bool have = wk != kKeyNone;
+        const int64_t wi = ((int64_t)__builtin_amdgcn_readlane((int)(bi >> 32), win) << 32) |
+                           (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)bi, win);
+        if (lane == 0) {
+            ids[q * k + r] = poisoned ? (int64_t)-2 : (have ? wi + id_base : (int64_t)-1);
+            dists[q * k + r] = have ? key_dist(wk) : __builtin_inff();
+        }
+        if (have && lane == win) {  // advance the winning list
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-            const float od = __shfl_xor(bd, off, 64);
-            const int64_t oi = __shfl_xor(bi, off, 64);
-            const int ol = __shfl_xor(bl, off, 64);
-            if (od < bd || (od == bd && oi < bi)) {
-                bd = od;
-                bi = oi;
-                bl = ol;
+            for (int t = 0; t < OWN; ++t) {
+                if (t == bt) {
+                    hk[t] = nk[t];
+                    hi[t] = ni[t];
+                    ++pos[t];
+                    fetch(lane + 64 * t, pos[t] + 1, nk[t], ni[t]);
+                }
             }
         }
-        if (bl >= 0) {
-#pragma unroll
-            for (int t = 0; t < kMaxOwn; ++t)
-                if (bl == lane + 64 * t) ++hd[t];
-        }
-        if (lane == 0) {
-            const bool have = bl >= 0;
-            ids[q * k + r] = poisoned ? (int64_t)-2 : (have ? bi + id_base : (int64_t)-1);
-            dists[q * k + r] = have ? bd : __builtin_inff();
-        }
     }
+}
+
+// One wave per query; the lists are spread over the lanes, OWN to a lane.
+int launch_merge(const float *part_d, const int64_t *part_i, int64_t nq, int nlists, int k, const int *status,
+                 int64_t *ids, float *dists, hipStream_t s)
+{
+    PSC_REQUIRE(nlists >= 1 && nlists <= 1024, "between 1 and 1024 partial lists per query, got %d", nlists);
+    const dim3 grid((unsigned)nq), block(64);
+    if (nlists <= 64)
+        hipLaunchKernelGGL(merge_kernel<1>, grid, block, 0, s, part_d, part_i, nlists, k, (int64_t)0, status, ids, dists);
+    else if (nlists <= 128)
+        hipLaunchKernelGGL(merge_kernel<2>, grid, block, 0, s, part_d, part_i, nlists, k, (int64_t)0, status, ids, dists);
+    else if (nlists <= 256)
+        hipLaunchKernelGGL(merge_kernel<4>, grid, block, 0, s, part_d, part_i, nlists, k, (int64_t)0, status, ids, dists);
+    else
+        hipLaunchKernelGGL(merge_kernel<16>, grid, block, 0, s, part_d, part_i, nlists, k, (int64_t)0, status, ids, dists);
+    PSC_HIP_TRY(hipGetLastError());
+    return PSC_OK;
 }
 
 __global__ void fill_padding_kernel(int64_t *ids, float *dists, int64_t total)
@@ -1016,10 +1079,7 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
         rc = p.nslice >= 4 ? dispatch_scan<false, true>(m, p.tq, a, p.ntiles, p.lds_bytes, s)
                            : dispatch_scan<false, false>(m, p.tq, a, p.ntiles, p.lds_bytes, s);
     if (rc != PSC_OK) return rc;
-    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)nq), dim3(64), 0, s, a.part_d, a.part_i, p.nslice, k,
-                       (int64_t)0, a.status, ids_dev, dists_dev);
-    PSC_HIP_TRY(hipGetLastError());
-    return PSC_OK;
+    return launch_merge(a.part_d, a.part_i, nq, p.nslice, k, a.status, ids_dev, dists_dev, s);
 }
 
 // Inverted-file scan: one workgroup per tile descriptor (up to `max_tiles`; the actual count is
@@ -1065,10 +1125,7 @@ int launch_ivf_scan(int m, int tq, int kpad, size_t lds_bytes, const float *lut_
         int rc = dispatch_scan<true, true>(m, tq, a, max_tiles, lds_bytes, s);
         if (rc != PSC_OK) return rc;
     }
-    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)nq), dim3(64), 0, s, part_d, part_i, nprobe, k,
-                       (int64_t)0, status, ids_dev, dists_dev);
-    PSC_HIP_TRY(hipGetLastError());
-    return PSC_OK;
+    return launch_merge(part_d, part_i, nq, nprobe, k, status, ids_dev, dists_dev, s);
 }
 
 int launch_hamming_filter(int m, const uint8_t *qcodes_dev, int64_t nq, const uint8_t *codes_dev,
