@@ -967,25 +967,23 @@ int plan_scan(int m, int64_t nq, int64_t n, int k, ScanPlan *plan)
         return PSC_EINVAL;
     }
     const int64_t nqt = (nq + p.tq - 1) / p.tq;
-    // Slices: enough workgroups to fill 256 compute units a few times over, a whole number of
-    // blocks each, and short enough for the position field of a ring entry.
+    // Slices: one workgroup per (query tile, slice) and one workgroup per compute unit at a
+    // time, so the launch runs in rounds of 256.  Every slice of a query builds its own list of
+    // k, which costs insertions and merge work, so the fewest slices win that fill the rounds:
+    // score = share of the rounds' places that are used, less 1% per round.
     const int64_t block = 512;  // codes per wave and step, at most (64 lanes x 8 codes)
     int64_t want = 1;
     if (nqt > 0) {
-        const int64_t target_wg = 1024;
-        want = (target_wg + nqt - 1) / nqt;
-        // among want..want+3 prefer the count whose last round of workgroups is fullest
-        double best_eff = -1.0;
-        int64_t best = want;
-        for (int64_t sN = want; sN < want + 4; ++sN) {
-            const int64_t wg = nqt * sN;
-            const double eff = (double)wg / (double)(((wg + 255) / 256) * 256);
-            if (eff > best_eff + 1e-9) {
-                best_eff = eff;
-                best = sN;
+        const int64_t wg_limit = 2048;
+        double best_score = -1.0;
+        for (int64_t sN = 1; sN * nqt <= std::max<int64_t>(wg_limit, nqt); ++sN) {
+            const int64_t wg = nqt * sN, rounds = (wg + 255) / 256;
+            const double score = (double)wg / (double)(rounds * 256) - 0.01 * (double)rounds;
+            if (score > best_score + 1e-9) {
+                best_score = score;
+                want = sN;
             }
         }
-        want = best;
     }
     const int64_t min_slice = 16 * block;  // at least one block per wave
     int64_t max_by_size = std::max<int64_t>(1, n / min_slice);
