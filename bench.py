@@ -7,7 +7,7 @@ scan over the 10,000,000 64-bit codes, and the merge of the partial lists -- wit
 codebook and codes already resident in HBM.  Inputs are seeded and synthetic (SIFT-like
 mixture, see workloads/).  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--ht 24] [--small] [--no-sweep] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--ht 24] [--small] [--no-sweep] [--no-cpu] [--no-small-batch]
 """
 from __future__ import annotations
 
@@ -47,6 +47,8 @@ def main():
     ap.add_argument("--small", action="store_true", help="1M codes / 1000 queries (quick check)")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-small-batch", action="store_true",
+                    help="skip the memory-bound side measurement (1 and 16 queries over 400M codes)")
     ap.add_argument("--cpu-queries", type=int, default=192)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (known traffic, for scaling the "
@@ -160,9 +162,46 @@ def main():
             ns = psc.hamming_filter(idx.build_lut(q_dev[:256])[1], codes, ht)
             torch.cuda.synchronize()
             sweep.append(dict(ht=ht, ms_per_step=round(w, 3), scan_ms=round(sms, 3),
-                              pairs_per_s=pairs / (w * 1e-3), recall_at_10=r10, recall_at_100=r100,
+                              pairs_per_s=pairs / (w * 1e-3),
+                              alu_frac=OPS_PER_PAIR[m] * pairs / (sms * 1e-3) / 1e12 / PEAK_INT_TOPS,
+                              recall_at_10=r10, recall_at_100=r100,
                               survivor_rate=float(ns.double().mean()) / n_db))
             log(f"[sweep] {sweep[-1]}")
+
+    # ------------------------------------------------------------------ side measurement: few queries
+    # One pass over a database much larger than the 256 MB last-level cache for 1 and 16 queries:
+    # with so little reuse of a code the scan is bound by HBM reads (8 B per code), not by the ALUs.
+    # Uniformly random codes and tables; reported beside the headline, never part of `value`.
+    small_batch = []
+    if not (args.no_small_batch or args.small):
+        n_big = 400_000_000
+        g = torch.Generator(device=dev)
+        g.manual_seed(cfg.seed)
+        big = torch.randint(0, 2 ** 31, (n_big * m // 4,), dtype=torch.int32, device=dev,
+                            generator=g).view(torch.uint8).view(n_big, m)
+        for nqs in (1, 16):
+            qcs = torch.randint(0, 256, (nqs, m), dtype=torch.uint8, device=dev, generator=g)
+            luts = torch.rand((nqs, m, 256), device=dev, generator=g) * 1000.0
+            wss = torch.empty(psc.scan_workspace_bytes(m, nqs, n_big, k), dtype=torch.uint8, device=dev)
+            outs = (torch.empty((nqs, k), dtype=torch.int64, device=dev),
+                    torch.empty((nqs, k), dtype=torch.float32, device=dev))
+            for hts in (0, 20):
+                for _ in range(2):
+                    psc.scan(luts, qcs, big, hts, k, workspace=wss, out=outs)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                e0.record()
+                for _ in range(5):
+                    psc.scan(luts, qcs, big, hts, k, workspace=wss, out=outs)
+                e1.record()
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1) / 5
+                gbs = n_big * m / (ms * 1e-3) / 1e9
+                small_batch.append(dict(n_db=n_big, n_query=nqs, ht=hts, k=k, ms=round(ms, 4),
+                                        code_bytes_GBps=round(gbs, 1), frac_of_8TBps=round(gbs / 8000.0, 4),
+                                        pairs_per_s=n_big * nqs / (ms * 1e-3)))
+                log(f"[small-batch] {small_batch[-1]}")
+        del big
 
     # ------------------------------------------------------------------ CPU baseline: the oracle
     cpu = None
@@ -207,6 +246,7 @@ def main():
                      "traffic": None if args.small else MEASURED_TRAFFIC_BYTES.get(("flat64", args.ht))},
         "cpu_baseline": cpu,
         "sweep": sweep,
+        "small_batch": small_batch,
         "paper_context": {"adc_evals_per_s_per_core": 222e6, "hamming_evals_per_s_per_core": 1.19e9,
                           "note": "paper's CPU figures for 8-byte codes, one 2.8 GHz core (Fig. 1)"},
     }

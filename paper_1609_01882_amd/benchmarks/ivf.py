@@ -1,0 +1,78 @@
+"""Inverted-file batch search (Section 4.3): 100M vectors in 4096 lists of residual 64-bit codes,
+10k queries, 64 lists probed each, ht=24, k=100.  The database is drawn on the GPU (same recipe as
+the host generator) because 100M x 128 floats do not fit in host memory at once.
+One step = the whole psc_ivf_search call."""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import time
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--n", type=int, default=0, help="database size (default: the workload's 100M)")
+    args = ap.parse_args()
+    import torch
+
+    import paper_1609_01882_amd as psc
+    import workloads as W
+    from ._common import log, time_ms
+
+    cfg = W.get_config("ivf")
+    n = args.n or cfg.n_db
+    nlist, nprobe, k, ht, nq = cfg.nlist, cfg.nprobe, cfg.k, cfg.hts[0], cfg.n_query
+    threads = min(16, os.cpu_count() or 1)
+    dev = torch.device("cuda:0")
+
+    t0 = time.time()
+    xt = cfg.vectors("train", threads=threads)
+    idx = psc.Index(cfg.dim, cfg.m)
+    idx.ivf_train_coarse(W.sift_like(500_000, cfg.seed, 7, threads=threads), nlist, iters=10, seed=cfg.seed)
+    coarse = idx.ivf_get_coarse()
+    lt, _ = idx.ivf_assign_encode(torch.from_numpy(xt).to(dev), want_codes=False)
+    idx.train_pq(xt - coarse[lt.cpu().numpy()], iters=20, seed=cfg.seed)   # PQ of the residuals
+    idx.optimize_index_assignment(seed=cfg.seed)
+    log(f"[setup] coarse quantizer, residual PQ, index assignment in {time.time() - t0:.1f}s")
+
+    t0 = time.time()
+    list_no = torch.empty(n, dtype=torch.int32, device=dev)
+    codes = torch.empty((n, cfg.m), dtype=torch.uint8, device=dev)
+    for s in range(0, n, 4_000_000):
+        c = min(4_000_000, n - s)
+        ln, cd = idx.ivf_assign_encode(W.sift_like_torch(c, cfg.seed, 2, start=s, device=dev))
+        list_no[s:s + c] = ln
+        codes[s:s + c] = cd
+    order = torch.sort(list_no.to(torch.int64), stable=True).indices
+    counts = torch.bincount(list_no.to(torch.int64), minlength=nlist)
+    offsets = torch.zeros(nlist + 1, dtype=torch.int64, device=dev)
+    offsets[1:] = torch.cumsum(counts, 0)
+    lcodes, lids = codes[order].contiguous(), order.to(torch.int32).contiguous()
+    del codes, order, list_no
+    idx.ivf_set_lists(offsets, lcodes, lids)
+    torch.cuda.synchronize()
+    log(f"[setup] {n} vectors assigned, encoded and grouped into lists in {time.time() - t0:.1f}s "
+        f"(list sizes {counts.min().item()} / {counts.float().mean().item():.0f} / {counts.max().item()})")
+
+    xq = torch.from_numpy(cfg.vectors("query", n=nq, threads=threads)).to(dev)
+    ws = torch.empty(idx.ivf_search_workspace_bytes(nq, nprobe, k), dtype=torch.uint8, device=dev)
+    out = (torch.empty((nq, k), dtype=torch.int64, device=dev), torch.empty((nq, k), dtype=torch.float32, device=dev))
+    ms = time_ms(lambda: idx.ivf_search(xq, nprobe, ht, k, workspace=ws, out=out), args.steps, args.warmup)
+    psc.workspace_status(ws)
+    # codes visited: lengths of the probed lists, from a sample of queries
+    ns = 64
+    _, _, probed, _ = idx.ivf_search(xq[:ns].contiguous(), nprobe, ht, k, want_debug=True)
+    torch.cuda.synchronize()
+    pairs = float(counts[probed.long()].sum().item()) / ns * nq
+    res = {"workload": "ivf", "n_db": n, "nlist": nlist, "nprobe": nprobe, "n_query": nq, "k": k, "ht": ht,
+           "ms_per_step": round(ms, 3), "us_per_query": ms * 1e3 / nq, "pairs_per_step": pairs,
+           "pairs_per_s": pairs / (ms * 1e-3), "workspace_GB": ws.numel() / 1e9}
+    log(f"[ivf] {res}")
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

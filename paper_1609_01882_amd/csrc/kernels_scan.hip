@@ -121,9 +121,9 @@ template <int M, int TQ>
 struct Lds {
     lds_f32 *lut;    // [TQ][M][256]
     lds_vu64 *top;   // [TQ][kpad] sorted ascending
-    lds_vf32 *thr;   // [TQ] current k-th best distance (+inf until the list is full)
-    lds_vi32 *cnt;   // [TQ] entries in the list
-    lds_i32 *lock;   // [TQ]
+    lds_vf32 *thr;   // [TQ] bound on the query's k-th best distance (+inf while nothing is known)
+    lds_i32 *lock;   // [TQ] number of entries in the list, or kLocked while a wave works on it
+    lds_i32 *gidx;   // [TQ] the slot's query as an index into the shared thresholds (-1: empty slot)
     lds_u32 *queue;  // [nwaves][kQueueCap]; private to a wave: LDS keeps a wave's accesses in order
     lds_u32 *dump;   // [nwaves][64] where lanes with nothing to queue write
     __device__ __forceinline__ Lds(PSC_LDS unsigned char *base, int kpad, int nwaves)
@@ -131,66 +131,128 @@ struct Lds {
         lut = (lds_f32 *)base;
         top = (lds_vu64 *)(lut + TQ * M * 256);
         thr = (lds_vf32 *)(top + TQ * kpad);
-        cnt = (lds_vi32 *)(thr + TQ);
-        lock = (lds_i32 *)(cnt + TQ);
-        queue = (lds_u32 *)(lock + TQ);
+        lock = (lds_i32 *)(thr + TQ);
+        gidx = lock + TQ;
+        queue = (lds_u32 *)(gidx + TQ);
         dump = queue + nwaves * kQueueCap;
     }
 };
 
-// Insert the candidates held by the lanes in `mine` (all for query slot q) into q's list.
-// Executed by the whole wave; mine is wave-uniform.
-template <int M, int TQ, bool SHARE>
-__device__ __forceinline__ void insert_candidates(const Lds<M, TQ> &s, const ScanArgs &a, int q, int64_t qid,
-                                                  uint64_t mine, float d, uint32_t id)
+constexpr int kLocked = -1;
+
+// The 64-bit value held by the lane below (lane 0 receives `first`): a whole-wave shift by one
+// lane on the data-parallel path.
+__device__ __forceinline__ uint64_t from_lane_below(uint64_t v, uint64_t first)
+{
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)first, (int)(uint32_t)v, 0x138, 0xf,
+                                                              0xf, false);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)(first >> 32), (int)(uint32_t)(v >> 32),
+                                                              0x138, 0xf, 0xf, false);
+    return ((uint64_t)hi << 32) | lo;
+}
+__device__ __forceinline__ uint64_t lane_value_u64(uint64_t v, int l)
+{
+    return ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), l) << 32) |
+           (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, l);
+}
+// Lower a threshold in LDS, no answer awaited.
+__device__ __forceinline__ void lower_threshold(lds_vf32 *p, float v)
+{
+    (void)__hip_atomic_fetch_min((lds_f32 *)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+// Insert the candidates held by the lanes in `mine` (all for query slot q) into q's sorted list.
+// Executed by the whole wave; mine is wave-uniform.  The slot's lock word doubles as the entry
+// count, so taking the lock also fetches the count and releasing it stores the new one.
+// Lists of up to 128 entries (two per lane) are read into registers once, every candidate is
+// ranked by ballot and spliced in with a one-lane shift, and the list is written back once: two
+// trips to LDS per call however many candidates it brings.
+// SHARE: the list's k-th best is published to the other workgroups of the query.  EAGER: every
+// call also reads what they have published (worth the wait at its end when a query is spread
+// over hundreds of workgroups; with the few dozen lists of an inverted-file probe the reads made
+// once per batch of candidates are enough).
+template <int M, int TQ, bool SHARE, bool EAGER>
+__device__ __forceinline__ void insert_candidates(const Lds<M, TQ> &s, const ScanArgs &a, int q, uint64_t mine,
+                                                  float d, uint32_t id)
 {
     const int lane = lane_id();
-    // What other workgroups of this query have reached so far; asked for now, used at the end,
-    // so that the trip to memory overlaps the work on the list.
-    uint32_t seen = kKeyInf;
-    if constexpr (SHARE) {
-        if (lane == 0) seen = __hip_atomic_load(&a.gthr[qid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    int got = 0;
+    // The other waves of the SIMD are busy filtering and would get three of every four issue
+    // slots: whoever works on a list (and may hold its lock) goes first.
+    __builtin_amdgcn_s_setprio(3);
+    int cnt = kLocked;
     if (lane == 0) {
         int spins = 0;
         while (true) {
-            if (__hip_atomic_exchange(&s.lock[q], 1, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0) {
-                got = 1;
-                break;
-            }
-            if (++spins > kSpinLimit) break;
+            cnt = __hip_atomic_exchange(&s.lock[q], kLocked, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (cnt != kLocked || ++spins > kSpinLimit) break;
             __builtin_amdgcn_s_sleep(2);
         }
     }
-    got = __builtin_amdgcn_readfirstlane(got);
-    if (!got) {  // never expected: flag the run instead of waiting for ever
+    cnt = __builtin_amdgcn_readfirstlane(cnt);
+    if (cnt == kLocked) {  // never expected: flag the run instead of waiting for ever
         if (lane == 0) atomicExch(a.status, 1);
+        __builtin_amdgcn_s_setprio(0);
         return;
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    // Everything the lock protects lives in LDS, which serves the accesses of a wave in the order
+    // they were issued and those of different waves one after the other: a lock word taken by
+    // an exchange and given back by a plain store after the data needs no hardware fence.  (A
+    // workgroup-scope fence would also wait for every global load the wave has in flight, its
+    // prefetched codes included, with the lock held.)  Only the compiler must keep the order.
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    // What the other workgroups of this query have reached by now: asked for here, used after
+    // the lock is given back, so the trip to memory overlaps the work on the list.
+    uint32_t seen = kKeyInf;
+    int gi = -1;
+    if constexpr (SHARE) {
+        if (lane == 0) {
+            gi = s.gidx[q];
+            if constexpr (EAGER) seen = __hip_atomic_load(&a.gthr[gi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
     lds_vu64 *list = s.top + q * a.kpad;
-    int cnt = s.cnt[q];
     const int k = a.k;
-    while (mine) {
-        const int src = __builtin_ctzll(mine);
-        mine &= mine - 1;
-        const uint64_t cand = pack_entry(bcast_f(d, src), bcast_u(id, src));
-        if (cnt == k && !(cand < list[k - 1])) continue;
-        // entries pos..last-1 move one place down the list (the k-th falls off when full)
-        const int last = cnt < k ? cnt : k - 1;
-        int pos = 0;
-        if (k <= 128) {
-            // whole list in two registers per lane: rank and shift in one pass
-            const int p0 = lane, p1 = 64 + lane;
-            uint64_t e0 = ~0ull, e1 = ~0ull;
-            if (p0 < cnt) e0 = list[p0];
-            if (p1 < cnt) e1 = list[p1];
-            const bool b0 = e0 < cand, b1 = e1 < cand;
-            pos = __builtin_popcountll(ballot64(b0)) + __builtin_popcountll(ballot64(b1));
-            if (!b0 && p0 < last) list[p0 + 1] = e0;
-            if (!b1 && p1 < last) list[p1 + 1] = e1;
-        } else {
+    uint32_t own_key = kKeyInf;  // the list's k-th best once it is full
+    bool changed = false;
+    float thr_old;
+    if (k <= 128) {
+        const int i0 = lane, i1 = 64 + lane;  // the two list places of the lane
+        uint64_t e0 = ~0ull, e1 = ~0ull;      // places past the end hold the largest key
+        if (i0 < cnt) e0 = list[i0];
+        if (i1 < cnt) e1 = list[i1];
+        thr_old = s.thr[q];
+        mine &= ballot64(d <= thr_old);  // the threshold may have dropped since the candidates were scored
+        while (mine) {
+            const int src = __builtin_ctzll(mine);
+            mine &= mine - 1;
+            const uint64_t cand = pack_entry(bcast_f(d, src), bcast_u(id, src));
+            const int pos = __builtin_popcountll(ballot64(e0 < cand)) + __builtin_popcountll(ballot64(e1 < cand));
+            if (pos >= k) continue;
+            // places pos.. move one down the list; what falls off the end is forgotten
+            const uint64_t up0 = from_lane_below(e0, e0);
+            const uint64_t up1 = from_lane_below(e1, lane_value_u64(e0, 63));
+            e0 = i0 > pos ? up0 : (i0 == pos ? cand : e0);
+            e1 = i1 > pos ? up1 : (i1 == pos ? cand : e1);
+            if (i0 >= k) e0 = ~0ull;
+            if (i1 >= k) e1 = ~0ull;
+            if (cnt < k) ++cnt;
+            changed = true;
+        }
+        if (changed) {
+            if (i0 < cnt) list[i0] = e0;
+            if (i1 < cnt) list[i1] = e1;
+            if (cnt == k) own_key = (uint32_t)(lane_value_u64(k <= 64 ? e0 : e1, (k - 1) & 63) >> 32);
+        }
+    } else {
+        thr_old = s.thr[q];
+        while (mine) {
+            const int src = __builtin_ctzll(mine);
+            mine &= mine - 1;
+            const uint64_t cand = pack_entry(bcast_f(d, src), bcast_u(id, src));
+            if (cnt == k && !(cand < list[k - 1])) continue;
+            // entries pos..last-1 move one place down the list (the k-th falls off when full)
+            const int last = cnt < k ? cnt : k - 1;
+            int pos = 0;
             for (int base = 0; base < cnt; base += 64) {
                 const int p = base + lane;
                 const bool before = p < cnt && list[p] < cand;
@@ -207,46 +269,72 @@ __device__ __forceinline__ void insert_candidates(const Lds<M, TQ> &s, const Sca
                     __builtin_amdgcn_wave_barrier();
                 }
             }
+            if (lane == 0) list[pos] = cand;
+            if (cnt < k) ++cnt;
+            changed = true;
+            __builtin_amdgcn_wave_barrier();
         }
-        if (lane == 0) list[pos] = cand;
-        if (cnt < k) ++cnt;
-        __builtin_amdgcn_wave_barrier();
+        if (changed && cnt == k) own_key = (uint32_t)(list[k - 1] >> 32);
     }
-    uint32_t own_key = kKeyInf;
+    const float own = key_dist(own_key);
+    const bool lowered = own < thr_old;  // this list's k-th best is below everything known so far
+    if (lowered && lane == 0) lower_threshold(&s.thr[q], own);
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
     if (lane == 0) {
-        s.cnt[q] = cnt;
-        if (cnt == k) {
-            own_key = (uint32_t)(list[k - 1] >> 32);
-            const float own = key_dist(own_key);
-            if (own < s.thr[q]) s.thr[q] = own;
-        }
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    if (lane == 0) {
-        __hip_atomic_store(&s.lock[q], 0, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
-        // Outside the lock: publish this list's k-th best (no reply awaited) and adopt what the
-        // other workgroups of the query had reached.  A concurrent, lower local threshold may be
-        // overwritten by a slightly higher one here; that only admits a few more candidates.
+        __hip_atomic_store(&s.lock[q], cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        // Outside the lock: adopt what the others had reached, and tell them (no answer awaited).
         if constexpr (SHARE) {
-            const float other = key_dist(seen);
-            if (other < s.thr[q]) s.thr[q] = other;
-            if (own_key < seen)  // last, so that nothing here waits for it
-                (void)__hip_atomic_fetch_min(&a.gthr[qid], own_key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (seen != kKeyInf && key_dist(seen) < (lowered ? own : thr_old)) lower_threshold(&s.thr[q], key_dist(seen));
+            if (lowered && own_key < seen)
+                (void)__hip_atomic_fetch_min(&a.gthr[gi], own_key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
+    __builtin_amdgcn_s_setprio(0);
 }
+
+// What the other workgroups of the tile's queries have reached.  `ask`: lane q < TQ requests the
+// shared threshold of slot q.  `adopt`: lowers the slots' own thresholds to the answers.  Callers
+// ask where a batch of candidates starts, next to a memory access of their own that they wait
+// for anyway, and adopt before the candidates are tested -- but only while lists are changing
+// (the previous batch inserted something), so that a settled scan asks nothing.
+template <int M, int TQ>
+__device__ __forceinline__ uint32_t ask_shared_thresholds(const Lds<M, TQ> &s, const ScanArgs &a)
+{
+    const int lane = lane_id();
+    uint32_t g = kKeyInf;
+    if (lane < TQ) {
+        const int gi = s.gidx[lane];
+        if (gi >= 0) g = __hip_atomic_load(&a.gthr[gi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    return g;
+}
+template <int M, int TQ>
+__device__ __forceinline__ void adopt_shared_thresholds(const Lds<M, TQ> &s, uint32_t g)
+{
+    const int lane = lane_id();
+    if (lane < TQ && g != kKeyInf) lower_threshold(&s.thr[lane], key_dist(g));
+}
+
+// State a wave carries from one batch of candidates to the next for the exchange above.
+struct SharedAsk {
+    bool wanted = true;  // wave-uniform: the previous batch changed a list (or there was none yet)
+};
 
 // Score the first `nvalid` (<= 64) entries of the wave's queue and feed the ones that beat the
 // current threshold to the lists.
 template <int M, int TQ, bool IVF, bool SHARE>
 __device__ __forceinline__ void drain(const Lds<M, TQ> &s, const ScanArgs &a, const lds_u32 *ring,
-                                      int nvalid, int64_t slice_begin, int64_t q0)
+                                      int nvalid, int64_t slice_begin, int64_t q0, SharedAsk &ask)
 {
     const int lane = lane_id();
     const bool act = lane < nvalid;
     float d = __builtin_inff();
     uint32_t rel = 0;
     int q = 0;
+    uint32_t shared = kKeyInf;
+    if constexpr (SHARE) {
+        if (ask.wanted) shared = ask_shared_thresholds<M, TQ>(s, a);
+    }
     if (act) {
         // entry = (b << kRelBits) | position of the lane's first code; b = c * TQ + (TQ - 1 - q)
         const uint32_t e = ring[lane];
@@ -275,6 +363,9 @@ __device__ __forceinline__ void drain(const Lds<M, TQ> &s, const ScanArgs &a, co
         }
         d = acc;
     }
+    if constexpr (SHARE) {
+        if (ask.wanted) adopt_shared_thresholds<M, TQ>(s, shared);
+    }
     bool pass = act && d <= s.thr[q];
     uint32_t key = rel;  // what breaks distance ties: the position, or the stored id
     if constexpr (IVF) {
@@ -284,12 +375,13 @@ __device__ __forceinline__ void drain(const Lds<M, TQ> &s, const ScanArgs &a, co
             pass = pass && (slice_begin + (int64_t)rel) != a.skip_first + q0 + q;
     }
     uint64_t pm = ballot64(pass);
+    ask.wanted = pm != 0;
     while (pm) {
         const int leader = __builtin_ctzll(pm);
         const int qcur = __builtin_amdgcn_readlane(q, leader);
         const uint64_t mine = ballot64(pass && q == qcur);
         pm &= ~mine;
-        insert_candidates<M, TQ, SHARE>(s, a, qcur, IVF ? (int64_t)a.job_q[q0 + qcur] : q0 + qcur, mine, d, key);
+        insert_candidates<M, TQ, SHARE, SHARE && !IVF>(s, a, qcur, mine, d, key);
     }
 }
 
@@ -354,8 +446,8 @@ scan_kernel(ScanArgs a)
                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
             }
             s.thr[tid] = t0;
-            s.cnt[tid] = 0;
             s.lock[tid] = 0;
+            s.gidx[tid] = tid < nvq ? (int)(IVF ? (int64_t)a.job_q[q0 + tid] : q0 + tid) : -1;
         }
     }
     // ---- query codes -> scalar registers
@@ -380,6 +472,7 @@ scan_kernel(ScanArgs a)
     lds_u32 *ring = s.queue + wave * kQueueCap;
     const uint32_t ring_base = (uint32_t)(uintptr_t)ring;  // LDS byte address of the wave's queue
     int fill = 0;  // wave-uniform: entries waiting in the queue (< 64 between turns)
+    SharedAsk ask;
 
     const uint32_t bias = a.bias;
     const int64_t stride = (int64_t)NW * 64 * CB;
@@ -512,7 +605,7 @@ scan_kernel(ScanArgs a)
                 static_assert(kRelBits == 27, "the shift in the queueing loop");
                 if (fill < 64) break;  // every lane is out of bits
                 __builtin_amdgcn_wave_barrier();
-                drain<M, TQ, IVF, SHARE>(s, a, ring, 64, slice_begin, q0);
+                drain<M, TQ, IVF, SHARE>(s, a, ring, 64, slice_begin, q0, ask);
                 // entries 64..fill-1 move to the front
                 fill -= 64;
                 uint32_t e = 0u;
@@ -529,14 +622,14 @@ scan_kernel(ScanArgs a)
     }
     if (fill > 0) {
         __builtin_amdgcn_wave_barrier();
-        drain<M, TQ, IVF, SHARE>(s, a, ring, fill, slice_begin, q0);
+        drain<M, TQ, IVF, SHARE>(s, a, ring, fill, slice_begin, q0, ask);
     }
     __syncthreads();
 
     // ---- write the tile's lists (padded) to the workspace
     for (int e = tid; e < nvq * a.k; e += NW * 64) {
         const int q = e / a.k, r = e - q * a.k;
-        const bool have = r < s.cnt[q];
+        const bool have = r < s.lock[q];
         const uint64_t ent = s.top[q * a.kpad + r];
         int64_t o, id;
         if constexpr (IVF) {
@@ -599,8 +692,8 @@ adc_kernel(ScanArgs a)
                     t0 = key_dist(__hip_atomic_load(&a.gthr[q0 + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
             }
             s.thr[tid] = t0;
-            s.cnt[tid] = 0;
             s.lock[tid] = 0;
+            s.gidx[tid] = tid < nvq ? (int)(q0 + tid) : -1;
         }
     }
     // ---- query codes -> scalar registers (only the filtering variant reads them)
@@ -617,11 +710,16 @@ adc_kernel(ScanArgs a)
     __syncthreads();
 
     const PSC_LDS f32x4 *lut4 = (const PSC_LDS f32x4 *)s.lut;
+    SharedAsk ask;
     const int64_t stride = (int64_t)NW * 64 * CPL;
     const int64_t skip_rel = a.skip_first + q0 - slice_begin;
     const bool skipping = a.skip_first >= 0 && skip_rel > -(int64_t)TQ && skip_rel < kMaxSliceLen;
     for (int64_t blk = slice_begin + (int64_t)wave * 64 * CPL; blk < slice_end; blk += stride) {
         const int64_t p0 = blk + (int64_t)lane * CPL;
+        uint32_t shared = kKeyInf;
+        const bool asking = SHARE && ask.wanted;
+        if (asking) shared = ask_shared_thresholds<M, TQ>(s, a);
+        ask.wanted = false;
         uint32_t w[4] = {0u, 0u, 0u, 0u};
         if (p0 + CPL <= slice_end) {
             const uint4 v = *(const uint4 *)(a.codes + p0 * M);
@@ -634,6 +732,7 @@ adc_kernel(ScanArgs a)
             w[0] = v.x;
             w[1] = v.y;
         }
+        if (asking) adopt_shared_thresholds<M, TQ>(s, shared);
         // thresholds of the tile, refreshed once per block: lane q holds thr[q]
         const float thr_v = s.thr[lane & (TQ - 1)];
 #pragma unroll
@@ -666,10 +765,11 @@ adc_kernel(ScanArgs a)
                     any |= ballot64(pass[i]);
                 }
                 if (any) {
+                    ask.wanted = true;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const uint64_t mine = ballot64(pass[i]);
-                        if (mine) insert_candidates<M, TQ, SHARE>(s, a, g * 4 + i, q0 + g * 4 + i, mine, d[i], rel);
+                        if (mine) insert_candidates<M, TQ, SHARE, SHARE>(s, a, g * 4 + i, mine, d[i], rel);
                     }
                 }
             }
@@ -679,7 +779,7 @@ adc_kernel(ScanArgs a)
 
     for (int e = tid; e < nvq * a.k; e += NW * 64) {
         const int q = e / a.k, r = e - q * a.k;
-        const bool have = r < s.cnt[q];
+        const bool have = r < s.lock[q];
         const uint64_t ent = s.top[q * a.kpad + r];
         const int64_t o = ((q0 + q) * a.nslice + slice) * a.k + r;
         a.part_d[o] = have ? entry_dist(ent) : __builtin_inff();
