@@ -63,9 +63,25 @@ def test_assignment_and_residual_codes(ivf):
     assert sorted(s["lids"].tolist()) == list(range(len(s["xb"])))
 
 
+@pytest.fixture(scope="module")
+def ivf_many_lists():
+    import paper_1609_01882_amd as psc
+    return psc, build_ivf(psc, 60_001, 320, seed=72)
+
+
 @pytest.mark.parametrize("nprobe,ht,k", [(8, 24, 10), (8, 64, 100), (1, 20, 10), (64, 28, 100), (3, 0, 5)])
 def test_ivf_search_matches_oracle(ivf, nprobe, ht, k):
-    psc, s = ivf
+    _check_ivf_search(ivf, nprobe, ht, k)
+
+
+@pytest.mark.parametrize("nprobe,ht,k", [(100, 28, 10), (200, 64, 20), (320, 24, 100)])
+def test_ivf_search_with_many_probes(ivf_many_lists, nprobe, ht, k):
+    """More than 64 / 128 / 256 partial lists per query: the merge spreads several over a lane."""
+    _check_ivf_search(ivf_many_lists, nprobe, ht, k)
+
+
+def _check_ivf_search(fixture, nprobe, ht, k):
+    psc, s = fixture
     idx = s["idx"]
     xq = W.sift_like(37, seed=70, stream=3)
     ids, d, probed, qcodes = idx.ivf_search(_dev(xq), nprobe, ht, k, want_debug=True)
@@ -78,7 +94,7 @@ def test_ivf_search_matches_oracle(ivf, nprobe, ht, k):
     for q, p in diff:
         a, b = own["coarse_d"][q, own["probed"][q, p]], own["coarse_d"][q, probed[q, p]]
         assert abs(a - b) <= RTOL * a
-    assert len(diff) <= 2
+    assert len(diff) <= max(2, 0.005 * probed.size)   # a near-tie swaps two neighbouring places
     # same decisions (probed lists, per-list bit strings) -> same survivors, ids and distances
     ref = O.ivf_search(xq, s["cb"], s["coarse"], s["offsets"], s["lcodes"], s["lids"], nprobe, ht, k,
                        probed_in=probed, qcodes_in=qcodes)

@@ -68,6 +68,15 @@ def test_scan_random_codes(psc, m, n, nq, k, lut_kind):
             assert nd == 0 and np.array_equal(got_d[ref["ids"] >= 0], ref["dists"][ref["ids"] >= 0])
 
 
+def test_many_slices_for_few_queries(psc):
+    """Two queries over 3M codes: 256 database slices, whose partial lists the merge takes four to a lane."""
+    codes, qcodes, lut = _rand_problem(8, 3_000_001, 2, seed=321, lut_kind="float")
+    for ht, k in ((22, 10), (64, 3)):
+        got_ids, got_d = _run(psc, lut, qcodes, codes, ht, k)
+        ref = O.scan(lut.astype(np.float64), qcodes, codes, ht, k)
+        assert_topk_matches(got_ids, got_d, ref, lut.astype(np.float64), qcodes, codes, ht, what=f"many slices ht={ht}")
+
+
 @pytest.mark.parametrize("m", [8, 16])
 def test_hamming_filter_is_bit_exact(psc, m):
     codes, qcodes, _ = _rand_problem(m, 20_011, 23, seed=7 + m, lut_kind="int")
