@@ -280,6 +280,9 @@ int psc_search(const psc_index *idx, const float *q_dev, int64_t nq, const uint8
 // codes are the stored codes of the chunk's rows and which never returns a row to itself.
 // ---------------------------------------------------------------------------------------------
 static const int64_t kGraphChunk = 32768;
+// Inverted file: the jobs of this many nearest lists of every query are scanned ahead of the rest.
+// (100M vectors, 4096 lists, 64 probes, k=100: 17.8 ms with none, 15.4 with 2, 15.9 with 16.)
+static const int kPilotProbes = 2;
 
 // Scan workspace that serves both the full chunks and the shorter last chunk (whose plan may
 // cut the database into more slices).
@@ -541,7 +544,7 @@ int ivf_layout(const psc_index *idx, int64_t nq, int nprobe, int k, IvfLayout *L
     int rc = plan_scan(idx->m, L->njobs > 0 ? L->njobs : 1, idx->list_n, k, &L->plan);
     if (rc != PSC_OK) return rc;
     L->nblk = (nq + 15) / 16;
-    L->max_tiles = L->njobs / L->plan.tq + idx->nlist;
+    L->max_tiles = L->njobs / L->plan.tq + 2 * (int64_t)idx->nlist;
     size_t o = 0;
     auto take = [&](size_t bytes) {
         size_t at = o;
@@ -552,9 +555,9 @@ int ivf_layout(const psc_index *idx, int64_t nq, int nprobe, int k, IvfLayout *L
     L->off_gthr = take((size_t)nq * sizeof(uint32_t));
     L->off_dist = take((size_t)nq * idx->nlist * sizeof(float));
     L->off_probed = take((size_t)L->njobs * sizeof(int32_t));
-    L->off_hist = take((size_t)L->nblk * idx->nlist * sizeof(int32_t));
-    L->off_list_begin = take((size_t)(idx->nlist + 1) * sizeof(int32_t));
-    L->off_tile_begin = take((size_t)(idx->nlist + 1) * sizeof(int32_t));
+    L->off_hist = take((size_t)L->nblk * 2 * idx->nlist * sizeof(int32_t));
+    L->off_list_begin = take((size_t)(2 * idx->nlist + 1) * sizeof(int32_t));
+    L->off_tile_begin = take((size_t)(2 * idx->nlist + 1) * sizeof(int32_t));
     L->off_job_q = take((size_t)L->njobs * sizeof(int32_t));
     L->off_job_list = take((size_t)L->njobs * sizeof(int32_t));
     L->off_job_slot = take((size_t)L->njobs * sizeof(int32_t));
@@ -621,7 +624,7 @@ int psc_ivf_search(const psc_index *idx, const float *q_dev, int64_t nq, int npr
         PSC_HIP_TRY(hipMemcpyAsync(probed_out_dev, probed, (size_t)L.njobs * sizeof(int32_t),
                                    hipMemcpyDeviceToDevice, s));
     // 2. jobs grouped by list, cut into tiles
-    rc = launch_build_jobs(probed, nq, nprobe, idx->nlist, L.plan.tq, jb, s);
+    rc = launch_build_jobs(probed, nq, nprobe, idx->nlist, kPilotProbes, L.plan.tq, jb, s);
     if (rc != PSC_OK) return rc;
     // 3. per-job residual tables and query codes (rows in job order)
     RowMap map;
@@ -638,7 +641,7 @@ int psc_ivf_search(const psc_index *idx, const float *q_dev, int64_t nq, int npr
     }
     // 4. the fused scan over the tiles, 5. one merge per query over its nprobe partial lists
     return launch_ivf_scan(idx->m, L.plan.tq, L.plan.kpad, L.plan.lds_bytes, lut, qcodes, idx->list_codes_dev,
-                           idx->list_n, ht, k, jb.tiles, jb.tile_begin + idx->nlist, L.max_tiles,
+                           idx->list_n, ht, k, jb.tiles, jb.tile_begin + 2 * idx->nlist, L.max_tiles,
                            idx->list_off_dev, idx->list_ids_dev, jb.job_slot, jb.job_q,
                            (uint32_t *)(w + L.off_gthr), (float *)(w + L.off_part_d),
                            (int64_t *)(w + L.off_part_i), (int *)(w + L.off_status), nq, nprobe, ids_dev,

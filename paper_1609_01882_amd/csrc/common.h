@@ -99,17 +99,18 @@ int launch_select_probes(const float *dist_dev, int64_t n, int nlist, int nprobe
 int launch_nearest_centroid(const float *x_dev, int64_t n, int dim, const float *cent_dev, int nlist,
                             int32_t *assign_dev, hipStream_t s);
 struct IvfJobBuffers {
-    int32_t *hist;       // [nblk][nlist]
-    int32_t *list_begin; // [nlist+1] first sorted job of each list
-    int32_t *tile_begin; // [nlist+1] first tile of each list; tile_begin[nlist] = tile count
+    int32_t *hist;       // [nblk][2 nlist]
+    int32_t *list_begin; // [2 nlist + 1] first sorted job of each sort key (see launch_build_jobs)
+    int32_t *tile_begin; // [2 nlist + 1] first tile of each key; tile_begin[2 nlist] = tile count
     int32_t *job_q;      // [njobs] query of the sorted job
     int32_t *job_list;   // [njobs]
     int32_t *job_slot;   // [njobs] query * nprobe + probe rank
     void *tiles;         // [max_tiles] x 16 bytes
 };
-// Sort the (query, probe) jobs by list (stable in query order) and cut each list's jobs into
-// tiles of at most tq.
-int launch_build_jobs(const int32_t *probed_dev, int64_t nq, int nprobe, int nlist, int tq,
+// Sort the (query, probe) jobs by key (stable in query order) and cut each key's jobs into tiles
+// of at most tq.  Key = list for the jobs of a query's `pilot` nearest lists, nlist + list for
+// the others: the nearest lists' tiles come first.
+int launch_build_jobs(const int32_t *probed_dev, int64_t nq, int nprobe, int nlist, int pilot, int tq,
                       const IvfJobBuffers &b, hipStream_t s);
 
 int launch_unsort_rows(const uint8_t *src_dev, const int32_t *job_slot_dev, int64_t njobs, int row_bytes,

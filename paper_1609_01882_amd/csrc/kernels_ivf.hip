@@ -168,13 +168,21 @@ __global__ void zero_i32_kernel(int32_t *p, int64_t n)
     if (e < n) p[e] = 0;
 }
 
-__global__ void job_hist_kernel(const int32_t *__restrict__ probed, int64_t nq, int nprobe, int nlist,
+// Sort key of job (q, p): its list, with the jobs of a query's `pilot` nearest lists ahead of all
+// others (keys [0, nlist) before keys [nlist, 2 nlist)).  Workgroups start in tile order, so the
+// nearest lists of every query are scanned first and their k-th best distances are published
+// before the bulk of the lists is looked at, which then rejects most survivors at the threshold
+// test instead of inserting them into lists.
+__device__ __forceinline__ int job_key(int list, int p, int nlist, int pilot) { return list + (p >= pilot ? nlist : 0); }
+
+__global__ void job_hist_kernel(const int32_t *__restrict__ probed, int64_t nq, int nprobe, int nlist, int pilot,
                                 int32_t *__restrict__ hist)
 {
     const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= nq * nprobe) return;
     const int64_t q = j / nprobe;
-    atomicAdd(&hist[(q / kJobBlockQ) * nlist + probed[j]], 1);
+    const int p = (int)(j - q * nprobe);
+    atomicAdd(&hist[(q / kJobBlockQ) * (2 * nlist) + job_key(probed[j], p, nlist, pilot)], 1);
 }
 
 // hist[b][l] -> number of jobs of list l in blocks before b; totals[l] = jobs of list l.
@@ -233,19 +241,20 @@ job_list_prefix_kernel(int32_t *__restrict__ list_begin, int32_t *__restrict__ t
 // One workgroup per block of kJobBlockQ queries, queries taken in order: job (q, p) goes to
 // list_begin[l] + (jobs of l in earlier blocks) + (jobs of l earlier in this block).
 __global__ void __launch_bounds__(256)
-job_scatter_kernel(const int32_t *__restrict__ probed, int64_t nq, int nprobe, int nlist,
+job_scatter_kernel(const int32_t *__restrict__ probed, int64_t nq, int nprobe, int nlist, int pilot,
                    int32_t *__restrict__ hist, const int32_t *__restrict__ list_begin,
                    int32_t *__restrict__ job_q, int32_t *__restrict__ job_list, int32_t *__restrict__ job_slot)
 {
     const int64_t b = blockIdx.x;
-    int32_t *run = hist + b * nlist;
+    int32_t *run = hist + b * (2 * nlist);
     for (int qi = 0; qi < kJobBlockQ; ++qi) {
         const int64_t q = b * kJobBlockQ + qi;
         if (q >= nq) break;
         for (int p = threadIdx.x; p < nprobe; p += 256) {  // the lists of one query are distinct
             const int l = probed[q * nprobe + p];
-            // the only writer of run[l] in this turn; the atomic keeps it coherent across turns
-            const int32_t at = list_begin[l] + atomicAdd(&run[l], 1);
+            const int key = job_key(l, p, nlist, pilot);
+            // the only writer of run[key] in this turn; the atomic keeps it coherent across turns
+            const int32_t at = list_begin[key] + atomicAdd(&run[key], 1);
             job_q[at] = (int32_t)q;
             job_list[at] = l;
             job_slot[at] = (int32_t)(q * nprobe + p);
@@ -261,10 +270,11 @@ struct TileRec {
 __global__ void job_tiles_kernel(const int32_t *__restrict__ list_begin, const int32_t *__restrict__ tile_begin,
                                  int nlist, int tq, TileRec *__restrict__ tiles)
 {
-    const int l = blockIdx.x * blockDim.x + threadIdx.x;
-    if (l >= nlist) return;
-    const int32_t jb = list_begin[l], cnt = list_begin[l + 1] - jb;
-    int32_t t = tile_begin[l];
+    const int key = blockIdx.x * blockDim.x + threadIdx.x;
+    if (key >= 2 * nlist) return;
+    const int l = key < nlist ? key : key - nlist;
+    const int32_t jb = list_begin[key], cnt = list_begin[key + 1] - jb;
+    int32_t t = tile_begin[key];
     for (int32_t o = 0; o < cnt; o += tq, ++t) tiles[t] = TileRec{jb + o, min(tq, cnt - o), l, 0};
 }
 
@@ -345,22 +355,23 @@ int launch_nearest_centroid(const float *x_dev, int64_t n, int dim, const float 
     return PSC_OK;
 }
 
-int launch_build_jobs(const int32_t *probed_dev, int64_t nq, int nprobe, int nlist, int tq,
+int launch_build_jobs(const int32_t *probed_dev, int64_t nq, int nprobe, int nlist, int pilot, int tq,
                       const IvfJobBuffers &b, hipStream_t s)
 {
     const int64_t njobs = nq * nprobe;
     const int64_t nblk = (nq + kJobBlockQ - 1) / kJobBlockQ;
-    PSC_REQUIRE(njobs < 0x7fffffffLL && nblk * nlist < ((int64_t)1 << 40), "too many jobs");
-    const int64_t hcells = nblk * nlist;
+    const int nkeys = 2 * nlist;
+    PSC_REQUIRE(njobs < 0x7fffffffLL && nblk * nkeys < ((int64_t)1 << 40), "too many jobs");
+    const int64_t hcells = nblk * nkeys;
     hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)((hcells + 255) / 256)), dim3(256), 0, s, b.hist, hcells);
     hipLaunchKernelGGL(job_hist_kernel, dim3((unsigned)((njobs + 255) / 256)), dim3(256), 0, s, probed_dev, nq,
-                       nprobe, nlist, b.hist);
-    hipLaunchKernelGGL(job_column_prefix_kernel, dim3((unsigned)((nlist + 255) / 256)), dim3(256), 0, s, b.hist,
-                       nblk, nlist, b.list_begin);
-    hipLaunchKernelGGL(job_list_prefix_kernel, dim3(1), dim3(1024), 0, s, b.list_begin, b.tile_begin, nlist, tq);
+                       nprobe, nlist, pilot, b.hist);
+    hipLaunchKernelGGL(job_column_prefix_kernel, dim3((unsigned)((nkeys + 255) / 256)), dim3(256), 0, s, b.hist,
+                       nblk, nkeys, b.list_begin);
+    hipLaunchKernelGGL(job_list_prefix_kernel, dim3(1), dim3(1024), 0, s, b.list_begin, b.tile_begin, nkeys, tq);
     hipLaunchKernelGGL(job_scatter_kernel, dim3((unsigned)nblk), dim3(256), 0, s, probed_dev, nq, nprobe, nlist,
-                       b.hist, b.list_begin, b.job_q, b.job_list, b.job_slot);
-    hipLaunchKernelGGL(job_tiles_kernel, dim3((unsigned)((nlist + 255) / 256)), dim3(256), 0, s, b.list_begin,
+                       pilot, b.hist, b.list_begin, b.job_q, b.job_list, b.job_slot);
+    hipLaunchKernelGGL(job_tiles_kernel, dim3((unsigned)((nkeys + 255) / 256)), dim3(256), 0, s, b.list_begin,
                        b.tile_begin, nlist, tq, (TileRec *)b.tiles);
     PSC_HIP_TRY(hipGetLastError());
     return PSC_OK;
