@@ -352,13 +352,22 @@ int psc_knn_graph(const psc_index *idx, const float *x_dev, const uint8_t *codes
 static int sync_coarse_to_device(const psc_index *idx)
 {
     if (idx->coarse_current) return PSC_OK;
-    const size_t bytes = idx->coarse_host.size() * sizeof(float);
+    // device image: the nlist centroids, then their mean (the origin the search's tables are taken from)
+    const size_t dim = (size_t)idx->dim, nl = (size_t)idx->nlist;
+    std::vector<float> img(idx->coarse_host);
+    img.resize((nl + 1) * dim);
+    for (size_t t = 0; t < dim; ++t) {
+        double acc = 0.0;
+        for (size_t l = 0; l < nl; ++l) acc += idx->coarse_host[l * dim + t];
+        img[nl * dim + t] = (float)(acc / (double)nl);
+    }
+    const size_t bytes = img.size() * sizeof(float);
     if (idx->coarse_dev) {
         PSC_HIP_TRY(hipFree(idx->coarse_dev));
         idx->coarse_dev = nullptr;
     }
     PSC_HIP_TRY(hipMalloc((void **)&idx->coarse_dev, bytes));
-    PSC_HIP_TRY(hipMemcpy(idx->coarse_dev, idx->coarse_host.data(), bytes, hipMemcpyHostToDevice));
+    PSC_HIP_TRY(hipMemcpy(idx->coarse_dev, img.data(), bytes, hipMemcpyHostToDevice));
     idx->coarse_current = true;
     return PSC_OK;
 }
@@ -530,7 +539,7 @@ struct IvfLayout {
     ScanPlan plan;
     int64_t njobs, nblk, max_tiles;
     size_t off_status, off_gthr, off_dist, off_probed, off_hist, off_list_begin, off_tile_begin, off_job_q, off_job_list,
-        off_job_slot, off_tiles, off_lut, off_qcodes, off_part_d, off_part_i, total;
+        off_job_slot, off_tiles, off_lut, off_list_tab, off_qcodes, off_part_d, off_part_i, total;
 };
 
 int ivf_layout(const psc_index *idx, int64_t nq, int nprobe, int k, IvfLayout *L)
@@ -562,7 +571,8 @@ int ivf_layout(const psc_index *idx, int64_t nq, int nprobe, int k, IvfLayout *L
     L->off_job_list = take((size_t)L->njobs * sizeof(int32_t));
     L->off_job_slot = take((size_t)L->njobs * sizeof(int32_t));
     L->off_tiles = take((size_t)L->max_tiles * 16);
-    L->off_lut = take((size_t)L->njobs * idx->m * kCentroids * sizeof(float));
+    L->off_lut = take((size_t)nq * idx->m * kCentroids * sizeof(float));
+    L->off_list_tab = take((size_t)idx->nlist * idx->m * kCentroids * sizeof(float));
     L->off_qcodes = take((size_t)L->njobs * idx->m);
     L->off_part_d = take((size_t)L->njobs * k * sizeof(float));
     L->off_part_i = take((size_t)L->njobs * k * sizeof(int64_t));
@@ -626,26 +636,25 @@ int psc_ivf_search(const psc_index *idx, const float *q_dev, int64_t nq, int npr
     // 2. jobs grouped by list, cut into tiles
     rc = launch_build_jobs(probed, nq, nprobe, idx->nlist, kPilotProbes, L.plan.tq, jb, s);
     if (rc != PSC_OK) return rc;
-    // 3. per-job residual tables and query codes (rows in job order)
+    // 3. the queries' and the lists' shares of the residual tables (put together per tile by the
+    //    scan, which also derives each job's query code from them)
     RowMap map;
-    map.row_idx = jb.job_q;
-    map.sub = idx->coarse_dev;
-    map.sub_idx = jb.job_list;
-    rc = launch_lut(idx->cb_dev, idx->dim, idx->m, q_dev, L.njobs, map, lut, s);
+    map.sub = idx->coarse_dev + (size_t)idx->nlist * idx->dim;  // the mean coarse centroid
+    rc = launch_lut(idx->cb_dev, idx->dim, idx->m, q_dev, nq, map, lut, s);
     if (rc != PSC_OK) return rc;
-    rc = launch_encode(idx->cb_dev, idx->dim, idx->m, q_dev, L.njobs, map, qcodes, s);
+    float *list_tab = (float *)(w + L.off_list_tab);
+    rc = launch_list_tables(idx->cb_dev, idx->dim, idx->m, idx->coarse_dev, idx->nlist, list_tab, s);
     if (rc != PSC_OK) return rc;
-    if (qcodes_out_dev) {
-        rc = launch_unsort_rows(qcodes, jb.job_slot, L.njobs, idx->m, qcodes_out_dev, s);
-        if (rc != PSC_OK) return rc;
-    }
     // 4. the fused scan over the tiles, 5. one merge per query over its nprobe partial lists
-    return launch_ivf_scan(idx->m, L.plan.tq, L.plan.kpad, L.plan.lds_bytes, lut, qcodes, idx->list_codes_dev,
-                           idx->list_n, ht, k, jb.tiles, jb.tile_begin + 2 * idx->nlist, L.max_tiles,
-                           idx->list_off_dev, idx->list_ids_dev, jb.job_slot, jb.job_q,
-                           (uint32_t *)(w + L.off_gthr), (float *)(w + L.off_part_d),
-                           (int64_t *)(w + L.off_part_i), (int *)(w + L.off_status), nq, nprobe, ids_dev,
-                           dists_dev, s);
+    rc = launch_ivf_scan(idx->m, L.plan.tq, L.plan.kpad, L.plan.lds_bytes, lut, list_tab, q_dev, idx->coarse_dev,
+                         idx->dim, idx->nlist, qcodes, idx->list_codes_dev, idx->list_n, ht, k, jb.tiles,
+                         jb.tile_begin + 2 * idx->nlist, L.max_tiles, idx->list_off_dev, idx->list_ids_dev,
+                         jb.job_slot, jb.job_q, (uint32_t *)(w + L.off_gthr), (float *)(w + L.off_part_d),
+                         (int64_t *)(w + L.off_part_i), (int *)(w + L.off_status), nq, nprobe, ids_dev,
+                         dists_dev, s);
+    if (rc != PSC_OK) return rc;
+    if (qcodes_out_dev) rc = launch_unsort_rows(qcodes, jb.job_slot, L.njobs, idx->m, qcodes_out_dev, s);
+    return rc;
 }
 
 int psc_workspace_status(void *workspace_dev, psc_stream stream)

@@ -47,7 +47,7 @@ void host_anneal(const float *cent, int dsub, int64_t n_iter, double t0, double 
 struct RowMap {
     const int32_t *row_idx = nullptr;
     const float *sub = nullptr;       // [*][dim] vectors to subtract (coarse centroids)
-    const int32_t *sub_idx = nullptr; // which one, per row
+    const int32_t *sub_idx = nullptr; // which one, per row (none: the first, for every row)
 };
 int launch_lut(const float *cb_dev, int dim, int m, const float *x_dev, int64_t nrows,
                const RowMap &map, float *lut_dev, hipStream_t s);
@@ -79,8 +79,12 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
                 const uint8_t *codes_dev, int64_t n, int ht, int k, int64_t skip_first,
                 bool clear_status, int64_t *ids_dev, float *dists_dev, void *ws, size_t ws_bytes,
                 hipStream_t s);
-int launch_ivf_scan(int m, int tq, int kpad, size_t lds_bytes, const float *lut_dev,
-                    const uint8_t *qcodes_dev, const uint8_t *codes_dev, int64_t n, int ht, int k,
+// lut_dev: tables of the queries minus the mean coarse centroid, [nq][m][256]; list_tab_dev:
+// the lists' share of the residual tables (launch_list_tables); job_qcodes_dev: out, the query
+// code of every job, in job order.
+int launch_ivf_scan(int m, int tq, int kpad, size_t lds_bytes, const float *lut_dev, const float *list_tab_dev,
+                    const float *queries_dev, const float *coarse_dev, int dim, int nlist,
+                    uint8_t *job_qcodes_dev, const uint8_t *codes_dev, int64_t n, int ht, int k,
                     const void *tiles_dev, const int *ntiles_dev, int64_t max_tiles,
                     const int64_t *list_off_dev, const int32_t *ext_ids_dev, const int32_t *job_slot_dev,
                     const int32_t *job_q_dev, uint32_t *gthr_dev, float *part_d, int64_t *part_i, int *status,
@@ -112,6 +116,11 @@ struct IvfJobBuffers {
 // the others: the nearest lists' tiles come first.
 int launch_build_jobs(const int32_t *probed_dev, int64_t nq, int nprobe, int nlist, int pilot, int tq,
                       const IvfJobBuffers &b, hipStream_t s);
+
+// list_tab[l][j][c] = 2 (g_l - o)_j . C[j][c] for the coarse centroids g_l = rows 0..nlist-1 of
+// coarse_dev and their mean o = row nlist.
+int launch_list_tables(const float *cb_dev, int dim, int m, const float *coarse_dev, int nlist,
+                       float *list_tab_dev, hipStream_t s);
 
 int launch_unsort_rows(const uint8_t *src_dev, const int32_t *job_slot_dev, int64_t njobs, int row_bytes,
                        uint8_t *dst_dev, hipStream_t s);

@@ -278,6 +278,24 @@ __global__ void job_tiles_kernel(const int32_t *__restrict__ list_begin, const i
     for (int32_t o = 0; o < cnt; o += tq, ++t) tiles[t] = TileRec{jb + o, min(tq, cnt - o), l, 0};
 }
 
+// The lists' share of the residual tables: see launch_list_tables.  One workgroup per (list,
+// sub-quantizer), thread c owns centroid c.
+__global__ void __launch_bounds__(256)
+list_tables_kernel(const float *__restrict__ cb, int dim, int m, const float *__restrict__ coarse, int nlist,
+                   float *__restrict__ out)
+{
+    extern __shared__ float gt[];  // (g_l - o)_j
+    const int l = blockIdx.x, j = blockIdx.y, c = threadIdx.x;
+    const int dsub = dim / m;
+    for (int t = threadIdx.x; t < dsub; t += 256)
+        gt[t] = coarse[(int64_t)l * dim + j * dsub + t] - coarse[(int64_t)nlist * dim + j * dsub + t];
+    __syncthreads();
+    const float *crow = cb + ((int64_t)j * 256 + c) * dsub;
+    float acc = 0.f;
+    for (int t = 0; t < dsub; ++t) acc = fmaf(gt[t], crow[t], acc);
+    out[((int64_t)l * m + j) * 256 + c] = 2.0f * acc;
+}
+
 // Copy per-job rows (job-sorted) back to (query, probe) order.
 __global__ void unsort_rows_kernel(const uint8_t *__restrict__ src, const int32_t *__restrict__ job_slot,
                                    int64_t njobs, int row_bytes, uint8_t *__restrict__ dst)
@@ -289,6 +307,16 @@ __global__ void unsort_rows_kernel(const uint8_t *__restrict__ src, const int32_
 }
 
 }  // namespace
+
+int launch_list_tables(const float *cb_dev, int dim, int m, const float *coarse_dev, int nlist,
+                       float *list_tab_dev, hipStream_t s)
+{
+    PSC_REQUIRE(dim % m == 0 && nlist >= 1, "bad shape");
+    hipLaunchKernelGGL(list_tables_kernel, dim3((unsigned)nlist, (unsigned)m), dim3(256),
+                       (size_t)(dim / m) * sizeof(float), s, cb_dev, dim, m, coarse_dev, nlist, list_tab_dev);
+    PSC_HIP_TRY(hipGetLastError());
+    return PSC_OK;
+}
 
 int launch_unsort_rows(const uint8_t *src_dev, const int32_t *job_slot_dev, int64_t njobs, int row_bytes,
                        uint8_t *dst_dev, hipStream_t s)

@@ -16,7 +16,7 @@ namespace {
 
 __device__ __forceinline__ float sub_term(const RowMap &map, int64_t r, int dim, int col)
 {
-    return map.sub ? map.sub[(int64_t)map.sub_idx[r] * dim + col] : 0.0f;
+    return map.sub ? map.sub[(int64_t)(map.sub_idx ? map.sub_idx[r] : 0) * dim + col] : 0.0f;
 }
 
 // One workgroup = one sub-quantizer j and ROWS consecutive rows; thread c owns centroid c,

@@ -63,6 +63,16 @@ struct ScanArgs {
     const int64_t *list_off;  // [nlist+1] list boundaries in `codes`
     const int32_t *ext_ids;   // [n] id of each stored code
     const int32_t *job_slot;  // [njobs] partial list (query * nprobe + probe) a job writes
+    // Residual tables of the inverted file, never stored per job.  With o the mean coarse
+    // centroid, q~ = q - o and g~ = g - o for the coarse centroid g of the tile's list,
+    //   ||(q - g)_j - c||^2 = ||q~_j - c||^2  +  2 g~_j . c  +  g~_j . (g~_j - 2 q~_j)
+    //                       = lut[query][j][c] + list_tab[list][j][c] + (one number per job and j),
+    // which a tile puts together in LDS.  The query code of a job is the arg-min of those rows.
+    const float *list_tab;    // [nlist][M][256]
+    const float *queries;     // [nq][dim] raw query vectors
+    const float *coarse;      // [nlist + 1][dim] coarse centroids, then their mean
+    uint8_t *job_qcodes;      // [njobs][M] out: query code of each job
+    int dim, nlist;
 };
 
 __device__ __forceinline__ uint64_t ballot64(bool p) { return __ballot(p); }
@@ -124,6 +134,8 @@ struct Lds {
     lds_vf32 *thr;   // [TQ] bound on the query's k-th best distance (+inf while nothing is known)
     lds_i32 *lock;   // [TQ] number of entries in the list, or kLocked while a wave works on it
     lds_i32 *gidx;   // [TQ] the slot's query as an index into the shared thresholds (-1: empty slot)
+    lds_f32 *sterm;  // [TQ][M] inverted file: the per-job, per-sub-quantizer constant of the tables
+    lds_u32 *qcw;    // [TQ][M/4] inverted file: the jobs' query codes
     lds_u32 *queue;  // [nwaves][kQueueCap]; private to a wave: LDS keeps a wave's accesses in order
     lds_u32 *dump;   // [nwaves][64] where lanes with nothing to queue write
     __device__ __forceinline__ Lds(PSC_LDS unsigned char *base, int kpad, int nwaves)
@@ -133,10 +145,28 @@ struct Lds {
         thr = (lds_vf32 *)(top + TQ * kpad);
         lock = (lds_i32 *)(thr + TQ);
         gidx = lock + TQ;
-        queue = (lds_u32 *)(gidx + TQ);
+        sterm = (lds_f32 *)(gidx + TQ);
+        qcw = (lds_u32 *)(sterm + TQ * M);
+        queue = qcw + TQ * M / 4;
         dump = queue + nwaves * kQueueCap;
     }
 };
+
+// Smallest value of v over the wave, in every lane: four row-local steps on the data-parallel
+// path, then the four row results through scalar registers.
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v)
+{
+    auto step = [](uint32_t x, uint32_t y) { return y < x ? y : x; };
+    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xB1, 0xf, 0xf, false));   // lane ^ 1
+    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x4E, 0xf, 0xf, false));   // lane ^ 2
+    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x141, 0xf, 0xf, false));  // mirror in 8
+    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x140, 0xf, 0xf, false));  // mirror in 16
+    const uint32_t r0 = (uint32_t)__builtin_amdgcn_readlane((int)v, 0);
+    const uint32_t r1 = (uint32_t)__builtin_amdgcn_readlane((int)v, 16);
+    const uint32_t r2 = (uint32_t)__builtin_amdgcn_readlane((int)v, 32);
+    const uint32_t r3 = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+    return step(step(r0, r1), step(r2, r3));
+}
 
 constexpr int kLocked = -1;
 
@@ -406,12 +436,13 @@ scan_kernel(ScanArgs a)
     // flat mode: tile -> (query tile, database slice); inverted-file mode: tile -> descriptor.
     // [valid_begin, slice_end) is scanned; slice_begin (<= valid_begin) is where positions count
     // from and is a whole number of 16-byte loads into `codes`.
-    int slice = 0;
+    int slice = 0, tile_list = 0;
     int64_t q0, slice_begin, valid_begin, slice_end;
     int nvq;
     if constexpr (IVF) {
         if ((int)blockIdx.x >= *a.ntiles) return;  // the grid is an upper bound on the tile count
         const IvfTile t = a.tiles[blockIdx.x];
+        tile_list = t.list;
         q0 = t.job_begin;
         nvq = t.njobs;
         valid_begin = a.list_off[t.list];
@@ -427,9 +458,74 @@ scan_kernel(ScanArgs a)
         slice_end = (slice_begin + a.slice_len) < a.n ? (slice_begin + a.slice_len) : a.n;
     }
 
-    // ---- stage the tables, reset the lists
-    {
-        typedef float f32x4 __attribute__((ext_vector_type(4)));
+    // ---- per-slot state
+    if (tid < TQ) {
+        const int gi = tid < nvq ? (int)(IVF ? (int64_t)a.job_q[q0 + tid] : q0 + tid) : -1;
+        float t0 = __builtin_inff();
+        if constexpr (SHARE) {
+            if (gi >= 0) t0 = key_dist(__hip_atomic_load(&a.gthr[gi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        }
+        s.thr[tid] = t0;
+        s.lock[tid] = 0;
+        s.gidx[tid] = gi;
+    }
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    uint32_t qw[TQ][WPC];  // the tile's query codes, in scalar registers
+    if constexpr (IVF) {
+        // ---- residual tables put together in LDS (see ScanArgs::list_tab), query codes from them
+        const int dsub = a.dim / M;
+        if (tid < TQ * M) {  // the per-job constant g~_j . (g~_j - 2 q~_j)
+            const int q = tid / M, j = tid - q * M;
+            float acc = 0.f;
+            if (q < nvq) {
+                const float *qv = a.queries + (int64_t)a.job_q[q0 + q] * a.dim + j * dsub;
+                const float *gv = a.coarse + (int64_t)tile_list * a.dim + j * dsub;
+                const float *ov = a.coarse + (int64_t)a.nlist * a.dim + j * dsub;
+                for (int t = 0; t < dsub; ++t) {
+                    const float g = gv[t] - ov[t], x = qv[t] - ov[t];
+                    acc = fmaf(g, g - 2.0f * x, acc);
+                }
+            }
+            s.sterm[tid] = acc;
+        }
+        __syncthreads();
+        {
+            const f32x4 *tab = (const f32x4 *)(a.list_tab + (int64_t)tile_list * (M * 256));
+            PSC_LDS f32x4 *dst = (PSC_LDS f32x4 *)s.lut;
+            for (int e = tid; e < TQ * (M * 64); e += NW * 64) {
+                const int q = e / (M * 64), r = e - q * (M * 64);  // r: 16-byte entry of the job's table
+                f32x4 v = {0.f, 0.f, 0.f, 0.f};
+                if (q < nvq) {
+                    const f32x4 x = ((const f32x4 *)(a.lut + (int64_t)s.gidx[q] * (M * 256)))[r];
+                    v = (x + tab[r]) + s.sterm[q * M + (r >> 6)];
+                }
+                dst[e] = v;
+            }
+        }
+        __syncthreads();
+        // arg-min of every table row (lowest index on ties): one wave per row
+        for (int row = wave; row < TQ * M; row += NW) {
+            const f32x4 v = ((const PSC_LDS f32x4 *)s.lut)[row * 64 + lane];
+            float best = v.x;
+            int bi = 4 * lane;
+            if (v.y < best) { best = v.y; bi = 4 * lane + 1; }
+            if (v.z < best) { best = v.z; bi = 4 * lane + 2; }
+            if (v.w < best) { best = v.w; bi = 4 * lane + 3; }
+            const uint32_t key = dist_key(best);
+            const uint32_t wk = wave_min_u32(key);
+            const int win = __builtin_ctzll(ballot64(key == wk));  // lower lanes hold lower indices
+            const int code = __builtin_amdgcn_readlane(bi, win);
+            if (lane == 0) ((PSC_LDS volatile uint8_t *)s.qcw)[row] = (uint8_t)code;
+        }
+        __syncthreads();
+        if (tid < nvq * WPC) ((uint32_t *)a.job_qcodes)[q0 * WPC + tid] = s.qcw[tid];
+#pragma unroll
+        for (int q = 0; q < TQ; ++q) {
+#pragma unroll
+            for (int w = 0; w < WPC; ++w) qw[q][w] = __builtin_amdgcn_readfirstlane(s.qcw[q * WPC + w]);
+        }
+    } else {
+        // ---- stage the tables
         const f32x4 *src = (const f32x4 *)(a.lut + q0 * (M * 256));
         PSC_LDS f32x4 *dst = (PSC_LDS f32x4 *)s.lut;
         const int nvec = nvq * (M * 256 / 4);
@@ -438,21 +534,7 @@ scan_kernel(ScanArgs a)
             if (e < nvec) v = src[e];
             dst[e] = v;
         }
-        if (tid < TQ) {
-            float t0 = __builtin_inff();
-            if constexpr (SHARE) {
-                if (tid < nvq)
-                    t0 = key_dist(__hip_atomic_load(&a.gthr[IVF ? (int64_t)a.job_q[q0 + tid] : q0 + tid],
-                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-            }
-            s.thr[tid] = t0;
-            s.lock[tid] = 0;
-            s.gidx[tid] = tid < nvq ? (int)(IVF ? (int64_t)a.job_q[q0 + tid] : q0 + tid) : -1;
-        }
-    }
-    // ---- query codes -> scalar registers
-    uint32_t qw[TQ][WPC];
-    {
+        // ---- query codes -> scalar registers
         const uint32_t *qc = (const uint32_t *)a.qcodes;
 #pragma unroll
         for (int q = 0; q < TQ; ++q) {
@@ -461,8 +543,8 @@ scan_kernel(ScanArgs a)
             for (int w = 0; w < WPC; ++w)
                 qw[q][w] = __builtin_amdgcn_readfirstlane(qc[qq * WPC + w]);
         }
+        __syncthreads();
     }
-    __syncthreads();
 
     // bit TQ-1-q of a code's TQ-bit field <-> query slot q; only the first nvq slots are real
     const uint32_t qmask = ((1u << TQ) - 1u) & ~((1u << (TQ - nvq)) - 1u);
@@ -787,22 +869,6 @@ adc_kernel(ScanArgs a)
     }
 }
 
-// Smallest value of v over the wave, in every lane: four row-local steps on the data-parallel
-// path, then the four row results through scalar registers.
-__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v)
-{
-    auto step = [](uint32_t x, uint32_t y) { return y < x ? y : x; };
-    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xB1, 0xf, 0xf, false));   // lane ^ 1
-    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x4E, 0xf, 0xf, false));   // lane ^ 2
-    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x141, 0xf, 0xf, false));  // mirror in 8
-    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x140, 0xf, 0xf, false));  // mirror in 16
-    const uint32_t r0 = (uint32_t)__builtin_amdgcn_readlane((int)v, 0);
-    const uint32_t r1 = (uint32_t)__builtin_amdgcn_readlane((int)v, 16);
-    const uint32_t r2 = (uint32_t)__builtin_amdgcn_readlane((int)v, 32);
-    const uint32_t r3 = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
-    return step(step(r0, r1), step(r2, r3));
-}
-
 // Merge the nslice sorted partial lists of each query into the final k (one wave per query).
 // Lane l owns lists l, l + 64, ...: it keeps the head of each in registers together with the
 // entry after it, so that a step of the merge (pick the smallest head of the wave, advance that
@@ -1054,7 +1120,7 @@ int plan_scan(int m, int64_t nq, int64_t n, int k, ScanPlan *plan)
     for (int t : tq_options) {
         if (t > tq_cap) continue;
         if (m == 16 && t == 16) continue;  // 16 tables of 16 KiB do not fit
-        size_t need = (size_t)t * m * 256 * 4 + (size_t)t * p.kpad * 8 + (size_t)t * 12 +
+        size_t need = (size_t)t * m * 256 * 4 + (size_t)t * p.kpad * 8 + (size_t)t * 12 + (size_t)t * m * 5 +
                       (size_t)p.nwaves * (kQueueCap + 64) * 4;
         if (need <= kLdsBudget) {
             p.tq = t;
@@ -1159,6 +1225,12 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
     hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((nq + 255) / 256)), dim3(256), 0, s, a.gthr, nq, kKeyInf);
 
     if (clear_status) hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, s, a.status);
+    a.list_tab = nullptr;
+    a.queries = nullptr;
+    a.coarse = nullptr;
+    a.job_qcodes = nullptr;
+    a.dim = 0;
+    a.nlist = 0;
     a.tiles = nullptr;
     a.ntiles = nullptr;
     a.list_off = nullptr;
@@ -1183,20 +1255,28 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
 // Inverted-file scan: one workgroup per tile descriptor (up to `max_tiles`; the actual count is
 // read on the device), partial lists written at job_slot[job] * k, then one merge per query
 // over its nprobe partial lists.
-int launch_ivf_scan(int m, int tq, int kpad, size_t lds_bytes, const float *lut_dev,
-                    const uint8_t *qcodes_dev, const uint8_t *codes_dev, int64_t n, int ht, int k,
+int launch_ivf_scan(int m, int tq, int kpad, size_t lds_bytes, const float *lut_dev, const float *list_tab_dev,
+                    const float *queries_dev, const float *coarse_dev, int dim, int nlist,
+                    uint8_t *job_qcodes_dev, const uint8_t *codes_dev, int64_t n, int ht, int k,
                     const void *tiles_dev, const int *ntiles_dev, int64_t max_tiles,
                     const int64_t *list_off_dev, const int32_t *ext_ids_dev, const int32_t *job_slot_dev,
                     const int32_t *job_q_dev, uint32_t *gthr_dev, float *part_d, int64_t *part_i, int *status,
                     int64_t nq, int nprobe, int64_t *ids_dev, float *dists_dev, hipStream_t s)
 {
-    PSC_REQUIRE(((uintptr_t)codes_dev & 15) == 0 && ((uintptr_t)qcodes_dev & 15) == 0 &&
-                    ((uintptr_t)lut_dev & 15) == 0,
+    PSC_REQUIRE(((uintptr_t)codes_dev & 15) == 0 && ((uintptr_t)job_qcodes_dev & 15) == 0 &&
+                    ((uintptr_t)lut_dev & 15) == 0 && ((uintptr_t)list_tab_dev & 15) == 0,
                 "codes, query codes and tables must be 16-byte aligned");
     PSC_REQUIRE(max_tiles <= 0x7fffffffLL, "too many tiles");
+    PSC_REQUIRE(dim % m == 0, "dim must be a multiple of m");
     ScanArgs a;
     a.lut = lut_dev;
-    a.qcodes = qcodes_dev;
+    a.qcodes = nullptr;
+    a.list_tab = list_tab_dev;
+    a.queries = queries_dev;
+    a.coarse = coarse_dev;
+    a.job_qcodes = job_qcodes_dev;
+    a.dim = dim;
+    a.nlist = nlist;
     a.codes = codes_dev;
     a.skip_first = -1;
     a.nq = 0;
