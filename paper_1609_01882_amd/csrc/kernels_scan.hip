@@ -350,15 +350,19 @@ struct SharedAsk {
     bool wanted = true;  // wave-uniform: the previous batch changed a list (or there was none yet)
 };
 
-// Score the first `nvalid` (<= 64) entries of the wave's queue and feed the ones that beat the
-// current threshold to the lists.
+// Score `nvalid` (<= 64) entries of the wave's queue, starting at `ring`, and feed the ones that
+// beat the current threshold to the lists.  `slice_codes` = the codes of the tile's slice
+// (position 0 of the entries); `self0 + q` = the position query slot q must not return (graph
+// mode; a value no position can take otherwise).
 template <int M, int TQ, bool IVF, bool SHARE>
-__device__ __forceinline__ void drain(const Lds<M, TQ> &s, const ScanArgs &a, const lds_u32 *ring,
-                                      int nvalid, int64_t slice_begin, int64_t q0, SharedAsk &ask)
+__device__ __forceinline__ void drain(const Lds<M, TQ> &s, const ScanArgs &a, const lds_u32 *ring, int nvalid,
+                                      const uint8_t *slice_codes, int64_t slice_begin, uint32_t self0,
+                                      SharedAsk &ask)
 {
     const int lane = lane_id();
     const bool act = lane < nvalid;
     float d = __builtin_inff();
+    float thr = -__builtin_inff();
     uint32_t rel = 0;
     int q = 0;
     uint32_t shared = kKeyInf;
@@ -371,7 +375,7 @@ __device__ __forceinline__ void drain(const Lds<M, TQ> &s, const ScanArgs &a, co
         const uint32_t b = e >> kRelBits;
         q = (int)((TQ - 1) - (b & (TQ - 1)));
         rel = (e & kRelMask) + b / TQ;
-        const uint32_t *cw = (const uint32_t *)(a.codes + (slice_begin + rel) * M);
+        const uint32_t *cw = (const uint32_t *)(slice_codes + (uint64_t)rel * M);
         uint32_t w[M / 4];
         if constexpr (M == 8) {
             const uint2 v = *(const uint2 *)cw;
@@ -384,25 +388,35 @@ __device__ __forceinline__ void drain(const Lds<M, TQ> &s, const ScanArgs &a, co
             w[2] = v.z;
             w[3] = v.w;
         }
-        const lds_f32 *t = s.lut + q * (M * 256);
-        float acc = 0.f;
-#pragma unroll
-        for (int j = 0; j < M; ++j) {
-            const uint32_t byte = (w[j >> 2] >> (8 * (j & 3))) & 0xffu;
-            acc += t[j * 256 + byte];
+        if constexpr (SHARE) {
+            if (ask.wanted) adopt_shared_thresholds<M, TQ>(s, shared);
         }
+        // The gathers are issued last sub-quantizer first and summed first sub-quantizer first:
+        // LDS answers in order, so the first addition waits for all of them and the others for
+        // nothing (one wait instruction instead of one per addition).
+        const lds_f32 *t = s.lut + q * (M * 256);
+        thr = s.thr[q];
+        float tv[M];
+#pragma unroll
+        for (int j = M - 1; j >= 0; --j) {
+            const uint32_t byte = (w[j >> 2] >> (8 * (j & 3))) & 0xffu;
+            tv[j] = t[j * 256 + byte];
+        }
+        float acc = tv[0];
+#pragma unroll
+        for (int j = 1; j < M; ++j) acc += tv[j];
         d = acc;
+    } else {
+        if constexpr (SHARE) {
+            if (ask.wanted) adopt_shared_thresholds<M, TQ>(s, shared);
+        }
     }
-    if constexpr (SHARE) {
-        if (ask.wanted) adopt_shared_thresholds<M, TQ>(s, shared);
-    }
-    bool pass = act && d <= s.thr[q];
-    uint32_t key = rel;  // what breaks distance ties: the position, or the stored id
+    bool pass = d <= thr;  // (lanes without an entry: +inf <= -inf)
+    uint32_t key = rel;    // what breaks distance ties: the position, or the stored id
     if constexpr (IVF) {
         if (pass) key = (uint32_t)a.ext_ids[slice_begin + rel];
     } else {
-        if (a.skip_first >= 0)  // a vector is not its own neighbour
-            pass = pass && (slice_begin + (int64_t)rel) != a.skip_first + q0 + q;
+        pass = pass && rel != self0 + (uint32_t)q;  // a vector is not its own neighbour
     }
     uint64_t pm = ballot64(pass);
     ask.wanted = pm != 0;
@@ -555,6 +569,13 @@ scan_kernel(ScanArgs a)
     const uint32_t ring_base = (uint32_t)(uintptr_t)ring;  // LDS byte address of the wave's queue
     int fill = 0;  // wave-uniform: entries waiting in the queue (< 64 between turns)
     SharedAsk ask;
+    const uint8_t *slice_codes = a.codes + slice_begin * M;
+    // graph mode: slot q's own vector sits at position self0 + q of the slice (if it is in there)
+    uint32_t self0 = 0x80000000u;
+    if (!IVF && a.skip_first >= 0) {
+        const int64_t at = a.skip_first + q0 - slice_begin;
+        if (at > -64 && at < kMaxSliceLen) self0 = (uint32_t)at;
+    }
 
     const uint32_t bias = a.bias;
     const int64_t stride = (int64_t)NW * 64 * CB;
@@ -687,13 +708,8 @@ scan_kernel(ScanArgs a)
                 static_assert(kRelBits == 27, "the shift in the queueing loop");
                 if (fill < 64) break;  // every lane is out of bits
                 __builtin_amdgcn_wave_barrier();
-                drain<M, TQ, IVF, SHARE>(s, a, ring, 64, slice_begin, q0, ask);
-                // entries 64..fill-1 move to the front
-                fill -= 64;
-                uint32_t e = 0u;
-                if (lane < fill) e = ring[64 + lane];
-                __builtin_amdgcn_wave_barrier();
-                if (lane < fill) ring[lane] = e;
+                fill -= 64;  // the newest 64 entries go, the others stay where they are
+                drain<M, TQ, IVF, SHARE>(s, a, ring + fill, 64, slice_codes, slice_begin, self0, ask);
                 __builtin_amdgcn_wave_barrier();
             }
             // next mask of the super-block moves into place
@@ -704,7 +720,7 @@ scan_kernel(ScanArgs a)
     }
     if (fill > 0) {
         __builtin_amdgcn_wave_barrier();
-        drain<M, TQ, IVF, SHARE>(s, a, ring, fill, slice_begin, q0, ask);
+        drain<M, TQ, IVF, SHARE>(s, a, ring, fill, slice_codes, slice_begin, self0, ask);
     }
     __syncthreads();
 
