@@ -63,7 +63,7 @@ int launch_row_argmin(const float *lut_dev, int64_t nrows_total, uint8_t *codes_
 struct ScanPlan {
     int tq = 0;          // queries per workgroup tile
     int nwaves = 0;      // waves per workgroup
-    int kpad = 0;        // k rounded up to a multiple of 64
+    int kpad = 0;        // k rounded up to a multiple of 4: the stride of a list in LDS
     int nslice = 0;      // database slices (one workgroup per (query tile, slice))
     int64_t slice_len = 0;
     int64_t ntiles = 0;
