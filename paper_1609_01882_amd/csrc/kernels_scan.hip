@@ -21,6 +21,7 @@
 //
 // Ordering everywhere: (distance, id) ascending, lower id first on equal distance.
 #include <cstdlib>
+#include <type_traits>
 
 #include "common.h"
 
@@ -151,6 +152,81 @@ struct Lds {
         dump = queue + nwaves * kQueueCap;
     }
 };
+
+// ---- the Hamming test of Section 3.1, hand-written ------------------------------------------
+// For one code (words w) and NQ queries whose code words sit in scalar registers: per pair one
+// v_xor and one v_bcnt (population count plus accumulator) per 32-bit word, the accumulator
+// starting at `bias` = 0x7fffffff - ht so that its sign bit says "farther than ht", and one
+// v_alignbit that shifts that bit into `far`.  5 instructions per 64-bit pair, 9 per 128-bit
+// pair; written out because the compiler, left to itself, sometimes regroups the sum into
+// (count + count) + bias at the price of one more instruction per pair.
+#define PSC_PAIR_W2(QA, QB)                          \
+    "v_xor_b32_e32 %[t0], %[" QA "], %[w0]\n\t"       \
+    "v_bcnt_u32_b32 %[t0], %[t0], %[b]\n\t"           \
+    "v_xor_b32_e32 %[t1], %[" QB "], %[w1]\n\t"       \
+    "v_bcnt_u32_b32 %[t0], %[t1], %[t0]\n\t"          \
+    "v_alignbit_b32 %[far], %[far], %[t0], 31\n\t"
+#define PSC_PAIR_W4(QA, QB, QC, QD)                  \
+    "v_xor_b32_e32 %[t0], %[" QA "], %[w0]\n\t"       \
+    "v_bcnt_u32_b32 %[t0], %[t0], %[b]\n\t"           \
+    "v_xor_b32_e32 %[t1], %[" QB "], %[w1]\n\t"       \
+    "v_bcnt_u32_b32 %[t0], %[t1], %[t0]\n\t"          \
+    "v_xor_b32_e32 %[t1], %[" QC "], %[w2]\n\t"       \
+    "v_bcnt_u32_b32 %[t0], %[t1], %[t0]\n\t"          \
+    "v_xor_b32_e32 %[t1], %[" QD "], %[w3]\n\t"       \
+    "v_bcnt_u32_b32 %[t0], %[t1], %[t0]\n\t"          \
+    "v_alignbit_b32 %[far], %[far], %[t0], 31\n\t"
+
+// four queries, 64-bit codes
+__device__ __forceinline__ void hamming_test4(uint32_t &far, const uint32_t (&w)[2], uint32_t bias,
+                                              const uint32_t (*q)[2])
+{
+    uint32_t t0, t1;
+    asm(PSC_PAIR_W2("q0a", "q0b") PSC_PAIR_W2("q1a", "q1b") PSC_PAIR_W2("q2a", "q2b") PSC_PAIR_W2("q3a", "q3b")
+        : [far] "+v"(far), [t0] "=&v"(t0), [t1] "=&v"(t1)
+        : [w0] "v"(w[0]), [w1] "v"(w[1]), [b] "s"(bias), [q0a] "s"(q[0][0]), [q0b] "s"(q[0][1]),
+          [q1a] "s"(q[1][0]), [q1b] "s"(q[1][1]), [q2a] "s"(q[2][0]), [q2b] "s"(q[2][1]), [q3a] "s"(q[3][0]),
+          [q3b] "s"(q[3][1]));
+}
+// eight queries, 64-bit codes
+__device__ __forceinline__ void hamming_test8(uint32_t &far, const uint32_t (&w)[2], uint32_t bias,
+                                              const uint32_t (*q)[2])
+{
+    uint32_t t0, t1;
+    asm(PSC_PAIR_W2("q0a", "q0b") PSC_PAIR_W2("q1a", "q1b") PSC_PAIR_W2("q2a", "q2b") PSC_PAIR_W2("q3a", "q3b")
+            PSC_PAIR_W2("q4a", "q4b") PSC_PAIR_W2("q5a", "q5b") PSC_PAIR_W2("q6a", "q6b") PSC_PAIR_W2("q7a", "q7b")
+        : [far] "+v"(far), [t0] "=&v"(t0), [t1] "=&v"(t1)
+        : [w0] "v"(w[0]), [w1] "v"(w[1]), [b] "s"(bias), [q0a] "s"(q[0][0]), [q0b] "s"(q[0][1]),
+          [q1a] "s"(q[1][0]), [q1b] "s"(q[1][1]), [q2a] "s"(q[2][0]), [q2b] "s"(q[2][1]), [q3a] "s"(q[3][0]),
+          [q3b] "s"(q[3][1]), [q4a] "s"(q[4][0]), [q4b] "s"(q[4][1]), [q5a] "s"(q[5][0]), [q5b] "s"(q[5][1]),
+          [q6a] "s"(q[6][0]), [q6b] "s"(q[6][1]), [q7a] "s"(q[7][0]), [q7b] "s"(q[7][1]));
+}
+// four queries, 128-bit codes
+__device__ __forceinline__ void hamming_test4(uint32_t &far, const uint32_t (&w)[4], uint32_t bias,
+                                              const uint32_t (*q)[4])
+{
+    uint32_t t0, t1;
+    asm(PSC_PAIR_W4("q0a", "q0b", "q0c", "q0d") PSC_PAIR_W4("q1a", "q1b", "q1c", "q1d")
+            PSC_PAIR_W4("q2a", "q2b", "q2c", "q2d") PSC_PAIR_W4("q3a", "q3b", "q3c", "q3d")
+        : [far] "+v"(far), [t0] "=&v"(t0), [t1] "=&v"(t1)
+        : [w0] "v"(w[0]), [w1] "v"(w[1]), [w2] "v"(w[2]), [w3] "v"(w[3]), [b] "s"(bias), [q0a] "s"(q[0][0]),
+          [q0b] "s"(q[0][1]), [q0c] "s"(q[0][2]), [q0d] "s"(q[0][3]), [q1a] "s"(q[1][0]), [q1b] "s"(q[1][1]),
+          [q1c] "s"(q[1][2]), [q1d] "s"(q[1][3]), [q2a] "s"(q[2][0]), [q2b] "s"(q[2][1]), [q2c] "s"(q[2][2]),
+          [q2d] "s"(q[2][3]), [q3a] "s"(q[3][0]), [q3b] "s"(q[3][1]), [q3c] "s"(q[3][2]), [q3d] "s"(q[3][3]));
+}
+// all TQ queries of a tile against one code
+template <int TQ, int WPC>
+__device__ __forceinline__ void hamming_test_tile(uint32_t &far, const uint32_t (&w)[WPC], uint32_t bias,
+                                                  const uint32_t (&qw)[TQ][WPC])
+{
+    if constexpr (WPC == 2 && TQ % 8 == 0) {
+#pragma unroll
+        for (int q = 0; q < TQ; q += 8) hamming_test8(far, w, bias, &qw[q]);
+    } else {
+#pragma unroll
+        for (int q = 0; q < TQ; q += 4) hamming_test4(far, w, bias, &qw[q]);
+    }
+}
 
 // Smallest value of v over the wave, in every lane: four row-local steps on the data-parallel
 // path, then the four row results through scalar registers.
@@ -633,7 +709,11 @@ scan_kernel(ScanArgs a)
     // Lanes without a survivor in a turn write to a private dump word instead of being masked
     // off: cheaper than switching the execution mask twice per turn.
     const uint32_t dump_addr = (uint32_t)(uintptr_t)(s.dump + wave * 64 + lane);
-    for (int64_t sb = wave_first; sb < slice_end; sb += sstride) {
+    // One super-block of the wave, starting at code `sb` of the database.  INSIDE: this
+    // super-block and the next one lie entirely inside the scanned range, so no code needs masking
+    // and the next loads need no bounds -- the form all but the first and last turns take.
+    auto superblock = [&](auto inside, const int64_t sb) {
+        constexpr bool INSIDE = decltype(inside)::value;
         // ---- Hamming filter: bit c*TQ + (TQ-1-q) of a mask <=> code c is within ht of query q
         uint32_t svs[U];
 #pragma unroll
@@ -642,21 +722,20 @@ scan_kernel(ScanArgs a)
             uint32_t far = 0u;
 #pragma unroll
             for (int c = CB - 1; c >= 0; --c) {
+                uint32_t wc[WPC];
 #pragma unroll
-                for (int q = 0; q < TQ; ++q) {
-                    uint32_t acc = bias;
-#pragma unroll
-                    for (int w = 0; w < WPC; ++w) acc += (uint32_t)__popc(cur[u][c * WPC + w] ^ qw[q][w]);
-                    far = __builtin_amdgcn_alignbit(far, acc, 31);
-                }
+                for (int w = 0; w < WPC; ++w) wc[w] = cur[u][c * WPC + w];
+                hamming_test_tile<TQ, WPC>(far, wc, bias, qw);
             }
             uint32_t valid = qmask_all;
-            if (!(blk + 64 * CB <= slice_end && blk >= valid_begin)) {  // ragged or absent block
-                valid = 0u;
+            if constexpr (!INSIDE) {
+                if (!(blk + 64 * CB <= slice_end && blk >= valid_begin)) {  // ragged or absent block
+                    valid = 0u;
 #pragma unroll
-                for (int c = 0; c < CB; ++c) {
-                    const int64_t p = blk + (int64_t)lane * CB + c;
-                    valid |= (p < slice_end && p >= valid_begin) ? (qmask << (c * TQ)) : 0u;
+                    for (int c = 0; c < CB; ++c) {
+                        const int64_t p = blk + (int64_t)lane * CB + c;
+                        valid |= (p < slice_end && p >= valid_begin) ? (qmask << (c * TQ)) : 0u;
+                    }
                 }
             }
             svs[u] = ~far & valid;
@@ -665,8 +744,12 @@ scan_kernel(ScanArgs a)
         lane_ptr += sstride * M;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int64_t b = sb + sstride + u * stride;
-            if (b < slice_end) load_block(lane_ptr + u * stride * M, b, b + 64 * CB <= slice_end, cur[u]);
+            if constexpr (INSIDE) {
+                load_block(lane_ptr + u * stride * M, 0, true, cur[u]);
+            } else {
+                const int64_t b = sb + sstride + u * stride;
+                if (b < slice_end) load_block(lane_ptr + u * stride * M, b, b + 64 * CB <= slice_end, cur[u]);
+            }
         }
         // ---- survivors -> queue (one entry per lane and turn), full wavefronts -> ADC
         uint32_t rel0 = (uint32_t)(sb - slice_begin) + (uint32_t)lane * CB;
@@ -681,7 +764,8 @@ scan_kernel(ScanArgs a)
                 // counted (vcc), each takes slot fill + (number of such lanes below it), writes
                 // (bit number << kRelBits) | position, and clears that bit; lanes without a bit
                 // write to their dump word.  `base` = byte address of queue slot `fill`.
-                uint32_t base = ring_base + 4u * (uint32_t)fill, t0, t1, n;
+                fill = __builtin_amdgcn_readfirstlane(fill);  // (wave-uniform already; keeps it scalar)
+                uint32_t base = (uint32_t)__builtin_amdgcn_readfirstlane((int)(ring_base + 4u * (uint32_t)fill)), t0, t1, n;
                 asm volatile(
                     "1:\n\t"
                     "v_cmp_ne_u32_e32 vcc, 0, %[sv]\n\t"
@@ -717,7 +801,17 @@ scan_kernel(ScanArgs a)
             for (int v = 0; v + 1 < U; ++v) svs[v] = svs[v + 1];
             rel0 += (uint32_t)stride;
         }
+    };
+    int64_t sb = wave_first;
+    if (sb < slice_end && valid_begin != slice_begin) {  // a list that starts inside a 16-byte load
+        superblock(std::false_type{}, sb);
+        sb += sstride;
     }
+    // turns with two whole super-blocks ahead of sb (computed once, counted in 32 bits)
+    const int64_t room = slice_end - sb - (2 * sstride - stride + 64 * CB);
+    const int ninside = room >= 0 ? (int)(room / sstride) + 1 : 0;
+    for (int i = 0; i < ninside; ++i, sb += sstride) superblock(std::true_type{}, sb);
+    for (; sb < slice_end; sb += sstride) superblock(std::false_type{}, sb);
     if (fill > 0) {
         __builtin_amdgcn_wave_barrier();
         drain<M, TQ, IVF, SHARE>(s, a, ring, fill, slice_codes, slice_begin, self0, ask);
