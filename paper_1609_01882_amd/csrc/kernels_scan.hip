@@ -753,9 +753,7 @@ scan_kernel(ScanArgs a)
         }
         // ---- survivors -> queue (one entry per lane and turn), full wavefronts -> ADC
         uint32_t rel0 = (uint32_t)(sb - slice_begin) + (uint32_t)lane * CB;
-#pragma nounroll
-        for (int u = 0; u < U; ++u) {
-            uint32_t sv = svs[0];
+        auto queue_block = [&](uint32_t sv) {
             while (true) {
                 // Queue one survivor bit per lane and turn until no lane has bits left or 64 entries
                 // wait.  Hand-scheduled: the compiler's version of this loop spends more scalar
@@ -796,10 +794,21 @@ scan_kernel(ScanArgs a)
                 drain<M, TQ, IVF, SHARE>(s, a, ring + fill, 64, slice_codes, slice_begin, self0, ask);
                 __builtin_amdgcn_wave_barrier();
             }
-            // next mask of the super-block moves into place
+        };
+        if constexpr (INSIDE) {  // the hot form: one copy of the queueing code per block, no loop around them
 #pragma unroll
-            for (int v = 0; v + 1 < U; ++v) svs[v] = svs[v + 1];
-            rel0 += (uint32_t)stride;
+            for (int u = 0; u < U; ++u) {
+                queue_block(svs[u]);
+                rel0 += (uint32_t)stride;
+            }
+        } else {
+#pragma nounroll
+            for (int u = 0; u < U; ++u) {
+                queue_block(svs[0]);
+#pragma unroll
+                for (int v = 0; v + 1 < U; ++v) svs[v] = svs[v + 1];  // the next mask moves into place
+                rel0 += (uint32_t)stride;
+            }
         }
     };
     int64_t sb = wave_first;
