@@ -179,9 +179,14 @@ int psc_ivf_set_lists(psc_index *idx, const int64_t *offsets_dev, const uint8_t 
  * into ||(q-o)_j - c||^2 (one table per query), 2 (centroid[l]-o)_j . c (one per list) and a
  * number per (query, list, j), which are added up as a list is scanned; the bit string is the
  * arg-min of the summed float32 rows, lowest index on ties.
- * The workspace (psc_ivf_search_workspace_bytes: coarse distances nq*nlist*4 bytes, the two
- * families of tables (nq + nlist)*m KiB, and nq*nprobe*(12 k + 24) bytes of jobs and partial
- * lists) starts with the status word psc_workspace_status reads. */
+ * The per-list tables (nlist*m KiB) belong to the index's device image and are rebuilt by the
+ * first search after the codebook or the coarse centroids changed (that call blocks).
+ * Up to 2048 (query, list) pairs are scanned one per workgroup in order of coarse rank (low
+ * latency for a few queries); larger batches are grouped by list so that up to 16 queries share
+ * every code load.
+ * The workspace (psc_ivf_search_workspace_bytes: coarse distances nq*nlist*4 bytes, the
+ * queries' tables nq*m KiB, and nq*nprobe*(12 k + 24) bytes of jobs and partial lists) starts
+ * with the status word psc_workspace_status reads. */
 size_t psc_ivf_search_workspace_bytes(const psc_index *idx, int64_t nq, int nprobe, int k);
 int psc_ivf_search(const psc_index *idx, const float *q_dev, int64_t nq, int nprobe, int ht, int k,
                    int64_t *ids_dev, float *dists_dev, int32_t *probed_out_dev, uint8_t *qcodes_out_dev,

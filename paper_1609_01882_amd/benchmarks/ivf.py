@@ -67,9 +67,18 @@ def main():
     _, _, probed, _ = idx.ivf_search(xq[:ns].contiguous(), nprobe, ht, k, want_debug=True)
     torch.cuda.synchronize()
     pairs = float(counts[probed.long()].sum().item()) / ns * nq
+    # small batches: latency of one call (the paper's single-query mode, Section 4.3 / Table 2)
+    small = []
+    for nqs in (1, 16, 256):
+        xs = xq[:nqs].contiguous()
+        wss = torch.empty(idx.ivf_search_workspace_bytes(nqs, nprobe, k), dtype=torch.uint8, device=dev)
+        outs = (torch.empty((nqs, k), dtype=torch.int64, device=dev), torch.empty((nqs, k), dtype=torch.float32, device=dev))
+        mss = time_ms(lambda: idx.ivf_search(xs, nprobe, ht, k, workspace=wss, out=outs), 20, 3)
+        small.append({"n_query": nqs, "ms_per_call": round(mss, 4), "us_per_query": round(mss * 1e3 / nqs, 2)})
+        log(f"[ivf] small batch {small[-1]}")
     res = {"workload": "ivf", "n_db": n, "nlist": nlist, "nprobe": nprobe, "n_query": nq, "k": k, "ht": ht,
            "ms_per_step": round(ms, 3), "us_per_query": ms * 1e3 / nq, "pairs_per_step": pairs,
-           "pairs_per_s": pairs / (ms * 1e-3), "workspace_GB": ws.numel() / 1e9}
+           "pairs_per_s": pairs / (ms * 1e-3), "workspace_GB": ws.numel() / 1e9, "small_batches": small}
     log(f"[ivf] {res}")
     print(json.dumps(res), flush=True)
 

@@ -27,6 +27,7 @@ static int mark_codebook_changed(psc_index *idx)
 {
     idx->has_codebook = true;
     idx->dev_current = false;
+    idx->list_tab_current = false;
     return PSC_OK;
 }
 
@@ -96,6 +97,7 @@ void psc_destroy(psc_index *idx)
     if (!idx) return;
     if (idx->cb_dev) (void)hipFree(idx->cb_dev);
     if (idx->coarse_dev) (void)hipFree(idx->coarse_dev);
+    if (idx->list_tab_dev) (void)hipFree(idx->list_tab_dev);
     delete idx;
 }
 
@@ -372,6 +374,26 @@ static int sync_coarse_to_device(const psc_index *idx)
     return PSC_OK;
 }
 
+// Part of the index's device image, like the codebook: built by the first search after the
+// codebook or the coarse centroids changed (blocking, as their uploads are).
+static int sync_list_tables(const psc_index *idx, hipStream_t s)
+{
+    if (idx->list_tab_current) return PSC_OK;
+    if (idx->list_tab_dev && idx->list_tab_nlist != idx->nlist) {
+        PSC_HIP_TRY(hipFree(idx->list_tab_dev));
+        idx->list_tab_dev = nullptr;
+    }
+    if (!idx->list_tab_dev) {
+        PSC_HIP_TRY(hipMalloc((void **)&idx->list_tab_dev, (size_t)idx->nlist * idx->m * kCentroids * sizeof(float)));
+        idx->list_tab_nlist = idx->nlist;
+    }
+    int rc = launch_list_tables(idx->cb_dev, idx->dim, idx->m, idx->coarse_dev, idx->nlist, idx->list_tab_dev, s);
+    if (rc != PSC_OK) return rc;
+    PSC_HIP_TRY(hipStreamSynchronize(s));
+    idx->list_tab_current = true;
+    return PSC_OK;
+}
+
 static int need_coarse(const psc_index *idx)
 {
     PSC_REQUIRE(idx != nullptr, "null index");
@@ -395,6 +417,7 @@ int psc_ivf_set_coarse(psc_index *idx, const float *centroids_host, int nlist)
     }
     idx->nlist = nlist;
     idx->coarse_current = false;
+    idx->list_tab_current = false;
     idx->list_off_dev = nullptr;  // lists built for another quantizer no longer apply
     idx->list_codes_dev = nullptr;
     idx->list_ids_dev = nullptr;
@@ -539,7 +562,7 @@ struct IvfLayout {
     ScanPlan plan;
     int64_t njobs, nblk, max_tiles;
     size_t off_status, off_gthr, off_dist, off_probed, off_hist, off_list_begin, off_tile_begin, off_job_q, off_job_list,
-        off_job_slot, off_tiles, off_lut, off_list_tab, off_qcodes, off_part_d, off_part_i, total;
+        off_job_slot, off_tiles, off_lut, off_qcodes, off_part_d, off_part_i, total;
 };
 
 int ivf_layout(const psc_index *idx, int64_t nq, int nprobe, int k, IvfLayout *L)
@@ -550,10 +573,11 @@ int ivf_layout(const psc_index *idx, int64_t nq, int nprobe, int k, IvfLayout *L
     PSC_REQUIRE(nprobe <= 1024, "at most 1024 probes");
     L->njobs = nq * nprobe;
     PSC_REQUIRE(L->njobs < 0x7fffffffLL, "too many (query, list) jobs");
-    int rc = plan_scan(idx->m, L->njobs > 0 ? L->njobs : 1, idx->list_n, k, &L->plan);
+    // (few jobs are tiles of their own: the narrowest tile shape then wastes the least filter work)
+    int rc = plan_scan(idx->m, L->njobs > kDirectJobs ? L->njobs : 1, idx->list_n, k, &L->plan);
     if (rc != PSC_OK) return rc;
     L->nblk = (nq + 15) / 16;
-    L->max_tiles = L->njobs / L->plan.tq + 2 * (int64_t)idx->nlist;
+    L->max_tiles = L->njobs <= kDirectJobs ? L->njobs : L->njobs / L->plan.tq + 2 * (int64_t)idx->nlist;
     size_t o = 0;
     auto take = [&](size_t bytes) {
         size_t at = o;
@@ -572,7 +596,6 @@ int ivf_layout(const psc_index *idx, int64_t nq, int nprobe, int k, IvfLayout *L
     L->off_job_slot = take((size_t)L->njobs * sizeof(int32_t));
     L->off_tiles = take((size_t)L->max_tiles * 16);
     L->off_lut = take((size_t)nq * idx->m * kCentroids * sizeof(float));
-    L->off_list_tab = take((size_t)idx->nlist * idx->m * kCentroids * sizeof(float));
     L->off_qcodes = take((size_t)L->njobs * idx->m);
     L->off_part_d = take((size_t)L->njobs * k * sizeof(float));
     L->off_part_i = take((size_t)L->njobs * k * sizeof(int64_t));
@@ -642,9 +665,9 @@ int psc_ivf_search(const psc_index *idx, const float *q_dev, int64_t nq, int npr
     map.sub = idx->coarse_dev + (size_t)idx->nlist * idx->dim;  // the mean coarse centroid
     rc = launch_lut(idx->cb_dev, idx->dim, idx->m, q_dev, nq, map, lut, s);
     if (rc != PSC_OK) return rc;
-    float *list_tab = (float *)(w + L.off_list_tab);
-    rc = launch_list_tables(idx->cb_dev, idx->dim, idx->m, idx->coarse_dev, idx->nlist, list_tab, s);
+    rc = sync_list_tables(idx, s);
     if (rc != PSC_OK) return rc;
+    const float *list_tab = idx->list_tab_dev;
     // 4. the fused scan over the tiles, 5. one merge per query over its nprobe partial lists
     rc = launch_ivf_scan(idx->m, L.plan.tq, L.plan.kpad, L.plan.lds_bytes, lut, list_tab, q_dev, idx->coarse_dev,
                          idx->dim, idx->nlist, qcodes, idx->list_codes_dev, idx->list_n, ht, k, jb.tiles,

@@ -111,6 +111,8 @@ struct IvfJobBuffers {
     int32_t *job_slot;   // [njobs] query * nprobe + probe rank
     void *tiles;         // [max_tiles] x 16 bytes
 };
+// Up to this many (query, probe) jobs are not grouped by list: each is a tile of its own.
+constexpr int64_t kDirectJobs = 2048;
 // Sort the (query, probe) jobs by key (stable in query order) and cut each key's jobs into tiles
 // of at most tq.  Key = list for the jobs of a query's `pilot` nearest lists, nlist + list for
 // the others: the nearest lists' tiles come first.
@@ -139,6 +141,11 @@ struct psc_index {
     std::vector<float> coarse_host;  // [nlist][dim]
     mutable float *coarse_dev = nullptr;
     mutable bool coarse_current = false;
+    // the lists' share of the residual tables [nlist][m][256] (launch_list_tables); follows the
+    // codebook and the coarse centroids
+    mutable float *list_tab_dev = nullptr;
+    mutable int list_tab_nlist = 0;
+    mutable bool list_tab_current = false;
     const int64_t *list_off_dev = nullptr;  // [nlist+1]
     const uint8_t *list_codes_dev = nullptr;
     const int32_t *list_ids_dev = nullptr;

@@ -68,7 +68,76 @@ __device__ __forceinline__ uint64_t wave_min_u64(uint64_t v)
     return v;
 }
 
-// One workgroup per row: nprobe times take the smallest remaining (distance, list) key.
+// Sum of v over the wave, in every lane (row-local steps on the data-parallel path, the four row
+// sums through scalar registers).
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v)
+{
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, false);   // lane ^ 1
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xf, 0xf, false);   // lane ^ 2
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xf, 0xf, false);  // mirror in 8
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xf, 0xf, false);  // mirror in 16
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 0) + (uint32_t)__builtin_amdgcn_readlane((int)v, 16) +
+           (uint32_t)__builtin_amdgcn_readlane((int)v, 32) + (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+}
+
+// The nprobe nearest lists of a row, one wave per row, the row's nlist <= 64 KPL distance keys
+// in registers (lane l holds lists l, l + 64, ...).
+//  1. the nprobe-th smallest distance key, bit by bit: a bit of the answer is 0 iff at least
+//     nprobe keys lie below (the bits found so far, this bit set);
+//  2. selected = keys below it, plus the lowest-numbered lists among the keys equal to it;
+//  3. the selected (key, list) pairs go to LDS and every one is written to its rank.
+template <int KPL>
+__global__ void __launch_bounds__(256)
+select_probes_wave_kernel(const float *__restrict__ dist, int64_t n, int nlist, int nprobe,
+                          int32_t *__restrict__ probed)
+{
+    extern __shared__ __align__(16) uint64_t sel[];  // [4][nprobe]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t r = (int64_t)blockIdx.x * 4 + wave;
+    if (r >= n) return;
+    uint64_t *mine = sel + (size_t)wave * nprobe;
+    uint32_t dk[KPL];
+#pragma unroll
+    for (int i = 0; i < KPL; ++i) {
+        const int c = i * 64 + lane;
+        // (real keys stay below the filler of the places past the last list, whatever the distance)
+        dk[i] = c < nlist ? min((uint32_t)(order_key(dist[r * nlist + c], 0u) >> 32), 0xfffffffeu) : 0xffffffffu;
+    }
+    uint32_t pivot = 0;
+    for (int b = 31; b >= 0; --b) {
+        const uint32_t mid = pivot | (1u << b);
+        uint32_t cnt = 0;
+#pragma unroll
+        for (int i = 0; i < KPL; ++i) cnt += dk[i] < mid ? 1u : 0u;
+        if (wave_sum_u32(cnt) < (uint32_t)nprobe) pivot = mid;
+    }
+    uint32_t below = 0;
+#pragma unroll
+    for (int i = 0; i < KPL; ++i) below += dk[i] < pivot ? 1u : 0u;
+    int take = nprobe - (int)wave_sum_u32(below);  // how many of the keys equal to the pivot belong
+    int at = 0;                                     // selected so far
+#pragma unroll
+    for (int i = 0; i < KPL; ++i) {
+        const bool eq = dk[i] == pivot;
+        const uint64_t eqm = __ballot(eq);
+        const int before = __builtin_popcountll(eqm & ((1ull << lane) - 1ull));
+        const bool chosen = dk[i] < pivot || (eq && before < take);
+        take -= __builtin_popcountll(eqm);
+        const uint64_t cm = __ballot(chosen);
+        if (chosen) mine[at + __builtin_popcountll(cm & ((1ull << lane) - 1ull))] = ((uint64_t)dk[i] << 32) | (uint32_t)(i * 64 + lane);
+        at += __builtin_popcountll(cm);
+    }
+    __builtin_amdgcn_wave_barrier();
+    for (int e = lane; e < nprobe; e += 64) {
+        const uint64_t key = mine[e];
+        int rank = 0;
+        for (int j = 0; j < nprobe; ++j) rank += mine[j] < key ? 1 : 0;
+        probed[r * nprobe + rank] = (int32_t)(uint32_t)key;
+    }
+}
+
+// More than 4096 lists.  One workgroup per row: nprobe times take the smallest remaining
+// (distance, list) key.
 __global__ void __launch_bounds__(256)
 select_probes_kernel(const float *__restrict__ dist, int nlist, int nprobe, int32_t *__restrict__ probed)
 {
@@ -278,6 +347,25 @@ __global__ void job_tiles_kernel(const int32_t *__restrict__ list_begin, const i
     for (int32_t o = 0; o < cnt; o += tq, ++t) tiles[t] = TileRec{jb + o, min(tq, cnt - o), l, 0};
 }
 
+// Few jobs: no grouping by list.  Every job becomes a tile of its own, the jobs of every query's
+// nearest list first, then all second nearest, ...: tile t = (query t % nq, probe t / nq).
+__global__ void direct_jobs_kernel(const int32_t *__restrict__ probed, int nq, int nprobe,
+                                   int32_t *__restrict__ job_q, int32_t *__restrict__ job_list,
+                                   int32_t *__restrict__ job_slot, TileRec *__restrict__ tiles,
+                                   int32_t *__restrict__ ntiles)
+{
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    const int njobs = nq * nprobe;
+    if (t == 0) *ntiles = njobs;
+    if (t >= njobs) return;
+    const int p = t / nq, q = t - p * nq;
+    const int l = probed[q * nprobe + p];
+    job_q[t] = q;
+    job_list[t] = l;
+    job_slot[t] = q * nprobe + p;
+    tiles[t] = TileRec{t, 1, l, 0};
+}
+
 // The lists' share of the residual tables: see launch_list_tables.  One workgroup per (list,
 // sub-quantizer), thread c owns centroid c.
 __global__ void __launch_bounds__(256)
@@ -362,8 +450,17 @@ int launch_select_probes(const float *dist_dev, int64_t n, int nlist, int nprobe
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 16384 * 8));
         configured = true;
     }
-    hipLaunchKernelGGL(select_probes_kernel, dim3((unsigned)n), dim3(256), (size_t)nlist * sizeof(uint64_t), s,
-                       dist_dev, nlist, nprobe, probed_dev);
+    const dim3 wgrid((unsigned)((n + 3) / 4));
+    const size_t wlds = (size_t)4 * nprobe * sizeof(uint64_t);
+    if (nlist <= 1024)
+        hipLaunchKernelGGL(select_probes_wave_kernel<16>, wgrid, dim3(256), wlds, s, dist_dev, n, nlist, nprobe,
+                           probed_dev);
+    else if (nlist <= 4096)
+        hipLaunchKernelGGL(select_probes_wave_kernel<64>, wgrid, dim3(256), wlds, s, dist_dev, n, nlist, nprobe,
+                           probed_dev);
+    else
+        hipLaunchKernelGGL(select_probes_kernel, dim3((unsigned)n), dim3(256), (size_t)nlist * sizeof(uint64_t), s,
+                           dist_dev, nlist, nprobe, probed_dev);
     PSC_HIP_TRY(hipGetLastError());
     return PSC_OK;
 }
@@ -387,6 +484,13 @@ int launch_build_jobs(const int32_t *probed_dev, int64_t nq, int nprobe, int nli
                       const IvfJobBuffers &b, hipStream_t s)
 {
     const int64_t njobs = nq * nprobe;
+    if (njobs <= kDirectJobs) {  // a few queries: latency matters, sharing of code loads does not
+        hipLaunchKernelGGL(direct_jobs_kernel, dim3((unsigned)((njobs + 255) / 256)), dim3(256), 0, s, probed_dev,
+                           (int)nq, nprobe, b.job_q, b.job_list, b.job_slot, (TileRec *)b.tiles,
+                           b.tile_begin + 2 * nlist);
+        PSC_HIP_TRY(hipGetLastError());
+        return PSC_OK;
+    }
     const int64_t nblk = (nq + kJobBlockQ - 1) / kJobBlockQ;
     const int nkeys = 2 * nlist;
     PSC_REQUIRE(njobs < 0x7fffffffLL && nblk * nkeys < ((int64_t)1 << 40), "too many jobs");

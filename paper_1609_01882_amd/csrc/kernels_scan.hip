@@ -1103,7 +1103,13 @@ __global__ void fill_padding_kernel(int64_t *ids, float *dists, int64_t total)
     }
 }
 
-__global__ void clear_status_kernel(int *status) { *status = 0; }
+// Start of a scan: every shared threshold at +infinity and, if asked, the status word cleared.
+__global__ void init_scan_kernel(uint32_t *gthr, int64_t n, int *status)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < n) gthr[e] = kKeyInf;
+    if (e == 0 && status) *status = 0;
+}
 
 __global__ void fill_u32_kernel(uint32_t *p, int64_t n, uint32_t v)
 {
@@ -1341,9 +1347,8 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
     a.job_q = nullptr;
     a.part_d = (float *)((char *)ws + 256 + p.gthr_bytes);
     a.part_i = (int64_t *)((char *)a.part_d + (((size_t)nq * p.nslice * k * sizeof(float) + 255) / 256 * 256));
-    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((nq + 255) / 256)), dim3(256), 0, s, a.gthr, nq, kKeyInf);
-
-    if (clear_status) hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, s, a.status);
+    hipLaunchKernelGGL(init_scan_kernel, dim3((unsigned)((nq + 255) / 256)), dim3(256), 0, s, a.gthr, nq,
+                       clear_status ? a.status : (int *)nullptr);
     a.list_tab = nullptr;
     a.queries = nullptr;
     a.coarse = nullptr;
@@ -1416,8 +1421,7 @@ int launch_ivf_scan(int m, int tq, int kpad, size_t lds_bytes, const float *lut_
     a.job_slot = job_slot_dev;
     a.job_q = job_q_dev;
     a.gthr = gthr_dev;
-    hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, s, a.status);
-    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((nq + 255) / 256)), dim3(256), 0, s, gthr_dev, nq, kKeyInf);
+    hipLaunchKernelGGL(init_scan_kernel, dim3((unsigned)((nq + 255) / 256)), dim3(256), 0, s, gthr_dev, nq, a.status);
     if (max_tiles > 0) {
         int rc = dispatch_scan<true, true>(m, tq, a, max_tiles, lds_bytes, s);
         if (rc != PSC_OK) return rc;
