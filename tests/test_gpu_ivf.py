@@ -163,3 +163,28 @@ def test_ivf_odd_list_boundaries_and_empty_lists():
     assert (ids == ref["ids"]).mean() > 0.99
     for q in range(5):
         assert sorted(ids[q][ids[q] >= 0].tolist()) == list(range(n))
+
+
+def test_more_than_4096_lists():
+    """5000 lists: the probe selection's general form (the distance keys no longer fit in registers)
+    and many empty or tiny lists; coarse centroids are database rows set directly."""
+    import paper_1609_01882_amd as psc
+    rng = np.random.default_rng(11)
+    nlist, n = 5000, 12_000
+    xt = W.sift_like(3000, seed=73, stream=1)
+    xb = W.sift_like(n, seed=73, stream=2)
+    idx = psc.Index(128, 8)
+    coarse = xb[rng.choice(n, size=nlist, replace=False)].copy()
+    idx.ivf_set_coarse(coarse)
+    lt, _ = idx.ivf_assign_encode(_dev(xt), want_codes=False)
+    idx.train_pq(xt - coarse[lt.cpu().numpy()], iters=4, seed=2)
+    list_no, codes = idx.ivf_assign_encode(_dev(xb))
+    order = torch.sort(list_no.to(torch.int64), stable=True).indices
+    counts = torch.bincount(list_no.to(torch.int64), minlength=nlist)
+    offsets = torch.zeros(nlist + 1, dtype=torch.int64, device="cuda")
+    offsets[1:] = torch.cumsum(counts, 0)
+    lcodes, lids = codes[order].contiguous(), order.to(torch.int32).contiguous()
+    idx.ivf_set_lists(offsets, lcodes, lids)
+    s = dict(idx=idx, cb=idx.get_codebook(), coarse=coarse, offsets=offsets.cpu().numpy(),
+             lcodes=lcodes.cpu().numpy(), lids=lids.cpu().numpy())
+    _check_ivf_search((psc, s), 70, 30, 20)
