@@ -24,6 +24,8 @@ if ROOT not in sys.path:
 # MI355X: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3e12 32-bit integer lane-ops/s
 # (half of the 78.6 TFLOP/s non-packed fp32 vector rate, which counts an FMA as two).
 PEAK_INT_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+# LDS: 128 bytes per clock and compute unit.  The ADC of a survivor gathers m 4-byte table entries.
+PEAK_LDS_TBPS = 256 * 128 * 2.4e9 / 1e12
 # Algorithmic integer work per (query, code) pair: per 32-bit word one xor and one
 # popcount-accumulate, plus one compare against the threshold.
 OPS_PER_PAIR = {8: 5, 16: 9}
@@ -161,11 +163,14 @@ def main():
             r100 = float((ids[:, :100] == best_i[:, None]).any(dim=1).float().mean())
             ns = psc.hamming_filter(idx.build_lut(q_dev[:256])[1], codes, ht)
             torch.cuda.synchronize()
+            rate = float(ns.double().mean()) / n_db
             sweep.append(dict(ht=ht, ms_per_step=round(w, 3), scan_ms=round(sms, 3),
                               pairs_per_s=pairs / (w * 1e-3),
+                              # the two rooflines of the path: integer ALU for the filter (every pair),
+                              # LDS gathers for the ADC (survivors only); whichever is larger binds
                               alu_frac=OPS_PER_PAIR[m] * pairs / (sms * 1e-3) / 1e12 / PEAK_INT_TOPS,
-                              recall_at_10=r10, recall_at_100=r100,
-                              survivor_rate=float(ns.double().mean()) / n_db))
+                              lds_frac=rate * pairs * m * 4 / (sms * 1e-3) / 1e12 / PEAK_LDS_TBPS,
+                              recall_at_10=r10, recall_at_100=r100, survivor_rate=rate))
             log(f"[sweep] {sweep[-1]}")
 
     # ------------------------------------------------------------------ side measurement: few queries
