@@ -85,6 +85,12 @@ def main():
     log(f"[setup] PQ trained + index assignment optimised in {time.time() - t0:.1f}s "
         f"(loss {losses[:, 0].mean():.0f} -> {losses[:, 1].mean():.0f})")
 
+    # the paper's rule for the threshold (Section 4.2): the largest ht that filters out at least
+    # 95 % of the pairs of the training set (here: 1000 training vectors against all 100k)
+    tcodes = idx.encode(torch.from_numpy(xt).to(dev))
+    ht_rule = psc.threshold_for_rate(psc.hamming_histogram(tcodes[:1000].contiguous(), tcodes), 0.05)
+    log(f"[setup] threshold that removes >= 95 % of the training pairs: ht = {ht_rule}")
+
     xq = cfg.vectors("query", n=nq, threads=threads)
     q_dev = torch.from_numpy(xq).to(dev)
     qn = (q_dev * q_dev).sum(dim=1)
@@ -243,6 +249,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "flat64" + ("-small" if args.small else ""), "n_db": n_db, "n_query": nq,
                    "code_bits": 8 * m, "ht": args.ht, "k": k},
+        "ht_removing_95pct_of_training_pairs": ht_rule,
         "recall_at_10": recall10,
         "survivor_rate": surv_rate,
         "roofline": {"bound": "alu", "kernel": "scan_kernel<8,16,16>", "achieved": achieved,

@@ -116,6 +116,17 @@ int psc_hamming_filter(int m, const uint8_t *qcodes_dev, int64_t nq, const uint8
                        int64_t n, int ht, int64_t *nsurv_dev, uint8_t *hdist_dev,
                        psc_stream stream);
 
+/* Adjusting the threshold (Section 4.2: thresholds are set on a training set so that the Hamming
+ * comparison removes at least a given share of the points).
+ * psc_hamming_histogram: hist_dev [8m+1] int64 (device; overwritten) receives, for h = 0..8m, the
+ * number of (query code, code) pairs at Hamming distance exactly h, over all nq*n pairs.
+ * psc_threshold_for_rate (host only, no GPU work): the largest ht such that the pairs at
+ * distance <= ht are at most max_keep_fraction of all pairs of hist_host [nbits+1]; -1 if not
+ * even ht = 0 keeps that few, PSC_EINVAL (-1 as well) on a null or empty histogram. */
+int psc_hamming_histogram(int m, const uint8_t *qcodes_dev, int64_t nq, const uint8_t *codes_dev,
+                          int64_t n, int64_t *hist_dev, psc_stream stream);
+int psc_threshold_for_rate(const int64_t *hist_host, int nbits, double max_keep_fraction);
+
 /* The fused scan (Section 3.3; Section 4.2 "dual"): for every query q and code i,
  * keep i iff hamming(qcodes[q], codes[i]) <= ht (ht >= 8m keeps everything = pure
  * ADC search); score survivors with dist = sum_j lut[q][j][codes[i][j]] (float32,

@@ -20,7 +20,7 @@ import numpy as np
 from . import build as _build
 
 __all__ = [
-    "hamming", "hamming_matrix", "encode", "decode", "build_lut", "query_codes", "scan",
+    "hamming", "hamming_matrix", "hamming_histogram", "threshold_for_rate", "encode", "decode", "build_lut", "query_codes", "scan",
     "search_flat", "ivf_search", "knn_graph", "exact_knn", "recall_at", "train_pq",
     "centroid_distances", "distance_stats", "f_map", "targets_weights", "polyd_loss",
     "swap_delta", "anneal", "apply_assignment", "optimize_index_assignment", "draw_u64",
@@ -79,6 +79,36 @@ def hamming_matrix(qcodes, codes) -> np.ndarray:
     out = np.empty((nq, n), dtype=np.int32)
     _L().orc_hamming_matrix(_p(qcodes), C.c_int64(nq), _p(codes), C.c_int64(n), C.c_int(m), _p(out))
     return out
+
+
+def hamming_histogram(qcodes, codes, chunk: int = 1 << 20) -> np.ndarray:
+    """Number of (query code, code) pairs at every Hamming distance 0..8m, int64 [8m+1]: the
+    statistic the threshold is adjusted on (Section 4.2, "adjusted on the training sets")."""
+    qcodes, codes = _u8(qcodes), _u8(codes)
+    nbits = 8 * qcodes.shape[1]
+    hist = np.zeros(nbits + 1, dtype=np.int64)
+    for s in range(0, codes.shape[0], chunk):
+        h = hamming_matrix(qcodes, codes[s:s + chunk])
+        hist += np.bincount(h.ravel(), minlength=nbits + 1)
+    return hist
+
+
+def threshold_for_rate(hist, max_keep_fraction: float) -> int:
+    """Largest ht such that the filter keeps at most `max_keep_fraction` of the pairs counted in
+    `hist` (Section 4.2: the threshold that filters out at least 1 - max_keep_fraction of the
+    points); -1 if even ht = 0 keeps more."""
+    hist = np.asarray(hist, dtype=np.int64)
+    total = int(hist.sum())
+    assert total > 0
+    ht = -1
+    kept = 0
+    for h, c in enumerate(hist.tolist()):
+        kept += c
+        if kept <= max_keep_fraction * total:
+            ht = h
+        else:
+            break
+    return ht
 
 
 # ----------------------------------------------------------------------------- PQ codes, tables

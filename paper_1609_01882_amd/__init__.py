@@ -9,9 +9,11 @@ from .binding import (  # noqa: F401
     PSC_MAX_K,
     exported_symbols,
     hamming_filter,
+    hamming_histogram,
     lib_path,
     scan,
     scan_workspace_bytes,
+    threshold_for_rate,
     version,
     workspace_status,
 )

@@ -47,6 +47,8 @@ def _load():
         "psc_encode": (i32, [vp, vp, i64, vp, vp]),
         "psc_build_lut": (i32, [vp, vp, i64, vp, vp, vp]),
         "psc_hamming_filter": (i32, [i32, vp, i64, vp, i64, i32, vp, vp, vp]),
+        "psc_hamming_histogram": (i32, [i32, vp, i64, vp, i64, vp, vp]),
+        "psc_threshold_for_rate": (i32, [vp, i32, dbl]),
         "psc_scan_workspace_bytes": (sz, [i32, i64, i64, i32]),
         "psc_scan": (i32, [i32, vp, vp, i64, vp, i64, i32, i32, vp, vp, vp, sz, vp]),
         "psc_search_workspace_bytes": (sz, [vp, i64, i64, i32]),
@@ -75,7 +77,8 @@ def exported_symbols():
     _load()
     return ["psc_version", "psc_last_error", "psc_create", "psc_destroy", "psc_train_pq",
             "psc_optimize_index_assignment", "psc_set_codebook", "psc_get_codebook", "psc_encode",
-            "psc_build_lut", "psc_hamming_filter", "psc_scan_workspace_bytes", "psc_scan",
+            "psc_build_lut", "psc_hamming_filter", "psc_hamming_histogram", "psc_threshold_for_rate",
+            "psc_scan_workspace_bytes", "psc_scan",
             "psc_search_workspace_bytes", "psc_search", "psc_knn_graph_workspace_bytes",
             "psc_knn_graph", "psc_ivf_train_coarse", "psc_ivf_set_coarse", "psc_ivf_get_coarse",
             "psc_ivf_assign_encode", "psc_ivf_set_lists", "psc_ivf_search_workspace_bytes",
@@ -297,6 +300,24 @@ def hamming_filter(qcodes: torch.Tensor, codes: torch.Tensor, ht: int, want_dist
                                       _dev(nsurv, torch.int64, "nsurv"),
                                       _dev(hd, torch.uint8, "hdist") if want_distances else None, _stream()))
     return (nsurv, hd) if want_distances else nsurv
+
+
+def hamming_histogram(qcodes: torch.Tensor, codes: torch.Tensor) -> torch.Tensor:
+    """Number of (query code, code) pairs at every Hamming distance 0..8m (int64 [8m+1])."""
+    nq, m = qcodes.shape
+    hist = torch.empty(8 * m + 1, dtype=torch.int64, device=qcodes.device)
+    _check(_load().psc_hamming_histogram(m, _dev(qcodes, torch.uint8, "qcodes"), nq,
+                                         _dev(codes, torch.uint8, "codes"), codes.shape[0],
+                                         _dev(hist, torch.int64, "hist"), _stream()))
+    return hist
+
+
+def threshold_for_rate(hist, max_keep_fraction: float) -> int:
+    """Largest ht that keeps at most `max_keep_fraction` of the pairs of a histogram (-1: none)."""
+    h = np.ascontiguousarray(hist.cpu().numpy() if isinstance(hist, torch.Tensor) else hist, dtype=np.int64)
+    if h.size < 2 or h.sum() <= 0:
+        raise PscError("empty histogram")
+    return int(_load().psc_threshold_for_rate(h.ctypes.data_as(C.c_void_p), h.size - 1, float(max_keep_fraction)))
 
 
 def workspace_status(ws: torch.Tensor) -> None:

@@ -218,6 +218,35 @@ int psc_build_lut(const psc_index *idx, const float *q_dev, int64_t nq, float *l
     return rc;
 }
 
+int psc_hamming_histogram(int m, const uint8_t *qcodes_dev, int64_t nq, const uint8_t *codes_dev,
+                          int64_t n, int64_t *hist_dev, psc_stream stream)
+{
+    return launch_hamming_histogram(m, qcodes_dev, nq, codes_dev, n, hist_dev, (hipStream_t)stream);
+}
+
+int psc_threshold_for_rate(const int64_t *hist_host, int nbits, double max_keep_fraction)
+{
+    if (!hist_host || nbits < 1) {
+        set_error("null or empty histogram");
+        return PSC_EINVAL;
+    }
+    double total = 0.0;
+    for (int h = 0; h <= nbits; ++h) total += (double)hist_host[h];
+    if (total <= 0.0) {
+        set_error("empty histogram");
+        return PSC_EINVAL;
+    }
+    // largest ht with (pairs at distance <= ht) <= max_keep_fraction * total
+    double kept = 0.0;
+    int ht = -1;
+    for (int h = 0; h <= nbits; ++h) {
+        kept += (double)hist_host[h];
+        if (kept <= max_keep_fraction * total) ht = h;
+        else break;
+    }
+    return ht;
+}
+
 int psc_hamming_filter(int m, const uint8_t *qcodes_dev, int64_t nq, const uint8_t *codes_dev,
                        int64_t n, int ht, int64_t *nsurv_dev, uint8_t *hdist_dev, psc_stream stream)
 {

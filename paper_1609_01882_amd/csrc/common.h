@@ -89,6 +89,8 @@ int launch_ivf_scan(int m, int tq, int kpad, size_t lds_bytes, const float *lut_
                     const int64_t *list_off_dev, const int32_t *ext_ids_dev, const int32_t *job_slot_dev,
                     const int32_t *job_q_dev, uint32_t *gthr_dev, float *part_d, int64_t *part_i, int *status,
                     int64_t nq, int nprobe, int64_t *ids_dev, float *dists_dev, hipStream_t s);
+int launch_hamming_histogram(int m, const uint8_t *qcodes_dev, int64_t nq, const uint8_t *codes_dev,
+                             int64_t n, int64_t *hist_dev, hipStream_t s);
 int launch_hamming_filter(int m, const uint8_t *qcodes_dev, int64_t nq, const uint8_t *codes_dev,
                           int64_t n, int ht, int64_t *nsurv_dev, uint8_t *hdist_dev, hipStream_t s);
 

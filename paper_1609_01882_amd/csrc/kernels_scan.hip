@@ -1143,6 +1143,33 @@ hamming_filter_kernel(const uint8_t *__restrict__ qcodes, int64_t nq, const uint
     if ((threadIdx.x & 63) == 0 && local) atomicAdd(&nsurv[q], local);
 }
 
+// Histogram of the Hamming distances of all pairs: per workgroup (one query, a stride of the
+// codes) a histogram in LDS, added to the global one at the end.
+template <int M>
+__global__ void __launch_bounds__(256)
+hamming_histogram_kernel(const uint8_t *__restrict__ qcodes, const uint8_t *__restrict__ codes, int64_t n,
+                         unsigned long long *__restrict__ hist)
+{
+    __shared__ unsigned int bins[8 * M + 1];
+    const int64_t q = blockIdx.y;
+    constexpr int WPC = M / 4;
+    for (int b = threadIdx.x; b <= 8 * M; b += 256) bins[b] = 0u;
+    uint32_t qw[WPC];
+#pragma unroll
+    for (int w = 0; w < WPC; ++w) qw[w] = ((const uint32_t *)qcodes)[q * WPC + w];
+    __syncthreads();
+    // (a workgroup sees fewer than 2^32 codes: the grid has at least n / 2^31 columns)
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        int h = 0;
+#pragma unroll
+        for (int w = 0; w < WPC; ++w) h += __popc(((const uint32_t *)codes)[i * WPC + w] ^ qw[w]);
+        atomicAdd(&bins[h], 1u);
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b <= 8 * M; b += 256)
+        if (bins[b]) atomicAdd(&hist[b], (unsigned long long)bins[b]);
+}
+
 __global__ void zero_u64_kernel(unsigned long long *p, int64_t n)
 {
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -1452,6 +1479,30 @@ int launch_hamming_filter(int m, const uint8_t *qcodes_dev, int64_t nq, const ui
     else
         hipLaunchKernelGGL((hamming_filter_kernel<16>), dim3(gx, (unsigned)nq), dim3(256), 0, s, qcodes_dev, nq,
                            codes_dev, n, ht, (unsigned long long *)nsurv_dev, hdist_dev);
+    PSC_HIP_TRY(hipGetLastError());
+    return PSC_OK;
+}
+
+int launch_hamming_histogram(int m, const uint8_t *qcodes_dev, int64_t nq, const uint8_t *codes_dev,
+                             int64_t n, int64_t *hist_dev, hipStream_t s)
+{
+    if (m != 8 && m != 16) {
+        set_error("m must be 8 or 16, got %d", m);
+        return PSC_EINVAL;
+    }
+    PSC_REQUIRE(nq >= 0 && n >= 0 && hist_dev, "bad sizes or null histogram");
+    PSC_REQUIRE(nq <= 65535, "at most 65535 queries per histogram call");
+    hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(256), 0, s, (unsigned long long *)hist_dev, (int64_t)(8 * m + 1));
+    if (nq == 0 || n == 0) return PSC_OK;
+    PSC_REQUIRE(qcodes_dev && codes_dev, "null pointer");
+    PSC_REQUIRE(((uintptr_t)codes_dev & 3) == 0 && ((uintptr_t)qcodes_dev & 3) == 0, "codes must be 4-byte aligned");
+    const unsigned gx = (unsigned)std::max<int64_t>(std::min<int64_t>((n + 255) / 256, 2048), (n >> 31) + 1);
+    if (m == 8)
+        hipLaunchKernelGGL((hamming_histogram_kernel<8>), dim3(gx, (unsigned)nq), dim3(256), 0, s, qcodes_dev,
+                           codes_dev, n, (unsigned long long *)hist_dev);
+    else
+        hipLaunchKernelGGL((hamming_histogram_kernel<16>), dim3(gx, (unsigned)nq), dim3(256), 0, s, qcodes_dev,
+                           codes_dev, n, (unsigned long long *)hist_dev);
     PSC_HIP_TRY(hipGetLastError());
     return PSC_OK;
 }

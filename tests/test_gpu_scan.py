@@ -151,3 +151,17 @@ def test_scan_is_deterministic(psc):
     a = _run(psc, lut, qcodes, codes, 26, 100)
     b = _run(psc, lut, qcodes, codes, 26, 100)
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+@pytest.mark.parametrize("m", [8, 16])
+def test_hamming_histogram_is_bit_exact(psc, m):
+    """Threshold adjustment (Section 4.2): the pair histogram equals the oracle's, count for count,
+    and both sides pick the same threshold for a 95 % filter."""
+    codes, qcodes, _ = _rand_problem(m, 300_007, 29, seed=40 + m, lut_kind="int")
+    got = psc.hamming_histogram(_dev(qcodes), _dev(codes))
+    torch.cuda.synchronize()
+    want = O.hamming_histogram(qcodes, codes)
+    assert np.array_equal(got.cpu().numpy(), want)
+    assert psc.threshold_for_rate(got, 0.05) == O.threshold_for_rate(want, 0.05)
+    empty = psc.hamming_histogram(_dev(qcodes), torch.empty((0, m), dtype=torch.uint8, device="cuda"))
+    assert int(empty.sum()) == 0

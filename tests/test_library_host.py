@@ -93,3 +93,21 @@ def test_annealing_matches_oracle_trajectory(psc):
     for j in range(8):
         assert sorted(pi[j].tolist()) == list(range(256))
     assert np.all(loss[:, 1] < loss[:, 0])
+
+
+def test_threshold_for_rate_agrees_with_the_oracle():
+    """Host-only entry point: same choice as the oracle's rule on random and hand-built histograms."""
+    import paper_1609_01882_amd as psc
+    rng = np.random.default_rng(12)
+    for nbits in (64, 128):
+        for _ in range(20):
+            hist = rng.integers(0, 1000, size=nbits + 1).astype(np.int64)
+            hist[rng.integers(0, nbits + 1, size=nbits // 2)] = 0
+            if hist.sum() == 0:
+                hist[3] = 1
+            for keep in (0.0, 0.001, 0.05, 0.3, 0.999, 1.0):
+                assert psc.threshold_for_rate(hist, keep) == O.threshold_for_rate(hist, keep)
+    toy = np.array([1, 2, 3, 4], dtype=np.int64)
+    assert [psc.threshold_for_rate(toy, r) for r in (0.05, 0.10, 0.30, 0.60, 1.0)] == [-1, 0, 1, 2, 3]
+    with pytest.raises(psc.PscError):
+        psc.threshold_for_rate(np.zeros(65, dtype=np.int64), 0.5)

@@ -109,3 +109,31 @@ def test_query_against_its_own_code_is_zero(tiny_pq):
     assert np.array_equal(qc, codes[:20])  # the query's bit string is its PQ code
     h = O.hamming_matrix(qc, codes[:20])
     assert np.all(np.diag(h) == 0)
+
+
+def test_histogram_and_threshold_for_rate():
+    """Pins for the threshold adjustment (Section 4.2): the histogram of uniformly random codes
+    follows the binomial law; the chosen threshold is the largest one within the allowed rate."""
+    from math import comb
+    qc = W.random_codes(40, 8, seed=5)
+    codes = W.random_codes(50_000, 8, seed=6)
+    hist = O.hamming_histogram(qc, codes, chunk=7001)
+    assert hist.shape == (65,) and hist.sum() == 40 * 50_000
+    # against the matrix, and against the binomial pmf within 6 sigma
+    assert np.array_equal(hist, np.bincount(O.hamming_matrix(qc, codes).ravel(), minlength=65))
+    tot = hist.sum()
+    for h in range(65):
+        p = comb(64, h) / 2.0 ** 64
+        assert abs(hist[h] - tot * p) <= 6.0 * np.sqrt(tot * p * (1 - p)) + 1.0
+    # hand-built histogram: 1, 2, 3, 4 pairs at distances 0..3 (10 in all)
+    toy = np.array([1, 2, 3, 4], dtype=np.int64)
+    assert O.threshold_for_rate(toy, 0.05) == -1      # even ht = 0 keeps 10 %
+    assert O.threshold_for_rate(toy, 0.10) == 0
+    assert O.threshold_for_rate(toy, 0.29) == 0
+    assert O.threshold_for_rate(toy, 0.30) == 1
+    assert O.threshold_for_rate(toy, 0.60) == 2
+    assert O.threshold_for_rate(toy, 1.00) == 3
+    # binomial law: P[h <= 24] = 3.0 %, P[h <= 25] = 5.2 % for 64 fair bits, so 5 % means ht = 24
+    cdf = np.cumsum([comb(64, h) / 2.0 ** 64 for h in range(65)])
+    want = int(np.max(np.nonzero(cdf <= 0.05)[0]))
+    assert want == 24 and O.threshold_for_rate(hist, 0.05) == want
