@@ -1111,12 +1111,6 @@ __global__ void init_scan_kernel(uint32_t *gthr, int64_t n, int *status)
     if (e == 0 && status) *status = 0;
 }
 
-__global__ void fill_u32_kernel(uint32_t *p, int64_t n, uint32_t v)
-{
-    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e < n) p[e] = v;
-}
-
 // Hamming filter alone: per query the number of codes within ht (and optionally every distance).
 template <int M>
 __global__ void __launch_bounds__(256)
