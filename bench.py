@@ -33,7 +33,7 @@ OPS_PER_PAIR = {8: 5, 16: 9}
 # Bytes per scan launch between L2 and the memory fabric, measured with rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE (two runs, scaled by what the same counters read for a 1 GiB copy:
 # x2.0 and x1.0), see profiles/scan_kernel_flat64_ht24.md; keyed by (workload, ht).
-MEASURED_TRAFFIC_BYTES = {("flat64", 24): 14.124e9 + 24.3e6}
+MEASURED_TRAFFIC_BYTES = {("flat64", 24): 14.039e9 + 24.3e6}
 
 
 def log(*a):
