@@ -5,18 +5,19 @@
 //     the lifetime of the workgroup;
 //   * the TQ query codes live in scalar registers;
 //   * every wave streams blocks of 64 x CB codes from memory into vector registers (16-byte
-//     loads, the next block prefetched; CB = 32 / TQ codes per lane) and compares each code with
-//     all TQ query codes: xor + popcount-accumulate per 32-bit word, then one funnel shift that
-//     appends the "too far" bit to a 32-bit per-lane mask (one bit per (code, query)):
-//     5 integer instructions per (query, 64-bit code) pair;
+//     loads, four blocks per turn with the next four already requested; CB = 32 / TQ codes per
+//     lane) and compares each code with all TQ query codes: xor + popcount-accumulate per
+//     32-bit word, then one funnel shift that appends the "too far" bit to a 32-bit per-lane
+//     mask (one bit per (code, query)): 5 integer instructions per (query, 64-bit code) pair;
 //   * lanes that hold survivors append one (bit number, code position) entry per turn to a
-//     per-wave ring in LDS, positions assigned with ballot + prefix popcount, so that the
+//     per-wave queue in LDS, positions assigned with ballot + prefix popcount, so that the
 //     expensive step runs on full wavefronts;
-//   * whenever the ring holds 64 entries the wave drains them: re-reads the 64 codes, gathers
-//     m table entries each from LDS, sums them in float32 (j ascending) and compares with the
-//     query's current k-th best distance;
-//   * the few candidates that pass are inserted into the query's sorted list in LDS by the whole
-//     wave, under a per-query lock (waves of the workgroup share the lists).
+//   * whenever the queue holds 64 entries the wave scores the newest 64: re-reads the codes,
+//     gathers m table entries each from LDS, sums them in float32 (j ascending) and compares
+//     with the query's current bound on its k-th best distance;
+//   * the few candidates that pass are spliced into the query's sorted list in LDS by the whole
+//     wave, under a per-query lock (waves of the workgroup share the lists); workgroups of one
+//     query tell each other their k-th best distances through a word in global memory.
 // Partial lists (one per query and slice) go to the workspace; a second kernel merges them.
 //
 // Ordering everywhere: (distance, id) ascending, lower id first on equal distance.
@@ -505,9 +506,9 @@ __device__ __forceinline__ void drain(const Lds<M, TQ> &s, const ScanArgs &a, co
     }
 }
 
-// SHARE: the workgroups of one query exchange their k-th-best distance through `gthr`.  Worth
-// a trip to memory per insertion when a query is served by many workgroups (inverted lists,
-// many slices), not when there are two.
+// IVF: tiles are (inverted list, up to TQ of its jobs) instead of (query tile, slice).
+// SHARE: the workgroups of one query exchange their k-th-best distance through `gthr`; worth
+// it when a query is served by many workgroups (inverted lists, four slices or more).
 template <int M, int TQ, int NW, bool IVF, bool SHARE>
 __global__ void __launch_bounds__(NW * 64)
 scan_kernel(ScanArgs a)
