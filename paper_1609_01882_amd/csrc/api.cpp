@@ -255,9 +255,7 @@ int psc_hamming_filter(int m, const uint8_t *qcodes_dev, int64_t nq, const uint8
 
 size_t psc_scan_workspace_bytes(int m, int64_t nq, int64_t n, int k)
 {
-    ScanPlan p;
-    if (plan_scan(m, nq, n, k, &p) != PSC_OK) return 0;
-    return p.total_bytes;
+    return flat_scan_workspace_bytes(m, nq, n, k);
 }
 
 int psc_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t nq,
@@ -273,9 +271,9 @@ static size_t round256(size_t v) { return (v + 255) / 256 * 256; }
 size_t psc_search_workspace_bytes(const psc_index *idx, int64_t nq, int64_t n, int k)
 {
     if (!idx) return 0;
-    ScanPlan p;
-    if (plan_scan(idx->m, nq, n, k, &p) != PSC_OK) return 0;
-    return round256(p.total_bytes) + round256((size_t)nq * idx->m * kCentroids * sizeof(float)) +
+    const size_t scan_bytes = flat_scan_workspace_bytes(idx->m, nq, n, k);
+    if (scan_bytes == 0) return 0;
+    return round256(scan_bytes) + round256((size_t)nq * idx->m * kCentroids * sizeof(float)) +
            round256((size_t)nq * idx->m);
 }
 
@@ -292,17 +290,15 @@ int psc_search(const psc_index *idx, const float *q_dev, int64_t nq, const uint8
                 need, workspace_bytes);
     PSC_REQUIRE(((uintptr_t)workspace_dev & 255) == 0, "workspace must be 256-byte aligned");
     // layout: [scan workspace (status word first)] [tables] [query codes]
-    ScanPlan p;
-    rc = plan_scan(idx->m, nq, n, k, &p);
-    if (rc != PSC_OK) return rc;
-    char *w = (char *)workspace_dev + round256(p.total_bytes);
+    const size_t scan_bytes = round256(flat_scan_workspace_bytes(idx->m, nq, n, k));
+    char *w = (char *)workspace_dev + scan_bytes;
     float *lut = (float *)w;
     w += round256((size_t)nq * idx->m * kCentroids * sizeof(float));
     uint8_t *qcodes = (uint8_t *)w;
     rc = psc_build_lut(idx, q_dev, nq, lut, qcodes, stream);
     if (rc != PSC_OK) return rc;
     return launch_scan(idx->m, lut, qcodes, nq, codes_dev, n, ht, k, -1, true, ids_dev, dists_dev,
-                       workspace_dev, round256(p.total_bytes), (hipStream_t)stream);
+                       workspace_dev, scan_bytes, (hipStream_t)stream);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -321,12 +317,12 @@ static size_t graph_scan_workspace(const psc_index *idx, int64_t n, int k)
 {
     const int64_t qc = n < kGraphChunk ? n : kGraphChunk;
     const int64_t tail = n % kGraphChunk;
-    ScanPlan p, pt;
-    if (plan_scan(idx->m, qc, n, k, &p) != PSC_OK) return 0;
-    size_t bytes = p.total_bytes;
+    size_t bytes = flat_scan_workspace_bytes(idx->m, qc, n, k);
+    if (bytes == 0) return 0;
     if (n > kGraphChunk && tail != 0) {
-        if (plan_scan(idx->m, tail, n, k, &pt) != PSC_OK) return 0;
-        if (pt.total_bytes > bytes) bytes = pt.total_bytes;
+        const size_t tb = flat_scan_workspace_bytes(idx->m, tail, n, k);
+        if (tb == 0) return 0;
+        if (tb > bytes) bytes = tb;
     }
     return round256(bytes);
 }
@@ -603,7 +599,7 @@ int ivf_layout(const psc_index *idx, int64_t nq, int nprobe, int k, IvfLayout *L
     L->njobs = nq * nprobe;
     PSC_REQUIRE(L->njobs < 0x7fffffffLL, "too many (query, list) jobs");
     // (few jobs are tiles of their own: the narrowest tile shape then wastes the least filter work)
-    int rc = plan_scan(idx->m, L->njobs > kDirectJobs ? L->njobs : 1, idx->list_n, k, &L->plan);
+    int rc = plan_scan(idx->m, L->njobs > kDirectJobs ? L->njobs : 1, idx->list_n, k, kScanLists, &L->plan);
     if (rc != PSC_OK) return rc;
     L->nblk = (nq + 15) / 16;
     L->max_tiles = L->njobs <= kDirectJobs ? L->njobs : L->njobs / L->plan.tq + 2 * (int64_t)idx->nlist;
@@ -698,7 +694,7 @@ int psc_ivf_search(const psc_index *idx, const float *q_dev, int64_t nq, int npr
     if (rc != PSC_OK) return rc;
     const float *list_tab = idx->list_tab_dev;
     // 4. the fused scan over the tiles, 5. one merge per query over its nprobe partial lists
-    rc = launch_ivf_scan(idx->m, L.plan.tq, L.plan.kpad, L.plan.lds_bytes, lut, list_tab, q_dev, idx->coarse_dev,
+    rc = launch_ivf_scan(idx->m, L.plan.tq, L.plan.nwaves, L.plan.kpad, L.plan.lds_bytes, lut, list_tab, q_dev, idx->coarse_dev,
                          idx->dim, idx->nlist, qcodes, idx->list_codes_dev, idx->list_n, ht, k, jb.tiles,
                          jb.tile_begin + 2 * idx->nlist, L.max_tiles, idx->list_off_dev, idx->list_ids_dev,
                          jb.job_slot, jb.job_q, (uint32_t *)(w + L.off_gthr), (float *)(w + L.off_part_d),

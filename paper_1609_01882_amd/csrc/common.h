@@ -63,6 +63,7 @@ int launch_row_argmin(const float *lut_dev, int64_t nrows_total, uint8_t *codes_
 struct ScanPlan {
     int tq = 0;          // queries per workgroup tile
     int nwaves = 0;      // waves per workgroup
+    int wgs_per_cu = 1;  // workgroups of this shape a compute unit holds at a time
     int kpad = 0;        // k rounded up to a multiple of 4: the stride of a list in LDS
     int nslice = 0;      // database slices (one workgroup per (query tile, slice))
     int64_t slice_len = 0;
@@ -72,7 +73,11 @@ struct ScanPlan {
     size_t part_bytes = 0;  // partial result lists
     size_t total_bytes = 0; // whole workspace
 };
-int plan_scan(int m, int64_t nq, int64_t n, int k, ScanPlan *plan);
+// kind: which scan the plan is for (the shapes differ)
+enum { kScanFused = 0, kScanDense = 1, kScanLists = 2 };
+int plan_scan(int m, int64_t nq, int64_t n, int k, int kind, ScanPlan *plan);
+// Workspace that serves a flat scan whatever route (fused or dense) the threshold selects.
+size_t flat_scan_workspace_bytes(int m, int64_t nq, int64_t n, int k);
 // skip_first >= 0: query q never returns database row skip_first + q (k-NN-graph mode).
 // clear_status: reset the workspace's status word first (false for follow-up chunks of one call).
 int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t nq,
@@ -82,7 +87,8 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
 // lut_dev: tables of the queries minus the mean coarse centroid, [nq][m][256]; list_tab_dev:
 // the lists' share of the residual tables (launch_list_tables); job_qcodes_dev: out, the query
 // code of every job, in job order.
-int launch_ivf_scan(int m, int tq, int kpad, size_t lds_bytes, const float *lut_dev, const float *list_tab_dev,
+int launch_ivf_scan(int m, int tq, int nwaves, int kpad, size_t lds_bytes, const float *lut_dev,
+                    const float *list_tab_dev,
                     const float *queries_dev, const float *coarse_dev, int dim, int nlist,
                     uint8_t *job_qcodes_dev, const uint8_t *codes_dev, int64_t n, int ht, int k,
                     const void *tiles_dev, const int *ntiles_dev, int64_t max_tiles,

@@ -1225,24 +1225,43 @@ double random_code_survival(int nbits, int ht)
     return sum;
 }
 
+// The tile shapes plan_scan hands out (queries per tile x waves per workgroup).
 template <bool IVF, bool SHARE>
-int dispatch_scan(int m, int tq, const ScanArgs &a, int64_t ntiles, size_t lds, hipStream_t s)
+int dispatch_scan(int m, int tq, int nwaves, const ScanArgs &a, int64_t ntiles, size_t lds, hipStream_t s)
 {
-    if (m == 8) {
-        if (tq == 16) return run_scan<8, 16, 16, IVF, SHARE>(a, ntiles, lds, s);
-        if (tq == 8) return run_scan<8, 8, 16, IVF, SHARE>(a, ntiles, lds, s);
-        return run_scan<8, 4, 16, IVF, SHARE>(a, ntiles, lds, s);
+    if constexpr (IVF) {
+        if (m == 8 && tq == 4 && nwaves == 8) return run_scan<8, 4, 8, true, SHARE>(a, ntiles, lds, s);
+        if (m == 8 && tq == 4 && nwaves == 16) return run_scan<8, 4, 16, true, SHARE>(a, ntiles, lds, s);
+        if (m == 16 && tq == 8 && nwaves == 16) return run_scan<16, 8, 16, true, SHARE>(a, ntiles, lds, s);
+        if (m == 16 && tq == 4 && nwaves == 16) return run_scan<16, 4, 16, true, SHARE>(a, ntiles, lds, s);
+    } else {
+        if (m == 8 && tq == 8 && nwaves == 8) return run_scan<8, 8, 8, false, SHARE>(a, ntiles, lds, s);
+        if (m == 8 && tq == 16 && nwaves == 16) return run_scan<8, 16, 16, false, SHARE>(a, ntiles, lds, s);
+        if (m == 8 && tq == 8 && nwaves == 16) return run_scan<8, 8, 16, false, SHARE>(a, ntiles, lds, s);
+        if (m == 8 && tq == 4 && nwaves == 16) return run_scan<8, 4, 16, false, SHARE>(a, ntiles, lds, s);
+        if (m == 16 && tq == 8 && nwaves == 16) return run_scan<16, 8, 16, false, SHARE>(a, ntiles, lds, s);
+        if (m == 16 && tq == 4 && nwaves == 16) return run_scan<16, 4, 16, false, SHARE>(a, ntiles, lds, s);
     }
-    if (tq == 8) return run_scan<16, 8, 16, IVF, SHARE>(a, ntiles, lds, s);
-    return run_scan<16, 4, 16, IVF, SHARE>(a, ntiles, lds, s);
+    set_error("no kernel for tile shape m=%d tq=%d waves=%d", m, tq, nwaves);
+    return PSC_EINVAL;
 }
 
 constexpr size_t kLdsBudget = 160 * 1024;
 
 }  // namespace
 
-// Tile shape: as many queries per tile as fit in LDS with their tables and lists.
-int plan_scan(int m, int64_t nq, int64_t n, int k, ScanPlan *plan)
+// Tile shape and database slices.
+// Shapes (queries per tile x waves per workgroup), per kind of scan, first one that fits:
+//  * fused scan, 64-bit codes, more than 16 queries: 8 x 8, two workgroups per compute unit (one
+//    stages its tables or waits on a list lock while the other filters; fewer waves per list
+//    lock) -- measured 4% (clustered codes) to 11% (random codes) ahead of 16 x 16 at ht=24;
+//    falls back to 16 x 16, 8 x 16, 4 x 16 as k grows (the lists share LDS with the tables);
+//  * up to 4 / 8 / 16 queries: no more query slots than queries (every slot costs filter work),
+//    which keeps a one-pass scan of few queries bound by memory bandwidth;
+//  * grouped inverted-file jobs: 4 x 8, three workgroups per compute unit (tiles are short, so
+//    their set-up and tail overlap better: 12.4 -> 9.3 ms on the 100M workload);
+//  * dense route and 128-bit codes: 16-wave workgroups, as many queries as fit.
+int plan_scan(int m, int64_t nq, int64_t n, int k, int kind, ScanPlan *plan)
 {
     if (m != 8 && m != 16) {
         set_error("m must be 8 or 16, got %d", m);
@@ -1258,19 +1277,27 @@ int plan_scan(int m, int64_t nq, int64_t n, int k, ScanPlan *plan)
     }
     ScanPlan p;
     p.kpad = (k + 3) / 4 * 4;
-    p.nwaves = 16;
-    const int tq_options[3] = {16, 8, 4};
-    p.tq = 0;
-    // small batches: no more query slots than queries (every slot costs filter work), which
-    // keeps a one-pass scan of few queries bound by memory bandwidth rather than by the ALUs
+    struct Shape {
+        int tq, nwaves;
+        size_t max_lds;  // the shape is meant for this many bytes at most (several workgroups per unit)
+    };
     const int tq_cap = nq <= 4 ? 4 : (nq <= 8 ? 8 : 16);
-    for (int t : tq_options) {
+    Shape options[5];
+    int nopt = 0;
+    if (m == 8 && kind == kScanLists) options[nopt++] = Shape{4, 8, kLdsBudget / 2};
+    if (m == 8 && kind == kScanFused && nq > 16) options[nopt++] = Shape{8, 8, kLdsBudget / 2};
+    if (m == 8 && kind != kScanLists) options[nopt++] = Shape{16, 16, kLdsBudget};
+    if (kind != kScanLists || m == 16) options[nopt++] = Shape{8, 16, kLdsBudget};
+    options[nopt++] = Shape{4, 16, kLdsBudget};
+    p.tq = 0;
+    for (int o = 0; o < nopt; ++o) {
+        const int t = options[o].tq, nw = options[o].nwaves;
         if (t > tq_cap) continue;
-        if (m == 16 && t == 16) continue;  // 16 tables of 16 KiB do not fit
-        size_t need = (size_t)t * m * 256 * 4 + (size_t)t * p.kpad * 8 + (size_t)t * 12 + (size_t)t * m * 5 +
-                      (size_t)p.nwaves * (kQueueCap + 64) * 4;
-        if (need <= kLdsBudget) {
+        const size_t need = (size_t)t * m * 256 * 4 + (size_t)t * p.kpad * 8 + (size_t)t * 12 + (size_t)t * m * 5 +
+                            (size_t)nw * (kQueueCap + 64) * 4;
+        if (need <= options[o].max_lds) {
             p.tq = t;
+            p.nwaves = nw;
             p.lds_bytes = need;
             break;
         }
@@ -1279,26 +1306,31 @@ int plan_scan(int m, int64_t nq, int64_t n, int k, ScanPlan *plan)
         set_error("no tile shape fits LDS for m=%d k=%d", m, k);
         return PSC_EINVAL;
     }
+    // workgroups of this shape a compute unit holds at a time (LDS, and 32 waves)
+    p.wgs_per_cu = (int)std::max<size_t>(1, std::min<size_t>(kLdsBudget / p.lds_bytes, (size_t)(32 / p.nwaves)));
+    // (one workgroup per unit already saturates memory for a handful of queries, and every further
+    //  slice costs list and merge work: measured best at 256 workgroups for 1 to 128 queries)
+    const int64_t round = 256 * (int64_t)(nq <= 16 ? 1 : p.wgs_per_cu);
     const int64_t nqt = (nq + p.tq - 1) / p.tq;
-    // Slices: one workgroup per (query tile, slice) and one workgroup per compute unit at a
-    // time, so the launch runs in rounds of 256.  Every slice of a query builds its own list of
-    // k, which costs insertions and merge work, so the fewest slices win that fill the rounds:
-    // score = share of the rounds' places that are used, less 1% per round.
+    // Slices: one workgroup per (query tile, slice); the launch runs in rounds of `round`
+    // workgroups.  Every slice of a query builds its own list of k, which costs insertions and
+    // merge work, so the fewest slices win that fill the rounds: score = share of the rounds'
+    // places that are used, less 1% per round.
     const int64_t block = 512;  // codes per wave and step, at most (64 lanes x 8 codes)
     int64_t want = 1;
     if (nqt > 0) {
-        const int64_t wg_limit = 2048;
+        const int64_t wg_limit = 8 * round;
         double best_score = -1.0;
         for (int64_t sN = 1; sN * nqt <= std::max<int64_t>(wg_limit, nqt); ++sN) {
-            const int64_t wg = nqt * sN, rounds = (wg + 255) / 256;
-            const double score = (double)wg / (double)(rounds * 256) - 0.01 * (double)rounds;
+            const int64_t wg = nqt * sN, rounds = (wg + round - 1) / round;
+            const double score = (double)wg / (double)(rounds * round) - 0.01 * (double)rounds;
             if (score > best_score + 1e-9) {
                 best_score = score;
                 want = sN;
             }
         }
     }
-    const int64_t min_slice = 16 * block;  // at least one block per wave
+    const int64_t min_slice = p.nwaves * block;  // at least one block per wave
     int64_t max_by_size = std::max<int64_t>(1, n / min_slice);
     int64_t nslice = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, max_by_size), 1024));
     int64_t slice_len = (((n + nslice - 1) / nslice) + block - 1) / block * block;
@@ -1323,15 +1355,27 @@ int plan_scan(int m, int64_t nq, int64_t n, int k, ScanPlan *plan)
     return PSC_OK;
 }
 
+size_t flat_scan_workspace_bytes(int m, int64_t nq, int64_t n, int k)
+{
+    ScanPlan fused, dense;
+    if (plan_scan(m, nq, n, k, kScanFused, &fused) != PSC_OK) return 0;
+    if (plan_scan(m, nq, n, k, kScanDense, &dense) != PSC_OK) return 0;
+    return std::max(fused.total_bytes, dense.total_bytes);
+}
+
 int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t nq,
                 const uint8_t *codes_dev, int64_t n, int ht, int k, int64_t skip_first,
                 bool clear_status, int64_t *ids_dev, float *dists_dev, void *ws, size_t ws_bytes,
                 hipStream_t s)
 {
-    ScanPlan p;
-    int rc = plan_scan(m, nq, n, k, &p);
-    if (rc != PSC_OK) return rc;
     PSC_REQUIRE(ht >= 0, "ht must be >= 0, got %d", ht);
+    // survivor share from which scoring every pair is the faster route (measured at 10M x 10k:
+    // 64-bit codes cross between ht = 30 and 31, 128-bit codes between ht = 61 and 62)
+    const double dense_from = 0.36;
+    const bool dense = ht >= 8 * m || random_code_survival(8 * m, ht) >= dense_from;
+    ScanPlan p;
+    int rc = plan_scan(m, nq, n, k, dense ? kScanDense : kScanFused, &p);
+    if (rc != PSC_OK) return rc;
     if (nq == 0) return PSC_OK;
     PSC_REQUIRE(ids_dev && dists_dev, "null result pointer");
     if (n == 0) {
@@ -1382,18 +1426,15 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
     a.list_off = nullptr;
     a.ext_ids = nullptr;
     a.job_slot = nullptr;
-    // survivor share from which scoring every pair is the faster route (measured at 10M x 10k:
-    // 64-bit codes cross between ht = 30 and 31, 128-bit codes between ht = 61 and 62)
-    const double dense_from = 0.36;
     if (ht >= nbits)  // nothing to filter: the pure-ADC kernel
         rc = p.nslice >= 4 ? dispatch_adc<true, false>(m, p.tq, a, p.ntiles, p.lds_bytes, s)
                            : dispatch_adc<false, false>(m, p.tq, a, p.ntiles, p.lds_bytes, s);
-    else if (random_code_survival(nbits, ht) >= dense_from)
+    else if (dense)
         rc = p.nslice >= 4 ? dispatch_adc<true, true>(m, p.tq, a, p.ntiles, p.lds_bytes, s)
                            : dispatch_adc<false, true>(m, p.tq, a, p.ntiles, p.lds_bytes, s);
     else
-        rc = p.nslice >= 4 ? dispatch_scan<false, true>(m, p.tq, a, p.ntiles, p.lds_bytes, s)
-                           : dispatch_scan<false, false>(m, p.tq, a, p.ntiles, p.lds_bytes, s);
+        rc = p.nslice >= 4 ? dispatch_scan<false, true>(m, p.tq, p.nwaves, a, p.ntiles, p.lds_bytes, s)
+                           : dispatch_scan<false, false>(m, p.tq, p.nwaves, a, p.ntiles, p.lds_bytes, s);
     if (rc != PSC_OK) return rc;
     return launch_merge(a.part_d, a.part_i, nq, p.nslice, k, a.status, ids_dev, dists_dev, s);
 }
@@ -1401,7 +1442,8 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
 // Inverted-file scan: one workgroup per tile descriptor (up to `max_tiles`; the actual count is
 // read on the device), partial lists written at job_slot[job] * k, then one merge per query
 // over its nprobe partial lists.
-int launch_ivf_scan(int m, int tq, int kpad, size_t lds_bytes, const float *lut_dev, const float *list_tab_dev,
+int launch_ivf_scan(int m, int tq, int nwaves, int kpad, size_t lds_bytes, const float *lut_dev,
+                    const float *list_tab_dev,
                     const float *queries_dev, const float *coarse_dev, int dim, int nlist,
                     uint8_t *job_qcodes_dev, const uint8_t *codes_dev, int64_t n, int ht, int k,
                     const void *tiles_dev, const int *ntiles_dev, int64_t max_tiles,
@@ -1445,7 +1487,7 @@ int launch_ivf_scan(int m, int tq, int kpad, size_t lds_bytes, const float *lut_
     a.gthr = gthr_dev;
     hipLaunchKernelGGL(init_scan_kernel, dim3((unsigned)((nq + 255) / 256)), dim3(256), 0, s, gthr_dev, nq, a.status);
     if (max_tiles > 0) {
-        int rc = dispatch_scan<true, true>(m, tq, a, max_tiles, lds_bytes, s);
+        int rc = dispatch_scan<true, true>(m, tq, nwaves, a, max_tiles, lds_bytes, s);
         if (rc != PSC_OK) return rc;
     }
     return launch_merge(part_d, part_i, nq, nprobe, k, status, ids_dev, dists_dev, s);
