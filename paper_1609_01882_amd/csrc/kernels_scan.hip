@@ -1200,8 +1200,15 @@ int run_adc(const ScanArgs &a, int64_t ntiles, size_t lds, hipStream_t s)
 }
 
 template <bool SHARE, bool FILTER>
-int dispatch_adc(int m, int tq, const ScanArgs &a, int64_t ntiles, size_t lds, hipStream_t s)
+int dispatch_adc(int m, int tq, int nwaves, const ScanArgs &a, int64_t ntiles, size_t lds, hipStream_t s)
 {
+    if constexpr (FILTER) {
+        if (m == 8 && tq == 8 && nwaves == 8) return run_adc<8, 8, 8, SHARE, true>(a, ntiles, lds, s);
+    }
+    if (nwaves != 16) {
+        set_error("no kernel for tile shape m=%d tq=%d waves=%d", m, tq, nwaves);
+        return PSC_EINVAL;
+    }
     if (m == 8) {
         if (tq == 16) return run_adc<8, 16, 16, SHARE, FILTER>(a, ntiles, lds, s);
         if (tq == 8) return run_adc<8, 8, 16, SHARE, FILTER>(a, ntiles, lds, s);
@@ -1260,7 +1267,8 @@ constexpr size_t kLdsBudget = 160 * 1024;
 //    which keeps a one-pass scan of few queries bound by memory bandwidth;
 //  * grouped inverted-file jobs: 4 x 8, three workgroups per compute unit (tiles are short, so
 //    their set-up and tail overlap better: 12.4 -> 9.3 ms on the 100M workload);
-//  * dense route and 128-bit codes: 16-wave workgroups, as many queries as fit.
+//  * dense route with the Hamming test: 8 x 8 as well (103 -> 91 ms at ht=32); without it the
+//    16-wave shapes are ahead (70 against 76 ms), as they are for 128-bit codes.
 int plan_scan(int m, int64_t nq, int64_t n, int k, int kind, ScanPlan *plan)
 {
     if (m != 8 && m != 16) {
@@ -1285,7 +1293,8 @@ int plan_scan(int m, int64_t nq, int64_t n, int k, int kind, ScanPlan *plan)
     Shape options[5];
     int nopt = 0;
     if (m == 8 && kind == kScanLists) options[nopt++] = Shape{4, 8, kLdsBudget / 2};
-    if (m == 8 && kind == kScanFused && nq > 16) options[nopt++] = Shape{8, 8, kLdsBudget / 2};
+    if (m == 8 && (kind == kScanFused || kind == kScanDenseFiltered) && nq > 16)
+        options[nopt++] = Shape{8, 8, kLdsBudget / 2};
     if (m == 8 && kind != kScanLists) options[nopt++] = Shape{16, 16, kLdsBudget};
     if (kind != kScanLists || m == 16) options[nopt++] = Shape{8, 16, kLdsBudget};
     options[nopt++] = Shape{4, 16, kLdsBudget};
@@ -1357,10 +1366,13 @@ int plan_scan(int m, int64_t nq, int64_t n, int k, int kind, ScanPlan *plan)
 
 size_t flat_scan_workspace_bytes(int m, int64_t nq, int64_t n, int k)
 {
-    ScanPlan fused, dense;
-    if (plan_scan(m, nq, n, k, kScanFused, &fused) != PSC_OK) return 0;
-    if (plan_scan(m, nq, n, k, kScanDense, &dense) != PSC_OK) return 0;
-    return std::max(fused.total_bytes, dense.total_bytes);
+    size_t bytes = 0;
+    for (int kind : {kScanFused, kScanDense, kScanDenseFiltered}) {
+        ScanPlan p;
+        if (plan_scan(m, nq, n, k, kind, &p) != PSC_OK) return 0;
+        bytes = std::max(bytes, p.total_bytes);
+    }
+    return bytes;
 }
 
 int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t nq,
@@ -1374,7 +1386,7 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
     const double dense_from = 0.36;
     const bool dense = ht >= 8 * m || random_code_survival(8 * m, ht) >= dense_from;
     ScanPlan p;
-    int rc = plan_scan(m, nq, n, k, dense ? kScanDense : kScanFused, &p);
+    int rc = plan_scan(m, nq, n, k, !dense ? kScanFused : (ht >= 8 * m ? kScanDense : kScanDenseFiltered), &p);
     if (rc != PSC_OK) return rc;
     if (nq == 0) return PSC_OK;
     PSC_REQUIRE(ids_dev && dists_dev, "null result pointer");
@@ -1427,11 +1439,11 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
     a.ext_ids = nullptr;
     a.job_slot = nullptr;
     if (ht >= nbits)  // nothing to filter: the pure-ADC kernel
-        rc = p.nslice >= 4 ? dispatch_adc<true, false>(m, p.tq, a, p.ntiles, p.lds_bytes, s)
-                           : dispatch_adc<false, false>(m, p.tq, a, p.ntiles, p.lds_bytes, s);
+        rc = p.nslice >= 4 ? dispatch_adc<true, false>(m, p.tq, p.nwaves, a, p.ntiles, p.lds_bytes, s)
+                           : dispatch_adc<false, false>(m, p.tq, p.nwaves, a, p.ntiles, p.lds_bytes, s);
     else if (dense)
-        rc = p.nslice >= 4 ? dispatch_adc<true, true>(m, p.tq, a, p.ntiles, p.lds_bytes, s)
-                           : dispatch_adc<false, true>(m, p.tq, a, p.ntiles, p.lds_bytes, s);
+        rc = p.nslice >= 4 ? dispatch_adc<true, true>(m, p.tq, p.nwaves, a, p.ntiles, p.lds_bytes, s)
+                           : dispatch_adc<false, true>(m, p.tq, p.nwaves, a, p.ntiles, p.lds_bytes, s);
     else
         rc = p.nslice >= 4 ? dispatch_scan<false, true>(m, p.tq, p.nwaves, a, p.ntiles, p.lds_bytes, s)
                            : dispatch_scan<false, false>(m, p.tq, p.nwaves, a, p.ntiles, p.lds_bytes, s);
