@@ -33,7 +33,7 @@ OPS_PER_PAIR = {8: 5, 16: 9}
 # Bytes per scan launch between L2 and the memory fabric, measured with rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE (two runs, scaled by what the same counters read for a 1 GiB copy:
 # x2.0 and x1.0), see profiles/scan_kernel_flat64_ht24.md; keyed by (workload, ht).
-MEASURED_TRAFFIC_BYTES = {("flat64", 24): 14.039e9 + 24.3e6}
+MEASURED_TRAFFIC_BYTES = {("flat64", 24): 75.656e9 + 24.3e6}
 
 
 def log(*a):
@@ -252,7 +252,7 @@ def main():
         "ht_removing_95pct_of_training_pairs": ht_rule,
         "recall_at_10": recall10,
         "survivor_rate": surv_rate,
-        "roofline": {"bound": "alu", "kernel": "scan_kernel<8,16,16>", "achieved": achieved,
+        "roofline": {"bound": "alu", "kernel": "scan_kernel<8,8,8>", "achieved": achieved,
                      "peak": PEAK_INT_TOPS, "unit": "TOP/s (int32 lane-ops)", "frac": achieved / PEAK_INT_TOPS,
                      "ops_per_pair": OPS_PER_PAIR[m], "kernel_ms": scan_ms,
                      "traffic": None if args.small else MEASURED_TRAFFIC_BYTES.get(("flat64", args.ht))},
