@@ -51,7 +51,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-small-batch", action="store_true",
                     help="skip the memory-bound side measurement (1 and 16 queries over 400M codes)")
-    ap.add_argument("--cpu-queries", type=int, default=192)
+    ap.add_argument("--cpu-queries", type=int, default=1024)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (known traffic, for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
