@@ -7,8 +7,9 @@ sub-quantizers around the annealing of the index assignment.
 
 Nothing in the product path may import this module.
 
-Unpinned (only invariants are tested): the k-means codebook and the annealing
-trajectory; see the tests named test_oracle_*.
+Parity unpinned (only invariants are tested): the k-means codebook (`kmeans`, `train_pq`,
+`ivf_train_coarse`) and which local minimum the annealing ends in (`anneal`,
+`optimize_index_assignment`); see the tests named test_oracle_*.
 """
 from __future__ import annotations
 

@@ -27,9 +27,12 @@
  *   - results are ordered by (distance, id) ascending, lower id first on equal
  *     distance; short lists are padded with id -1 and distance +infinity.
  *
- * Pins: see tests/test_oracle_*.py.  Unpinned parts are named there and in
- * the design notes: the k-means codebook itself and the simulated-annealing
- * trajectory (only their invariants are pinned).
+ * Pins: see tests/test_oracle_*.py.
+ * Parity unpinned: the k-means codebook (kmeans, train_pq, ivf_train_coarse on
+ * the Python side) and which local minimum the simulated annealing ends in
+ * (orc_anneal): nothing printed in the paper fixes them, so only their
+ * invariants are pinned (objective never rises, result is a permutation,
+ * incremental cost change = full recomputation, final loss below initial).
  */
 #include <math.h>
 #include <stdint.h>
