@@ -111,3 +111,24 @@ def test_threshold_for_rate_agrees_with_the_oracle():
     assert [psc.threshold_for_rate(toy, r) for r in (0.05, 0.10, 0.30, 0.60, 1.0)] == [-1, 0, 1, 2, 3]
     with pytest.raises(psc.PscError):
         psc.threshold_for_rate(np.zeros(65, dtype=np.int64), 0.5)
+
+
+def test_workspace_sizes_over_a_grid(psc):
+    """The planner (host logic, no GPU): a workspace size for every valid shape of problem, always
+    covering status word + shared thresholds + one partial list per query and never more than 1024
+    partial lists per query; search and inverted-file workspaces add their tables on top."""
+    for m in (8, 16):
+        for k in (1, 10, 100, 121, 157, 400, psc.PSC_MAX_K):
+            for nq in (1, 4, 5, 16, 17, 1000, 10_000):
+                for n in (0, 1, 10_000, 10_000_000, 400_000_000):
+                    b = psc.scan_workspace_bytes(m, nq, n, k)
+                    assert 256 + 4 * nq + 12 * nq * k <= b <= 1024 + 4 * nq + 256 + 12 * nq * k * 1024, (m, k, nq, n, b)
+    idx = psc.Index(128, 8)
+    idx.set_codebook(np.zeros((8, 256, 16), np.float32))
+    assert idx.search_workspace_bytes(100, 1_000_000, 10) >= psc.scan_workspace_bytes(8, 100, 1_000_000, 10) + 100 * 8 * 1024
+    assert idx.knn_graph_workspace_bytes(100_000, 10) > 0
+    idx.ivf_set_coarse(np.zeros((50, 128), np.float32))
+    small, big = idx.ivf_search_workspace_bytes(1, 8, 10), idx.ivf_search_workspace_bytes(10_000, 8, 10)
+    assert 0 < small < big
+    # more probes than lists: clipped to the number of lists
+    assert idx.ivf_search_workspace_bytes(10, 2000, 10) == idx.ivf_search_workspace_bytes(10, 50, 10)
