@@ -153,6 +153,14 @@ def main():
         del src, dst
 
     ms_step, scan_ms = run(args.ht, args.steps, args.warmup)
+    # the tables and query codes alone (part of every step above), for the record
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        idx.build_lut(q_dev)
+    e1.record()
+    torch.cuda.synchronize()
+    lut_ms = e0.elapsed_time(e1) / 5
     pairs = float(nq) * float(n_db)
     recall10 = float((ids[:, :10] == best_i[:, None]).any(dim=1).float().mean())
     nsurv = psc.hamming_filter(idx.build_lut(q_dev[:256])[1], codes, args.ht)
@@ -242,6 +250,7 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": ms_step,
+        "lut_ms": lut_ms,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,

@@ -74,7 +74,7 @@ struct ScanPlan {
     size_t total_bytes = 0; // whole workspace
 };
 // kind: which scan the plan is for (the shapes differ)
-enum { kScanFused = 0, kScanDense = 1, kScanLists = 2, kScanDenseFiltered = 3 };
+enum { kScanFused = 0, kScanDense = 1, kScanLists = 2, kScanDenseFiltered = 3, kScanFusedMfma = 4 };
 int plan_scan(int m, int64_t nq, int64_t n, int k, int kind, ScanPlan *plan);
 // Workspace that serves a flat scan whatever route (fused or dense) the threshold selects.
 size_t flat_scan_workspace_bytes(int m, int64_t nq, int64_t n, int k);

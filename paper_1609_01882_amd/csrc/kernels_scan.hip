@@ -22,6 +22,7 @@
 //
 // Ordering everywhere: (distance, id) ascending, lower id first on equal distance.
 #include <cstdlib>
+#include <cstring>
 #include <type_traits>
 
 #include "common.h"
@@ -33,6 +34,10 @@ constexpr int kQueueCap = 128;        // ring entries per wave (power of two, >=
 constexpr int kRelBits = 27;          // bits of a ring entry holding the position inside the slice
 constexpr uint32_t kRelMask = (1u << kRelBits) - 1;
 constexpr int64_t kMaxSliceLen = (int64_t)1 << kRelBits;
+constexpr int kMfmaRelBits = 25;      // the same for the matrix-core filter (two more bits name the lane's row group)
+constexpr uint32_t kMfmaRelMask = (1u << kMfmaRelBits) - 1;
+constexpr int64_t kMfmaMaxSliceLen = (int64_t)1 << kMfmaRelBits;
+constexpr int kMfmaTableBytes = 256 * 8;  // the bits-to-elements table of the matrix-core filter
 constexpr int kSpinLimit = 1 << 22;   // bounded wait on a list lock (each turn sleeps)
 
 struct IvfTile {
@@ -427,11 +432,36 @@ struct SharedAsk {
     bool wanted = true;  // wave-uniform: the previous batch changed a list (or there was none yet)
 };
 
+// The queueing loop of the fused kernels, hand-scheduled (see the comment where it is used).
+// Operands: sv (survivor bits of the lane, consumed), fill (entries waiting, scalar), base (byte
+// address of queue slot `fill`, scalar), rel0 (low bits of the lane's entries), dump (address a
+// lane without a bit writes to); t0, t1 vector and n scalar temporaries.
+#define PSC_QUEUE_TURNS                                    \
+    "1:\n\t"                                               \
+    "v_cmp_ne_u32_e32 vcc, 0, %[sv]\n\t"                   \
+    "s_cbranch_vccz 2f\n\t"                                \
+    "v_mbcnt_lo_u32_b32 %[t0], vcc_lo, 0\n\t"              \
+    "v_mbcnt_hi_u32_b32 %[t0], vcc_hi, %[t0]\n\t"          \
+    "v_ffbl_b32_e32 %[t1], %[sv]\n\t"                      \
+    "v_lshl_add_u32 %[t0], %[t0], 2, %[base]\n\t"          \
+    "v_lshl_or_b32 %[t1], %[t1], 27, %[rel0]\n\t"          \
+    "v_cndmask_b32_e32 %[t0], %[dump], %[t0], vcc\n\t"     \
+    "ds_write_b32 %[t0], %[t1]\n\t"                        \
+    "s_bcnt1_i32_b64 %[n], vcc\n\t"                        \
+    "v_add_u32_e32 %[t0], -1, %[sv]\n\t"                   \
+    "s_lshl2_add_u32 %[base], %[n], %[base]\n\t"           \
+    "v_and_b32_e32 %[sv], %[sv], %[t0]\n\t"                \
+    "s_add_i32 %[fill], %[fill], %[n]\n\t"                 \
+    "s_cmp_lt_i32 %[fill], 64\n\t"                         \
+    "s_cbranch_scc1 1b\n\t"                                \
+    "2:"
+
 // Score `nvalid` (<= 64) entries of the wave's queue, starting at `ring`, and feed the ones that
 // beat the current threshold to the lists.  `slice_codes` = the codes of the tile's slice
 // (position 0 of the entries); `self0 + q` = the position query slot q must not return (graph
 // mode; a value no position can take otherwise).
-template <int M, int TQ, bool IVF, bool SHARE>
+// MFMA_BITS: the entries come from the matrix-core filter (see scan_mfma_kernel for their layout).
+template <int M, int TQ, bool IVF, bool SHARE, bool MFMA_BITS = false>
 __device__ __forceinline__ void drain(const Lds<M, TQ> &s, const ScanArgs &a, const lds_u32 *ring, int nvalid,
                                       const uint8_t *slice_codes, int64_t slice_begin, uint32_t self0,
                                       SharedAsk &ask)
@@ -449,9 +479,15 @@ __device__ __forceinline__ void drain(const Lds<M, TQ> &s, const ScanArgs &a, co
     if (act) {
         // entry = (b << kRelBits) | position of the lane's first code; b = c * TQ + (TQ - 1 - q)
         const uint32_t e = ring[lane];
-        const uint32_t b = e >> kRelBits;
-        q = (int)((TQ - 1) - (b & (TQ - 1)));
-        rel = (e & kRelMask) + b / TQ;
+        if constexpr (MFMA_BITS) {
+            const uint32_t idx = ~e >> kRelBits;  // 31 - (bit number): 4 * (16-code group) + row
+            q = (int)(4u * ((e >> kMfmaRelBits) & 3u) + (idx & 3u));
+            rel = (e & kMfmaRelMask) + 16u * (idx >> 2);
+        } else {
+            const uint32_t b = e >> kRelBits;
+            q = (int)((TQ - 1) - (b & (TQ - 1)));
+            rel = (e & kRelMask) + b / TQ;
+        }
         const uint32_t *cw = (const uint32_t *)(slice_codes + (uint64_t)rel * M);
         uint32_t w[M / 4];
         if constexpr (M == 8) {
@@ -765,29 +801,11 @@ scan_kernel(ScanArgs a)
                 // write to their dump word.  `base` = byte address of queue slot `fill`.
                 fill = __builtin_amdgcn_readfirstlane(fill);  // (wave-uniform already; keeps it scalar)
                 uint32_t base = (uint32_t)__builtin_amdgcn_readfirstlane((int)(ring_base + 4u * (uint32_t)fill)), t0, t1, n;
-                asm volatile(
-                    "1:\n\t"
-                    "v_cmp_ne_u32_e32 vcc, 0, %[sv]\n\t"
-                    "s_cbranch_vccz 2f\n\t"
-                    "v_mbcnt_lo_u32_b32 %[t0], vcc_lo, 0\n\t"
-                    "v_mbcnt_hi_u32_b32 %[t0], vcc_hi, %[t0]\n\t"
-                    "v_ffbl_b32_e32 %[t1], %[sv]\n\t"
-                    "v_lshl_add_u32 %[t0], %[t0], 2, %[base]\n\t"
-                    "v_lshl_or_b32 %[t1], %[t1], 27, %[rel0]\n\t"
-                    "v_cndmask_b32_e32 %[t0], %[dump], %[t0], vcc\n\t"
-                    "ds_write_b32 %[t0], %[t1]\n\t"
-                    "s_bcnt1_i32_b64 %[n], vcc\n\t"
-                    "v_add_u32_e32 %[t0], -1, %[sv]\n\t"
-                    "s_lshl2_add_u32 %[base], %[n], %[base]\n\t"
-                    "v_and_b32_e32 %[sv], %[sv], %[t0]\n\t"
-                    "s_add_i32 %[fill], %[fill], %[n]\n\t"
-                    "s_cmp_lt_i32 %[fill], 64\n\t"
-                    "s_cbranch_scc1 1b\n\t"
-                    "2:"
-                    : [sv] "+v"(sv), [fill] "+s"(fill), [base] "+s"(base), [t0] "=&v"(t0), [t1] "=&v"(t1),
-                      [n] "=&s"(n)
-                    : [rel0] "v"(rel0), [dump] "v"(dump_addr)
-                    : "vcc", "scc", "memory");
+                asm volatile(PSC_QUEUE_TURNS
+                             : [sv] "+v"(sv), [fill] "+s"(fill), [base] "+s"(base), [t0] "=&v"(t0), [t1] "=&v"(t1),
+                               [n] "=&s"(n)
+                             : [rel0] "v"(rel0), [dump] "v"(dump_addr)
+                             : "vcc", "scc", "memory");
                 static_assert(kRelBits == 27, "the shift in the queueing loop");
                 if (fill < 64) break;  // every lane is out of bits
                 __builtin_amdgcn_wave_barrier();
@@ -843,6 +861,237 @@ scan_kernel(ScanArgs a)
         }
         a.part_d[o] = have ? entry_dist(ent) : __builtin_inff();
         a.part_i[o] = have ? id : (int64_t)-1;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The fused scan with the Hamming test of Section 3.1 on the matrix cores (64-bit codes, tiles
+// of 16 queries, flat and graph mode).  With every bit b written as the byte +1 (b = 0) or -1
+// (b = 1), the dot product of two codes is 64 - 2 * (Hamming distance), so
+//     distance <= ht   <=>   (2 * ht - 64) + dot >= 0,
+// and v_mfma_i32_16x16x64_i8 takes that sum for 16 queries x 16 codes at once when the constant
+// goes in as the accumulator: the sign bit of each of the 256 results is the verdict "farther
+// than ht".  Per pair that leaves 1/64 of a vector instruction to move the sign into the lane's
+// survivor mask, plus the code's share of turning bits into bytes, against five instructions
+// of xor / popcount; queue, ADC and lists are those of scan_kernel.
+//
+// Operand layout (wave64, lane l, col = l % 16, grp = l / 16): the A operand is row `col`
+// (query slot col), K positions of group grp; the B operand is column `col` (a code), K
+// positions of group grp; lane l receives results (row 4 * grp + r, column col), r = 0..3.
+// Both operands give group grp bits 16 * grp .. 16 * grp + 15 of their code, expanded through
+// a 256-entry table in LDS (byte -> 8 bytes of +-1): which K positions a group holds does not
+// matter as long as both sides agree.
+//
+// A wave reads 64 codes with one 8-byte load per lane (lane l: code l of the block) and then
+// needs, for the four products of the block, the 16-bit part `grp` of codes col, 16 + col,
+// 32 + col, 48 + col: a 4 x 4 transpose of 16-bit parts between the four rows of 16 lanes,
+// done with one v_permlane32_swap, two v_perm and one v_permlane16_swap.
+//
+// Survivor masks: bit 31 - (4 * t + r) of a lane's mask <=> (code 16 * t + col of the 128-code
+// block, query slot 4 * grp + r), t = 0..7.  Queue entries carry the bit number, grp and the
+// position of the block's code `col` (kMfmaRelBits bits).
+// ---------------------------------------------------------------------------------------------
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// (One 16-wave workgroup per compute unit = 4 waves per SIMD: telling the compiler so lets it
+//  spend registers on keeping the eight products of a block in flight together.)
+template <int NW, bool SHARE>
+__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4, 4)))
+scan_mfma_kernel(ScanArgs a)
+{
+    constexpr int M = 8, TQ = 16;
+    constexpr int kBlock = 128;  // codes per wave and turn
+    extern __shared__ __align__(16) unsigned char smem[];
+    // [256] byte -> eight bytes of +-1, at LDS address 0 so that a look-up address is just byte * 8
+    PSC_LDS u32x2 *xtab = (PSC_LDS u32x2 *)smem;
+    const Lds<M, TQ> s((PSC_LDS unsigned char *)smem + kMfmaTableBytes, a.kpad, NW);
+    const int tid = (int)threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int col = lane & 15, grp = lane >> 4;
+
+    const int64_t tile = blockIdx.x;
+    const int slice = (int)(tile % a.nslice);
+    const int64_t q0 = (tile / a.nslice) * TQ;
+    const int nvq = (int)((a.nq - q0) < TQ ? (a.nq - q0) : TQ);
+    const int64_t slice_begin = (int64_t)slice * a.slice_len;
+    const int64_t slice_end = (slice_begin + a.slice_len) < a.n ? (slice_begin + a.slice_len) : a.n;
+
+    if (tid < TQ) {
+        const int gi = tid < nvq ? (int)(q0 + tid) : -1;
+        float t0 = __builtin_inff();
+        if constexpr (SHARE) {
+            if (gi >= 0) t0 = key_dist(__hip_atomic_load(&a.gthr[gi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        }
+        s.thr[tid] = t0;
+        s.lock[tid] = 0;
+        s.gidx[tid] = gi;
+    }
+    {
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        const f32x4 *src = (const f32x4 *)(a.lut + q0 * (M * 256));
+        PSC_LDS f32x4 *dst = (PSC_LDS f32x4 *)s.lut;
+        const int nvec = nvq * (M * 256 / 4);
+        for (int e = tid; e < TQ * (M * 256 / 4); e += NW * 64) {
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if (e < nvec) v = src[e];
+            dst[e] = v;
+        }
+    }
+    if ((uint32_t)(uintptr_t)xtab != 0u) {  // the look-ups below take the table to start at LDS address 0
+        if (tid == 0) atomicExch(a.status, 1);
+        return;
+    }
+    for (int v = tid; v < 256; v += NW * 64) {
+        uint32_t w[2] = {0u, 0u};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) w[i >> 2] |= (((v >> i) & 1) ? 0xffu : 0x01u) << (8 * (i & 3));
+        xtab[v] = u32x2{w[0], w[1]};
+    }
+    __syncthreads();
+
+    // A operand: part grp of query slot col (slots past nvq: any code, their results are masked)
+    i32x4 qa;
+    {
+        const uint32_t q16 = ((const uint16_t *)a.qcodes)[(q0 + (col < nvq ? col : 0)) * 4 + grp];
+        const u32x2 lo = xtab[q16 & 0xffu], hi = xtab[q16 >> 8];
+        qa = i32x4{(int)lo.x, (int)lo.y, (int)hi.x, (int)hi.y};
+    }
+    const int ht = (int)(0x7fffffffu - a.bias);
+    const int c0 = 2 * ht - 64;
+    const i32x4 cinit = {c0, c0, c0, c0};
+    uint32_t valid_q = 0u;  // the lane's rows that are real queries, for all eight groups of codes
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+        if (4 * grp + r < nvq) valid_q |= 0x11111111u << (3 - r);
+
+    lds_u32 *ring = s.queue + wave * kQueueCap;
+    const uint32_t ring_base = (uint32_t)(uintptr_t)ring;
+    const uint32_t dump_addr = (uint32_t)(uintptr_t)(s.dump + wave * 64 + lane);
+    int fill = 0;
+    SharedAsk ask;
+    const uint8_t *slice_codes = a.codes + slice_begin * M;
+    uint32_t self0 = 0x80000000u;
+    if (a.skip_first >= 0) {
+        const int64_t at = a.skip_first + q0 - slice_begin;
+        if (at > -64 && at < kMfmaMaxSliceLen) self0 = (uint32_t)at;
+    }
+    const uint32_t lane_bits = (uint32_t)col | ((uint32_t)grp << kMfmaRelBits);
+
+    auto queue_block = [&](uint32_t sv, const uint32_t rel0) {
+        while (true) {
+            fill = __builtin_amdgcn_readfirstlane(fill);
+            uint32_t base = (uint32_t)__builtin_amdgcn_readfirstlane((int)(ring_base + 4u * (uint32_t)fill)), t0, t1, n;
+            asm volatile(PSC_QUEUE_TURNS
+                         : [sv] "+v"(sv), [fill] "+s"(fill), [base] "+s"(base), [t0] "=&v"(t0), [t1] "=&v"(t1),
+                           [n] "=&s"(n)
+                         : [rel0] "v"(rel0), [dump] "v"(dump_addr)
+                         : "vcc", "scc", "memory");
+            if (fill < 64) break;
+            __builtin_amdgcn_wave_barrier();
+            fill -= 64;
+            drain<M, TQ, false, SHARE, true>(s, a, ring + fill, 64, slice_codes, slice_begin, self0, ask);
+            __builtin_amdgcn_wave_barrier();
+        }
+    };
+
+    // The wave's blocks: wave, wave + NW, ... of the slice's 128-code blocks; the next block's
+    // codes are asked for before the current one is worked on.  WHOLE: the block lies entirely
+    // inside the slice (all but the last turn or two of a wave).
+    const int64_t stride = (int64_t)NW * kBlock;
+    auto load_block = [&](auto whole, int64_t blk, uint2 (&c)[2]) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int64_t p = blk + 64 * h + lane;
+            if constexpr (decltype(whole)::value) {
+                c[h] = *(const uint2 *)(a.codes + p * M);
+            } else {
+                c[h] = make_uint2(0u, 0u);
+                if (p < slice_end) c[h] = *(const uint2 *)(a.codes + p * M);
+            }
+        }
+    };
+    auto filter_block = [&](auto whole, int64_t blk, const uint2 (&c)[2]) {
+        // In three phases kept apart for the scheduler (left alone it runs the eight products one
+        // after the other, each waiting for its table entries and then for its own result):
+        // all sixteen look-ups, the eight products, the thirty-two sign bits.
+        i32x4 cb[8];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            // rows 0,1 get the low words of all four rows' codes, rows 2,3 the high words ...
+            const auto r32 = __builtin_amdgcn_permlane32_swap(c[h].x, c[h].y, false, false);
+            // ... sorted by 16-bit part ...
+            uint32_t pa = __builtin_amdgcn_perm(r32[1], r32[0], 0x05040100u);
+            uint32_t pb = __builtin_amdgcn_perm(r32[1], r32[0], 0x07060302u);
+            // ... and odd rows trade their even parts for the even rows' odd parts: row grp now
+            // holds part grp of the codes of rows 0 (pa low), 1 (pb low), 2 (pa high), 3 (pb high)
+            const auto r16 = __builtin_amdgcn_permlane16_swap(pa, pb, false, false);
+            pa = r16[0];
+            pb = r16[1];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const uint32_t src = (t & 1) ? pb : pa;
+                const uint32_t c16 = (t & 2) ? (src >> 16) : (src & 0xffffu);
+                // (the table starts at LDS address 0: a look-up address is the byte times 8, which
+                //  the compiler then takes straight out of the word with a byte-select shift)
+                const u32x2 lo = *(PSC_LDS u32x2 *)(uintptr_t)((c16 & 0xffu) << 3);
+                const u32x2 hi = *(PSC_LDS u32x2 *)(uintptr_t)((c16 >> 8) << 3);
+                cb[4 * h + t] = i32x4{(int)lo.x, (int)lo.y, (int)hi.x, (int)hi.y};
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        i32x4 acc[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(qa, cb[t], cinit, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        uint32_t far = 0u;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) far = __builtin_amdgcn_alignbit(far, (uint32_t)acc[t][r], 31);
+        }
+        uint32_t valid = valid_q;
+        if constexpr (!decltype(whole)::value) {  // ragged block: codes past the end do not count
+            uint32_t in = 0u;
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+                if (blk + 16 * t + col < slice_end) in |= 0xf0000000u >> (4 * t);
+            valid &= in;
+        }
+        queue_block(~far & valid, (uint32_t)(blk - slice_begin) + lane_bits);
+    };
+    uint2 cur[2];
+    int64_t blk = slice_begin + (int64_t)wave * kBlock;
+    if (blk < slice_end) load_block(std::false_type{}, blk, cur);
+    while (blk + stride + kBlock <= slice_end) {  // this block and the next are whole
+        uint2 nxt[2];
+        load_block(std::true_type{}, blk + stride, nxt);
+        filter_block(std::true_type{}, blk, cur);
+        cur[0] = nxt[0];
+        cur[1] = nxt[1];
+        blk += stride;
+    }
+    for (; blk < slice_end; blk += stride) {
+        uint2 nxt[2] = {make_uint2(0u, 0u), make_uint2(0u, 0u)};
+        if (blk + stride < slice_end) load_block(std::false_type{}, blk + stride, nxt);
+        filter_block(std::false_type{}, blk, cur);
+        cur[0] = nxt[0];
+        cur[1] = nxt[1];
+    }
+    if (fill > 0) {
+        __builtin_amdgcn_wave_barrier();
+        drain<M, TQ, false, SHARE, true>(s, a, ring, fill, slice_codes, slice_begin, self0, ask);
+    }
+    __syncthreads();
+
+    for (int e = tid; e < nvq * a.k; e += NW * 64) {
+        const int q = e / a.k, r = e - q * a.k;
+        const bool have = r < s.lock[q];
+        const uint64_t ent = s.top[q * a.kpad + r];
+        const int64_t o = ((q0 + q) * a.nslice + slice) * a.k + r;
+        a.part_d[o] = have ? entry_dist(ent) : __builtin_inff();
+        a.part_i[o] = have ? slice_begin + (int64_t)entry_id(ent) : (int64_t)-1;
     }
 }
 
@@ -1185,6 +1434,20 @@ int run_scan(const ScanArgs &a, int64_t ntiles, size_t lds, hipStream_t s)
     return PSC_OK;
 }
 
+template <int NW, bool SHARE>
+int run_scan_mfma(const ScanArgs &a, int64_t ntiles, size_t lds, hipStream_t s)
+{
+    static bool configured = false;
+    if (!configured) {
+        PSC_HIP_TRY(hipFuncSetAttribute((const void *)scan_mfma_kernel<NW, SHARE>,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        configured = true;
+    }
+    hipLaunchKernelGGL((scan_mfma_kernel<NW, SHARE>), dim3((unsigned)ntiles), dim3(NW * 64), lds, s, a);
+    PSC_HIP_TRY(hipGetLastError());
+    return PSC_OK;
+}
+
 template <int M, int TQ, int NW, bool SHARE, bool FILTER>
 int run_adc(const ScanArgs &a, int64_t ntiles, size_t lds, hipStream_t s)
 {
@@ -1263,6 +1526,8 @@ constexpr size_t kLdsBudget = 160 * 1024;
 //    stages its tables or waits on a list lock while the other filters; fewer waves per list
 //    lock) -- measured 4% (clustered codes) to 11% (random codes) ahead of 16 x 16 at ht=24;
 //    falls back to 16 x 16, 8 x 16, 4 x 16 as k grows (the lists share LDS with the tables);
+//  * fused scan with the matrix-core filter (64-bit codes, more than 16 queries, few survivors):
+//    16 x 16, the only shape of scan_mfma_kernel (k up to 136);
 //  * up to 4 / 8 / 16 queries: no more query slots than queries (every slot costs filter work),
 //    which keeps a one-pass scan of few queries bound by memory bandwidth;
 //  * grouped inverted-file jobs: 4 x 8, three workgroups per compute unit (tiles are short, so
@@ -1292,18 +1557,26 @@ int plan_scan(int m, int64_t nq, int64_t n, int k, int kind, ScanPlan *plan)
     const int tq_cap = nq <= 4 ? 4 : (nq <= 8 ? 8 : 16);
     Shape options[5];
     int nopt = 0;
-    if (m == 8 && kind == kScanLists) options[nopt++] = Shape{4, 8, kLdsBudget / 2};
-    if (m == 8 && (kind == kScanFused || kind == kScanDenseFiltered) && nq > 16)
-        options[nopt++] = Shape{8, 8, kLdsBudget / 2};
-    if (m == 8 && kind != kScanLists) options[nopt++] = Shape{16, 16, kLdsBudget};
-    if (kind != kScanLists || m == 16) options[nopt++] = Shape{8, 16, kLdsBudget};
-    options[nopt++] = Shape{4, 16, kLdsBudget};
+    if (kind == kScanFusedMfma) {
+        if (m != 8 || nq <= 16) {
+            set_error("the matrix-core filter takes 64-bit codes and more than 16 queries");
+            return PSC_EINVAL;
+        }
+        options[nopt++] = Shape{16, 16, kLdsBudget};
+    } else {
+        if (m == 8 && kind == kScanLists) options[nopt++] = Shape{4, 8, kLdsBudget / 2};
+        if (m == 8 && (kind == kScanFused || kind == kScanDenseFiltered) && nq > 16)
+            options[nopt++] = Shape{8, 8, kLdsBudget / 2};
+        if (m == 8 && kind != kScanLists) options[nopt++] = Shape{16, 16, kLdsBudget};
+        if (kind != kScanLists || m == 16) options[nopt++] = Shape{8, 16, kLdsBudget};
+        options[nopt++] = Shape{4, 16, kLdsBudget};
+    }
     p.tq = 0;
     for (int o = 0; o < nopt; ++o) {
         const int t = options[o].tq, nw = options[o].nwaves;
         if (t > tq_cap) continue;
         const size_t need = (size_t)t * m * 256 * 4 + (size_t)t * p.kpad * 8 + (size_t)t * 12 + (size_t)t * m * 5 +
-                            (size_t)nw * (kQueueCap + 64) * 4;
+                            (size_t)nw * (kQueueCap + 64) * 4 + (kind == kScanFusedMfma ? kMfmaTableBytes : 0);
         if (need <= options[o].max_lds) {
             p.tq = t;
             p.nwaves = nw;
@@ -1343,8 +1616,9 @@ int plan_scan(int m, int64_t nq, int64_t n, int k, int kind, ScanPlan *plan)
     int64_t max_by_size = std::max<int64_t>(1, n / min_slice);
     int64_t nslice = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, max_by_size), 1024));
     int64_t slice_len = (((n + nslice - 1) / nslice) + block - 1) / block * block;
-    if (slice_len > kMaxSliceLen) {
-        slice_len = kMaxSliceLen;
+    const int64_t max_slice = kind == kScanFusedMfma ? kMfmaMaxSliceLen : kMaxSliceLen;
+    if (slice_len > max_slice) {
+        slice_len = max_slice;
         nslice = (n + slice_len - 1) / slice_len;
         if (nslice > 1024) {
             set_error("database too large for one scan call");
@@ -1372,6 +1646,8 @@ size_t flat_scan_workspace_bytes(int m, int64_t nq, int64_t n, int k)
         if (plan_scan(m, nq, n, k, kind, &p) != PSC_OK) return 0;
         bytes = std::max(bytes, p.total_bytes);
     }
+    ScanPlan p;  // the matrix-core route where it applies (it has shapes and slices of its own)
+    if (m == 8 && nq > 16 && plan_scan(m, nq, n, k, kScanFusedMfma, &p) == PSC_OK) bytes = std::max(bytes, p.total_bytes);
     return bytes;
 }
 
@@ -1386,7 +1662,22 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
     const double dense_from = 0.36;
     const bool dense = ht >= 8 * m || random_code_survival(8 * m, ht) >= dense_from;
     ScanPlan p;
-    int rc = plan_scan(m, nq, n, k, !dense ? kScanFused : (ht >= 8 * m ? kScanDense : kScanDenseFiltered), &p);
+    int rc = PSC_EINVAL;
+    // Matrix-core filter: 64-bit codes, more than one tile of queries, k small enough for its
+    // 16-query tile, and few survivors (beyond about one pair in ten the queue and the lists
+    // decide the time and the two filters tie: measured equal at ht = 26, behind at ht = 28).
+    // PSC_FILTER_ROUTE=popcount|mfma in the environment overrides the rule (for measurements).
+    bool mfma = !dense && m == 8 && nq > 16 && random_code_survival(8 * m, ht) < 0.10;
+    if (const char *route = std::getenv("PSC_FILTER_ROUTE")) {
+        if (!std::strcmp(route, "popcount")) mfma = false;
+        if (!std::strcmp(route, "mfma")) mfma = !dense && m == 8 && nq > 16;
+    }
+    if (mfma) {
+        rc = plan_scan(m, nq, n, k, kScanFusedMfma, &p);
+        mfma = rc == PSC_OK;  // (k too large for the shape: the popcount kernel's shapes take over)
+    }
+    if (!mfma)
+        rc = plan_scan(m, nq, n, k, !dense ? kScanFused : (ht >= 8 * m ? kScanDense : kScanDenseFiltered), &p);
     if (rc != PSC_OK) return rc;
     if (nq == 0) return PSC_OK;
     PSC_REQUIRE(ids_dev && dists_dev, "null result pointer");
@@ -1444,6 +1735,9 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
     else if (dense)
         rc = p.nslice >= 4 ? dispatch_adc<true, true>(m, p.tq, p.nwaves, a, p.ntiles, p.lds_bytes, s)
                            : dispatch_adc<false, true>(m, p.tq, p.nwaves, a, p.ntiles, p.lds_bytes, s);
+    else if (mfma)
+        rc = p.nslice >= 4 ? run_scan_mfma<16, true>(a, p.ntiles, p.lds_bytes, s)
+                           : run_scan_mfma<16, false>(a, p.ntiles, p.lds_bytes, s);
     else
         rc = p.nslice >= 4 ? dispatch_scan<false, true>(m, p.tq, p.nwaves, a, p.ntiles, p.lds_bytes, s)
                            : dispatch_scan<false, false>(m, p.tq, p.nwaves, a, p.ntiles, p.lds_bytes, s);

@@ -68,6 +68,44 @@ def test_scan_random_codes(psc, m, n, nq, k, lut_kind):
             assert nd == 0 and np.array_equal(got_d[ref["ids"] >= 0], ref["dists"][ref["ids"] >= 0])
 
 
+@pytest.mark.parametrize("route", ["mfma", "popcount"])
+@pytest.mark.parametrize("n,nq,k,lut_kind", [
+    (100_003, 37, 10, "float"),     # ragged last block (n % 128 = 35), ragged query tile (37 = 2 * 16 + 5)
+    (100_003, 37, 100, "int"),      # exact ties: ids must match exactly
+    (65_536 + 127, 160, 136, "int"),  # the largest k of the 16-query tile
+    (9_000, 17, 5, "float"),        # barely more than one tile of queries, one slice
+    (1_000_001, 48, 20, "float"),   # several slices per query tile
+])
+def test_both_filter_routes(psc, monkeypatch, route, n, nq, k, lut_kind):
+    """The Hamming test runs either as xor/popcount or on the matrix cores; the library picks by
+    shape and threshold.  Here each route is forced in turn (PSC_FILTER_ROUTE) on 64-bit codes
+    with more than 16 queries and must give the oracle's result at every threshold, including
+    those the rule would hand to the other route."""
+    monkeypatch.setenv("PSC_FILTER_ROUTE", route)
+    codes, qcodes, lut = _rand_problem(8, n, nq, seed=900 + k, lut_kind=lut_kind)
+    for ht in (0, 9, 16, 22, 24, 27, 31, 33):
+        print(f"case route={route} n={n} nq={nq} k={k} ht={ht}", flush=True)
+        got_ids, got_d = _run(psc, lut, qcodes, codes, ht, k)
+        ref = O.scan(lut.astype(np.float64), qcodes, codes, ht, k)
+        nd = assert_topk_matches(got_ids, got_d, ref, lut.astype(np.float64), qcodes, codes, ht,
+                                 what=f"route={route} ht={ht} k={k}")
+        if lut_kind == "int":
+            assert nd == 0 and np.array_equal(got_d[ref["ids"] >= 0], ref["dists"][ref["ids"] >= 0])
+
+
+def test_survivor_set_on_the_matrix_cores(psc, monkeypatch):
+    """k above the number of survivors: the matrix-core route lists exactly the survivor set, for
+    thresholds on both sides of every bit count the +-1 dot product can take near them."""
+    monkeypatch.setenv("PSC_FILTER_ROUTE", "mfma")
+    codes, qcodes, lut = _rand_problem(8, 40_000, 33, seed=77, lut_kind="float")
+    for ht in (17, 18, 19, 20):
+        ref = O.scan(lut.astype(np.float64), qcodes, codes, ht, 136, want_bitmap=True)
+        got_ids, _ = _run(psc, lut, qcodes, codes, ht, 136)
+        for q in range(33):
+            if ref["nsurv"][q] <= 136:
+                assert sorted(got_ids[q][got_ids[q] >= 0].tolist()) == np.flatnonzero(ref["bitmap"][q]).tolist()
+
+
 def test_many_slices_for_few_queries(psc):
     """Two queries over 3M codes: 256 database slices, whose partial lists the merge takes four to a lane."""
     codes, qcodes, lut = _rand_problem(8, 3_000_001, 2, seed=321, lut_kind="float")
