@@ -32,8 +32,8 @@ OPS_PER_PAIR = {8: 5, 16: 9}
 
 # Bytes per scan launch between L2 and the memory fabric, measured with rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE (two runs, scaled by what the same counters read for a 1 GiB copy:
-# x2.0 and x1.0), see profiles/scan_kernel_flat64_ht24.md; keyed by (workload, ht).
-MEASURED_TRAFFIC_BYTES = {("flat64", 24): 75.656e9 + 24.3e6}
+# x2.0 and x1.0), see profiles/; keyed by (kernel, ht) on the flat64 workload.
+MEASURED_TRAFFIC_BYTES = {("scan_mfma_kernel<16>", 24): 14.697e9 + 24.3e6, ("scan_kernel<8,8,8>", 24): 75.581e9 + 24.3e6}
 
 
 def log(*a):
@@ -52,10 +52,15 @@ def main():
     ap.add_argument("--no-small-batch", action="store_true",
                     help="skip the memory-bound side measurement (1 and 16 queries over 400M codes)")
     ap.add_argument("--cpu-queries", type=int, default=1024)
+    ap.add_argument("--filter-route", choices=["auto", "popcount", "mfma"], default="auto",
+                    help="which Hamming filter the fused scan uses: the library's own choice (matrix cores "
+                         "below about 10%% survivors), or one of the two forced (PSC_FILTER_ROUTE)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (known traffic, for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
+    if args.filter_route != "auto":
+        os.environ["PSC_FILTER_ROUTE"] = args.filter_route
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build measures one GPU only (the path shards without any exchange, "
             "see DESIGN.md); run with --gpus 1")
@@ -242,6 +247,9 @@ def main():
 
     ops = OPS_PER_PAIR[m] * pairs
     achieved = ops / (scan_ms * 1e-3) / 1e12
+    # the library's rule: matrix-core filter for 64-bit codes below about one survivor in ten pairs
+    on_mfma = args.filter_route != "popcount" and m == 8 and (args.ht <= 26 or args.filter_route == "mfma") and args.ht < 31
+    kernel = "scan_mfma_kernel<16>" if on_mfma else "scan_kernel<8,8,8>"
     out = {
         "metric": "codes scanned/sec (Hamming filter+ADC, 64-bit codes, 10M DB) + recall@10",
         "value": pairs / (ms_step * 1e-3),
@@ -254,17 +262,21 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "u32 popcount + f32 ADC",
+        "dtype": ("i8 MFMA Hamming test" if on_mfma else "u32 xor/popcount Hamming test") + " + f32 ADC",
         "data": "synthetic",
         "config": {"workload": "flat64" + ("-small" if args.small else ""), "n_db": n_db, "n_query": nq,
                    "code_bits": 8 * m, "ht": args.ht, "k": k},
         "ht_removing_95pct_of_training_pairs": ht_rule,
         "recall_at_10": recall10,
         "survivor_rate": surv_rate,
-        "roofline": {"bound": "alu", "kernel": "scan_kernel<8,8,8>", "achieved": achieved,
+        # `achieved` counts the algorithmic work of the filter (5 integer operations per 64-bit pair)
+        # against the vector-ALU peak, whichever unit executes it; with the test on the matrix
+        # cores the same pairs are also 128 int8 operations each against the 5 POP/s MFMA peak.
+        "roofline": {"bound": "alu", "kernel": kernel, "achieved": achieved,
                      "peak": PEAK_INT_TOPS, "unit": "TOP/s (int32 lane-ops)", "frac": achieved / PEAK_INT_TOPS,
                      "ops_per_pair": OPS_PER_PAIR[m], "kernel_ms": scan_ms,
-                     "traffic": None if args.small else MEASURED_TRAFFIC_BYTES.get(("flat64", args.ht))},
+                     "traffic": None if args.small else MEASURED_TRAFFIC_BYTES.get((kernel, args.ht)),
+                     "mfma_int8_frac": (128.0 * pairs / (scan_ms * 1e-3) / 5.0e15) if on_mfma else None},
         "cpu_baseline": cpu,
         "sweep": sweep,
         "small_batch": small_batch,

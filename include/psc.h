@@ -133,7 +133,12 @@ int psc_threshold_for_rate(const int64_t *hist_host, int nbits, double max_keep_
  * j ascending); return the k smallest by (dist, id) ascending, lower id first on
  * equal distance, in ids_dev [nq][k] (int64) and dists_dev [nq][k] (float32),
  * padded with id -1 / distance +inf when fewer than k survive.
- * 1 <= k <= PSC_MAX_K, ht >= 0, n < 2^40.  Workspace: psc_scan_workspace_bytes. */
+ * 1 <= k <= PSC_MAX_K, ht >= 0, n < 2^40.  Workspace: psc_scan_workspace_bytes.
+ * The Hamming test is exact on every route the library takes: xor / popcount on the vector
+ * units, or (64-bit codes, more than 16 queries, selective thresholds) an int8 dot product of
+ * +-1 expansions on the matrix cores, whose sign gives the same verdict.  The environment
+ * variable PSC_FILTER_ROUTE = "popcount" | "mfma", read at every call, forces one of the two
+ * where both apply (a measurement aid; results do not depend on it). */
 size_t psc_scan_workspace_bytes(int m, int64_t nq, int64_t n, int k);
 int psc_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t nq,
              const uint8_t *codes_dev, int64_t n, int ht, int k, int64_t *ids_dev,
