@@ -501,12 +501,20 @@ int psc_ivf_train_coarse(psc_index *idx, const float *x_host, int64_t n, int nli
         }                                                                                          \
     } while (0)
     IVF_TRY(hipMalloc((void **)&x_dev, (size_t)n * dim * sizeof(float)));
-    IVF_TRY(hipMalloc((void **)&c_dev, (size_t)nlist * dim * sizeof(float)));
+    IVF_TRY(hipMalloc((void **)&c_dev, (size_t)(nlist + 1) * dim * sizeof(float)));  // + the mean centroid
     IVF_TRY(hipMalloc((void **)&a_dev, (size_t)n * sizeof(int32_t)));
     IVF_TRY(hipMemcpy(x_dev, x_host, (size_t)n * dim * sizeof(float), hipMemcpyHostToDevice));
     for (int it = 0; it < iters; ++it) {
         IVF_TRY(hipMemcpy(c_dev, cent.data(), cent.size() * sizeof(float), hipMemcpyHostToDevice));
-        rc = launch_nearest_centroid(x_dev, n, dim, c_dev, nlist, a_dev, nullptr);
+        {   // the reference point of the matrix-core distance kernel
+            std::vector<double> acc((size_t)dim, 0.0);
+            for (int c = 0; c < nlist; ++c)
+                for (int t = 0; t < dim; ++t) acc[(size_t)t] += cent[(size_t)c * dim + t];
+            std::vector<float> mean((size_t)dim);
+            for (int t = 0; t < dim; ++t) mean[(size_t)t] = (float)(acc[(size_t)t] / nlist);
+            IVF_TRY(hipMemcpy(c_dev + (size_t)nlist * dim, mean.data(), (size_t)dim * sizeof(float), hipMemcpyHostToDevice));
+        }
+        rc = launch_nearest_centroid(x_dev, n, dim, c_dev, nlist, c_dev + (size_t)nlist * dim, a_dev, nullptr);
         if (rc != PSC_OK) {
             cleanup();
             return rc;
@@ -555,7 +563,8 @@ int psc_ivf_assign_encode(const psc_index *idx, const float *x_dev, int64_t n, i
     PSC_REQUIRE(n >= 0, "negative n");
     if (n == 0) return PSC_OK;
     PSC_REQUIRE(x_dev && list_no_dev, "null pointer");
-    rc = launch_nearest_centroid(x_dev, n, idx->dim, idx->coarse_dev, idx->nlist, list_no_dev, (hipStream_t)stream);
+    rc = launch_nearest_centroid(x_dev, n, idx->dim, idx->coarse_dev, idx->nlist,
+                                 idx->coarse_dev + (size_t)idx->nlist * idx->dim, list_no_dev, (hipStream_t)stream);
     if (rc != PSC_OK || !rescodes_dev) return rc;
     rc = need_codebook(idx);
     if (rc != PSC_OK) return rc;

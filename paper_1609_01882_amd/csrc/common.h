@@ -109,7 +109,7 @@ int launch_select_probes(const float *dist_dev, int64_t n, int nlist, int nprobe
                          hipStream_t s);
 // Nearest centroid of each row (lowest number on ties) -> assign [n] (int32).
 int launch_nearest_centroid(const float *x_dev, int64_t n, int dim, const float *cent_dev, int nlist,
-                            int32_t *assign_dev, hipStream_t s);
+                            const float *mu_dev, int32_t *assign_dev, hipStream_t s);
 struct IvfJobBuffers {
     int32_t *hist;       // [nblk][2 nlist]
     int32_t *list_begin; // [2 nlist + 1] first sorted job of each sort key (see launch_build_jobs)

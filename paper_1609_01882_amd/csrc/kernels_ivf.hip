@@ -225,6 +225,126 @@ nearest_centroid_kernel(const float *__restrict__ x, int64_t n, int dim, const f
 }
 
 // ---------------------------------------------------------------------------------------------
+// Nearest centroid on the matrix cores (the assignment step of Section 4.3's index, and of the
+// coarse k-means): arg-min over c of || x - c ||^2 = arg-min of || c' ||^2 - 2 x'.c' with
+// x' = x - mu, c' = c - mu (mu: any common reference point, here the mean centroid; centring keeps
+// the terms small and with them the rounding error of the expansion, about 1e-7 of the distance).
+// The cross term is a dense [rows x DIM] . [DIM x nlist] contraction in full float32
+// (v_mfma_f32_32x32x2f32, operand layout as in the table kernel: A[i][k] with i = lane % 32,
+// k = lane / 32; D[i][j] in 16 registers, register v = row 8 * (v / 4) + 4 * (lane / 32) + v % 4,
+// column j = lane % 32).
+// One workgroup = 4 waves x 32 rows; the rows sit in registers for the whole kernel (DIM / 2 per
+// lane), the centroids stream through LDS in tiles of 32 (double-buffered, centred and their
+// norms taken while staging), and every lane keeps the running minimum of its 16 outputs.  Ties
+// go to the lower centroid number, as in the plain kernel; the two kernels can differ where two
+// centroids are equally near within float32 rounding.
+// ---------------------------------------------------------------------------------------------
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+template <int DIM>
+__global__ void __launch_bounds__(256)
+nearest_centroid_mfma_kernel(const float *__restrict__ x, int64_t n, const float *__restrict__ cent,
+                             const float *__restrict__ mu, int nlist, int32_t *__restrict__ assign)
+{
+    static_assert(DIM % 8 == 0 && DIM <= 128, "rows are held in registers");
+    constexpr int KS = DIM / 2;
+    constexpr int LD = DIM + 2;  // row pitch of a staged tile: lanes (half, col) hit 64 different banks
+    __shared__ float tile[2][32 * LD];
+    __shared__ float cnorm[2][32];
+    const int tid = (int)threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int half = lane >> 5, col = lane & 31;
+    const int64_t r0 = (int64_t)blockIdx.x * 128 + wave * 32;
+
+    float a[KS];
+    {
+        const int64_t r = r0 + col;
+        const float *xr = x + (r < n ? r : n - 1) * DIM;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) a[kk] = xr[2 * kk + half] - mu[2 * kk + half];
+    }
+    // staging: thread -> centroid tid / 8 of the tile, coordinates (tid % 8) * 4 + 32 * i
+    const int sc = tid >> 3, sp = (tid & 7) * 4;
+    auto stage = [&](int t, int buf) {
+        const int c = t * 32 + sc;
+        float nrm = 0.f;
+#pragma unroll
+        for (int i = 0; i < DIM / 32; ++i) {
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (c < nlist) {
+                v = *(const float4 *)(cent + (int64_t)c * DIM + sp + 32 * i);
+                const float4 m = *(const float4 *)(mu + sp + 32 * i);
+                v.x -= m.x;
+                v.y -= m.y;
+                v.z -= m.z;
+                v.w -= m.w;
+            }
+            float *d = &tile[buf][sc * LD + sp + 32 * i];
+            d[0] = v.x;
+            d[1] = v.y;
+            d[2] = v.z;
+            d[3] = v.w;
+            nrm = fmaf(v.x, v.x, nrm);
+            nrm = fmaf(v.y, v.y, nrm);
+            nrm = fmaf(v.z, v.z, nrm);
+            nrm = fmaf(v.w, v.w, nrm);
+        }
+        nrm += __shfl_xor(nrm, 1, 64);
+        nrm += __shfl_xor(nrm, 2, 64);
+        nrm += __shfl_xor(nrm, 4, 64);
+        if ((tid & 7) == 0) cnorm[buf][sc] = c < nlist ? nrm : __builtin_inff();
+    };
+    float bestv[16];
+    int besti[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        bestv[v] = __builtin_inff();
+        besti[v] = 0;
+    }
+    const int ntiles = (nlist + 31) / 32;
+    stage(0, 0);
+    __syncthreads();
+    for (int t = 0; t < ntiles; ++t) {
+        const int buf = t & 1;
+        if (t + 1 < ntiles) stage(t + 1, buf ^ 1);
+        f32x16 acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+        const float *b = &tile[buf][col * LD + half];
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[kk], b[2 * kk], acc, 0, 0, 0);
+        const float cn = cnorm[buf][col];
+        const int ci = t * 32 + col;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const float d = fmaf(-2.0f, acc[v], cn);  // (+inf for the padding of the last tile)
+            if (d < bestv[v]) {
+                bestv[v] = d;
+                besti[v] = ci;
+            }
+        }
+        __syncthreads();
+    }
+    // the 32 lanes of a half hold the 32 columns of each of its 16 rows: smallest (value, number)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        float bv = bestv[v];
+        int bi = besti[v];
+#pragma unroll
+        for (int off = 16; off >= 1; off >>= 1) {
+            const float ov = __shfl_xor(bv, off, 64);
+            const int oi = __shfl_xor(bi, off, 64);
+            if (ov < bv || (ov == bv && oi < bi)) {
+                bv = ov;
+                bi = oi;
+            }
+        }
+        const int64_t r = r0 + 8 * (v / 4) + 4 * half + v % 4;
+        if (col == 0 && r < n) assign[r] = bi;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Job bookkeeping.  Jobs in query-major order are cut into blocks of kJobBlockQ queries; a
 // stable counting sort by list number (block histograms -> column prefix -> in-order scatter)
 // gives every list its jobs in ascending query order, reproducibly.
@@ -465,12 +585,33 @@ int launch_select_probes(const float *dist_dev, int64_t n, int nlist, int nprobe
     return PSC_OK;
 }
 
+template <int DIM>
+static int run_nearest_centroid_mfma(const float *x_dev, int64_t n, const float *cent_dev, const float *mu_dev,
+                                     int nlist, int32_t *assign_dev, hipStream_t s)
+{
+    hipLaunchKernelGGL((nearest_centroid_mfma_kernel<DIM>), dim3((unsigned)((n + 127) / 128)), dim3(256), 0, s,
+                       x_dev, n, cent_dev, mu_dev, nlist, assign_dev);
+    PSC_HIP_TRY(hipGetLastError());
+    return PSC_OK;
+}
+
+// mu_dev: a reference point [dim] for the matrix-core kernel (the mean centroid); null, or a
+// dimension that kernel is not built for, takes the plain kernel.
 int launch_nearest_centroid(const float *x_dev, int64_t n, int dim, const float *cent_dev, int nlist,
-                            int32_t *assign_dev, hipStream_t s)
+                            const float *mu_dev, int32_t *assign_dev, hipStream_t s)
 {
     int rc = check_dim(dim, nlist);
     if (rc != PSC_OK) return rc;
     if (n == 0) return PSC_OK;
+    if (mu_dev && (n + 127) / 128 <= 0x7fffffffLL) {
+        switch (dim) {
+        case 32: return run_nearest_centroid_mfma<32>(x_dev, n, cent_dev, mu_dev, nlist, assign_dev, s);
+        case 64: return run_nearest_centroid_mfma<64>(x_dev, n, cent_dev, mu_dev, nlist, assign_dev, s);
+        case 96: return run_nearest_centroid_mfma<96>(x_dev, n, cent_dev, mu_dev, nlist, assign_dev, s);
+        case 128: return run_nearest_centroid_mfma<128>(x_dev, n, cent_dev, mu_dev, nlist, assign_dev, s);
+        default: break;
+        }
+    }
     PSC_REQUIRE((n + kRows - 1) / kRows <= 0x7fffffffLL, "too many rows");
     size_t lds = (size_t)kRows * dim * sizeof(float);
     if (lds < 4 * kRows * sizeof(uint64_t)) lds = 4 * kRows * sizeof(uint64_t);

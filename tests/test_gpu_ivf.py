@@ -63,6 +63,35 @@ def test_assignment_and_residual_codes(ivf):
     assert sorted(s["lids"].tolist()) == list(range(len(s["xb"])))
 
 
+@pytest.mark.parametrize("dim,nlist,n", [(128, 37, 1003), (96, 64, 517), (64, 300, 4000), (32, 5, 129),
+                                         (40, 33, 700), (128, 4096, 3000)])
+def test_nearest_centroid_assignment(dim, nlist, n):
+    """Assignment to the nearest coarse centroid (Section 4.3) against the exact arg-min in float64:
+    sizes that are not multiples of the kernel's tiles (32 centroids, 128 rows), every dimension the
+    matrix-core kernel is built for, and one it is not (40: the plain kernel).  Only near-ties within
+    the 1e-5 tolerance may fall the other way."""
+    import paper_1609_01882_amd as psc
+    rng = np.random.default_rng(dim + nlist)
+    cent = (rng.random((nlist, dim)) * 100).astype(np.float32)
+    x = (cent[rng.integers(0, nlist, size=n)] + rng.normal(0, 15, size=(n, dim))).astype(np.float32)
+    if nlist > 2:
+        cent[1] = cent[0]                     # an exact tie: the lower number wins
+        x[0] = cent[0]
+    idx = psc.Index(dim, 8)
+    idx.ivf_set_coarse(cent)
+    got, _ = idx.ivf_assign_encode(_dev(x), want_codes=False)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    d = ((x[:, None, :].astype(np.float64) - cent[None, :, :].astype(np.float64)) ** 2).sum(axis=2)
+    ref = d.argmin(axis=1)
+    assert got.min() >= 0 and got.max() < nlist
+    for i in np.flatnonzero(got != ref):
+        assert abs(d[i, got[i]] - d[i, ref[i]]) <= RTOL * max(d[i, ref[i]], 1.0), (i, got[i], ref[i])
+    assert (got != ref).mean() < 0.002
+    if nlist > 2:
+        assert got[0] == 0
+
+
 @pytest.fixture(scope="module")
 def ivf_many_lists():
     import paper_1609_01882_amd as psc
