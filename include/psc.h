@@ -135,7 +135,7 @@ int psc_threshold_for_rate(const int64_t *hist_host, int nbits, double max_keep_
  * padded with id -1 / distance +inf when fewer than k survive.
  * 1 <= k <= PSC_MAX_K, ht >= 0, n < 2^40.  Workspace: psc_scan_workspace_bytes.
  * The Hamming test is exact on every route the library takes: xor / popcount on the vector
- * units, or (64-bit codes, more than 16 queries, selective thresholds) an int8 dot product of
+ * units, or (64-bit codes, 9 queries or more, selective thresholds) an int8 dot product of
  * +-1 expansions on the matrix cores, whose sign gives the same verdict.  The environment
  * variable PSC_FILTER_ROUTE = "popcount" | "mfma", read at every call, forces one of the two
  * where both apply (a measurement aid; results do not depend on it). */

@@ -37,6 +37,7 @@ constexpr int64_t kMaxSliceLen = (int64_t)1 << kRelBits;
 constexpr int kMfmaRelBits = 25;      // the same for the matrix-core filter (two more bits name the lane's row group)
 constexpr uint32_t kMfmaRelMask = (1u << kMfmaRelBits) - 1;
 constexpr int64_t kMfmaMaxSliceLen = (int64_t)1 << kMfmaRelBits;
+constexpr int64_t kMfmaMinQueries = 9;  // fewer queries than this take the narrower xor/popcount tiles
 constexpr int kMfmaTableBytes = 256 * 8;  // the bits-to-elements table of the matrix-core filter
 constexpr int kSpinLimit = 1 << 22;   // bounded wait on a list lock (each turn sleeps)
 
@@ -1526,7 +1527,7 @@ constexpr size_t kLdsBudget = 160 * 1024;
 //    stages its tables or waits on a list lock while the other filters; fewer waves per list
 //    lock) -- measured 4% (clustered codes) to 11% (random codes) ahead of 16 x 16 at ht=24;
 //    falls back to 16 x 16, 8 x 16, 4 x 16 as k grows (the lists share LDS with the tables);
-//  * fused scan with the matrix-core filter (64-bit codes, more than 16 queries, few survivors):
+//  * fused scan with the matrix-core filter (64-bit codes, 9 queries or more, few survivors):
 //    16 x 16, the only shape of scan_mfma_kernel (k up to 136);
 //  * up to 4 / 8 / 16 queries: no more query slots than queries (every slot costs filter work),
 //    which keeps a one-pass scan of few queries bound by memory bandwidth;
@@ -1558,8 +1559,8 @@ int plan_scan(int m, int64_t nq, int64_t n, int k, int kind, ScanPlan *plan)
     Shape options[5];
     int nopt = 0;
     if (kind == kScanFusedMfma) {
-        if (m != 8 || nq <= 16) {
-            set_error("the matrix-core filter takes 64-bit codes and more than 16 queries");
+        if (m != 8 || nq < kMfmaMinQueries) {
+            set_error("the matrix-core filter takes 64-bit codes and at least %d queries", (int)kMfmaMinQueries);
             return PSC_EINVAL;
         }
         options[nopt++] = Shape{16, 16, kLdsBudget};
@@ -1647,7 +1648,8 @@ size_t flat_scan_workspace_bytes(int m, int64_t nq, int64_t n, int k)
         bytes = std::max(bytes, p.total_bytes);
     }
     ScanPlan p;  // the matrix-core route where it applies (it has shapes and slices of its own)
-    if (m == 8 && nq > 16 && plan_scan(m, nq, n, k, kScanFusedMfma, &p) == PSC_OK) bytes = std::max(bytes, p.total_bytes);
+    if (m == 8 && nq >= kMfmaMinQueries && plan_scan(m, nq, n, k, kScanFusedMfma, &p) == PSC_OK)
+        bytes = std::max(bytes, p.total_bytes);
     return bytes;
 }
 
@@ -1667,10 +1669,10 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
     // 16-query tile, and few survivors (beyond about one pair in ten the queue and the lists
     // decide the time and the two filters tie: measured equal at ht = 26, behind at ht = 28).
     // PSC_FILTER_ROUTE=popcount|mfma in the environment overrides the rule (for measurements).
-    bool mfma = !dense && m == 8 && nq > 16 && random_code_survival(8 * m, ht) < 0.10;
+    bool mfma = !dense && m == 8 && nq >= kMfmaMinQueries && random_code_survival(8 * m, ht) < 0.10;
     if (const char *route = std::getenv("PSC_FILTER_ROUTE")) {
         if (!std::strcmp(route, "popcount")) mfma = false;
-        if (!std::strcmp(route, "mfma")) mfma = !dense && m == 8 && nq > 16;
+        if (!std::strcmp(route, "mfma")) mfma = !dense && m == 8 && nq >= kMfmaMinQueries;
     }
     if (mfma) {
         rc = plan_scan(m, nq, n, k, kScanFusedMfma, &p);

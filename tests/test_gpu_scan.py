@@ -74,12 +74,14 @@ def test_scan_random_codes(psc, m, n, nq, k, lut_kind):
     (100_003, 37, 100, "int"),      # exact ties: ids must match exactly
     (65_536 + 127, 160, 136, "int"),  # the largest k of the 16-query tile
     (9_000, 17, 5, "float"),        # barely more than one tile of queries, one slice
+    (300_001, 9, 10, "int"),        # the fewest queries the matrix-core route takes: many slices
+    (50_000, 16, 100, "float"),     # exactly one full tile
     (1_000_001, 48, 20, "float"),   # several slices per query tile
 ])
 def test_both_filter_routes(psc, monkeypatch, route, n, nq, k, lut_kind):
     """The Hamming test runs either as xor/popcount or on the matrix cores; the library picks by
     shape and threshold.  Here each route is forced in turn (PSC_FILTER_ROUTE) on 64-bit codes
-    with more than 16 queries and must give the oracle's result at every threshold, including
+    with 9 queries or more and must give the oracle's result at every threshold, including
     those the rule would hand to the other route."""
     monkeypatch.setenv("PSC_FILTER_ROUTE", route)
     codes, qcodes, lut = _rand_problem(8, n, nq, seed=900 + k, lut_kind=lut_kind)
