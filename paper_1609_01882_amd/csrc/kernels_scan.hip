@@ -330,31 +330,53 @@ __device__ __forceinline__ void insert_candidates(const Lds<M, TQ> &s, const Sca
     float thr_old;
     if (k <= 128) {
         const int i0 = lane, i1 = 64 + lane;  // the two list places of the lane
-        uint64_t e0 = ~0ull, e1 = ~0ull;      // places past the end hold the largest key
-        if (i0 < cnt) e0 = list[i0];
-        if (i1 < cnt) e1 = list[i1];
         thr_old = s.thr[q];
         mine &= ballot64(d <= thr_old);  // the threshold may have dropped since the candidates were scored
-        while (mine) {
-            const int src = __builtin_ctzll(mine);
-            mine &= mine - 1;
-            const uint64_t cand = pack_entry(bcast_f(d, src), bcast_u(id, src));
-            const int pos = __builtin_popcountll(ballot64(e0 < cand)) + __builtin_popcountll(ballot64(e1 < cand));
-            if (pos >= k) continue;
-            // places pos.. move one down the list; what falls off the end is forgotten
-            const uint64_t up0 = from_lane_below(e0, e0);
-            const uint64_t up1 = from_lane_below(e1, lane_value_u64(e0, 63));
-            e0 = i0 > pos ? up0 : (i0 == pos ? cand : e0);
-            e1 = i1 > pos ? up1 : (i1 == pos ? cand : e1);
-            if (i0 >= k) e0 = ~0ull;
-            if (i1 >= k) e1 = ~0ull;
-            if (cnt < k) ++cnt;
-            changed = true;
-        }
-        if (changed) {
-            if (i0 < cnt) list[i0] = e0;
-            if (i1 < cnt) list[i1] = e1;
-            if (cnt == k) own_key = (uint32_t)(lane_value_u64(k <= 64 ? e0 : e1, (k - 1) & 63) >> 32);
+        // Short lists (k <= 64, or a list that stays within 64 entries after this call: most lists
+        // of inverted-file jobs) live in one register per lane.
+        const bool one = k <= 64 || cnt + __builtin_popcountll(mine) <= 64;  // (wave-uniform)
+        uint64_t e0 = ~0ull, e1 = ~0ull;  // places past the end hold the largest key
+        if (i0 < cnt) e0 = list[i0];
+        if (one) {
+            while (mine) {
+                const int src = __builtin_ctzll(mine);
+                mine &= mine - 1;
+                const uint64_t cand = pack_entry(bcast_f(d, src), bcast_u(id, src));
+                const int pos = __builtin_popcountll(ballot64(e0 < cand));
+                if (pos >= k) continue;
+                const uint64_t up0 = from_lane_below(e0, e0);
+                e0 = i0 > pos ? up0 : (i0 == pos ? cand : e0);
+                if (i0 >= k) e0 = ~0ull;
+                if (cnt < k) ++cnt;
+                changed = true;
+            }
+            if (changed) {
+                if (i0 < cnt) list[i0] = e0;
+                if (cnt == k) own_key = (uint32_t)(lane_value_u64(e0, (k - 1) & 63) >> 32);  // (k <= 64 here)
+            }
+        } else {
+            if (i1 < cnt) e1 = list[i1];
+            while (mine) {
+                const int src = __builtin_ctzll(mine);
+                mine &= mine - 1;
+                const uint64_t cand = pack_entry(bcast_f(d, src), bcast_u(id, src));
+                const int pos = __builtin_popcountll(ballot64(e0 < cand)) + __builtin_popcountll(ballot64(e1 < cand));
+                if (pos >= k) continue;
+                // places pos.. move one down the list; what falls off the end is forgotten
+                const uint64_t up0 = from_lane_below(e0, e0);
+                const uint64_t up1 = from_lane_below(e1, lane_value_u64(e0, 63));
+                e0 = i0 > pos ? up0 : (i0 == pos ? cand : e0);
+                e1 = i1 > pos ? up1 : (i1 == pos ? cand : e1);
+                if (i0 >= k) e0 = ~0ull;
+                if (i1 >= k) e1 = ~0ull;
+                if (cnt < k) ++cnt;
+                changed = true;
+            }
+            if (changed) {
+                if (i0 < cnt) list[i0] = e0;
+                if (i1 < cnt) list[i1] = e1;
+                if (cnt == k) own_key = (uint32_t)(lane_value_u64(k <= 64 ? e0 : e1, (k - 1) & 63) >> 32);
+            }
         }
     } else {
         thr_old = s.thr[q];
