@@ -67,6 +67,7 @@ struct ScanPlan {
     int kpad = 0;        // k rounded up to a multiple of 4: the stride of a list in LDS
     int nslice = 0;      // database slices (one workgroup per (query tile, slice))
     int64_t slice_len = 0;
+    int64_t tiles_one = 0;  // leading query tiles that scan the whole database in one piece
     int64_t ntiles = 0;
     size_t lds_bytes = 0;
     size_t gthr_bytes = 0;  // per-query shared thresholds

@@ -53,6 +53,7 @@ struct ScanArgs {
     int64_t nq, n;
     int64_t slice_len;
     int nslice;
+    int64_t tiles_one;        // flat mode: the first tiles_one query tiles scan the whole database in one piece
     int k, kpad;
     uint32_t bias;            // 0x7fffffff - ht: bit 31 of (bias + distance) <=> distance > ht
     float *part_d;            // [nq][nslice][k]
@@ -82,6 +83,47 @@ struct ScanArgs {
     uint8_t *job_qcodes;      // [njobs][M] out: query code of each job
     int dim, nlist;
 };
+
+// Flat mode: which queries and which part of the database a workgroup works on.  Query tiles
+// 0 .. tiles_one-1 are scanned in one piece each (they fill whole rounds of workgroups that run
+// together); the tiles after them are cut into nslice slices each, so that the last, partial
+// round finishes in 1/nslice of the time instead of leaving compute units idle.  A query scanned
+// in one piece builds one list instead of nslice: fewer insertions and a cheaper merge.
+struct FlatTile {
+    int slice;
+    bool whole;  // one piece: the other slices' places in the partial lists get padding
+    int64_t q0, slice_begin, slice_end;
+};
+__device__ __forceinline__ FlatTile flat_tile(const ScanArgs &a, int64_t tile, int tq)
+{
+    FlatTile t;
+    if (tile < a.tiles_one) {
+        t.slice = 0;
+        t.whole = true;
+        t.q0 = tile * tq;
+        t.slice_begin = 0;
+        t.slice_end = a.n;
+    } else {
+        const int64_t u = tile - a.tiles_one;
+        t.slice = (int)(u % a.nslice);
+        t.whole = false;
+        t.q0 = (a.tiles_one + u / a.nslice) * tq;
+        t.slice_begin = (int64_t)t.slice * a.slice_len;
+        t.slice_end = (t.slice_begin + a.slice_len) < a.n ? (t.slice_begin + a.slice_len) : a.n;
+    }
+    return t;
+}
+// Padding for the partial lists a one-piece tile leaves unused (slices 1 .. nslice-1 of its queries).
+__device__ __forceinline__ void pad_unused_slices(const ScanArgs &a, int64_t q0, int nvq, int tid, int nthreads)
+{
+    const int per_q = (a.nslice - 1) * a.k;
+    for (int e = tid; e < nvq * per_q; e += nthreads) {
+        const int q = e / per_q, r = e - q * per_q;
+        const int64_t o = ((q0 + q) * a.nslice + 1) * a.k + r;
+        a.part_d[o] = __builtin_inff();
+        a.part_i[o] = (int64_t)-1;
+    }
+}
 
 __device__ __forceinline__ uint64_t ballot64(bool p) { return __ballot(p); }
 
@@ -587,6 +629,7 @@ scan_kernel(ScanArgs a)
     // [valid_begin, slice_end) is scanned; slice_begin (<= valid_begin) is where positions count
     // from and is a whole number of 16-byte loads into `codes`.
     int slice = 0, tile_list = 0;
+    bool whole_db = false;
     int64_t q0, slice_begin, valid_begin, slice_end;
     int nvq;
     if constexpr (IVF) {
@@ -599,13 +642,14 @@ scan_kernel(ScanArgs a)
         slice_end = a.list_off[t.list + 1];
         slice_begin = valid_begin - valid_begin % CPL;
     } else {
-        const int64_t tile = blockIdx.x;
-        slice = (int)(tile % a.nslice);
-        q0 = (tile / a.nslice) * TQ;
+        const FlatTile t = flat_tile(a, blockIdx.x, TQ);
+        slice = t.slice;
+        whole_db = t.whole;
+        q0 = t.q0;
         nvq = (int)((a.nq - q0) < TQ ? (a.nq - q0) : TQ);
-        slice_begin = (int64_t)slice * a.slice_len;
+        slice_begin = t.slice_begin;
         valid_begin = slice_begin;
-        slice_end = (slice_begin + a.slice_len) < a.n ? (slice_begin + a.slice_len) : a.n;
+        slice_end = t.slice_end;
     }
 
     // ---- per-slot state
@@ -885,6 +929,9 @@ scan_kernel(ScanArgs a)
         a.part_d[o] = have ? entry_dist(ent) : __builtin_inff();
         a.part_i[o] = have ? id : (int64_t)-1;
     }
+    if constexpr (!IVF) {
+        if (whole_db && a.nslice > 1) pad_unused_slices(a, q0, nvq, tid, NW * 64);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -934,12 +981,12 @@ scan_mfma_kernel(ScanArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 15, grp = lane >> 4;
 
-    const int64_t tile = blockIdx.x;
-    const int slice = (int)(tile % a.nslice);
-    const int64_t q0 = (tile / a.nslice) * TQ;
+    const FlatTile ft = flat_tile(a, blockIdx.x, TQ);
+    const int slice = ft.slice;
+    const int64_t q0 = ft.q0;
     const int nvq = (int)((a.nq - q0) < TQ ? (a.nq - q0) : TQ);
-    const int64_t slice_begin = (int64_t)slice * a.slice_len;
-    const int64_t slice_end = (slice_begin + a.slice_len) < a.n ? (slice_begin + a.slice_len) : a.n;
+    const int64_t slice_begin = ft.slice_begin;
+    const int64_t slice_end = ft.slice_end;
 
     if (tid < TQ) {
         const int gi = tid < nvq ? (int)(q0 + tid) : -1;
@@ -1116,6 +1163,7 @@ scan_mfma_kernel(ScanArgs a)
         a.part_d[o] = have ? entry_dist(ent) : __builtin_inff();
         a.part_i[o] = have ? slice_begin + (int64_t)entry_id(ent) : (int64_t)-1;
     }
+    if (ft.whole && a.nslice > 1) pad_unused_slices(a, q0, nvq, tid, NW * 64);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1144,12 +1192,12 @@ adc_kernel(ScanArgs a)
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    const int64_t tile = blockIdx.x;
-    const int slice = (int)(tile % a.nslice);
-    const int64_t q0 = (tile / a.nslice) * TQ;
+    const FlatTile ft = flat_tile(a, blockIdx.x, TQ);
+    const int slice = ft.slice;
+    const int64_t q0 = ft.q0;
     const int nvq = (int)((a.nq - q0) < TQ ? (a.nq - q0) : TQ);
-    const int64_t slice_begin = (int64_t)slice * a.slice_len;
-    const int64_t slice_end = (slice_begin + a.slice_len) < a.n ? (slice_begin + a.slice_len) : a.n;
+    const int64_t slice_begin = ft.slice_begin;
+    const int64_t slice_end = ft.slice_end;
 
     // ---- stage the tables interleaved, reset the lists
     {
@@ -1259,6 +1307,7 @@ adc_kernel(ScanArgs a)
         a.part_d[o] = have ? entry_dist(ent) : __builtin_inff();
         a.part_i[o] = have ? (slice_begin + (int64_t)entry_id(ent)) : (int64_t)-1;
     }
+    if (ft.whole && a.nslice > 1) pad_unused_slices(a, q0, nvq, tid, NW * 64);
 }
 
 // Merge the nslice sorted partial lists of each query into the final k (one wave per query).
@@ -1619,14 +1668,17 @@ int plan_scan(int m, int64_t nq, int64_t n, int k, int kind, ScanPlan *plan)
     const int64_t nqt = (nq + p.tq - 1) / p.tq;
     // Slices: one workgroup per (query tile, slice); the launch runs in rounds of `round`
     // workgroups.  Every slice of a query builds its own list of k, which costs insertions and
-    // merge work, so the fewest slices win that fill the rounds: score = share of the rounds'
-    // places that are used, less 1% per round.
+    // merge work, so the fewest slices win that keep the compute units busy.
     const int64_t block = 512;  // codes per wave and step, at most (64 lanes x 8 codes)
-    int64_t want = 1;
-    if (nqt > 0) {
-        const int64_t wg_limit = 8 * round;
+    const int64_t min_slice = p.nwaves * block;  // at least one block per wave
+    const int64_t max_by_size = std::max<int64_t>(1, n / min_slice);
+    const int64_t max_slice = kind == kScanFusedMfma ? kMfmaMaxSliceLen : kMaxSliceLen;
+    const int64_t wg_limit = std::max<int64_t>(8 * round, nqt);
+    int64_t want = 1, tiles_one = 0;
+    if (nqt > 0 && nq <= 16) {
+        // a handful of queries: score = share of the rounds' places that are used, less 1% per round
         double best_score = -1.0;
-        for (int64_t sN = 1; sN * nqt <= std::max<int64_t>(wg_limit, nqt); ++sN) {
+        for (int64_t sN = 1; sN * nqt <= wg_limit; ++sN) {
             const int64_t wg = nqt * sN, rounds = (wg + round - 1) / round;
             const double score = (double)wg / (double)(rounds * round) - 0.01 * (double)rounds;
             if (score > best_score + 1e-9) {
@@ -1634,12 +1686,33 @@ int plan_scan(int m, int64_t nq, int64_t n, int k, int kind, ScanPlan *plan)
                 want = sN;
             }
         }
+    } else if (nqt > 0) {
+        // Batches: the query tiles that fill whole rounds are scanned in one piece each, only the
+        // tiles of the last, partial round are cut into slices (see flat_tile) -- or all tiles are
+        // cut alike, whichever is estimated cheaper.  Time in units of "one workgroup scans the
+        // whole database": the whole rounds, plus the rounds of the sliced tiles at 1/S each;
+        // every extra list of a query is charged 4% (measured: two lists instead of one for all
+        // queries cost about 8% at the headline size).
+        double best_cost = 1e300;
+        const int64_t whole_rounds_tiles = n <= max_slice ? (nqt / round) * round : 0;
+        for (int64_t t1 : {whole_rounds_tiles, (int64_t)0}) {
+            const int64_t rest = nqt - t1;
+            for (int64_t sN = 1; sN <= std::min<int64_t>(max_by_size, 1024) && rest * sN <= wg_limit; ++sN) {
+                const double time = (double)t1 / (double)round +
+                                    (rest ? (double)((rest * sN + round - 1) / round) / (double)sN : 0.0);
+                const double extra = (double)(rest * (sN - 1)) / (double)nqt;
+                const double cost = time * (1.0 + 0.04 * extra);
+                if (cost < best_cost - 1e-12) {
+                    best_cost = cost;
+                    want = sN;
+                    tiles_one = t1;
+                }
+                if (!rest) break;
+            }
+        }
     }
-    const int64_t min_slice = p.nwaves * block;  // at least one block per wave
-    int64_t max_by_size = std::max<int64_t>(1, n / min_slice);
     int64_t nslice = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, max_by_size), 1024));
     int64_t slice_len = (((n + nslice - 1) / nslice) + block - 1) / block * block;
-    const int64_t max_slice = kind == kScanFusedMfma ? kMfmaMaxSliceLen : kMaxSliceLen;
     if (slice_len > max_slice) {
         slice_len = max_slice;
         nslice = (n + slice_len - 1) / slice_len;
@@ -1652,7 +1725,8 @@ int plan_scan(int m, int64_t nq, int64_t n, int k, int kind, ScanPlan *plan)
     nslice = std::max<int64_t>(1, (n + slice_len - 1) / slice_len);
     p.nslice = (int)nslice;
     p.slice_len = slice_len;
-    p.ntiles = nqt * nslice;
+    p.tiles_one = tiles_one;
+    p.ntiles = tiles_one + (nqt - tiles_one) * nslice;
     const size_t dist_bytes = ((size_t)nq * nslice * k * sizeof(float) + 255) / 256 * 256;
     p.part_bytes = dist_bytes + (size_t)nq * nslice * k * sizeof(int64_t);
     p.gthr_bytes = ((size_t)nq * sizeof(uint32_t) + 255) / 256 * 256;
@@ -1730,6 +1804,7 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
     a.n = n;
     a.slice_len = p.slice_len;
     a.nslice = p.nslice;
+    a.tiles_one = p.tiles_one;
     a.k = k;
     a.kpad = p.kpad;
     const int nbits = 8 * m;
@@ -1801,6 +1876,7 @@ int launch_ivf_scan(int m, int tq, int nwaves, int kpad, size_t lds_bytes, const
     a.n = n;
     a.slice_len = 0;
     a.nslice = 1;
+    a.tiles_one = 0;
     a.k = k;
     a.kpad = kpad;
     const int nbits = 8 * m;
