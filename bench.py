@@ -62,8 +62,8 @@ def main():
     if args.filter_route != "auto":
         os.environ["PSC_FILTER_ROUTE"] = args.filter_route
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        log("bench.py: this build measures one GPU only (the path shards without any exchange, "
-            "see DESIGN.md); run with --gpus 1")
+        log("bench.py: this build measures one GPU only (the path would shard by splitting the query "
+            "batch, or the database rows with one k-way merge of the partial lists); run with --gpus 1")
         sys.exit(2)
 
     import numpy as np
