@@ -108,6 +108,43 @@ def test_survivor_set_on_the_matrix_cores(psc, monkeypatch):
                 assert sorted(got_ids[q][got_ids[q] >= 0].tolist()) == np.flatnonzero(ref["bitmap"][q]).tolist()
 
 
+@pytest.mark.parametrize("route", ["mfma", "popcount"])
+def test_nested_prefix_patterns_at_every_threshold(psc, monkeypatch, route):
+    """Database row r = the first r bits set (r = 0..64, repeated to fill several blocks), query q =
+    the first 3q bits set: their Hamming distance is |r - 3q| exactly, so the survivor set at every
+    threshold is known in closed form.  Both filters, every threshold up to where the dense route
+    takes over; the table makes the distance itself the score."""
+    monkeypatch.setenv("PSC_FILTER_ROUTE", route)
+    m, reps, nq = 8, 7, 20
+    def prefix(r):
+        c = np.zeros(m, np.uint8)
+        full, rem = divmod(r, 8)
+        c[:full] = 0xFF
+        if rem:
+            c[full] = (1 << rem) - 1
+        return c
+    rows = np.array([r for _ in range(reps) for r in range(65)])
+    codes = np.stack([prefix(r) for r in rows])
+    qbits = np.array([3 * q for q in range(nq)])
+    qc = np.stack([prefix(b) for b in qbits])
+    lut = np.zeros((nq, m, 256), np.float32)
+    pc = np.array([bin(v).count("1") for v in range(256)], np.float32)
+    for q in range(nq):  # score = Hamming distance to the query code: sum over bytes of popcount(byte xor query byte)
+        for j in range(m):
+            lut[q, j] = pc[np.arange(256) ^ int(qc[q, j])]
+    k = 136
+    for ht in range(0, 31):
+        ids, d = _run(psc, lut, qc, codes, ht, k)
+        for q in range(nq):
+            want = np.flatnonzero(np.abs(rows - qbits[q]) <= ht)
+            got = ids[q][ids[q] >= 0]
+            if len(want) <= k:
+                assert sorted(got.tolist()) == want.tolist(), (route, ht, q)
+            else:
+                assert len(got) == k
+            assert np.array_equal(d[q][: len(got)], np.abs(rows[got] - qbits[q]).astype(np.float32)), (route, ht, q)
+
+
 def test_many_slices_for_few_queries(psc):
     """Two queries over 3M codes: 256 database slices, whose partial lists the merge takes four to a lane."""
     codes, qcodes, lut = _rand_problem(8, 3_000_001, 2, seed=321, lut_kind="float")
