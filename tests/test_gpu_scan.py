@@ -145,6 +145,27 @@ def test_nested_prefix_patterns_at_every_threshold(psc, monkeypatch, route):
             assert np.array_equal(d[q][: len(got)], np.abs(rows[got] - qbits[q]).astype(np.float32)), (route, ht, q)
 
 
+@pytest.mark.parametrize("route", ["mfma", "popcount"])
+def test_whole_and_sliced_query_tiles_in_one_launch(psc, monkeypatch, route):
+    """More query tiles than workgroups run at a time: the tiles of the whole rounds scan the
+    database in one piece, those of the last partial round in slices.  Queries from both regions
+    (and the last, ragged tile) against the oracle."""
+    monkeypatch.setenv("PSC_FILTER_ROUTE", route)
+    n, nq, k = 150_011, 4100 + 13, 20
+    codes, qcodes, lut = _rand_problem(8, n, nq, seed=4242, lut_kind="float")
+    sel = np.array([0, 1, 15, 16, 2047, 4079, 4080, 4095, 4096, 4097, 4111, 4112])
+    for ht in (14, 22):
+        got_ids, got_d = _run(psc, lut, qcodes, codes, ht, k)
+        ref = O.scan(lut[sel].astype(np.float64), qcodes[sel], codes, ht, k)
+        assert_topk_matches(got_ids[sel], got_d[sel], ref, lut[sel].astype(np.float64), qcodes[sel], codes, ht,
+                            what=f"two regions route={route} ht={ht}")
+        # all queries: as many results as the (separately tested) filter counts survivors, up to k
+        ns = psc.hamming_filter(_dev(qcodes), _dev(codes), ht)
+        torch.cuda.synchronize()
+        assert got_ids.max() < n
+        assert np.array_equal((got_ids >= 0).sum(axis=1), np.minimum(ns.cpu().numpy(), k))
+
+
 def test_many_slices_for_few_queries(psc):
     """Two queries over 3M codes: 256 database slices, whose partial lists the merge takes four to a lane."""
     codes, qcodes, lut = _rand_problem(8, 3_000_001, 2, seed=321, lut_kind="float")
