@@ -683,7 +683,8 @@ int psc_ivf_search(const psc_index *idx, const float *q_dev, int64_t nq, int npr
     uint8_t *qcodes = (uint8_t *)(w + L.off_qcodes);
 
     // 1. coarse quantization of the queries and choice of the lists
-    rc = launch_coarse_distances(q_dev, nq, idx->dim, idx->coarse_dev, idx->nlist, dist, s);
+    rc = launch_coarse_distances(q_dev, nq, idx->dim, idx->coarse_dev, idx->nlist,
+                                 idx->coarse_dev + (size_t)idx->nlist * idx->dim, dist, s);
     if (rc != PSC_OK) return rc;
     rc = launch_select_probes(dist, nq, idx->nlist, nprobe, probed, s);
     if (rc != PSC_OK) return rc;

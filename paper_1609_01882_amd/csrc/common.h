@@ -104,7 +104,7 @@ int launch_hamming_filter(int m, const uint8_t *qcodes_dev, int64_t nq, const ui
 // ---- inverted-file helpers (kernels_ivf.hip)
 // Squared distances of rows x [n][dim] to centroids [nlist][dim] -> dist [n][nlist] (float32).
 int launch_coarse_distances(const float *x_dev, int64_t n, int dim, const float *cent_dev, int nlist,
-                            float *dist_dev, hipStream_t s);
+                            const float *mu_dev, float *dist_dev, hipStream_t s);
 // Per row the nprobe smallest of dist [n][nlist] by (distance, list number) -> probed [n][nprobe].
 int launch_select_probes(const float *dist_dev, int64_t n, int nlist, int nprobe, int32_t *probed_dev,
                          hipStream_t s);

@@ -241,16 +241,23 @@ nearest_centroid_kernel(const float *__restrict__ x, int64_t n, int dim, const f
 // ---------------------------------------------------------------------------------------------
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-template <int DIM>
+// DIST: instead of the arg-min, all distances || x - c ||^2 = || x' ||^2 + || c' ||^2 - 2 x'.c' are
+// written (dist [n][nlist], clamped at 0), and the grid's second dimension splits the centroid
+// tiles into groups of kDistTilesPerGroup so that a small batch of rows still fills the chip.
+constexpr int kDistTilesPerGroup = 8;
+
+template <int DIM, bool DIST>
 __global__ void __launch_bounds__(256)
 nearest_centroid_mfma_kernel(const float *__restrict__ x, int64_t n, const float *__restrict__ cent,
-                             const float *__restrict__ mu, int nlist, int32_t *__restrict__ assign)
+                             const float *__restrict__ mu, int nlist, int32_t *__restrict__ assign,
+                             float *__restrict__ dist)
 {
     static_assert(DIM % 8 == 0 && DIM <= 128, "rows are held in registers");
     constexpr int KS = DIM / 2;
     constexpr int LD = DIM + 2;  // row pitch of a staged tile: lanes (half, col) hit 64 different banks
     __shared__ float tile[2][32 * LD];
     __shared__ float cnorm[2][32];
+    __shared__ float xnorm[4][32];
     const int tid = (int)threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
     const int half = lane >> 5, col = lane & 31;
@@ -262,6 +269,14 @@ nearest_centroid_mfma_kernel(const float *__restrict__ x, int64_t n, const float
         const float *xr = x + (r < n ? r : n - 1) * DIM;
 #pragma unroll
         for (int kk = 0; kk < KS; ++kk) a[kk] = xr[2 * kk + half] - mu[2 * kk + half];
+    }
+    if constexpr (DIST) {  // || x' ||^2 of row `col`: this lane's coordinates plus the other half's
+        float xn = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) xn = fmaf(a[kk], a[kk], xn);
+        xn += __shfl_xor(xn, 32, 64);
+        if (half == 0) xnorm[wave][col] = xn;
+        __builtin_amdgcn_wave_barrier();
     }
     // staging: thread -> centroid tid / 8 of the tile, coordinates (tid % 8) * 4 + 32 * i
     const int sc = tid >> 3, sp = (tid & 7) * 4;
@@ -301,10 +316,12 @@ nearest_centroid_mfma_kernel(const float *__restrict__ x, int64_t n, const float
         bestv[v] = __builtin_inff();
         besti[v] = 0;
     }
-    const int ntiles = (nlist + 31) / 32;
-    stage(0, 0);
+    const int tiles_all = (nlist + 31) / 32;
+    const int tbeg = DIST ? (int)blockIdx.y * kDistTilesPerGroup : 0;
+    const int ntiles = DIST ? (tiles_all < tbeg + kDistTilesPerGroup ? tiles_all : tbeg + kDistTilesPerGroup) : tiles_all;
+    stage(tbeg, tbeg & 1);
     __syncthreads();
-    for (int t = 0; t < ntiles; ++t) {
+    for (int t = tbeg; t < ntiles; ++t) {
         const int buf = t & 1;
         if (t + 1 < ntiles) stage(t + 1, buf ^ 1);
         f32x16 acc;
@@ -318,13 +335,20 @@ nearest_centroid_mfma_kernel(const float *__restrict__ x, int64_t n, const float
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const float d = fmaf(-2.0f, acc[v], cn);  // (+inf for the padding of the last tile)
-            if (d < bestv[v]) {
+            if constexpr (DIST) {
+                const int i = 8 * (v / 4) + 4 * half + v % 4;
+                if (r0 + i < n && ci < nlist) {
+                    const float full = d + xnorm[wave][i];
+                    dist[(r0 + i) * nlist + ci] = full > 0.f ? full : 0.f;
+                }
+            } else if (d < bestv[v]) {
                 bestv[v] = d;
                 besti[v] = ci;
             }
         }
         __syncthreads();
     }
+    if constexpr (DIST) return;
     // the 32 lanes of a half hold the 32 columns of each of its 16 rows: smallest (value, number)
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
@@ -381,7 +405,18 @@ __global__ void job_column_prefix_kernel(int32_t *__restrict__ hist, int64_t nbl
     const int l = blockIdx.x * blockDim.x + threadIdx.x;
     if (l >= nlist) return;
     int32_t run = 0;
-    for (int64_t b = 0; b < nblk; ++b) {
+    int64_t b = 0;
+    for (; b + 16 <= nblk; b += 16) {  // sixteen loads in flight instead of one (the walk is latency-bound)
+        int32_t c[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) c[i] = hist[(b + i) * nlist + l];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            hist[(b + i) * nlist + l] = run;
+            run += c[i];
+        }
+    }
+    for (; b < nblk; ++b) {
         const int32_t c = hist[b * nlist + l];
         hist[b * nlist + l] = run;
         run += c;
@@ -544,12 +579,35 @@ static int check_dim(int dim, int nlist)
     return PSC_OK;
 }
 
+template <int DIM>
+static int run_coarse_dist_mfma(const float *x_dev, int64_t n, const float *cent_dev, const float *mu_dev, int nlist,
+                                float *dist_dev, hipStream_t s)
+{
+    const int tiles = (nlist + 31) / 32;
+    dim3 grid((unsigned)((n + 127) / 128), (unsigned)((tiles + kDistTilesPerGroup - 1) / kDistTilesPerGroup));
+    hipLaunchKernelGGL((nearest_centroid_mfma_kernel<DIM, true>), grid, dim3(256), 0, s, x_dev, n, cent_dev, mu_dev,
+                       nlist, (int32_t *)nullptr, dist_dev);
+    PSC_HIP_TRY(hipGetLastError());
+    return PSC_OK;
+}
+
+// mu_dev: reference point [dim] of the matrix-core kernel (the mean centroid), which takes batches
+// of 256 rows and more in the dimensions it is built for; everything else takes the plain kernel.
 int launch_coarse_distances(const float *x_dev, int64_t n, int dim, const float *cent_dev, int nlist,
-                            float *dist_dev, hipStream_t s)
+                            const float *mu_dev, float *dist_dev, hipStream_t s)
 {
     int rc = check_dim(dim, nlist);
     if (rc != PSC_OK) return rc;
     if (n == 0) return PSC_OK;
+    if (mu_dev && n >= 256 && (n + 127) / 128 <= 0x7fffffffLL) {
+        switch (dim) {
+        case 32: return run_coarse_dist_mfma<32>(x_dev, n, cent_dev, mu_dev, nlist, dist_dev, s);
+        case 64: return run_coarse_dist_mfma<64>(x_dev, n, cent_dev, mu_dev, nlist, dist_dev, s);
+        case 96: return run_coarse_dist_mfma<96>(x_dev, n, cent_dev, mu_dev, nlist, dist_dev, s);
+        case 128: return run_coarse_dist_mfma<128>(x_dev, n, cent_dev, mu_dev, nlist, dist_dev, s);
+        default: break;
+        }
+    }
     PSC_REQUIRE((n + kRows - 1) / kRows <= 0x7fffffffLL, "too many rows");
     dim3 grid((unsigned)((n + kRows - 1) / kRows), (unsigned)((nlist + 255) / 256));
     hipLaunchKernelGGL(coarse_dist_kernel, grid, dim3(256), (size_t)kRows * dim * sizeof(float), s, x_dev, n, dim,
@@ -589,8 +647,8 @@ template <int DIM>
 static int run_nearest_centroid_mfma(const float *x_dev, int64_t n, const float *cent_dev, const float *mu_dev,
                                      int nlist, int32_t *assign_dev, hipStream_t s)
 {
-    hipLaunchKernelGGL((nearest_centroid_mfma_kernel<DIM>), dim3((unsigned)((n + 127) / 128)), dim3(256), 0, s,
-                       x_dev, n, cent_dev, mu_dev, nlist, assign_dev);
+    hipLaunchKernelGGL((nearest_centroid_mfma_kernel<DIM, false>), dim3((unsigned)((n + 127) / 128)), dim3(256), 0, s,
+                       x_dev, n, cent_dev, mu_dev, nlist, assign_dev, (float *)nullptr);
     PSC_HIP_TRY(hipGetLastError());
     return PSC_OK;
 }
