@@ -134,6 +134,9 @@ int psc_threshold_for_rate(const int64_t *hist_host, int nbits, double max_keep_
  * equal distance, in ids_dev [nq][k] (int64) and dists_dev [nq][k] (float32),
  * padded with id -1 / distance +inf when fewer than k survive.
  * 1 <= k <= PSC_MAX_K, ht >= 0, n < 2^40.  Workspace: psc_scan_workspace_bytes.
+ * Table entries must not be negative (they are squared distances; psc_build_lut clamps at 0):
+ * the scan rejects a survivor as soon as the sum over its first sub-quantizers exceeds the
+ * query's current k-th best distance.
  * The Hamming test is exact on every route the library takes: xor / popcount on the vector
  * units, or (64-bit codes, 9 queries or more, selective thresholds) an int8 dot product of
  * +-1 expansions on the matrix cores, whose sign gives the same verdict.  The environment

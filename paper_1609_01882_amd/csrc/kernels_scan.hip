@@ -574,16 +574,44 @@ __device__ __forceinline__ void drain(const Lds<M, TQ> &s, const ScanArgs &a, co
         // nothing (one wait instruction instead of one per addition).
         const lds_f32 *t = s.lut + q * (M * 256);
         thr = s.thr[q];
-        float tv[M];
+        if constexpr (IVF) {
+            float tv[M];
 #pragma unroll
-        for (int j = M - 1; j >= 0; --j) {
-            const uint32_t byte = (w[j >> 2] >> (8 * (j & 3))) & 0xffu;
-            tv[j] = t[j * 256 + byte];
+            for (int j = M - 1; j >= 0; --j) {
+                const uint32_t byte = (w[j >> 2] >> (8 * (j & 3))) & 0xffu;
+                tv[j] = t[j * 256 + byte];
+            }
+            float acc = tv[0];
+#pragma unroll
+            for (int j = 1; j < M; ++j) acc += tv[j];
+            d = acc;
+        } else {
+            // Tables of squared distances have no negative entries, so the sum over the first
+            // sub-quantizers already bounds the distance from below: once the lists are warm it
+            // rejects nearly every survivor, and the other gathers are issued only if some lane
+            // of the wave still needs them.  The additions keep their order (j ascending), so a
+            // distance that is finished is the same float32 as without the shortcut.
+            constexpr int M0 = (M * 3) / 8;
+            float tv[M];
+#pragma unroll
+            for (int j = M0 - 1; j >= 0; --j) {
+                const uint32_t byte = (w[j >> 2] >> (8 * (j & 3))) & 0xffu;
+                tv[j] = t[j * 256 + byte];
+            }
+            float acc = tv[0];
+#pragma unroll
+            for (int j = 1; j < M0; ++j) acc += tv[j];
+            if (acc <= thr) {
+#pragma unroll
+                for (int j = M - 1; j >= M0; --j) {
+                    const uint32_t byte = (w[j >> 2] >> (8 * (j & 3))) & 0xffu;
+                    tv[j] = t[j * 256 + byte];
+                }
+#pragma unroll
+                for (int j = M0; j < M; ++j) acc += tv[j];
+                d = acc;
+            }
         }
-        float acc = tv[0];
-#pragma unroll
-        for (int j = 1; j < M; ++j) acc += tv[j];
-        d = acc;
     } else {
         if constexpr (SHARE) {
             if (ask.wanted) adopt_shared_thresholds<M, TQ>(s, shared);
