@@ -1462,42 +1462,71 @@ __global__ void init_scan_kernel(uint32_t *gthr, int64_t n, int *status)
 }
 
 // Hamming filter alone: per query the number of codes within ht (and optionally every distance).
+// A workgroup column serves kFilterTQ queries at a time, so that a code is loaded once for all of
+// them (their code words are the same for every lane: scalar registers).
+constexpr int kFilterTQ = 16;
 template <int M>
 __global__ void __launch_bounds__(256)
 hamming_filter_kernel(const uint8_t *__restrict__ qcodes, int64_t nq, const uint8_t *__restrict__ codes,
                       int64_t n, int ht, unsigned long long *__restrict__ nsurv,
                       uint8_t *__restrict__ hdist)
 {
-    const int64_t q = blockIdx.y;
     constexpr int WPC = M / 4;
-    uint32_t qw[WPC];
+    const int64_t q0 = (int64_t)blockIdx.y * kFilterTQ;
+    const int nvq = (int)((nq - q0) < kFilterTQ ? (nq - q0) : kFilterTQ);
+    uint32_t qw[kFilterTQ][WPC];
 #pragma unroll
-    for (int w = 0; w < WPC; ++w) qw[w] = ((const uint32_t *)qcodes)[q * WPC + w];
-    unsigned long long local = 0;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-        int h = 0;
+    for (int t = 0; t < kFilterTQ; ++t) {
+        const int64_t q = q0 + (t < nvq ? t : 0);
 #pragma unroll
-        for (int w = 0; w < WPC; ++w) h += __popc(((const uint32_t *)codes)[i * WPC + w] ^ qw[w]);
-        if (hdist) hdist[q * n + i] = (uint8_t)h;
-        local += (h <= ht) ? 1u : 0u;
+        for (int w = 0; w < WPC; ++w) qw[t][w] = ((const uint32_t *)qcodes)[q * WPC + w];
     }
-    // wave reduction, then one atomic per wave
+    uint32_t local[kFilterTQ];
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) local += __shfl_xor(local, off, 64);
-    if ((threadIdx.x & 63) == 0 && local) atomicAdd(&nsurv[q], local);
+    for (int t = 0; t < kFilterTQ; ++t) local[t] = 0u;
+    // (a thread counts at most n / (256 * gridDim.x) < 2^32 codes per query)
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        uint32_t cw[WPC];
+#pragma unroll
+        for (int w = 0; w < WPC; ++w) cw[w] = ((const uint32_t *)codes)[i * WPC + w];
+#pragma unroll
+        for (int t = 0; t < kFilterTQ; ++t) {
+            int h = 0;
+#pragma unroll
+            for (int w = 0; w < WPC; ++w) h += __popc(cw[w] ^ qw[t][w]);
+            if (hdist && t < nvq) hdist[(q0 + t) * n + i] = (uint8_t)h;
+            local[t] += (h <= ht) ? 1u : 0u;
+        }
+    }
+    // wave reduction, workgroup reduction, then one atomic per workgroup and query (many waves
+    // adding to the same few counters would queue up behind each other)
+    __shared__ uint32_t part[4][kFilterTQ];
+#pragma unroll
+    for (int t = 0; t < kFilterTQ; ++t) {
+        uint32_t v = local[t];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) v += (uint32_t)__shfl_xor((int)v, off, 64);
+        if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6][t] = v;
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < nvq) {
+        const unsigned long long v = (unsigned long long)part[0][threadIdx.x] + part[1][threadIdx.x] +
+                                     part[2][threadIdx.x] + part[3][threadIdx.x];
+        if (v) atomicAdd(&nsurv[q0 + threadIdx.x], v);
+    }
 }
 
-// Histogram of the Hamming distances of all pairs: per workgroup (one query, a stride of the
-// codes) a histogram in LDS, added to the global one at the end.
 template <int M>
 __global__ void __launch_bounds__(256)
 hamming_histogram_kernel(const uint8_t *__restrict__ qcodes, const uint8_t *__restrict__ codes, int64_t n,
                          unsigned long long *__restrict__ hist)
 {
-    __shared__ unsigned int bins[8 * M + 1];
+    constexpr int NB = 8 * M + 1;
+    __shared__ unsigned int wbins[4][NB];  // one set of bins per wave: fewer lanes fight over a counter
+    unsigned int *bins = wbins[threadIdx.x >> 6];
     const int64_t q = blockIdx.y;
     constexpr int WPC = M / 4;
-    for (int b = threadIdx.x; b <= 8 * M; b += 256) bins[b] = 0u;
+    for (int b = threadIdx.x; b < 4 * NB; b += 256) (&wbins[0][0])[b] = 0u;
     uint32_t qw[WPC];
 #pragma unroll
     for (int w = 0; w < WPC; ++w) qw[w] = ((const uint32_t *)qcodes)[q * WPC + w];
@@ -1510,8 +1539,10 @@ hamming_histogram_kernel(const uint8_t *__restrict__ qcodes, const uint8_t *__re
         atomicAdd(&bins[h], 1u);
     }
     __syncthreads();
-    for (int b = threadIdx.x; b <= 8 * M; b += 256)
-        if (bins[b]) atomicAdd(&hist[b], (unsigned long long)bins[b]);
+    for (int b = threadIdx.x; b < NB; b += 256) {
+        const unsigned long long v = (unsigned long long)wbins[0][b] + wbins[1][b] + wbins[2][b] + wbins[3][b];
+        if (v) atomicAdd(&hist[b], v);
+    }
 }
 
 __global__ void zero_u64_kernel(unsigned long long *p, int64_t n)
@@ -1937,18 +1968,19 @@ int launch_hamming_filter(int m, const uint8_t *qcodes_dev, int64_t nq, const ui
     PSC_REQUIRE(nq >= 0 && n >= 0 && ht >= 0, "bad sizes");
     if (nq == 0) return PSC_OK;
     PSC_REQUIRE(nsurv_dev && qcodes_dev, "null pointer");
-    PSC_REQUIRE(nq <= 65535, "at most 65535 queries per filter call");
+    PSC_REQUIRE(nq <= 65535 * (int64_t)kFilterTQ, "too many queries for one filter call");
     hipLaunchKernelGGL(zero_u64_kernel, dim3((unsigned)((nq + 255) / 256)), dim3(256), 0, s,
                        (unsigned long long *)nsurv_dev, nq);
     if (n == 0) return PSC_OK;
     PSC_REQUIRE(codes_dev, "null pointer");
     PSC_REQUIRE(((uintptr_t)codes_dev & 3) == 0 && ((uintptr_t)qcodes_dev & 3) == 0, "codes must be 4-byte aligned");
-    const unsigned gx = (unsigned)std::min<int64_t>((n + 255) / 256, 2048);
+    const unsigned gx = (unsigned)std::min<int64_t>((n + 255) / 256, 1024);
+    const unsigned gy = (unsigned)((nq + kFilterTQ - 1) / kFilterTQ);
     if (m == 8)
-        hipLaunchKernelGGL((hamming_filter_kernel<8>), dim3(gx, (unsigned)nq), dim3(256), 0, s, qcodes_dev, nq,
+        hipLaunchKernelGGL((hamming_filter_kernel<8>), dim3(gx, gy), dim3(256), 0, s, qcodes_dev, nq,
                            codes_dev, n, ht, (unsigned long long *)nsurv_dev, hdist_dev);
     else
-        hipLaunchKernelGGL((hamming_filter_kernel<16>), dim3(gx, (unsigned)nq), dim3(256), 0, s, qcodes_dev, nq,
+        hipLaunchKernelGGL((hamming_filter_kernel<16>), dim3(gx, gy), dim3(256), 0, s, qcodes_dev, nq,
                            codes_dev, n, ht, (unsigned long long *)nsurv_dev, hdist_dev);
     PSC_HIP_TRY(hipGetLastError());
     return PSC_OK;
@@ -1967,7 +1999,8 @@ int launch_hamming_histogram(int m, const uint8_t *qcodes_dev, int64_t nq, const
     if (nq == 0 || n == 0) return PSC_OK;
     PSC_REQUIRE(qcodes_dev && codes_dev, "null pointer");
     PSC_REQUIRE(((uintptr_t)codes_dev & 3) == 0 && ((uintptr_t)qcodes_dev & 3) == 0, "codes must be 4-byte aligned");
-    const unsigned gx = (unsigned)std::max<int64_t>(std::min<int64_t>((n + 255) / 256, 2048), (n >> 31) + 1);
+    // (64k codes or more per workgroup: every workgroup ends with up to 8m + 1 global additions)
+    const unsigned gx = (unsigned)std::max<int64_t>(std::min<int64_t>((n + 65535) / 65536, 2048), (n >> 31) + 1);
     if (m == 8)
         hipLaunchKernelGGL((hamming_histogram_kernel<8>), dim3(gx, (unsigned)nq), dim3(256), 0, s, qcodes_dev,
                            codes_dev, n, (unsigned long long *)hist_dev);
