@@ -109,10 +109,10 @@ def test_ivf_search_with_many_probes(ivf_many_lists, nprobe, ht, k):
     _check_ivf_search(ivf_many_lists, nprobe, ht, k)
 
 
-def _check_ivf_search(fixture, nprobe, ht, k):
+def _check_ivf_search(fixture, nprobe, ht, k, nq=37):
     psc, s = fixture
     idx = s["idx"]
-    xq = W.sift_like(37, seed=70, stream=3)
+    xq = W.sift_like(nq, seed=70, stream=3)
     ids, d, probed, qcodes = idx.ivf_search(_dev(xq), nprobe, ht, k, want_debug=True)
     torch.cuda.synchronize()
     ids, d, probed, qcodes = ids.cpu().numpy(), d.cpu().numpy(), probed.cpu().numpy(), qcodes.cpu().numpy()
@@ -139,6 +139,12 @@ def _check_ivf_search(fixture, nprobe, ht, k):
     own_q = O.ivf_search(xq, s["cb"], s["coarse"], s["offsets"], s["lcodes"], s["lids"], nprobe, ht, k,
                          probed_in=probed)
     assert np.array_equal(own_q["nsurv"], ref["nsurv"]) or (own_q["nsurv"] != ref["nsurv"]).mean() < 0.1
+
+
+def test_ivf_search_with_a_batch_of_300(ivf):
+    """256 queries and more take their coarse distances from the matrix-core kernel (centred
+    expansion instead of direct differences): same probed lists up to near-ties, same results."""
+    _check_ivf_search(ivf, 8, 24, 10, nq=300)
 
 
 def test_single_list_is_flat_search():
