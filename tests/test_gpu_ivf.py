@@ -147,6 +147,43 @@ def test_ivf_search_with_a_batch_of_300(ivf):
     _check_ivf_search(ivf, 8, 24, 10, nq=300)
 
 
+@pytest.mark.parametrize("dim", [32, 64, 96])
+def test_probed_lists_in_other_dimensions(dim):
+    """The coarse stage in the other dimensions the matrix-core kernels are built for (batch of 300
+    queries): the probed lists are the exactly nearest ones in order, up to near-ties, and the whole
+    search agrees with the oracle run on the same decisions."""
+    import paper_1609_01882_amd as psc
+    rng = np.random.default_rng(dim)
+    nlist, n, nq, nprobe, m = 70, 20_000, 300, 6, 8
+    cent = (rng.random((nlist, dim)) * 100).astype(np.float32)
+    xb = (cent[rng.integers(0, nlist, size=n)] + rng.normal(0, 12, size=(n, dim))).astype(np.float32)
+    xq = (cent[rng.integers(0, nlist, size=nq)] + rng.normal(0, 12, size=(nq, dim))).astype(np.float32)
+    idx = psc.Index(dim, m)
+    idx.ivf_set_coarse(cent)
+    idx.set_codebook((rng.normal(0, 12, size=(m, 256, dim // m))).astype(np.float32))
+    list_no, codes = idx.ivf_assign_encode(_dev(xb))
+    order = torch.sort(list_no.to(torch.int64), stable=True).indices
+    counts = torch.bincount(list_no.to(torch.int64), minlength=nlist)
+    offsets = torch.zeros(nlist + 1, dtype=torch.int64, device="cuda")
+    offsets[1:] = torch.cumsum(counts, 0)
+    lcodes, lids = codes[order].contiguous(), order.to(torch.int32).contiguous()
+    idx.ivf_set_lists(offsets, lcodes, lids)
+    ids, d, probed, qcodes = idx.ivf_search(_dev(xq), nprobe, 30, 10, want_debug=True)
+    torch.cuda.synchronize()
+    probed = probed.cpu().numpy()
+    dc = ((xq[:, None, :].astype(np.float64) - cent[None, :, :].astype(np.float64)) ** 2).sum(axis=2)
+    want = np.argsort(dc, axis=1, kind="stable")[:, :nprobe]
+    diff = np.argwhere(want != probed)
+    for q, p in diff:
+        assert abs(dc[q, want[q, p]] - dc[q, probed[q, p]]) <= RTOL * dc[q, want[q, p]]
+    assert len(diff) <= max(2, 0.005 * probed.size)
+    ref = O.ivf_search(xq, idx.get_codebook(), cent, offsets.cpu().numpy(), lcodes.cpu().numpy(), lids.cpu().numpy(),
+                       nprobe, 30, 10, probed_in=probed, qcodes_in=qcodes.cpu().numpy())
+    pad = ref["ids"] < 0
+    assert np.array_equal(ids.cpu().numpy() < 0, pad)
+    assert np.allclose(d.cpu().numpy()[~pad], ref["dists"][~pad], rtol=RTOL)
+
+
 def test_single_list_is_flat_search():
     import paper_1609_01882_amd as psc
     xt = W.sift_like(3000, seed=71, stream=1)
