@@ -7,9 +7,12 @@ sub-quantizers around the annealing of the index assignment.
 
 Nothing in the product path may import this module.
 
-Parity unpinned (only invariants are tested): the k-means codebook (`kmeans`, `train_pq`,
-`ivf_train_coarse`) and which local minimum the annealing ends in (`anneal`,
-`optimize_index_assignment`); see the tests named test_oracle_*.
+`kmeans` is pinned on small inputs whose result the mathematics fixes (one centroid, as many
+centroids as points, separated pairs from every start, the refill of an empty cluster, the fixed
+point checked by brute force).  Parity unpinned: which local minimum k-means reaches on real data
+(`train_pq`, `ivf_train_coarse`: it depends on the rows the start draws; objective never rises) and
+which local minimum the annealing ends in (`anneal`, `optimize_index_assignment`); see the tests
+named test_oracle_*.
 """
 from __future__ import annotations
 

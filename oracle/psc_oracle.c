@@ -28,9 +28,10 @@
  *     distance; short lists are padded with id -1 and distance +infinity.
  *
  * Pins: see tests/test_oracle_*.py.
- * Parity unpinned: the k-means codebook (kmeans, train_pq, ivf_train_coarse on
- * the Python side) and which local minimum the simulated annealing ends in
- * (orc_anneal): nothing printed in the paper fixes them, so only their
+ * Parity unpinned: which local minimum k-means reaches on real data (train_pq,
+ * ivf_train_coarse on the Python side; kmeans itself is pinned on small inputs
+ * with a closed-form result) and which local minimum the simulated annealing
+ * ends in (orc_anneal): nothing printed in the paper fixes them, so only their
  * invariants are pinned (objective never rises, result is a permutation,
  * incremental cost change = full recomputation, final loss below initial).
  */

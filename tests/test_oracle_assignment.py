@@ -129,3 +129,58 @@ def test_kmeans_objective_never_rises():
     cent, obj = O.kmeans(x, 256, 8, seed=1)
     assert np.all(np.diff(obj) <= 1e-6 * obj[0])
     assert cent.shape == (256, 16) and np.isfinite(cent).all()
+
+
+def test_kmeans_closed_forms():
+    """Cases where Lloyd's result is fixed by the mathematics, whatever rows the start draws:
+    one centroid is the mean and its objective n times the variance; as many centroids as
+    (distinct) points reproduce the points with objective zero; two well separated pairs on a
+    line end at the pair means from every possible start."""
+    rng = np.random.default_rng(5)
+    x = rng.normal(size=(200, 3)) * [1.0, 4.0, 0.5] + [2.0, -1.0, 7.0]
+    cent, obj = O.kmeans(x, 1, 3, seed=0)
+    assert np.allclose(cent[0], x.mean(axis=0), rtol=0, atol=1e-12)
+    assert np.isclose(obj[-1], 200 * x.var(axis=0).sum(), rtol=1e-12)
+
+    pts = rng.permutation(40).astype(np.float64).reshape(20, 2)
+    cent, obj = O.kmeans(pts, 20, 2, seed=3)
+    assert sorted(map(tuple, cent)) == sorted(map(tuple, pts))
+    assert obj[-1] == 0.0
+
+    line = np.array([[0.0], [1.0], [10.0], [11.0]])
+    starts = set()
+    for seed in range(40):
+        starts.add(tuple(sorted(np.random.default_rng(seed).choice(4, size=2, replace=False).tolist())))
+        cent, obj = O.kmeans(line, 2, 4, seed=seed)
+        assert sorted(cent[:, 0].tolist()) == [0.5, 10.5], seed
+        assert obj[-1] == 1.0  # four points at distance 1/2 from their centroid
+    assert len(starts) == 6  # every possible pair of starting rows was tried
+
+
+def test_kmeans_refills_an_empty_cluster():
+    """Three copies of one point and one point apart: whenever the start draws two of the copies
+    the second centroid attracts nothing (ties go to the lower index) and must be re-seeded with
+    the point farthest from the crowded centroid, so every start ends at {0, 5} with objective 0."""
+    x = np.array([[0.0, 0.0], [0.0, 0.0], [0.0, 0.0], [5.0, 0.0]])
+    seen_refill = False
+    for seed in range(12):
+        start = x[np.random.default_rng(seed).choice(4, size=2, replace=False)]
+        seen_refill |= bool((start == 0).all())
+        cent, obj = O.kmeans(x, 2, 3, seed=seed)
+        assert sorted(cent[:, 0].tolist()) == [0.0, 5.0] and (cent[:, 1] == 0).all(), seed
+        assert obj[-1] == 0.0
+    assert seen_refill
+
+
+def test_kmeans_ends_on_a_fixed_point():
+    """After convergence on a small set every centroid is the mean of exactly the points that are
+    nearest to it (brute-force distances in numpy, not the oracle's own assignment routine)."""
+    x = W.sift_like(300, seed=9, stream=1)[:, :4].astype(np.float64)
+    cent, obj = O.kmeans(x, 5, 60, seed=2)
+    d = ((x[:, None, :] - cent[None, :, :]) ** 2).sum(axis=2)
+    a = d.argmin(axis=1)
+    assert obj[-1] == obj[-2]
+    for c in range(5):
+        assert (a == c).any()
+        assert np.allclose(cent[c], x[a == c].mean(axis=0), rtol=0, atol=1e-9)
+    assert np.isclose(obj[-1], d.min(axis=1).sum(), rtol=1e-12)
