@@ -78,6 +78,21 @@ def test_host_kmeans_quality(psc):
     assert np.isfinite(cb).all()
 
 
+def test_host_kmeans_with_as_many_centroids_as_points(psc):
+    """256 distinct training rows for 256 centroids: every sub-quantizer's codebook must be exactly
+    the set of the rows' sub-vectors (each cell holds one point, whose mean is the point), and
+    the training set is then quantized without error."""
+    rng = np.random.default_rng(21)
+    xt = rng.permutation(256 * 64).astype(np.float32).reshape(256, 64)
+    idx = psc.Index(64, 8)
+    idx.train_pq(xt, iters=3, seed=9)
+    cb = idx.get_codebook()
+    for j in range(8):
+        sub = xt[:, 8 * j:8 * j + 8]
+        assert sorted(map(tuple, cb[j])) == sorted(map(tuple, sub)), j
+    assert np.array_equal(O.decode(O.encode(xt, cb), cb), xt.astype(np.float64))
+
+
 def test_annealing_matches_oracle_trajectory(psc):
     """Same counter-based draws, same double-precision objective: the library's annealing
     must end on the oracle's permutation and renumber the codebook the same way."""
