@@ -67,8 +67,31 @@ void psc_destroy(psc_index *idx);
 /* ------------------------------------------------------------------ training (host side, synchronous) */
 /* Product quantizer (Section 3, opening): one k-means with 256 centroids per
  * sub-space, `iters` Lloyd iterations, on n >= 256 training vectors
- * x_host [n][dim] (float32).  Replaces the codebook. */
+ * x_host [n][dim] (float32).  Replaces the codebook.
+ * Start of sub-quantizer j: 256 distinct rows by a partial Fisher-Yates shuffle of the row
+ * numbers 0..n-1: for c = 0..255, swap entry c with entry c + (draw c of SplitMix64 stream
+ * seed + j) mod (n - c); row c of the start is the sub-vector of entry c.  (The coarse
+ * quantizer's training starts the same way, nlist rows from stream `seed`.)
+ * An empty cell takes the member of the (currently) most populated cell that lies farthest from
+ * that cell's centroid. */
 int psc_train_pq(psc_index *idx, const float *x_host, int64_t n, int iters, uint64_t seed);
+
+/* The same training on the current device (Section 3, opening): x_dev [n][dim] float32 in device
+ * memory, 256 <= n < 2^31.  start = PSC_START_SEEDED draws the same 256 starting rows per
+ * sub-quantizer as psc_train_pq does for that seed; PSC_START_CURRENT continues from the index's
+ * codebook (seed unused).  Each iteration assigns every sub-vector to its nearest centroid
+ * (float32, coordinates in ascending order, lowest index on equal distance), replaces every centroid
+ * by the mean of its members (sums in double precision) and refills an empty cell with the member
+ * of the (currently) most populated cell that lies farthest from that cell's centroid (lowest row
+ * on ties; the donor cell's mean still counts that member in the same iteration).
+ * objective_out_host (may be NULL) [iters][m] receives, per iteration and sub-quantizer, the sum
+ * of squared distances at the assignment step.  The sums are added atomically, so two runs agree
+ * to rounding, not bit for bit.  Synchronous on `stream`; allocates and frees 5*n*m bytes of
+ * device scratch (plus the sums).  Replaces the codebook. */
+#define PSC_START_SEEDED 0
+#define PSC_START_CURRENT 1
+int psc_train_pq_device(psc_index *idx, const float *x_dev, int64_t n, int iters, uint64_t seed, int start,
+                        double *objective_out_host, psc_stream stream);
 
 /* Index assignment (Section 3.1 weighted distance-estimator objective, Section
  * 3.2 simulated annealing): for each sub-quantizer, anneal a bijection pi from
@@ -171,6 +194,13 @@ int psc_knn_graph(const psc_index *idx, const float *x_dev, const uint8_t *codes
  * given centroids.  Either call forgets previously set lists. */
 int psc_ivf_train_coarse(psc_index *idx, const float *x_host, int64_t n, int nlist, int iters, uint64_t seed);
 int psc_ivf_set_coarse(psc_index *idx, const float *centroids_host, int nlist);
+/* psc_ivf_train_coarse with the training vectors already in device memory (x_dev [n][dim],
+ * n < 2^31) and the whole iteration on the device: same seeded start, assignment by the
+ * nearest-centroid kernel, sums in double precision (atomic adds: runs agree to rounding), an
+ * empty cell restarts on the lowest-numbered member of the most populated cell.  Synchronous on
+ * `stream`; allocates and frees its scratch. */
+int psc_ivf_train_coarse_device(psc_index *idx, const float *x_dev, int64_t n, int nlist, int iters,
+                                uint64_t seed, psc_stream stream);
 int psc_ivf_get_coarse(const psc_index *idx, float *centroids_host);
 
 /* Index construction: list_no_dev [n] (int32) = nearest coarse centroid of each row of

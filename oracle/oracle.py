@@ -269,15 +269,20 @@ def nearest(x, cent):
     return assign, dmin
 
 
-def kmeans(x, ncent: int, iters: int, seed: int):
-    """Lloyd k-means.  Start: `ncent` distinct training rows drawn with numpy's default
-    generator seeded by `seed`.  An empty cluster is re-seeded with the point of the most
-    populated cluster that lies farthest from that cluster's centroid.  Returns
-    (centroids [ncent, d] float64, objective after each assignment step)."""
+def kmeans(x, ncent: int, iters: int, seed: int, start=None):
+    """Lloyd k-means.  Start: the centroids `start` [ncent, d] if given, else `ncent` distinct
+    training rows drawn with numpy's default generator seeded by `seed`.  An empty cluster is
+    re-seeded with the point of the most populated cluster that lies farthest from that
+    cluster's centroid (that cluster's own mean is not recomputed in the same iteration).
+    Returns (centroids [ncent, d] float64, objective after each assignment step)."""
     x = _f64(x)
     n, _ = x.shape
-    rng = np.random.default_rng(seed)
-    cent = x[rng.choice(n, size=ncent, replace=False)].copy()
+    if start is not None:
+        cent = _f64(start).copy()
+        assert cent.shape == (ncent, x.shape[1])
+    else:
+        rng = np.random.default_rng(seed)
+        cent = x[rng.choice(n, size=ncent, replace=False)].copy()
     objective = []
     for _ in range(iters):
         assign, dmin = nearest(x, cent)

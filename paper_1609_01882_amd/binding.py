@@ -41,6 +41,7 @@ def _load():
         "psc_create": (i32, [C.POINTER(vp), i32, i32]),
         "psc_destroy": (None, [vp]),
         "psc_train_pq": (i32, [vp, vp, i64, i32, u64]),
+        "psc_train_pq_device": (i32, [vp, vp, i64, i32, u64, i32, vp, vp]),
         "psc_optimize_index_assignment": (i32, [vp, i64, dbl, dbl, dbl, u64, vp, vp]),
         "psc_set_codebook": (i32, [vp, vp]),
         "psc_get_codebook": (i32, [vp, vp]),
@@ -56,6 +57,7 @@ def _load():
         "psc_knn_graph_workspace_bytes": (sz, [vp, i64, i32]),
         "psc_knn_graph": (i32, [vp, vp, vp, i64, i32, i32, vp, vp, vp, sz, vp]),
         "psc_ivf_train_coarse": (i32, [vp, vp, i64, i32, i32, u64]),
+        "psc_ivf_train_coarse_device": (i32, [vp, vp, i64, i32, i32, u64, vp]),
         "psc_ivf_set_coarse": (i32, [vp, vp, i32]),
         "psc_ivf_get_coarse": (i32, [vp, vp]),
         "psc_ivf_assign_encode": (i32, [vp, vp, i64, vp, vp, vp]),
@@ -76,6 +78,7 @@ def exported_symbols():
     """Names this binding expects the library to export."""
     _load()
     return ["psc_version", "psc_last_error", "psc_create", "psc_destroy", "psc_train_pq",
+            "psc_train_pq_device", "psc_ivf_train_coarse_device",
             "psc_optimize_index_assignment", "psc_set_codebook", "psc_get_codebook", "psc_encode",
             "psc_build_lut", "psc_hamming_filter", "psc_hamming_histogram", "psc_threshold_for_rate",
             "psc_scan_workspace_bytes", "psc_scan",
@@ -130,6 +133,14 @@ class Index:
         x = np.ascontiguousarray(x, dtype=np.float32)
         assert x.ndim == 2 and x.shape[1] == self.dim
         _check(_load().psc_train_pq(self._h, x.ctypes.data_as(C.c_void_p), x.shape[0], iters, seed))
+
+    def train_pq_device(self, x: torch.Tensor, iters: int = 20, seed: int = 0, from_current: bool = False):
+        """Lloyd iterations on the GPU; returns the objective [iters, m] (float64)."""
+        assert x.ndim == 2 and x.shape[1] == self.dim
+        obj = np.empty((iters, self.m), dtype=np.float64)
+        _check(_load().psc_train_pq_device(self._h, _dev(x, torch.float32, "x"), x.shape[0], iters, seed,
+                                           1 if from_current else 0, obj.ctypes.data_as(C.c_void_p), _stream()))
+        return obj
 
     def optimize_index_assignment(self, n_iter: int = 500_000, t0: float = 0.7,
                                   t_decay: float = 0.9 ** (1.0 / 500.0), alpha: float = 0.5,
@@ -205,6 +216,12 @@ class Index:
         x = np.ascontiguousarray(x, dtype=np.float32)
         assert x.ndim == 2 and x.shape[1] == self.dim
         _check(_load().psc_ivf_train_coarse(self._h, x.ctypes.data_as(C.c_void_p), x.shape[0], nlist, iters, seed))
+        self.nlist = nlist
+
+    def ivf_train_coarse_device(self, x: torch.Tensor, nlist: int, iters: int = 10, seed: int = 0):
+        assert x.ndim == 2 and x.shape[1] == self.dim
+        _check(_load().psc_ivf_train_coarse_device(self._h, _dev(x, torch.float32, "x"), x.shape[0], nlist, iters,
+                                                   seed, _stream()))
         self.nlist = nlist
 
     def ivf_set_coarse(self, cent: np.ndarray):

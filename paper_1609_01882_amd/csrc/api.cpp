@@ -56,6 +56,29 @@ static int sync_codebook_to_device(const psc_index *idx)
     return PSC_OK;
 }
 
+// Device scratch of one training call, released when the call returns.
+struct DeviceScratch {
+    std::vector<void *> owned;
+    ~DeviceScratch()
+    {
+        for (void *p : owned) (void)hipFree(p);
+    }
+    template <class T>
+    int get(T **out, size_t count)
+    {
+        void *p = nullptr;
+        PSC_HIP_TRY(hipMalloc(&p, (count ? count : 1) * sizeof(T)));
+        owned.push_back(p);
+        *out = (T *)p;
+        return PSC_OK;
+    }
+};
+#define PSC_TRY(expr)                \
+    do {                             \
+        int rc_ = (expr);            \
+        if (rc_ != PSC_OK) return rc_; \
+    } while (0)
+
 }  // namespace psc
 
 using namespace psc;
@@ -528,22 +551,21 @@ int psc_ivf_train_coarse(psc_index *idx, const float *x_host, int64_t n, int nli
             for (int t = 0; t < dim; ++t) sp[t] += xi[t];
             ++count[assign[i]];
         }
+        // empty cells: each restarts on the first member of the (currently) most populated cell;
+        // the donor's own mean is left as computed
+        std::vector<int64_t> pop(count);
         for (int c = 0; c < nlist; ++c) {
-            if (count[c] == 0) {
-                // empty cell: restart it on a member of the most populated cell
-                const int big = (int)(std::max_element(count.begin(), count.end()) - count.begin());
-                for (int64_t i = 0; i < n; ++i)
-                    if (assign[i] == big) {
-                        for (int t = 0; t < dim; ++t) {
-                            sum[(size_t)big * dim + t] -= x_host[(size_t)i * dim + t];
-                            sum[(size_t)c * dim + t] = x_host[(size_t)i * dim + t];
-                        }
-                        --count[big];
-                        count[c] = 1;
-                        assign[i] = c;
-                        break;
-                    }
-            }
+            if (pop[(size_t)c] != 0) continue;
+            const int big = (int)(std::max_element(pop.begin(), pop.end()) - pop.begin());
+            for (int64_t i = 0; i < n; ++i)
+                if (assign[i] == big) {
+                    for (int t = 0; t < dim; ++t) sum[(size_t)c * dim + t] = x_host[(size_t)i * dim + t];
+                    count[(size_t)c] = 1;
+                    --pop[(size_t)big];
+                    pop[(size_t)c] = 1;
+                    assign[i] = c;
+                    break;
+                }
         }
         for (int c = 0; c < nlist; ++c)
             if (count[c] > 0)
@@ -553,6 +575,136 @@ int psc_ivf_train_coarse(psc_index *idx, const float *x_host, int64_t n, int nli
 #undef IVF_TRY
     cleanup();
     return psc_ivf_set_coarse(idx, cent.data(), nlist);
+}
+
+int psc_train_pq_device(psc_index *idx, const float *x_dev, int64_t n, int iters, uint64_t seed, int start,
+                        double *objective_out_host, psc_stream stream)
+{
+    PSC_REQUIRE(idx && x_dev, "null pointer");
+    PSC_REQUIRE(n >= kCentroids && n < (1LL << 31), "need 256 <= n < 2^31 training vectors, got %lld", (long long)n);
+    PSC_REQUIRE(iters >= 1, "iters must be >= 1");
+    PSC_REQUIRE(start == PSC_START_SEEDED || start == PSC_START_CURRENT, "start must be 0 (seeded) or 1 (current codebook)");
+    if (start == PSC_START_CURRENT && !idx->has_codebook) {
+        set_error("no codebook to continue from");
+        return PSC_ESTATE;
+    }
+    const int dim = idx->dim, m = idx->m, dsub = idx->dsub;
+    const size_t ncell = (size_t)m * kCentroids;
+    hipStream_t s = (hipStream_t)stream;
+    DeviceScratch scratch;
+    float *cb = nullptr, *dmin = nullptr;
+    double *sum = nullptr, *obj = nullptr;
+    uint32_t *count = nullptr;
+    uint8_t *cell = nullptr;
+    unsigned long long *key = nullptr;
+    int64_t *rows = nullptr;
+    PSC_TRY(scratch.get(&cb, ncell * dsub));
+    PSC_TRY(scratch.get(&sum, ncell * dsub));
+    PSC_TRY(scratch.get(&count, ncell));
+    PSC_TRY(scratch.get(&obj, (size_t)m));
+    PSC_TRY(scratch.get(&cell, (size_t)n * m));
+    PSC_TRY(scratch.get(&dmin, (size_t)n * m));
+    PSC_TRY(scratch.get(&key, 1));
+    PSC_TRY(scratch.get(&rows, ncell));
+    std::vector<uint32_t> hcount;
+    try {
+        hcount.resize(ncell);
+        if (start == PSC_START_SEEDED) {
+            std::vector<int64_t> hrows(ncell);
+            for (int j = 0; j < m; ++j) kmeans_start_rows(n, kCentroids, seed + (uint64_t)j, &hrows[(size_t)j * kCentroids]);
+            PSC_HIP_TRY(hipMemcpyAsync(rows, hrows.data(), ncell * sizeof(int64_t), hipMemcpyHostToDevice, s));
+            PSC_HIP_TRY(hipStreamSynchronize(s));  // hrows leaves scope
+            PSC_TRY(launch_pq_gather_start(x_dev, dim, m, rows, cb, s));
+        } else {
+            PSC_HIP_TRY(hipMemcpyAsync(cb, idx->cb_host.data(), ncell * dsub * sizeof(float), hipMemcpyHostToDevice, s));
+        }
+    } catch (const std::bad_alloc &) {
+        set_error("out of host memory");
+        return PSC_ENOMEM;
+    }
+    for (int it = 0; it < iters; ++it) {
+        PSC_TRY(launch_pq_lloyd_step(cb, dim, m, x_dev, n, cell, dmin, sum, count, obj, s));
+        PSC_HIP_TRY(hipMemcpyAsync(hcount.data(), count, ncell * sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+        if (objective_out_host)
+            PSC_HIP_TRY(hipMemcpyAsync(objective_out_host + (size_t)it * m, obj, (size_t)m * sizeof(double),
+                                       hipMemcpyDeviceToHost, s));
+        PSC_HIP_TRY(hipStreamSynchronize(s));
+        for (int j = 0; j < m; ++j) {
+            uint32_t *cj = &hcount[(size_t)j * kCentroids];
+            for (int c = 0; c < kCentroids; ++c) {
+                if (cj[c] != 0u) continue;
+                // empty cell: it takes the member of the (currently) most populated cell that lies
+                // farthest from that cell's centroid; the donor's own mean is left as computed
+                const int big = (int)(std::max_element(cj, cj + kCentroids) - cj);
+                if (cj[big] == 0u) continue;
+                PSC_TRY(launch_pq_refill(x_dev, n, dim, m, j, big, c, cell, dmin, sum, count, key, s));
+                --cj[big];
+                cj[c] = 1u;
+            }
+        }
+        PSC_TRY(launch_centroid_update(sum, count, (int64_t)ncell, dsub, cb, s));
+    }
+    PSC_HIP_TRY(hipMemcpyAsync(idx->cb_host.data(), cb, ncell * dsub * sizeof(float), hipMemcpyDeviceToHost, s));
+    PSC_HIP_TRY(hipStreamSynchronize(s));
+    return mark_codebook_changed(idx);
+}
+
+int psc_ivf_train_coarse_device(psc_index *idx, const float *x_dev, int64_t n, int nlist, int iters, uint64_t seed,
+                                psc_stream stream)
+{
+    PSC_REQUIRE(idx && x_dev, "null pointer");
+    PSC_REQUIRE(nlist >= 1 && nlist <= 16384 && n >= nlist && n < (1LL << 31) && iters >= 1,
+                "bad coarse training arguments");
+    PSC_REQUIRE(idx->dim % 4 == 0 && idx->dim <= 1024, "inverted file needs dim %% 4 == 0 and dim <= 1024");
+    const int dim = idx->dim;
+    hipStream_t s = (hipStream_t)stream;
+    DeviceScratch scratch;
+    float *cent = nullptr;
+    int32_t *assign = nullptr;
+    double *sum = nullptr;
+    uint32_t *count = nullptr;
+    unsigned long long *key = nullptr;
+    int64_t *rows = nullptr;
+    PSC_TRY(scratch.get(&cent, (size_t)(nlist + 1) * dim));  // + the mean centroid
+    PSC_TRY(scratch.get(&assign, (size_t)n));
+    PSC_TRY(scratch.get(&sum, (size_t)nlist * dim));
+    PSC_TRY(scratch.get(&count, (size_t)nlist));
+    PSC_TRY(scratch.get(&key, 1));
+    PSC_TRY(scratch.get(&rows, (size_t)nlist));
+    std::vector<uint32_t> hcount;
+    std::vector<float> hcent;
+    try {
+        hcount.resize((size_t)nlist);
+        hcent.resize((size_t)nlist * dim);
+        std::vector<int64_t> hrows((size_t)nlist);
+        kmeans_start_rows(n, nlist, seed, hrows.data());
+        PSC_HIP_TRY(hipMemcpyAsync(rows, hrows.data(), (size_t)nlist * sizeof(int64_t), hipMemcpyHostToDevice, s));
+        PSC_HIP_TRY(hipStreamSynchronize(s));
+    } catch (const std::bad_alloc &) {
+        set_error("out of host memory");
+        return PSC_ENOMEM;
+    }
+    PSC_TRY(launch_gather_rows(x_dev, dim, rows, nlist, cent, s));
+    for (int it = 0; it < iters; ++it) {
+        PSC_TRY(launch_mean_centroid(cent, nlist, dim, s));
+        PSC_TRY(launch_nearest_centroid(x_dev, n, dim, cent, nlist, cent + (size_t)nlist * dim, assign, s));
+        PSC_TRY(launch_coarse_accumulate(x_dev, n, dim, assign, nlist, sum, count, s));
+        PSC_HIP_TRY(hipMemcpyAsync(hcount.data(), count, (size_t)nlist * sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+        PSC_HIP_TRY(hipStreamSynchronize(s));
+        for (int c = 0; c < nlist; ++c) {
+            if (hcount[(size_t)c] != 0u) continue;
+            // empty cell: restart it on the first member of the (currently) most populated cell
+            const int big = (int)(std::max_element(hcount.begin(), hcount.end()) - hcount.begin());
+            if (hcount[(size_t)big] == 0u) continue;
+            PSC_TRY(launch_coarse_refill(x_dev, n, dim, big, c, assign, sum, count, key, s));
+            --hcount[(size_t)big];
+            hcount[(size_t)c] = 1u;
+        }
+        PSC_TRY(launch_centroid_update(sum, count, nlist, dim, cent, s));
+    }
+    PSC_HIP_TRY(hipMemcpyAsync(hcent.data(), cent, hcent.size() * sizeof(float), hipMemcpyDeviceToHost, s));
+    PSC_HIP_TRY(hipStreamSynchronize(s));
+    return psc_ivf_set_coarse(idx, hcent.data(), nlist);
 }
 
 int psc_ivf_assign_encode(const psc_index *idx, const float *x_dev, int64_t n, int32_t *list_no_dev,

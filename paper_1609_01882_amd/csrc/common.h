@@ -37,6 +37,8 @@ constexpr int kCentroids = 256;  // centroids per sub-quantizer: one byte per in
 // ---- host-side training (host_train.cpp)
 // Lloyd k-means on x [n][d] -> cent [ncent][d].
 int host_kmeans(const float *x, int64_t n, int d, int ncent, int iters, uint64_t seed, float *cent);
+// The rows k-means starts from: ncent distinct row numbers out of n (n >= ncent), from the seed.
+void kmeans_start_rows(int64_t n, int ncent, uint64_t seed, int64_t *rows);
 // Simulated annealing of the index assignment of one sub-quantizer; cent [256][dsub].
 void host_anneal(const float *cent, int dsub, int64_t n_iter, double t0, double t_decay,
                  double alpha, uint64_t seed, uint8_t *pi, double *loss_before, double *loss_after);
@@ -135,6 +137,34 @@ int launch_list_tables(const float *cb_dev, int dim, int m, const float *coarse_
 
 int launch_unsort_rows(const uint8_t *src_dev, const int32_t *job_slot_dev, int64_t njobs, int row_bytes,
                        uint8_t *dst_dev, hipStream_t s);
+
+// ---- k-means on the device (kernels_train.hip)
+// One Lloyd step of all m sub-quantizers: per row and sub-quantizer the nearest centroid
+// (cell [n][m]) and its squared distance (dmin [n][m]); per cell the sum of its members
+// (sum [m][256][dsub], double) and their number; per sub-quantizer the sum of the distances.
+int launch_pq_lloyd_step(const float *cb_dev, int dim, int m, const float *x_dev, int64_t n, uint8_t *cell_dev,
+                         float *dmin_dev, double *sum_dev, uint32_t *count_dev, double *obj_dev, hipStream_t s);
+// Starting centroids: sub-vector j of row rows[j][c] for every (j, c).
+int launch_pq_gather_start(const float *x_dev, int dim, int m, const int64_t *rows_dev, float *cb_dev, hipStream_t s);
+// The farthest member of cell `big` of sub-quantizer j becomes the only member of the empty cell c
+// (sums, counts, cell and dmin follow).  Synchronizes the stream.
+int launch_pq_refill(const float *x_dev, int64_t n, int dim, int m, int j, int big, int c, uint8_t *cell_dev,
+                     float *dmin_dev, double *sum_dev, uint32_t *count_dev, unsigned long long *key_dev,
+                     hipStream_t s);
+// cent[c] = sum[c] / count[c] where count[c] > 0 (cells of d floats).
+int launch_centroid_update(const double *sum_dev, const uint32_t *count_dev, int64_t ncell, int d, float *cent_dev,
+                           hipStream_t s);
+int launch_gather_rows(const float *x_dev, int dim, const int64_t *rows_dev, int64_t nrows, float *out_dev,
+                       hipStream_t s);
+// Sums and counts of the coarse cells from an assignment [n].
+int launch_coarse_accumulate(const float *x_dev, int64_t n, int dim, const int32_t *assign_dev, int ncent,
+                             double *sum_dev, uint32_t *count_dev, hipStream_t s);
+// The lowest-numbered member of cell `big` becomes the only member of the empty cell c.
+// Synchronizes the stream.
+int launch_coarse_refill(const float *x_dev, int64_t n, int dim, int big, int c, int32_t *assign_dev,
+                         double *sum_dev, uint32_t *count_dev, unsigned long long *key_dev, hipStream_t s);
+// Row ncent of cent_dev [ncent + 1][dim] := the mean of rows 0 .. ncent-1.
+int launch_mean_centroid(float *cent_dev, int ncent, int dim, hipStream_t s);
 
 }  // namespace psc
 

@@ -46,21 +46,30 @@ void parallel_rows(int64_t n, F &&body)
 
 }  // namespace
 
+// The start of k-means: ncent distinct rows out of n (partial Fisher-Yates on the row numbers,
+// draw c of the counter-based generator picks the c-th row).
+void kmeans_start_rows(int64_t n, int ncent, uint64_t seed, int64_t *rows)
+{
+    std::vector<int64_t> perm((size_t)n);
+    std::iota(perm.begin(), perm.end(), (int64_t)0);
+    for (int c = 0; c < ncent; ++c) {
+        int64_t r = c + (int64_t)(counter_draw(seed, (uint64_t)c) % (uint64_t)(n - c));
+        std::swap(perm[(size_t)c], perm[(size_t)r]);
+        rows[c] = perm[(size_t)c];
+    }
+}
+
 int host_kmeans(const float *x, int64_t n, int d, int ncent, int iters, uint64_t seed, float *cent)
 {
     if (n < ncent) {
         set_error("k-means needs at least %d training vectors, got %lld", ncent, (long long)n);
         return PSC_EINVAL;
     }
-    // start: ncent distinct rows (partial Fisher-Yates on the row numbers)
     {
-        std::vector<int64_t> perm(n);
-        std::iota(perm.begin(), perm.end(), (int64_t)0);
-        for (int c = 0; c < ncent; ++c) {
-            int64_t r = c + (int64_t)(counter_draw(seed, (uint64_t)c) % (uint64_t)(n - c));
-            std::swap(perm[c], perm[r]);
-            std::memcpy(cent + (size_t)c * d, x + (size_t)perm[c] * d, sizeof(float) * d);
-        }
+        std::vector<int64_t> rows((size_t)ncent);
+        kmeans_start_rows(n, ncent, seed, rows.data());
+        for (int c = 0; c < ncent; ++c)
+            std::memcpy(cent + (size_t)c * d, x + (size_t)rows[(size_t)c] * d, sizeof(float) * d);
     }
     std::vector<int32_t> assign(n);
     std::vector<float> dmin(n);
@@ -96,29 +105,27 @@ int host_kmeans(const float *x, int64_t n, int d, int ncent, int iters, uint64_t
             for (int t = 0; t < d; ++t) s[t] += xi[t];
             ++count[assign[i]];
         }
+        // empty cells: each takes the member of the (currently) most populated cell that lies
+        // farthest from that cell's centroid; the donor's own mean is left as computed
+        std::vector<int64_t> pop(count);
         for (int c = 0; c < ncent; ++c) {
-            if (count[c] == 0) {
-                // empty cell: take the member of the most populated cell that lies farthest
-                // from that cell's centroid
-                int big = (int)(std::max_element(count.begin(), count.end()) - count.begin());
-                int64_t far = -1;
-                float fd = -1.f;
-                for (int64_t i = 0; i < n; ++i)
-                    if (assign[i] == big && dmin[i] > fd) {
-                        fd = dmin[i];
-                        far = i;
-                    }
-                if (far < 0) continue;
-                const float *xf = x + (size_t)far * d;
-                for (int t = 0; t < d; ++t) {
-                    sum[(size_t)big * d + t] -= xf[t];
-                    sum[(size_t)c * d + t] = xf[t];
+            if (pop[c] != 0) continue;
+            int big = (int)(std::max_element(pop.begin(), pop.end()) - pop.begin());
+            int64_t far = -1;
+            float fd = -1.f;
+            for (int64_t i = 0; i < n; ++i)
+                if (assign[i] == big && dmin[i] > fd) {
+                    fd = dmin[i];
+                    far = i;
                 }
-                --count[big];
-                count[c] = 1;
-                assign[far] = c;
-                dmin[far] = 0.f;
-            }
+            if (far < 0) continue;
+            const float *xf = x + (size_t)far * d;
+            for (int t = 0; t < d; ++t) sum[(size_t)c * d + t] = xf[t];
+            count[c] = 1;
+            --pop[big];
+            pop[c] = 1;
+            assign[far] = c;
+            dmin[far] = 0.f;
         }
         for (int c = 0; c < ncent; ++c)
             if (count[c] > 0)
