@@ -507,42 +507,25 @@ int psc_ivf_train_coarse(psc_index *idx, const float *x_host, int64_t n, int nli
     }
     int rc = host_kmeans(x_host, n, dim, nlist, 0, seed, cent.data());  // 0 iterations: the seeded start only
     if (rc != PSC_OK) return rc;
+    DeviceScratch scratch;
     float *x_dev = nullptr, *c_dev = nullptr;
     int32_t *a_dev = nullptr;
-    auto cleanup = [&] {
-        if (x_dev) (void)hipFree(x_dev);
-        if (c_dev) (void)hipFree(c_dev);
-        if (a_dev) (void)hipFree(a_dev);
-    };
-#define IVF_TRY(expr)                                                                              \
-    do {                                                                                           \
-        hipError_t e_ = (expr);                                                                    \
-        if (e_ != hipSuccess) {                                                                    \
-            set_error("%s failed: %s", #expr, hipGetErrorString(e_));                              \
-            cleanup();                                                                             \
-            return PSC_EHIP;                                                                       \
-        }                                                                                          \
-    } while (0)
-    IVF_TRY(hipMalloc((void **)&x_dev, (size_t)n * dim * sizeof(float)));
-    IVF_TRY(hipMalloc((void **)&c_dev, (size_t)(nlist + 1) * dim * sizeof(float)));  // + the mean centroid
-    IVF_TRY(hipMalloc((void **)&a_dev, (size_t)n * sizeof(int32_t)));
-    IVF_TRY(hipMemcpy(x_dev, x_host, (size_t)n * dim * sizeof(float), hipMemcpyHostToDevice));
+    PSC_TRY(scratch.get(&x_dev, (size_t)n * dim));
+    PSC_TRY(scratch.get(&c_dev, (size_t)(nlist + 1) * dim));  // + the mean centroid
+    PSC_TRY(scratch.get(&a_dev, (size_t)n));
+    PSC_HIP_TRY(hipMemcpy(x_dev, x_host, (size_t)n * dim * sizeof(float), hipMemcpyHostToDevice));
     for (int it = 0; it < iters; ++it) {
-        IVF_TRY(hipMemcpy(c_dev, cent.data(), cent.size() * sizeof(float), hipMemcpyHostToDevice));
+        PSC_HIP_TRY(hipMemcpy(c_dev, cent.data(), cent.size() * sizeof(float), hipMemcpyHostToDevice));
         {   // the reference point of the matrix-core distance kernel
             std::vector<double> acc((size_t)dim, 0.0);
             for (int c = 0; c < nlist; ++c)
                 for (int t = 0; t < dim; ++t) acc[(size_t)t] += cent[(size_t)c * dim + t];
             std::vector<float> mean((size_t)dim);
             for (int t = 0; t < dim; ++t) mean[(size_t)t] = (float)(acc[(size_t)t] / nlist);
-            IVF_TRY(hipMemcpy(c_dev + (size_t)nlist * dim, mean.data(), (size_t)dim * sizeof(float), hipMemcpyHostToDevice));
+            PSC_HIP_TRY(hipMemcpy(c_dev + (size_t)nlist * dim, mean.data(), (size_t)dim * sizeof(float), hipMemcpyHostToDevice));
         }
-        rc = launch_nearest_centroid(x_dev, n, dim, c_dev, nlist, c_dev + (size_t)nlist * dim, a_dev, nullptr);
-        if (rc != PSC_OK) {
-            cleanup();
-            return rc;
-        }
-        IVF_TRY(hipMemcpy(assign.data(), a_dev, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost));
+        PSC_TRY(launch_nearest_centroid(x_dev, n, dim, c_dev, nlist, c_dev + (size_t)nlist * dim, a_dev, nullptr));
+        PSC_HIP_TRY(hipMemcpy(assign.data(), a_dev, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost));
         std::fill(sum.begin(), sum.end(), 0.0);
         std::fill(count.begin(), count.end(), (int64_t)0);
         for (int64_t i = 0; i < n; ++i) {
@@ -572,8 +555,6 @@ int psc_ivf_train_coarse(psc_index *idx, const float *x_host, int64_t n, int nli
                 for (int t = 0; t < dim; ++t)
                     cent[(size_t)c * dim + t] = (float)(sum[(size_t)c * dim + t] / (double)count[c]);
     }
-#undef IVF_TRY
-    cleanup();
     return psc_ivf_set_coarse(idx, cent.data(), nlist);
 }
 
