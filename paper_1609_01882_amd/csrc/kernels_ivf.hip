@@ -2,8 +2,10 @@
 // selection of the lists to probe, and the device-side bookkeeping that turns the
 // (query, probed list) jobs into list-major tiles for the fused scan.
 //
-// A query probes the nprobe coarse centroids nearest to it (exact squared L2 in float32,
-// coordinates ascending, lower list number on equal distance).  Jobs are then grouped by list so
+// A query probes the nprobe coarse centroids nearest to it (squared L2 in float32, lower list
+// number on equal distance; the three distance kernels -- plain, a handful of rows, matrix cores
+// -- add the coordinates up in different orders, so they can rank two centroids that are equally
+// near within float32 rounding differently).  Jobs are then grouped by list so
 // that the codes of a list are streamed once per tile of up to TQ queries that probe it.
 #include "common.h"
 
@@ -11,6 +13,9 @@ namespace psc {
 namespace {
 
 constexpr int kRows = 16;  // rows per workgroup in the distance kernels
+// Up to this many rows (queries) the coarse stage runs the kernels built for latency: many
+// workgroups per row instead of many rows per workgroup.
+constexpr int64_t kFewRowsMax = 8;
 
 // dist[r][c] = || x_r - cent_c ||^2 for a tile of kRows rows and 256 centroids per workgroup.
 // Rows sit in LDS (read as broadcasts), each thread walks its own centroid row.
@@ -49,6 +54,56 @@ coarse_dist_kernel(const float *__restrict__ x, int64_t n, int dim, const float 
 #pragma unroll
     for (int r = 0; r < kRows; ++r)
         if (r0 + r < n) dist[(r0 + r) * nlist + c] = acc[r];
+}
+
+// The same distances for a handful of rows (a single query is the case that matters): one
+// workgroup = 32 centroids x up to kFewRows rows, 8 lanes to a centroid, each lane taking every
+// eighth group of 4 coordinates, so that the centroid rows are read in 128-byte pieces by many
+// workgroups at once instead of one row per thread.  The 8 partial sums are added pairwise, so a
+// distance can differ from coarse_dist_kernel's in its last bits.
+constexpr int kFewRows = 4;
+
+__global__ void __launch_bounds__(256)
+coarse_dist_few_kernel(const float *__restrict__ x, int64_t n, int dim, const float *__restrict__ cent,
+                       int nlist, float *__restrict__ dist)
+{
+    extern __shared__ __align__(16) float rows[];  // [kFewRows][dim]
+    const int64_t r0 = (int64_t)blockIdx.y * kFewRows;
+    for (int e = threadIdx.x; e < kFewRows * dim; e += 256) {
+        const int64_t r = r0 + e / dim;
+        rows[e] = r < n ? x[r * dim + e % dim] : 0.f;
+    }
+    __syncthreads();
+    const int sub = threadIdx.x & 7;
+    const int c = blockIdx.x * 32 + (threadIdx.x >> 3);
+    float acc[kFewRows];
+#pragma unroll
+    for (int r = 0; r < kFewRows; ++r) acc[r] = 0.f;
+    if (c < nlist) {
+        const float *crow = cent + (int64_t)c * dim;
+        for (int d = sub * 4; d < dim; d += 32) {
+            const float4 cv = *(const float4 *)(crow + d);
+#pragma unroll
+            for (int r = 0; r < kFewRows; ++r) {
+                const float4 xv = *(const float4 *)(rows + r * dim + d);
+                float t = xv.x - cv.x;
+                acc[r] = fmaf(t, t, acc[r]);
+                t = xv.y - cv.y;
+                acc[r] = fmaf(t, t, acc[r]);
+                t = xv.z - cv.z;
+                acc[r] = fmaf(t, t, acc[r]);
+                t = xv.w - cv.w;
+                acc[r] = fmaf(t, t, acc[r]);
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < kFewRows; ++r) {
+        acc[r] += __shfl_xor(acc[r], 1, 64);
+        acc[r] += __shfl_xor(acc[r], 2, 64);
+        acc[r] += __shfl_xor(acc[r], 4, 64);
+        if (sub == 0 && c < nlist && r0 + r < n) dist[(r0 + r) * nlist + c] = acc[r];
+    }
 }
 
 __device__ __forceinline__ uint64_t order_key(float d, uint32_t idx)
@@ -132,6 +187,80 @@ select_probes_wave_kernel(const float *__restrict__ dist, int64_t n, int nlist, 
         const uint64_t key = mine[e];
         int rank = 0;
         for (int j = 0; j < nprobe; ++j) rank += mine[j] < key ? 1 : 0;
+        probed[r * nprobe + rank] = (int32_t)(uint32_t)key;
+    }
+}
+
+// The same selection by a whole workgroup of 16 waves per row, for a handful of rows (a single
+// query is the case that matters): thread t holds lists t, t + 1024, ...  The nprobe-th smallest
+// (distance, list) pair is found bit by bit as above -- first over the 32 bits of the distance
+// key, then, only if several lists share that distance, over the 14 bits of the list number --
+// with one workgroup-wide count per bit (per-wave sums through LDS, two buffers in turn so that
+// one barrier per bit is enough).  The pairs up to it are exactly the nprobe lists; each goes to
+// its rank.
+template <int KPL>
+__global__ void __launch_bounds__(1024)
+select_probes_block_kernel(const float *__restrict__ dist, int nlist, int nprobe, int32_t *__restrict__ probed)
+{
+    __shared__ uint32_t part[2][16];
+    __shared__ uint64_t sel[1024];
+    __shared__ uint32_t nsel;
+    const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t r = blockIdx.x;
+    uint32_t dk[KPL];
+#pragma unroll
+    for (int i = 0; i < KPL; ++i) {
+        const int c = i * 1024 + tid;
+        dk[i] = c < nlist ? min((uint32_t)(order_key(dist[r * nlist + c], 0u) >> 32), 0xfffffffeu) : 0xffffffffu;
+    }
+    if (tid == 0) nsel = 0u;
+    int turn = 0;
+    // number of keys for which `below(i)` holds, over the whole workgroup
+    auto count = [&](auto below) {
+        uint32_t cnt = 0;
+#pragma unroll
+        for (int i = 0; i < KPL; ++i) cnt += below(i) ? 1u : 0u;
+        cnt = wave_sum_u32(cnt);
+        if (lane == 0) part[turn][wave] = cnt;
+        __syncthreads();
+        uint32_t total = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) total += part[turn][w];
+        turn ^= 1;
+        return total;
+    };
+    uint32_t pivot = 0;
+    for (int b = 31; b >= 0; --b) {
+        const uint32_t mid = pivot | (1u << b);
+        if (count([&](int i) { return dk[i] < mid; }) < (uint32_t)nprobe) pivot = mid;
+    }
+    // lists at the pivot distance: all of them belong unless they are too many; then the
+    // lowest-numbered ones do, up to list number `last`
+    const uint32_t below = count([&](int i) { return dk[i] < pivot; });
+    const uint32_t upto = count([&](int i) { return dk[i] <= pivot; });
+    uint32_t last = 0xffffffffu;
+    if (upto > (uint32_t)nprobe) {
+        const uint32_t want = (uint32_t)nprobe - below;  // >= 1
+        uint32_t lp = 0;
+        for (int b = 13; b >= 0; --b) {
+            const uint32_t mid = lp | (1u << b);
+            if (count([&](int i) { return dk[i] == pivot && (uint32_t)(i * 1024 + tid) < mid; }) < want) lp = mid;
+        }
+        last = lp;
+    }
+#pragma unroll
+    for (int i = 0; i < KPL; ++i) {
+        const uint32_t c = (uint32_t)(i * 1024 + tid);
+        if (dk[i] < pivot || (dk[i] == pivot && c <= last)) {
+            const uint32_t slot = atomicAdd(&nsel, 1u);
+            if (slot < 1024u) sel[slot] = ((uint64_t)dk[i] << 32) | c;  // (exactly nprobe <= 1024 pass)
+        }
+    }
+    __syncthreads();
+    if (tid < nprobe) {
+        const uint64_t key = sel[tid];
+        int rank = 0;
+        for (int j = 0; j < nprobe; ++j) rank += sel[j] < key ? 1 : 0;
         probed[r * nprobe + rank] = (int32_t)(uint32_t)key;
     }
 }
@@ -608,6 +737,13 @@ int launch_coarse_distances(const float *x_dev, int64_t n, int dim, const float 
         default: break;
         }
     }
+    if (n <= kFewRowsMax) {
+        dim3 grid((unsigned)((nlist + 31) / 32), (unsigned)((n + kFewRows - 1) / kFewRows));
+        hipLaunchKernelGGL(coarse_dist_few_kernel, grid, dim3(256), (size_t)kFewRows * dim * sizeof(float), s, x_dev, n,
+                           dim, cent_dev, nlist, dist_dev);
+        PSC_HIP_TRY(hipGetLastError());
+        return PSC_OK;
+    }
     PSC_REQUIRE((n + kRows - 1) / kRows <= 0x7fffffffLL, "too many rows");
     dim3 grid((unsigned)((n + kRows - 1) / kRows), (unsigned)((nlist + 255) / 256));
     hipLaunchKernelGGL(coarse_dist_kernel, grid, dim3(256), (size_t)kRows * dim * sizeof(float), s, x_dev, n, dim,
@@ -627,6 +763,16 @@ int launch_select_probes(const float *dist_dev, int64_t n, int nlist, int nprobe
         PSC_HIP_TRY(hipFuncSetAttribute((const void *)select_probes_kernel,
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 16384 * 8));
         configured = true;
+    }
+    if (n <= kFewRowsMax) {  // a workgroup per row: the latency of a single query
+        if (nlist <= 4096)
+            hipLaunchKernelGGL(select_probes_block_kernel<4>, dim3((unsigned)n), dim3(1024), 0, s, dist_dev, nlist,
+                               nprobe, probed_dev);
+        else
+            hipLaunchKernelGGL(select_probes_block_kernel<16>, dim3((unsigned)n), dim3(1024), 0, s, dist_dev, nlist,
+                               nprobe, probed_dev);
+        PSC_HIP_TRY(hipGetLastError());
+        return PSC_OK;
     }
     const dim3 wgrid((unsigned)((n + 3) / 4));
     const size_t wlds = (size_t)4 * nprobe * sizeof(uint64_t);

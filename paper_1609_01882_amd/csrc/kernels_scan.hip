@@ -696,32 +696,56 @@ scan_kernel(ScanArgs a)
     if constexpr (IVF) {
         // ---- residual tables put together in LDS (see ScanArgs::list_tab), query codes from them
         const int dsub = a.dim / M;
-        if (tid < TQ * M) {  // the per-job constant g~_j . (g~_j - 2 q~_j)
-            const int q = tid / M, j = tid - q * M;
-            float acc = 0.f;
-            if (q < nvq) {
-                const float *qv = a.queries + (int64_t)a.job_q[q0 + q] * a.dim + j * dsub;
-                const float *gv = a.coarse + (int64_t)tile_list * a.dim + j * dsub;
-                const float *ov = a.coarse + (int64_t)a.nlist * a.dim + j * dsub;
-                for (int t = 0; t < dsub; ++t) {
-                    const float g = gv[t] - ov[t], x = qv[t] - ov[t];
-                    acc = fmaf(g, g - 2.0f * x, acc);
-                }
-            }
-            s.sterm[tid] = acc;
+        // the list's centroid and the jobs' queries, both minus the mean centroid, staged where
+        // the tables will go (all loads of the workgroup in flight together; (TQ + 1) * dim floats
+        // fit: dim <= 1024 = a quarter of one job's tables at M = 8)
+        PSC_LDS float *gs = (PSC_LDS float *)s.lut, *xs = gs + a.dim;
+        for (int e = tid; e < (nvq + 1) * a.dim; e += NW * 64) {
+            const int q = e / a.dim - 1, t = e % a.dim;
+            const float *row = q < 0 ? a.coarse + (int64_t)tile_list * a.dim
+                                     : a.queries + (int64_t)a.job_q[q0 + q] * a.dim;
+            gs[e] = row[t] - a.coarse[(int64_t)a.nlist * a.dim + t];
         }
         __syncthreads();
-        {
-            const f32x4 *tab = (const f32x4 *)(a.list_tab + (int64_t)tile_list * (M * 256));
-            PSC_LDS f32x4 *dst = (PSC_LDS f32x4 *)s.lut;
-            for (int e = tid; e < TQ * (M * 64); e += NW * 64) {
-                const int q = e / (M * 64), r = e - q * (M * 64);  // r: 16-byte entry of the job's table
-                f32x4 v = {0.f, 0.f, 0.f, 0.f};
-                if (q < nvq) {
-                    const f32x4 x = ((const f32x4 *)(a.lut + (int64_t)s.gidx[q] * (M * 256)))[r];
-                    v = (x + tab[r]) + s.sterm[q * M + (r >> 6)];
+        float sterm = 0.f;
+        if (tid < TQ * M) {  // the per-job constant g~_j . (g~_j - 2 q~_j)
+            const int q = tid / M, j = tid - q * M;
+            if (q < nvq) {
+                for (int t = j * dsub; t < (j + 1) * dsub; ++t) {
+                    const float g = gs[t], x = xs[q * a.dim + t];
+                    sterm = fmaf(g, g - 2.0f * x, sterm);
                 }
-                dst[e] = v;
+            }
+        }
+        __syncthreads();  // (the staged vectors are read; their place is the tables' from here on)
+        if (tid < TQ * M) s.sterm[tid] = sterm;
+        {
+            // the jobs' share and the list's share of every table entry: loads first, sums after
+            constexpr int kTurns = (TQ * M * 64 + NW * 64 - 1) / (NW * 64);
+            const f32x4 *tab = (const f32x4 *)(a.list_tab + (int64_t)tile_list * (M * 256));
+            f32x4 xv[kTurns], tv[kTurns];
+#pragma unroll
+            for (int u = 0; u < kTurns; ++u) {
+                const int e = tid + u * NW * 64;
+                const int q = e / (M * 64), r = e - q * (M * 64);  // r: 16-byte entry of the job's table
+                xv[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+                tv[u] = xv[u];
+                if (e < TQ * (M * 64) && q < nvq) {
+                    xv[u] = ((const f32x4 *)(a.lut + (int64_t)s.gidx[q] * (M * 256)))[r];
+                    tv[u] = tab[r];
+                }
+            }
+            __syncthreads();  // s.sterm
+            PSC_LDS f32x4 *dst = (PSC_LDS f32x4 *)s.lut;
+#pragma unroll
+            for (int u = 0; u < kTurns; ++u) {
+                const int e = tid + u * NW * 64;
+                const int q = e / (M * 64), r = e - q * (M * 64);
+                if (e < TQ * (M * 64)) {
+                    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+                    if (q < nvq) v = (xv[u] + tv[u]) + s.sterm[q * M + (r >> 6)];
+                    dst[e] = v;
+                }
             }
         }
         __syncthreads();
@@ -1426,12 +1450,133 @@ merge_kernel(const float *__restrict__ part_d, const int64_t *__restrict__ part_
     }
 }
 
+// The same merge for a handful of queries, where the hundred dependent steps of the wave above are
+// all there is to wait for: a workgroup of 16 waves per query selects the k smallest
+// (distance, id) pairs of all partial lists at once.  Thread t holds the distance keys of
+// entries t, t + 1024, ... of the query's lists; the k-th smallest key is found bit by bit with
+// one workgroup-wide count per bit (per-wave sums through LDS, two buffers in turn so that one
+// barrier per bit is enough); if more entries than needed share it, the same search over the bits
+// of the id finds the last id that belongs.  The selected entries go to LDS in any order and each
+// is written to its rank.
+constexpr int64_t kMergeSelectQueries = 8;       // up to this many queries
+constexpr int64_t kMergeSelectEntries = 32768;   // and this many entries per query
+// (its forty-odd counting steps take about 20 us whatever k is; the wave above takes 0.4 us per
+//  result: measured 32 against 42 us at k = 100, 20 against 5 us at k = 10)
+constexpr int kMergeSelectMinK = 64;
+
+// Sum of v over the wave, in every lane (row-local steps on the data-parallel path, the four row
+// sums through scalar registers).
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v)
+{
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, false);   // lane ^ 1
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xf, 0xf, false);   // lane ^ 2
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xf, 0xf, false);  // mirror in 8
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xf, 0xf, false);  // mirror in 16
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 0) + (uint32_t)__builtin_amdgcn_readlane((int)v, 16) +
+           (uint32_t)__builtin_amdgcn_readlane((int)v, 32) + (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+}
+
+template <int KPL>
+__global__ void __launch_bounds__(1024)
+merge_select_kernel(const float *__restrict__ part_d, const int64_t *__restrict__ part_i, int nslice, int k,
+                    const int *__restrict__ status, int64_t *__restrict__ ids, float *__restrict__ dists)
+{
+    __shared__ uint32_t part[2][16];
+    __shared__ uint32_t selk[1024];
+    __shared__ int64_t seli[1024];
+    __shared__ uint32_t nsel;
+    const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t q = blockIdx.x;
+    const int total = nslice * k;
+    const float *pd = part_d + q * total;
+    const int64_t *pi = part_i + q * total;
+    const bool poisoned = *status != 0;
+    constexpr uint32_t kNone = 0xffffffffu;  // padding and places past the end; real keys stay below
+    uint32_t dk[KPL];
+#pragma unroll
+    for (int i = 0; i < KPL; ++i) {
+        const int e = i * 1024 + tid;
+        dk[i] = kNone;
+        if (e < total && pi[e] >= 0) dk[i] = min(dist_key(pd[e]), kNone - 1u);
+    }
+    if (tid == 0) nsel = 0u;
+    int turn = 0;
+    auto count = [&](auto pred) {  // number of the workgroup's entries for which pred(i) holds
+        uint32_t cnt = 0;
+#pragma unroll
+        for (int i = 0; i < KPL; ++i) cnt += pred(i) ? 1u : 0u;
+        cnt = wave_sum_u32(cnt);
+        if (lane == 0) part[turn][wave] = cnt;
+        __syncthreads();
+        uint32_t all = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) all += part[turn][w];
+        turn ^= 1;
+        return all;
+    };
+    const uint32_t have = count([&](int i) { return dk[i] != kNone; });
+    const uint32_t kk = have < (uint32_t)k ? have : (uint32_t)k;  // entries to return
+    if (kk > 0) {
+        uint32_t pivot = 0;  // the kk-th smallest key
+        for (int b = 31; b >= 0; --b) {
+            const uint32_t mid = pivot | (1u << b);
+            if (count([&](int i) { return dk[i] < mid; }) < kk) pivot = mid;
+        }
+        const uint32_t below = count([&](int i) { return dk[i] < pivot; });
+        const uint32_t upto = count([&](int i) { return dk[i] <= pivot; });
+        int64_t last = INT64_MAX;  // entries at the pivot distance belong up to this id
+        if (upto > kk) {
+            int64_t eid[KPL];
+#pragma unroll
+            for (int i = 0; i < KPL; ++i) eid[i] = dk[i] == pivot ? pi[i * 1024 + tid] : INT64_MAX;
+            const uint32_t want = kk - below;  // >= 1
+            int64_t lp = 0;
+            for (int b = 62; b >= 0; --b) {
+                const int64_t mid = lp | ((int64_t)1 << b);
+                if (count([&](int i) { return eid[i] < mid; }) < want) lp = mid;
+            }
+            last = lp;
+        }
+#pragma unroll
+        for (int i = 0; i < KPL; ++i) {
+            if (dk[i] > pivot) continue;
+            const int64_t id = pi[i * 1024 + tid];
+            if (dk[i] == pivot && id > last) continue;
+            const uint32_t slot = atomicAdd(&nsel, 1u);
+            if (slot < 1024u) {  // (exactly kk <= 1024 entries pass)
+                selk[slot] = dist_key(pd[i * 1024 + tid]);
+                seli[slot] = id;
+            }
+        }
+    }
+    __syncthreads();
+    if (tid < (int)kk) {
+        const uint32_t key = selk[tid];
+        const int64_t id = seli[tid];
+        int rank = 0;
+        for (int j = 0; j < (int)kk; ++j) rank += (selk[j] < key || (selk[j] == key && seli[j] < id)) ? 1 : 0;
+        ids[q * k + rank] = poisoned ? (int64_t)-2 : id;
+        dists[q * k + rank] = key_dist(key);
+    } else if (tid < k) {
+        ids[q * k + tid] = poisoned ? (int64_t)-2 : (int64_t)-1;
+        dists[q * k + tid] = __builtin_inff();
+    }
+}
+
 // One wave per query; the lists are spread over the lanes, OWN to a lane.
 int launch_merge(const float *part_d, const int64_t *part_i, int64_t nq, int nlists, int k, const int *status,
                  int64_t *ids, float *dists, hipStream_t s)
 {
     PSC_REQUIRE(nlists >= 1 && nlists <= 1024, "between 1 and 1024 partial lists per query, got %d", nlists);
     const dim3 grid((unsigned)nq), block(64);
+    if (nq <= kMergeSelectQueries && (int64_t)nlists * k <= kMergeSelectEntries && k >= kMergeSelectMinK && k <= 1024) {
+        if ((int64_t)nlists * k <= 8 * 1024)
+            hipLaunchKernelGGL(merge_select_kernel<8>, grid, dim3(1024), 0, s, part_d, part_i, nlists, k, status, ids, dists);
+        else
+            hipLaunchKernelGGL(merge_select_kernel<32>, grid, dim3(1024), 0, s, part_d, part_i, nlists, k, status, ids, dists);
+        PSC_HIP_TRY(hipGetLastError());
+        return PSC_OK;
+    }
     if (nlists <= 64)
         hipLaunchKernelGGL(merge_kernel<1>, grid, block, 0, s, part_d, part_i, nlists, k, (int64_t)0, status, ids, dists);
     else if (nlists <= 128)

@@ -141,6 +141,42 @@ def _check_ivf_search(fixture, nprobe, ht, k, nq=37):
     assert np.array_equal(own_q["nsurv"], ref["nsurv"]) or (own_q["nsurv"] != ref["nsurv"]).mean() < 0.1
 
 
+@pytest.mark.parametrize("nq,nprobe,ht,k", [(1, 64, 24, 100), (1, 8, 64, 10), (3, 33, 26, 64), (8, 64, 28, 130),
+                                            (8, 1, 20, 1), (5, 300, 30, 100)])
+def test_ivf_search_with_a_handful_of_queries(ivf_many_lists, nq, nprobe, ht, k):
+    """Up to 8 queries run the coarse stage built for latency (many workgroups per query for the
+    distances, a whole workgroup per query for the selection of the lists) and, from k = 64, the
+    selecting merge."""
+    _check_ivf_search(ivf_many_lists, nprobe, ht, k, nq=nq)
+
+
+def test_probe_selection_with_tied_coarse_distances():
+    """Coarse centroids that repeat: equal distances are broken by the lower list number, also when
+    the tie straddles the last probed place (single query and a batch, 4096 and more lists)."""
+    import paper_1609_01882_amd as psc
+    rng = np.random.default_rng(21)
+    for nlist, nprobe in ((64, 10), (600, 37), (5000, 70)):
+        distinct = (rng.integers(0, 50, size=(max(nlist // 8, 3), 32))).astype(np.float32)
+        cent = distinct[rng.integers(0, len(distinct), size=nlist)]      # every centroid about 8 times
+        idx = psc.Index(32, 8)
+        idx.ivf_set_coarse(cent)
+        idx.set_codebook(rng.normal(0, 5, size=(8, 256, 4)).astype(np.float32))
+        xb = (cent[rng.integers(0, nlist, size=4000)] + rng.normal(0, 2, size=(4000, 32))).astype(np.float32)
+        list_no, codes = idx.ivf_assign_encode(_dev(xb))
+        order = torch.sort(list_no.to(torch.int64), stable=True).indices
+        counts = torch.bincount(list_no.to(torch.int64), minlength=nlist)
+        offsets = torch.zeros(nlist + 1, dtype=torch.int64, device="cuda")
+        offsets[1:] = torch.cumsum(counts, 0)
+        idx.ivf_set_lists(offsets, codes[order].contiguous(), order.to(torch.int32).contiguous())
+        for nq in (1, 7, 40):
+            xq = rng.integers(0, 50, size=(nq, 32)).astype(np.float32)   # integers: distances exact in float32
+            _, _, probed, _ = idx.ivf_search(_dev(xq), nprobe, 20, 5, want_debug=True)
+            torch.cuda.synchronize()
+            dc = ((xq[:, None, :].astype(np.float64) - cent[None, :, :].astype(np.float64)) ** 2).sum(axis=2)
+            want = np.argsort(dc, axis=1, kind="stable")[:, :nprobe]     # (distance, list number)
+            assert np.array_equal(probed.cpu().numpy(), want), (nlist, nprobe, nq)
+
+
 def test_ivf_search_with_a_batch_of_300(ivf):
     """256 queries and more take their coarse distances from the matrix-core kernel (centred
     expansion instead of direct differences): same probed lists up to near-ties, same results."""

@@ -175,6 +175,22 @@ def test_many_slices_for_few_queries(psc):
         assert_topk_matches(got_ids, got_d, ref, lut.astype(np.float64), qcodes, codes, ht, what=f"many slices ht={ht}")
 
 
+@pytest.mark.parametrize("nq,n,k,lut_kind", [(1, 3_000_001, 100, "int"), (3, 1_000_003, 64, "int"),
+                                             (8, 400_009, 128, "float"), (2, 70_001, 1024, "int"),
+                                             (1, 300, 500, "int")])
+def test_selecting_merge_for_a_handful_of_queries(psc, nq, n, k, lut_kind):
+    """Up to 8 queries and k >= 64: the partial lists of the slices are merged by a workgroup that
+    selects the k smallest (distance, id) pairs.  Integer tables put hundreds of entries at the
+    k-th distance, so the last place is decided by the id; short databases leave padding."""
+    codes, qcodes, lut = _rand_problem(8, n, nq, seed=77 + k, lut_kind=lut_kind)
+    for ht in (24, 64):
+        got_ids, got_d = _run(psc, lut, qcodes, codes, ht, k)
+        ref = O.scan(lut.astype(np.float64), qcodes, codes, ht, k)
+        nd = assert_topk_matches(got_ids, got_d, ref, lut.astype(np.float64), qcodes, codes, ht, what=f"nq={nq} k={k} ht={ht}")
+        if lut_kind == "int":
+            assert nd == 0  # exact sums: ties must resolve exactly as in the oracle
+
+
 @pytest.mark.parametrize("m", [8, 16])
 def test_hamming_filter_is_bit_exact(psc, m):
     codes, qcodes, _ = _rand_problem(m, 20_011, 23, seed=7 + m, lut_kind="int")
