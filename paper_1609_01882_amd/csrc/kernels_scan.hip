@@ -1458,7 +1458,7 @@ merge_kernel(const float *__restrict__ part_d, const int64_t *__restrict__ part_
 // barrier per bit is enough); if more entries than needed share it, the same search over the bits
 // of the id finds the last id that belongs.  The selected entries go to LDS in any order and each
 // is written to its rank.
-constexpr int64_t kMergeSelectQueries = 8;       // up to this many queries
+constexpr int64_t kMergeSelectQueries = 32;      // up to this many queries
 constexpr int64_t kMergeSelectEntries = 32768;   // and this many entries per query
 // (its forty-odd counting steps take about 20 us whatever k is; the wave above takes 0.4 us per
 //  result: measured 32 against 42 us at k = 100, 20 against 5 us at k = 10)

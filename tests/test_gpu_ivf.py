@@ -134,7 +134,7 @@ def _check_ivf_search(fixture, nprobe, ht, k, nq=37):
     for q, r in mism:  # only where oracle distances tie within tolerance
         near = np.abs(ref["dists"][q] - ref["dists"][q, r]) <= RTOL * ref["dists"][q, r]
         assert ids[q, r] in ref["ids"][q][near] or abs(d[q, r] - ref["dists"][q, r]) <= RTOL * ref["dists"][q, r]
-    assert len(mism) <= 0.01 * ids.size
+    assert len(mism) <= max(10, 0.01 * ids.size)  # (each one checked above; a single query with k = 400 had 6)
     # the per-list query codes agree with the oracle's own on all but near-ties
     own_q = O.ivf_search(xq, s["cb"], s["coarse"], s["offsets"], s["lcodes"], s["lids"], nprobe, ht, k,
                          probed_in=probed)
@@ -144,7 +144,7 @@ def _check_ivf_search(fixture, nprobe, ht, k, nq=37):
 @pytest.mark.parametrize("nq,nprobe,ht,k", [(1, 64, 24, 100), (1, 8, 64, 10), (3, 33, 26, 64), (8, 64, 28, 130),
                                             (8, 1, 20, 1), (5, 300, 30, 100)])
 def test_ivf_search_with_a_handful_of_queries(ivf_many_lists, nq, nprobe, ht, k):
-    """Up to 8 queries run the coarse stage built for latency (many workgroups per query for the
+    """Up to 32 queries run the coarse stage built for latency (many workgroups per query for the
     distances, a whole workgroup per query for the selection of the lists) and, from k = 64, the
     selecting merge."""
     _check_ivf_search(ivf_many_lists, nprobe, ht, k, nq=nq)
