@@ -33,7 +33,7 @@ OPS_PER_PAIR = {8: 5, 16: 9}
 # Bytes per scan launch between L2 and the memory fabric, measured with rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE (two runs, scaled by what the same counters read for a 1 GiB copy:
 # x2.0 and x1.0), see profiles/; keyed by (kernel, ht) on the flat64 workload.
-MEASURED_TRAFFIC_BYTES = {("scan_mfma_kernel<16>", 24): 1.9225e10, ("scan_kernel<8,8,8>", 24): 9.7250e10}
+MEASURED_TRAFFIC_BYTES = {("scan_mfma_kernel<16>", 24): 1.9229e10, ("scan_kernel<8,8,8>", 24): 9.7279e10}
 
 
 def log(*a):
