@@ -212,7 +212,9 @@ int psc_ivf_assign_encode(const psc_index *idx, const float *x_dev, int64_t n, i
 /* The inverted lists, borrowed (the caller keeps them alive and unchanged while searching):
  * codes_dev [n][m] residual codes grouped by list, ids_dev [n] (int32, >= 0) the id of each
  * stored code, offsets_dev [nlist+1] (int64, device memory) list l = rows offsets[l] ..
- * offsets[l+1]-1.  codes_dev must be 16-byte aligned. */
+ * offsets[l+1]-1.  codes_dev must be 16-byte aligned.  The call copies the offsets to the host
+ * once (synchronously) to check them (0 first, n last, never decreasing) and to note the longest
+ * list, which decides which scan kernels can serve the index. */
 int psc_ivf_set_lists(psc_index *idx, const int64_t *offsets_dev, const uint8_t *codes_dev,
                       const int32_t *ids_dev, int64_t n);
 
@@ -221,7 +223,9 @@ int psc_ivf_set_lists(psc_index *idx, const int64_t *offsets_dev, const uint8_t 
  * residual q - centroid[l] gives that list's ADC tables and the query's bit string for that
  * list; the list's codes are filtered (Hamming <= ht) and scored as in psc_scan; one ranking by
  * (distance, id) over the union of the probed lists, ids taken from ids_dev.  No cap on lists
- * or distance evaluations.
+ * or distance evaluations.  Both exact forms of the Hamming test of psc_scan exist here too (the
+ * matrix-core one is taken for 64-bit codes, thresholds up to 17 and a dozen or more (query,
+ * list) pairs per list; PSC_FILTER_ROUTE overrides as for psc_scan).
  * probed_out_dev (may be NULL) [nq][nprobe] int32 receives the probed lists in ascending
  * coarse distance; qcodes_out_dev (may be NULL) [nq][nprobe][m] the per-list query codes.
  * The tables are never stored per (query, list): with o the mean coarse centroid they split

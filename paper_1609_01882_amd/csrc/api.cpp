@@ -717,10 +717,25 @@ int psc_ivf_set_lists(psc_index *idx, const int64_t *offsets_dev, const uint8_t 
     }
     PSC_REQUIRE(offsets_dev && n >= 0 && (n == 0 || (codes_dev && ids_dev)), "null pointer");
     PSC_REQUIRE(((uintptr_t)codes_dev & 15) == 0, "list codes must be 16-byte aligned");
+    // the longest list decides which scan kernels can serve the index: read the boundaries once
+    int64_t longest = 0;
+    try {
+        std::vector<int64_t> off((size_t)idx->nlist + 1);
+        PSC_HIP_TRY(hipMemcpy(off.data(), offsets_dev, off.size() * sizeof(int64_t), hipMemcpyDeviceToHost));
+        PSC_REQUIRE(off[0] == 0 && off[(size_t)idx->nlist] == n, "list offsets must start at 0 and end at n");
+        for (int l = 0; l < idx->nlist; ++l) {
+            PSC_REQUIRE(off[(size_t)l + 1] >= off[(size_t)l], "list offsets must not decrease (list %d)", l);
+            longest = std::max(longest, off[(size_t)l + 1] - off[(size_t)l]);
+        }
+    } catch (const std::bad_alloc &) {
+        set_error("out of host memory");
+        return PSC_ENOMEM;
+    }
     idx->list_off_dev = offsets_dev;
     idx->list_codes_dev = codes_dev;
     idx->list_ids_dev = ids_dev;
     idx->list_n = n;
+    idx->list_max_len = longest;
     return PSC_OK;
 }
 
@@ -824,8 +839,11 @@ int psc_ivf_search(const psc_index *idx, const float *q_dev, int64_t nq, int npr
     if (probed_out_dev)
         PSC_HIP_TRY(hipMemcpyAsync(probed_out_dev, probed, (size_t)L.njobs * sizeof(int32_t),
                                    hipMemcpyDeviceToDevice, s));
-    // 2. jobs grouped by list, cut into tiles
-    rc = launch_build_jobs(probed, nq, nprobe, idx->nlist, kPilotProbes, L.plan.tq, jb, s);
+    // 2. jobs grouped by list, cut into tiles of the shape of the scan kernel that will run
+    ScanPlan plan = L.plan;
+    const bool on_matrix_cores = L.njobs > kDirectJobs &&
+                                 ivf_scan_on_matrix_cores(idx->m, ht, k, L.njobs, idx->nlist, idx->list_max_len, &plan);
+    rc = launch_build_jobs(probed, nq, nprobe, idx->nlist, kPilotProbes, plan.tq, jb, s);
     if (rc != PSC_OK) return rc;
     // 3. the queries' and the lists' shares of the residual tables (put together per tile by the
     //    scan, which also derives each job's query code from them)
@@ -837,12 +855,12 @@ int psc_ivf_search(const psc_index *idx, const float *q_dev, int64_t nq, int npr
     if (rc != PSC_OK) return rc;
     const float *list_tab = idx->list_tab_dev;
     // 4. the fused scan over the tiles, 5. one merge per query over its nprobe partial lists
-    rc = launch_ivf_scan(idx->m, L.plan.tq, L.plan.nwaves, L.plan.kpad, L.plan.lds_bytes, lut, list_tab, q_dev, idx->coarse_dev,
+    rc = launch_ivf_scan(idx->m, plan.tq, plan.nwaves, plan.kpad, plan.lds_bytes, lut, list_tab, q_dev, idx->coarse_dev,
                          idx->dim, idx->nlist, qcodes, idx->list_codes_dev, idx->list_n, ht, k, jb.tiles,
                          jb.tile_begin + 2 * idx->nlist, L.max_tiles, idx->list_off_dev, idx->list_ids_dev,
                          jb.job_slot, jb.job_q, (uint32_t *)(w + L.off_gthr), (float *)(w + L.off_part_d),
                          (int64_t *)(w + L.off_part_i), (int *)(w + L.off_status), nq, nprobe, ids_dev,
-                         dists_dev, s);
+                         dists_dev, on_matrix_cores, s);
     if (rc != PSC_OK) return rc;
     if (qcodes_out_dev) rc = launch_unsort_rows(qcodes, jb.job_slot, L.njobs, idx->m, qcodes_out_dev, s);
     return rc;

@@ -97,7 +97,11 @@ int launch_ivf_scan(int m, int tq, int nwaves, int kpad, size_t lds_bytes, const
                     const void *tiles_dev, const int *ntiles_dev, int64_t max_tiles,
                     const int64_t *list_off_dev, const int32_t *ext_ids_dev, const int32_t *job_slot_dev,
                     const int32_t *job_q_dev, uint32_t *gthr_dev, float *part_d, int64_t *part_i, int *status,
-                    int64_t nq, int nprobe, int64_t *ids_dev, float *dists_dev, hipStream_t s);
+                    int64_t nq, int nprobe, int64_t *ids_dev, float *dists_dev, bool on_matrix_cores,
+                    hipStream_t s);
+// Whether the grouped inverted-file scan of njobs (query, list) jobs runs its Hamming test on the
+// matrix cores; if so *plan receives that kernel's tile shape (16 jobs x 16 waves).
+bool ivf_scan_on_matrix_cores(int m, int ht, int k, int64_t njobs, int nlist, int64_t max_list_len, ScanPlan *plan);
 int launch_hamming_histogram(int m, const uint8_t *qcodes_dev, int64_t nq, const uint8_t *codes_dev,
                              int64_t n, int64_t *hist_dev, hipStream_t s);
 int launch_hamming_filter(int m, const uint8_t *qcodes_dev, int64_t nq, const uint8_t *codes_dev,
@@ -189,4 +193,5 @@ struct psc_index {
     const uint8_t *list_codes_dev = nullptr;
     const int32_t *list_ids_dev = nullptr;
     int64_t list_n = 0;
+    int64_t list_max_len = 0;  // the longest list
 };

@@ -635,6 +635,93 @@ __device__ __forceinline__ void drain(const Lds<M, TQ> &s, const ScanArgs &a, co
     }
 }
 
+// Inverted-file tile set-up, shared by the fused kernels: the residual tables of the tile's jobs
+// put together in LDS (see ScanArgs::list_tab) and the jobs' query codes taken from them (s.qcw).
+// Called by the whole workgroup (NW waves) after the per-slot state (s.gidx) is written; ends with
+// a barrier.
+template <int M, int TQ, int NW>
+__device__ __forceinline__ void stage_list_tables(const Lds<M, TQ> &s, const ScanArgs &a, int tile_list, int64_t q0,
+                                                  int nvq)
+{
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    const int tid = (int)threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int dsub = a.dim / M;
+    // the list's centroid and the jobs' queries, both minus the mean centroid, staged where
+    // the tables will go (all loads of the workgroup in flight together; (TQ + 1) * dim floats
+    // fit: dim <= 1024 = a quarter of one job's tables at M = 8)
+    PSC_LDS float *gs = (PSC_LDS float *)s.lut, *xs = gs + a.dim;
+    for (int e = tid; e < (nvq + 1) * a.dim; e += NW * 64) {
+        const int q = e / a.dim - 1, t = e % a.dim;
+        const float *row = q < 0 ? a.coarse + (int64_t)tile_list * a.dim
+                                 : a.queries + (int64_t)a.job_q[q0 + q] * a.dim;
+        gs[e] = row[t] - a.coarse[(int64_t)a.nlist * a.dim + t];
+    }
+    __syncthreads();
+    float sterm = 0.f;
+    if (tid < TQ * M) {  // the per-job constant g~_j . (g~_j - 2 q~_j)
+        const int q = tid / M, j = tid - q * M;
+        if (q < nvq) {
+            for (int t = j * dsub; t < (j + 1) * dsub; ++t) {
+                const float g = gs[t], x = xs[q * a.dim + t];
+                sterm = fmaf(g, g - 2.0f * x, sterm);
+            }
+        }
+    }
+    __syncthreads();  // (the staged vectors are read; their place is the tables' from here on)
+    if (tid < TQ * M) s.sterm[tid] = sterm;
+    __syncthreads();
+    {
+        // the jobs' share and the list's share of every table entry, four entries per thread at
+        // a time: their loads first, the sums after
+        constexpr int kTurns = (TQ * M * 64 + NW * 64 - 1) / (NW * 64);
+        constexpr int kChunk = kTurns < 4 ? kTurns : 4;
+        const f32x4 *tab = (const f32x4 *)(a.list_tab + (int64_t)tile_list * (M * 256));
+        PSC_LDS f32x4 *dst = (PSC_LDS f32x4 *)s.lut;
+#pragma unroll 1
+        for (int u0 = 0; u0 < kTurns; u0 += kChunk) {
+            f32x4 xv[kChunk], tv[kChunk];
+#pragma unroll
+            for (int u = 0; u < kChunk; ++u) {
+                const int e = tid + (u0 + u) * NW * 64;
+                const int q = e / (M * 64), r = e - q * (M * 64);  // r: 16-byte entry of the job's table
+                xv[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+                tv[u] = xv[u];
+                if (e < TQ * (M * 64) && q < nvq) {
+                    xv[u] = ((const f32x4 *)(a.lut + (int64_t)s.gidx[q] * (M * 256)))[r];
+                    tv[u] = tab[r];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kChunk; ++u) {
+                const int e = tid + (u0 + u) * NW * 64;
+                const int q = e / (M * 64), r = e - q * (M * 64);
+                if (e < TQ * (M * 64)) {
+                    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+                    if (q < nvq) v = (xv[u] + tv[u]) + s.sterm[q * M + (r >> 6)];
+                    dst[e] = v;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    // arg-min of every table row (lowest index on ties): one wave per row
+    for (int row = wave; row < TQ * M; row += NW) {
+        const f32x4 v = ((const PSC_LDS f32x4 *)s.lut)[row * 64 + lane];
+        float best = v.x;
+        int bi = 4 * lane;
+        if (v.y < best) { best = v.y; bi = 4 * lane + 1; }
+        if (v.z < best) { best = v.z; bi = 4 * lane + 2; }
+        if (v.w < best) { best = v.w; bi = 4 * lane + 3; }
+        const uint32_t key = dist_key(best);
+        const uint32_t wk = wave_min_u32(key);
+        const int win = __builtin_ctzll(ballot64(key == wk));  // lower lanes hold lower indices
+        const int code = __builtin_amdgcn_readlane(bi, win);
+        if (lane == 0) ((PSC_LDS volatile uint8_t *)s.qcw)[row] = (uint8_t)code;
+    }
+    __syncthreads();
+}
+
 // IVF: tiles are (inverted list, up to TQ of its jobs) instead of (query tile, slice).
 // SHARE: the workgroups of one query exchange their k-th-best distance through `gthr`; worth
 // it when a query is served by many workgroups (inverted lists, four slices or more).
@@ -694,76 +781,7 @@ scan_kernel(ScanArgs a)
     typedef float f32x4 __attribute__((ext_vector_type(4)));
     uint32_t qw[TQ][WPC];  // the tile's query codes, in scalar registers
     if constexpr (IVF) {
-        // ---- residual tables put together in LDS (see ScanArgs::list_tab), query codes from them
-        const int dsub = a.dim / M;
-        // the list's centroid and the jobs' queries, both minus the mean centroid, staged where
-        // the tables will go (all loads of the workgroup in flight together; (TQ + 1) * dim floats
-        // fit: dim <= 1024 = a quarter of one job's tables at M = 8)
-        PSC_LDS float *gs = (PSC_LDS float *)s.lut, *xs = gs + a.dim;
-        for (int e = tid; e < (nvq + 1) * a.dim; e += NW * 64) {
-            const int q = e / a.dim - 1, t = e % a.dim;
-            const float *row = q < 0 ? a.coarse + (int64_t)tile_list * a.dim
-                                     : a.queries + (int64_t)a.job_q[q0 + q] * a.dim;
-            gs[e] = row[t] - a.coarse[(int64_t)a.nlist * a.dim + t];
-        }
-        __syncthreads();
-        float sterm = 0.f;
-        if (tid < TQ * M) {  // the per-job constant g~_j . (g~_j - 2 q~_j)
-            const int q = tid / M, j = tid - q * M;
-            if (q < nvq) {
-                for (int t = j * dsub; t < (j + 1) * dsub; ++t) {
-                    const float g = gs[t], x = xs[q * a.dim + t];
-                    sterm = fmaf(g, g - 2.0f * x, sterm);
-                }
-            }
-        }
-        __syncthreads();  // (the staged vectors are read; their place is the tables' from here on)
-        if (tid < TQ * M) s.sterm[tid] = sterm;
-        {
-            // the jobs' share and the list's share of every table entry: loads first, sums after
-            constexpr int kTurns = (TQ * M * 64 + NW * 64 - 1) / (NW * 64);
-            const f32x4 *tab = (const f32x4 *)(a.list_tab + (int64_t)tile_list * (M * 256));
-            f32x4 xv[kTurns], tv[kTurns];
-#pragma unroll
-            for (int u = 0; u < kTurns; ++u) {
-                const int e = tid + u * NW * 64;
-                const int q = e / (M * 64), r = e - q * (M * 64);  // r: 16-byte entry of the job's table
-                xv[u] = f32x4{0.f, 0.f, 0.f, 0.f};
-                tv[u] = xv[u];
-                if (e < TQ * (M * 64) && q < nvq) {
-                    xv[u] = ((const f32x4 *)(a.lut + (int64_t)s.gidx[q] * (M * 256)))[r];
-                    tv[u] = tab[r];
-                }
-            }
-            __syncthreads();  // s.sterm
-            PSC_LDS f32x4 *dst = (PSC_LDS f32x4 *)s.lut;
-#pragma unroll
-            for (int u = 0; u < kTurns; ++u) {
-                const int e = tid + u * NW * 64;
-                const int q = e / (M * 64), r = e - q * (M * 64);
-                if (e < TQ * (M * 64)) {
-                    f32x4 v = {0.f, 0.f, 0.f, 0.f};
-                    if (q < nvq) v = (xv[u] + tv[u]) + s.sterm[q * M + (r >> 6)];
-                    dst[e] = v;
-                }
-            }
-        }
-        __syncthreads();
-        // arg-min of every table row (lowest index on ties): one wave per row
-        for (int row = wave; row < TQ * M; row += NW) {
-            const f32x4 v = ((const PSC_LDS f32x4 *)s.lut)[row * 64 + lane];
-            float best = v.x;
-            int bi = 4 * lane;
-            if (v.y < best) { best = v.y; bi = 4 * lane + 1; }
-            if (v.z < best) { best = v.z; bi = 4 * lane + 2; }
-            if (v.w < best) { best = v.w; bi = 4 * lane + 3; }
-            const uint32_t key = dist_key(best);
-            const uint32_t wk = wave_min_u32(key);
-            const int win = __builtin_ctzll(ballot64(key == wk));  // lower lanes hold lower indices
-            const int code = __builtin_amdgcn_readlane(bi, win);
-            if (lane == 0) ((PSC_LDS volatile uint8_t *)s.qcw)[row] = (uint8_t)code;
-        }
-        __syncthreads();
+        stage_list_tables<M, TQ, NW>(s, a, tile_list, q0, nvq);
         if (tid < nvq * WPC) ((uint32_t *)a.job_qcodes)[q0 * WPC + tid] = s.qcw[tid];
 #pragma unroll
         for (int q = 0; q < TQ; ++q) {
@@ -1018,7 +1036,8 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 // (One 16-wave workgroup per compute unit = 4 waves per SIMD: telling the compiler so lets it
 //  spend registers on keeping the eight products of a block in flight together.)
-template <int NW, bool SHARE>
+// IVF: tiles are (inverted list, up to 16 of its jobs), as in scan_kernel.
+template <int NW, bool SHARE, bool IVF = false>
 __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4, 4)))
 scan_mfma_kernel(ScanArgs a)
 {
@@ -1033,15 +1052,35 @@ scan_mfma_kernel(ScanArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 15, grp = lane >> 4;
 
-    const FlatTile ft = flat_tile(a, blockIdx.x, TQ);
-    const int slice = ft.slice;
-    const int64_t q0 = ft.q0;
-    const int nvq = (int)((a.nq - q0) < TQ ? (a.nq - q0) : TQ);
-    const int64_t slice_begin = ft.slice_begin;
-    const int64_t slice_end = ft.slice_end;
+    FlatTile ft{};
+    int slice = 0, tile_list = 0;
+    int64_t q0, slice_begin, slice_end;
+    int nvq;
+    if constexpr (IVF) {
+        if ((int)blockIdx.x >= *a.ntiles) return;  // the grid is an upper bound on the tile count
+        const IvfTile t = a.tiles[blockIdx.x];
+        tile_list = t.list;
+        q0 = t.job_begin;
+        nvq = t.njobs;
+        slice_begin = a.list_off[t.list];  // (8-byte loads, one code each: a list may start anywhere)
+        slice_end = a.list_off[t.list + 1];
+    } else {
+        ft = flat_tile(a, blockIdx.x, TQ);
+        slice = ft.slice;
+        q0 = ft.q0;
+        nvq = (int)((a.nq - q0) < TQ ? (a.nq - q0) : TQ);
+        slice_begin = ft.slice_begin;
+        slice_end = ft.slice_end;
+    }
+    // the look-ups below take the table to start at LDS address 0, the queue entries a position
+    // in kMfmaRelBits bits: flag the run instead of returning something wrong
+    if ((uint32_t)(uintptr_t)xtab != 0u || slice_end - slice_begin > kMfmaMaxSliceLen) {
+        if (tid == 0) atomicExch(a.status, 1);
+        return;
+    }
 
     if (tid < TQ) {
-        const int gi = tid < nvq ? (int)(q0 + tid) : -1;
+        const int gi = tid < nvq ? (int)(IVF ? (int64_t)a.job_q[q0 + tid] : q0 + tid) : -1;
         float t0 = __builtin_inff();
         if constexpr (SHARE) {
             if (gi >= 0) t0 = key_dist(__hip_atomic_load(&a.gthr[gi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
@@ -1050,7 +1089,16 @@ scan_mfma_kernel(ScanArgs a)
         s.lock[tid] = 0;
         s.gidx[tid] = gi;
     }
-    {
+    for (int v = tid; v < 256; v += NW * 64) {
+        uint32_t w[2] = {0u, 0u};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) w[i >> 2] |= (((v >> i) & 1) ? 0xffu : 0x01u) << (8 * (i & 3));
+        xtab[v] = u32x2{w[0], w[1]};
+    }
+    if constexpr (IVF) {
+        stage_list_tables<M, TQ, NW>(s, a, tile_list, q0, nvq);
+        if (tid < nvq * 2) ((uint32_t *)a.job_qcodes)[q0 * 2 + tid] = s.qcw[tid];
+    } else {
         typedef float f32x4 __attribute__((ext_vector_type(4)));
         const f32x4 *src = (const f32x4 *)(a.lut + q0 * (M * 256));
         PSC_LDS f32x4 *dst = (PSC_LDS f32x4 *)s.lut;
@@ -1060,23 +1108,17 @@ scan_mfma_kernel(ScanArgs a)
             if (e < nvec) v = src[e];
             dst[e] = v;
         }
+        __syncthreads();
     }
-    if ((uint32_t)(uintptr_t)xtab != 0u) {  // the look-ups below take the table to start at LDS address 0
-        if (tid == 0) atomicExch(a.status, 1);
-        return;
-    }
-    for (int v = tid; v < 256; v += NW * 64) {
-        uint32_t w[2] = {0u, 0u};
-#pragma unroll
-        for (int i = 0; i < 8; ++i) w[i >> 2] |= (((v >> i) & 1) ? 0xffu : 0x01u) << (8 * (i & 3));
-        xtab[v] = u32x2{w[0], w[1]};
-    }
-    __syncthreads();
 
     // A operand: part grp of query slot col (slots past nvq: any code, their results are masked)
     i32x4 qa;
     {
-        const uint32_t q16 = ((const uint16_t *)a.qcodes)[(q0 + (col < nvq ? col : 0)) * 4 + grp];
+        uint32_t q16;
+        if constexpr (IVF)
+            q16 = ((const PSC_LDS uint16_t *)s.qcw)[(col < nvq ? col : 0) * 4 + grp];
+        else
+            q16 = ((const uint16_t *)a.qcodes)[(q0 + (col < nvq ? col : 0)) * 4 + grp];
         const u32x2 lo = xtab[q16 & 0xffu], hi = xtab[q16 >> 8];
         qa = i32x4{(int)lo.x, (int)lo.y, (int)hi.x, (int)hi.y};
     }
@@ -1095,7 +1137,7 @@ scan_mfma_kernel(ScanArgs a)
     SharedAsk ask;
     const uint8_t *slice_codes = a.codes + slice_begin * M;
     uint32_t self0 = 0x80000000u;
-    if (a.skip_first >= 0) {
+    if (!IVF && a.skip_first >= 0) {
         const int64_t at = a.skip_first + q0 - slice_begin;
         if (at > -64 && at < kMfmaMaxSliceLen) self0 = (uint32_t)at;
     }
@@ -1113,7 +1155,7 @@ scan_mfma_kernel(ScanArgs a)
             if (fill < 64) break;
             __builtin_amdgcn_wave_barrier();
             fill -= 64;
-            drain<M, TQ, false, SHARE, true>(s, a, ring + fill, 64, slice_codes, slice_begin, self0, ask);
+            drain<M, TQ, IVF, SHARE, true>(s, a, ring + fill, 64, slice_codes, slice_begin, self0, ask);
             __builtin_amdgcn_wave_barrier();
         }
     };
@@ -1203,7 +1245,7 @@ scan_mfma_kernel(ScanArgs a)
     }
     if (fill > 0) {
         __builtin_amdgcn_wave_barrier();
-        drain<M, TQ, false, SHARE, true>(s, a, ring, fill, slice_codes, slice_begin, self0, ask);
+        drain<M, TQ, IVF, SHARE, true>(s, a, ring, fill, slice_codes, slice_begin, self0, ask);
     }
     __syncthreads();
 
@@ -1211,11 +1253,20 @@ scan_mfma_kernel(ScanArgs a)
         const int q = e / a.k, r = e - q * a.k;
         const bool have = r < s.lock[q];
         const uint64_t ent = s.top[q * a.kpad + r];
-        const int64_t o = ((q0 + q) * a.nslice + slice) * a.k + r;
+        int64_t o, id;
+        if constexpr (IVF) {
+            o = (int64_t)a.job_slot[q0 + q] * a.k + r;
+            id = (int64_t)entry_id(ent);
+        } else {
+            o = ((q0 + q) * a.nslice + slice) * a.k + r;
+            id = slice_begin + (int64_t)entry_id(ent);
+        }
         a.part_d[o] = have ? entry_dist(ent) : __builtin_inff();
-        a.part_i[o] = have ? slice_begin + (int64_t)entry_id(ent) : (int64_t)-1;
+        a.part_i[o] = have ? id : (int64_t)-1;
     }
-    if (ft.whole && a.nslice > 1) pad_unused_slices(a, q0, nvq, tid, NW * 64);
+    if constexpr (!IVF) {
+        if (ft.whole && a.nslice > 1) pad_unused_slices(a, q0, nvq, tid, NW * 64);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1710,16 +1761,16 @@ int run_scan(const ScanArgs &a, int64_t ntiles, size_t lds, hipStream_t s)
     return PSC_OK;
 }
 
-template <int NW, bool SHARE>
+template <int NW, bool SHARE, bool IVF = false>
 int run_scan_mfma(const ScanArgs &a, int64_t ntiles, size_t lds, hipStream_t s)
 {
     static bool configured = false;
     if (!configured) {
-        PSC_HIP_TRY(hipFuncSetAttribute((const void *)scan_mfma_kernel<NW, SHARE>,
+        PSC_HIP_TRY(hipFuncSetAttribute((const void *)scan_mfma_kernel<NW, SHARE, IVF>,
                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
         configured = true;
     }
-    hipLaunchKernelGGL((scan_mfma_kernel<NW, SHARE>), dim3((unsigned)ntiles), dim3(NW * 64), lds, s, a);
+    hipLaunchKernelGGL((scan_mfma_kernel<NW, SHARE, IVF>), dim3((unsigned)ntiles), dim3(NW * 64), lds, s, a);
     PSC_HIP_TRY(hipGetLastError());
     return PSC_OK;
 }
@@ -2048,6 +2099,31 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
     return launch_merge(a.part_d, a.part_i, nq, p.nslice, k, a.status, ids_dev, dists_dev, s);
 }
 
+// Which filter the grouped inverted-file scan takes.  The matrix-core kernel needs 64-bit codes,
+// k small enough for its 16-job tile, lists within its position field and enough jobs per list
+// to fill its tiles (a tile costs the same filter work whether 16 or 4 of its slots are taken).
+// It pays only while next to nothing survives the test: its one 16-wave workgroup per compute
+// unit cannot overlap one tile's set-up and list work with another tile's filtering as three
+// 8-wave workgroups do, and a list is 24k codes, not 10M.  Measured on 100M vectors / 4096 lists
+// / 10k queries x 64 probes, k = 100, whole search, xor/popcount against matrix cores:
+// ht = 0: 5.2 / 4.5 ms, 16: 5.4 / 4.9, 20: 7.1 / 9.0, 24: 8.6 / 10.5 (k = 1: 6.2 / 6.2).
+// Hence thresholds that let fewer than one random pair in 10^4 through (ht <= 17).
+// PSC_FILTER_ROUTE=popcount|mfma overrides the rule where the kernel can run at all.
+bool ivf_scan_on_matrix_cores(int m, int ht, int k, int64_t njobs, int nlist, int64_t max_list_len, ScanPlan *plan)
+{
+    if (m != 8 || ht >= 64 || max_list_len > kMfmaMaxSliceLen || njobs < kMfmaMinQueries) return false;
+    bool take = njobs >= 12 * (int64_t)nlist && random_code_survival(64, ht) < 1e-4;
+    if (const char *route = std::getenv("PSC_FILTER_ROUTE")) {
+        if (!std::strcmp(route, "popcount")) take = false;
+        if (!std::strcmp(route, "mfma")) take = true;
+    }
+    if (!take) return false;
+    ScanPlan p;
+    if (plan_scan(m, njobs, max_list_len, k, kScanFusedMfma, &p) != PSC_OK) return false;  // (k too large)
+    *plan = p;
+    return true;
+}
+
 // Inverted-file scan: one workgroup per tile descriptor (up to `max_tiles`; the actual count is
 // read on the device), partial lists written at job_slot[job] * k, then one merge per query
 // over its nprobe partial lists.
@@ -2058,7 +2134,7 @@ int launch_ivf_scan(int m, int tq, int nwaves, int kpad, size_t lds_bytes, const
                     const void *tiles_dev, const int *ntiles_dev, int64_t max_tiles,
                     const int64_t *list_off_dev, const int32_t *ext_ids_dev, const int32_t *job_slot_dev,
                     const int32_t *job_q_dev, uint32_t *gthr_dev, float *part_d, int64_t *part_i, int *status,
-                    int64_t nq, int nprobe, int64_t *ids_dev, float *dists_dev, hipStream_t s)
+                    int64_t nq, int nprobe, int64_t *ids_dev, float *dists_dev, bool on_matrix_cores, hipStream_t s)
 {
     PSC_REQUIRE(((uintptr_t)codes_dev & 15) == 0 && ((uintptr_t)job_qcodes_dev & 15) == 0 &&
                     ((uintptr_t)lut_dev & 15) == 0 && ((uintptr_t)list_tab_dev & 15) == 0,
@@ -2097,7 +2173,13 @@ int launch_ivf_scan(int m, int tq, int nwaves, int kpad, size_t lds_bytes, const
     a.gthr = gthr_dev;
     hipLaunchKernelGGL(init_scan_kernel, dim3((unsigned)((nq + 255) / 256)), dim3(256), 0, s, gthr_dev, nq, a.status);
     if (max_tiles > 0) {
-        int rc = dispatch_scan<true, true>(m, tq, nwaves, a, max_tiles, lds_bytes, s);
+        int rc;
+        if (on_matrix_cores) {
+            PSC_REQUIRE(m == 8 && tq == 16 && nwaves == 16, "the matrix-core scan has one tile shape");
+            rc = run_scan_mfma<16, true, true>(a, max_tiles, lds_bytes, s);
+        } else {
+            rc = dispatch_scan<true, true>(m, tq, nwaves, a, max_tiles, lds_bytes, s);
+        }
         if (rc != PSC_OK) return rc;
     }
     return launch_merge(part_d, part_i, nq, nprobe, k, status, ids_dev, dists_dev, s);

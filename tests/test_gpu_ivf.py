@@ -177,6 +177,52 @@ def test_probe_selection_with_tied_coarse_distances():
             assert np.array_equal(probed.cpu().numpy(), want), (nlist, nprobe, nq)
 
 
+@pytest.mark.parametrize("route", ["mfma", "popcount"])
+@pytest.mark.parametrize("nq,nprobe,ht,k", [(300, 8, 24, 10), (1000, 8, 20, 100), (700, 37, 26, 136), (500, 5, 0, 1),
+                                            (2100, 1, 30, 7)])
+def test_grouped_ivf_scan_on_both_filter_routes(ivf, monkeypatch, route, nq, nprobe, ht, k):
+    """More than 2048 (query, list) jobs are grouped by list; the Hamming test of the grouped scan
+    runs either as xor/popcount (tiles of 4 jobs) or on the matrix cores (tiles of 16 jobs): same
+    survivors, same results."""
+    monkeypatch.setenv("PSC_FILTER_ROUTE", route)
+    _check_ivf_search(ivf, nprobe, ht, k, nq=nq)
+
+
+@pytest.mark.parametrize("route", ["mfma", "popcount"])
+def test_grouped_ivf_scan_with_ragged_lists(monkeypatch, route):
+    """Lists of every length from 0 to a few blocks of the matrix-core kernel (128 codes a block per
+    wave, 2048 per workgroup turn), starting at odd positions, random codes, ids unrelated to
+    positions, enough queries for the grouped path: every query probes every list, so each must get
+    back exactly the codes within the threshold, and the oracle's distances."""
+    import paper_1609_01882_amd as psc
+    monkeypatch.setenv("PSC_FILTER_ROUTE", route)
+    rng = np.random.default_rng(15)
+    idx = psc.Index(128, 8)
+    cb = rng.normal(size=(8, 256, 16)).astype(np.float32) * 20
+    idx.set_codebook(cb)
+    sizes = [7, 0, 131, 1, 0, 64, 127, 128, 129, 2047, 2048, 2049, 4100, 63, 300]
+    nlist = len(sizes)
+    coarse = (rng.random(size=(nlist, 128)) * 100).astype(np.float32)
+    idx.ivf_set_coarse(coarse)
+    offsets = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    n = int(offsets[-1])
+    lcodes = W.random_codes(n, 8, seed=4)
+    lids = rng.permutation(n).astype(np.int32)
+    idx.ivf_set_lists(_dev(offsets), _dev(lcodes), _dev(lids))
+    nq = 150                                          # 150 x 15 = 2250 jobs
+    xq = (rng.random(size=(nq, 128)) * 100).astype(np.float32)
+    for ht, k in ((26, 50), (63, 100)):
+        ids, d, probed, qcodes = idx.ivf_search(_dev(xq), nlist, ht, k, want_debug=True)
+        torch.cuda.synchronize()
+        ref = O.ivf_search(xq, cb, coarse, offsets, lcodes, lids, nlist, ht, k,
+                           probed_in=probed.cpu().numpy(), qcodes_in=qcodes.cpu().numpy())
+        ids, d = ids.cpu().numpy(), d.cpu().numpy()
+        pad = ref["ids"] < 0
+        assert np.array_equal(ids < 0, pad)
+        assert np.allclose(d[~pad], ref["dists"][~pad], rtol=RTOL)
+        assert (ids == ref["ids"]).mean() > 0.99
+
+
 def test_ivf_search_with_a_batch_of_300(ivf):
     """256 queries and more take their coarse distances from the matrix-core kernel (centred
     expansion instead of direct differences): same probed lists up to near-ties, same results."""
