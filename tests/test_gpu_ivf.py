@@ -342,3 +342,15 @@ def test_more_than_4096_lists():
     s = dict(idx=idx, cb=idx.get_codebook(), coarse=coarse, offsets=offsets.cpu().numpy(),
              lcodes=lcodes.cpu().numpy(), lids=lids.cpu().numpy())
     _check_ivf_search((psc, s), 70, 30, 20)
+
+
+def test_list_offsets_are_checked():
+    import paper_1609_01882_amd as psc
+    idx = psc.Index(128, 8)
+    idx.ivf_set_coarse(np.zeros((3, 128), np.float32))
+    codes = torch.zeros((10, 8), dtype=torch.uint8, device="cuda")
+    ids = torch.arange(10, dtype=torch.int32, device="cuda")
+    for bad in ([0, 4, 8, 9], [1, 4, 8, 10], [0, 6, 4, 10]):   # wrong end, wrong start, decreasing
+        with pytest.raises(psc.PscError):
+            idx.ivf_set_lists(torch.tensor(bad, dtype=torch.int64, device="cuda"), codes, ids)
+    idx.ivf_set_lists(torch.tensor([0, 4, 4, 10], dtype=torch.int64, device="cuda"), codes, ids)
