@@ -17,6 +17,7 @@ _LIB_PATH = os.environ.get("PSC_LIB_PATH") or os.path.join(_HERE, "libpsc.so")
 _lib = None
 
 PSC_MAX_K = 1024
+PSC_START_SEEDED, PSC_START_CURRENT = 0, 1
 
 
 class PscError(RuntimeError):
@@ -139,7 +140,7 @@ class Index:
         assert x.ndim == 2 and x.shape[1] == self.dim
         obj = np.empty((iters, self.m), dtype=np.float64)
         _check(_load().psc_train_pq_device(self._h, _dev(x, torch.float32, "x"), x.shape[0], iters, seed,
-                                           1 if from_current else 0, obj.ctypes.data_as(C.c_void_p), _stream()))
+                                           PSC_START_CURRENT if from_current else PSC_START_SEEDED, obj.ctypes.data_as(C.c_void_p), _stream()))
         return obj
 
     def optimize_index_assignment(self, n_iter: int = 500_000, t0: float = 0.7,
