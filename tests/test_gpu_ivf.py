@@ -229,14 +229,15 @@ def test_ivf_search_with_a_batch_of_300(ivf):
     _check_ivf_search(ivf, 8, 24, 10, nq=300)
 
 
-@pytest.mark.parametrize("dim", [32, 64, 96])
-def test_probed_lists_in_other_dimensions(dim):
-    """The coarse stage in the other dimensions the matrix-core kernels are built for (batch of 300
-    queries): the probed lists are the exactly nearest ones in order, up to near-ties, and the whole
-    search agrees with the oracle run on the same decisions."""
+@pytest.mark.parametrize("dim,nq", [(32, 300), (64, 300), (96, 300), (48, 5), (16, 3), (96, 8), (48, 40)])
+def test_probed_lists_in_other_dimensions(dim, nq):
+    """The coarse stage in other dimensions -- those the matrix-core kernels are built for (batches of
+    300 queries), and a handful or a few dozen queries in dimensions that are no multiple of 32 (the
+    plain kernels): the probed lists are the exactly nearest ones in order, up to near-ties, and the
+    whole search agrees with the oracle run on the same decisions."""
     import paper_1609_01882_amd as psc
     rng = np.random.default_rng(dim)
-    nlist, n, nq, nprobe, m = 70, 20_000, 300, 6, 8
+    nlist, n, nprobe, m = 70, 20_000, 6, 8
     cent = (rng.random((nlist, dim)) * 100).astype(np.float32)
     xb = (cent[rng.integers(0, nlist, size=n)] + rng.normal(0, 12, size=(n, dim))).astype(np.float32)
     xq = (cent[rng.integers(0, nlist, size=nq)] + rng.normal(0, 12, size=(nq, dim))).astype(np.float32)
