@@ -860,7 +860,7 @@ int psc_ivf_search(const psc_index *idx, const float *q_dev, int64_t nq, int npr
                          jb.tile_begin + 2 * idx->nlist, L.max_tiles, idx->list_off_dev, idx->list_ids_dev,
                          jb.job_slot, jb.job_q, (uint32_t *)(w + L.off_gthr), (float *)(w + L.off_part_d),
                          (int64_t *)(w + L.off_part_i), (int *)(w + L.off_status), nq, nprobe, ids_dev,
-                         dists_dev, on_matrix_cores, s);
+                         dists_dev, on_matrix_cores, L.njobs <= kDirectJobs, s);
     if (rc != PSC_OK) return rc;
     if (qcodes_out_dev) rc = launch_unsort_rows(qcodes, jb.job_slot, L.njobs, idx->m, qcodes_out_dev, s);
     return rc;

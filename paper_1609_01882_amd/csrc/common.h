@@ -98,7 +98,7 @@ int launch_ivf_scan(int m, int tq, int nwaves, int kpad, size_t lds_bytes, const
                     const int64_t *list_off_dev, const int32_t *ext_ids_dev, const int32_t *job_slot_dev,
                     const int32_t *job_q_dev, uint32_t *gthr_dev, float *part_d, int64_t *part_i, int *status,
                     int64_t nq, int nprobe, int64_t *ids_dev, float *dists_dev, bool on_matrix_cores,
-                    hipStream_t s);
+                    bool one_job_per_tile, hipStream_t s);
 // Whether the grouped inverted-file scan of njobs (query, list) jobs runs its Hamming test on the
 // matrix cores; if so *plan receives that kernel's tile shape (16 jobs x 16 waves).
 bool ivf_scan_on_matrix_cores(int m, int ht, int k, int64_t njobs, int nlist, int64_t max_list_len, ScanPlan *plan);

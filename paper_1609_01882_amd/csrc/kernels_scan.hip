@@ -82,6 +82,10 @@ struct ScanArgs {
     const float *coarse;      // [nlist + 1][dim] coarse centroids, then their mean
     uint8_t *job_qcodes;      // [njobs][M] out: query code of each job
     int dim, nlist;
+    // A few jobs, one per tile (latency matters): the tile's unused query slots serve the same
+    // job, each wave feeding the list of slot wave % TQ, so that a list's lock is shared by a
+    // quarter of the waves while the lists fill; the lists are merged when the tile ends.
+    int spread_lists = 0;
 };
 
 // Flat mode: which queries and which part of the database a workgroup works on.  Query tiles
@@ -767,9 +771,11 @@ scan_kernel(ScanArgs a)
         slice_end = t.slice_end;
     }
 
+    const bool spread = IVF && a.spread_lists != 0 && nvq == 1;  // (workgroup-uniform)
     // ---- per-slot state
     if (tid < TQ) {
-        const int gi = tid < nvq ? (int)(IVF ? (int64_t)a.job_q[q0 + tid] : q0 + tid) : -1;
+        const int job = spread ? 0 : tid;
+        const int gi = job < nvq ? (int)(IVF ? (int64_t)a.job_q[q0 + job] : q0 + job) : -1;
         float t0 = __builtin_inff();
         if constexpr (SHARE) {
             if (gi >= 0) t0 = key_dist(__hip_atomic_load(&a.gthr[gi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
@@ -783,6 +789,12 @@ scan_kernel(ScanArgs a)
     if constexpr (IVF) {
         stage_list_tables<M, TQ, NW>(s, a, tile_list, q0, nvq);
         if (tid < nvq * WPC) ((uint32_t *)a.job_qcodes)[q0 * WPC + tid] = s.qcw[tid];
+        if (spread) {  // every slot gets the job's tables and query code
+            PSC_LDS f32x4 *tab = (PSC_LDS f32x4 *)s.lut;
+            for (int e = tid; e < (TQ - 1) * (M * 64); e += NW * 64) tab[M * 64 + e] = tab[e % (M * 64)];
+            if (tid >= WPC && tid < TQ * WPC) s.qcw[tid] = s.qcw[tid % WPC];
+            __syncthreads();
+        }
 #pragma unroll
         for (int q = 0; q < TQ; ++q) {
 #pragma unroll
@@ -811,7 +823,8 @@ scan_kernel(ScanArgs a)
     }
 
     // bit TQ-1-q of a code's TQ-bit field <-> query slot q; only the first nvq slots are real
-    const uint32_t qmask = ((1u << TQ) - 1u) & ~((1u << (TQ - nvq)) - 1u);
+    uint32_t qmask = ((1u << TQ) - 1u) & ~((1u << (TQ - nvq)) - 1u);
+    if (spread) qmask = 1u << (TQ - 1 - wave % TQ);  // the wave's own slot
     uint32_t qmask_all = 0u;
 #pragma unroll
     for (int c = 0; c < CB; ++c) qmask_all |= qmask << (c * TQ);
@@ -983,6 +996,46 @@ scan_kernel(ScanArgs a)
     }
     __syncthreads();
 
+    if (spread) {
+        // ---- one job, TQ lists: every entry goes to its rank in their union (its place in its
+        // own list plus the entries of the other lists below it), the first k ranks are the job's
+        int cnt[TQ], total = 0;
+#pragma unroll
+        for (int t = 0; t < TQ; ++t) {
+            cnt[t] = s.lock[t];
+            total += cnt[t];
+        }
+        const int64_t o = (int64_t)a.job_slot[q0] * a.k;
+        for (int e = tid; e < TQ * a.k; e += NW * 64) {
+            const int t = e / a.k, p = e - t * a.k;
+            int mine = 0;
+#pragma unroll
+            for (int u = 0; u < TQ; ++u) mine = u == t ? cnt[u] : mine;
+            if (p >= mine) continue;
+            const uint64_t ent = s.top[t * a.kpad + p];
+            int rank = p;
+#pragma unroll
+            for (int u = 0; u < TQ; ++u) {
+                if (u == t) continue;
+                int lo = 0, hi = cnt[u];  // number of entries of list u below ent
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (s.top[u * a.kpad + mid] < ent) lo = mid + 1; else hi = mid;
+                }
+                rank += lo;
+            }
+            if (rank < a.k) {
+                a.part_d[o + rank] = entry_dist(ent);
+                a.part_i[o + rank] = (int64_t)entry_id(ent);
+            }
+        }
+        for (int r = tid; r < a.k; r += NW * 64)
+            if (r >= total) {
+                a.part_d[o + r] = __builtin_inff();
+                a.part_i[o + r] = (int64_t)-1;
+            }
+        return;
+    }
     // ---- write the tile's lists (padded) to the workspace
     for (int e = tid; e < nvq * a.k; e += NW * 64) {
         const int q = e / a.k, r = e - q * a.k;
@@ -2134,7 +2187,8 @@ int launch_ivf_scan(int m, int tq, int nwaves, int kpad, size_t lds_bytes, const
                     const void *tiles_dev, const int *ntiles_dev, int64_t max_tiles,
                     const int64_t *list_off_dev, const int32_t *ext_ids_dev, const int32_t *job_slot_dev,
                     const int32_t *job_q_dev, uint32_t *gthr_dev, float *part_d, int64_t *part_i, int *status,
-                    int64_t nq, int nprobe, int64_t *ids_dev, float *dists_dev, bool on_matrix_cores, hipStream_t s)
+                    int64_t nq, int nprobe, int64_t *ids_dev, float *dists_dev, bool on_matrix_cores,
+                    bool one_job_per_tile, hipStream_t s)
 {
     PSC_REQUIRE(((uintptr_t)codes_dev & 15) == 0 && ((uintptr_t)job_qcodes_dev & 15) == 0 &&
                     ((uintptr_t)lut_dev & 15) == 0 && ((uintptr_t)list_tab_dev & 15) == 0,
@@ -2171,6 +2225,7 @@ int launch_ivf_scan(int m, int tq, int nwaves, int kpad, size_t lds_bytes, const
     a.job_slot = job_slot_dev;
     a.job_q = job_q_dev;
     a.gthr = gthr_dev;
+    a.spread_lists = one_job_per_tile ? 1 : 0;
     hipLaunchKernelGGL(init_scan_kernel, dim3((unsigned)((nq + 255) / 256)), dim3(256), 0, s, gthr_dev, nq, a.status);
     if (max_tiles > 0) {
         int rc;
