@@ -223,6 +223,20 @@ def test_grouped_ivf_scan_with_ragged_lists(monkeypatch, route):
         assert (ids == ref["ids"]).mean() > 0.99
 
 
+@pytest.fixture(scope="module")
+def ivf_128bit():
+    import paper_1609_01882_amd as psc
+    return psc, build_ivf(psc, 40_001, 50, seed=75, m=16)
+
+
+@pytest.mark.parametrize("nq,nprobe,ht,k", [(1, 20, 48, 100), (5, 50, 40, 10), (37, 8, 52, 100), (300, 10, 44, 20),
+                                            (2, 3, 128, 7)])
+def test_ivf_search_with_128_bit_codes(ivf_128bit, nq, nprobe, ht, k):
+    """16 sub-quantizers: one job per tile with the candidates spread over the tile's lists (up to 32
+    queries), a few queries, and the grouped scan."""
+    _check_ivf_search(ivf_128bit, nprobe, ht, k, nq=nq)
+
+
 def test_ivf_search_with_a_batch_of_300(ivf):
     """256 queries and more take their coarse distances from the matrix-core kernel (centred
     expansion instead of direct differences): same probed lists up to near-ties, same results."""
