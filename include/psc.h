@@ -234,7 +234,7 @@ int psc_ivf_set_lists(psc_index *idx, const int64_t *offsets_dev, const uint8_t 
  * arg-min of the summed float32 rows, lowest index on ties.
  * The per-list tables (nlist*m KiB) belong to the index's device image and are rebuilt by the
  * first search after the codebook or the coarse centroids changed (that call blocks).
- * Up to 2048 (query, list) pairs are scanned one per workgroup in order of coarse rank (low
+ * Up to 4096 (query, list) pairs are scanned one per workgroup in order of coarse rank (low
  * latency for a few queries); larger batches are grouped by list so that up to 16 queries share
  * every code load.
  * The workspace (psc_ivf_search_workspace_bytes: coarse distances nq*nlist*4 bytes, the

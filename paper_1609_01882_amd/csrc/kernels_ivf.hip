@@ -14,8 +14,9 @@ namespace {
 
 constexpr int kRows = 16;  // rows per workgroup in the distance kernels
 // Up to this many rows (queries) the coarse stage runs the kernels built for latency: many
-// workgroups per row instead of many rows per workgroup.
-constexpr int64_t kFewRowsMax = 32;
+// workgroups per row instead of many rows per workgroup (from 256 rows the distances come from the
+// matrix-core kernel where it is built for the dimension; the selection keeps a workgroup per row).
+constexpr int64_t kFewRowsMax = 512;
 
 // dist[r][c] = || x_r - cent_c ||^2 for a tile of kRows rows and 256 centroids per workgroup.
 // Rows sit in LDS (read as broadcasts), each thread walks its own centroid row.

@@ -1562,7 +1562,11 @@ merge_kernel(const float *__restrict__ part_d, const int64_t *__restrict__ part_
 // barrier per bit is enough); if more entries than needed share it, the same search over the bits
 // of the id finds the last id that belongs.  The selected entries go to LDS in any order and each
 // is written to its rank.
-constexpr int64_t kMergeSelectQueries = 32;      // up to this many queries
+constexpr int64_t kMergeSelectQueries = 32;      // up to this many queries,
+constexpr int64_t kMergeSelectManyQueries = 512; // or this many if each has 32 lists or more (probed lists:
+                                                 // 10k queries x 64 probes of 100M vectors, whole search, with the
+                                                 // wave above / with this kernel: 64 queries 0.45 / 0.34 ms,
+                                                 // 256: 0.61 / 0.57, 512: 0.84 / 0.81, 1024: 1.31 / 1.32)
 constexpr int64_t kMergeSelectEntries = 32768;   // and this many entries per query
 // (its forty-odd counting steps take about 20 us whatever k is; the wave above takes 0.4 us per
 //  result: measured 32 against 42 us at k = 100, 20 against 5 us at k = 10)
@@ -1673,7 +1677,8 @@ int launch_merge(const float *part_d, const int64_t *part_i, int64_t nq, int nli
 {
     PSC_REQUIRE(nlists >= 1 && nlists <= 1024, "between 1 and 1024 partial lists per query, got %d", nlists);
     const dim3 grid((unsigned)nq), block(64);
-    if (nq <= kMergeSelectQueries && (int64_t)nlists * k <= kMergeSelectEntries && k >= kMergeSelectMinK && k <= 1024) {
+    if ((nq <= kMergeSelectQueries || (nq <= kMergeSelectManyQueries && nlists >= 32)) &&
+        (int64_t)nlists * k <= kMergeSelectEntries && k >= kMergeSelectMinK && k <= 1024) {
         if ((int64_t)nlists * k <= 8 * 1024)
             hipLaunchKernelGGL(merge_select_kernel<8>, grid, dim3(1024), 0, s, part_d, part_i, nlists, k, status, ids, dists);
         else

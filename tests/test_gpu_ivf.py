@@ -144,7 +144,7 @@ def _check_ivf_search(fixture, nprobe, ht, k, nq=37):
 @pytest.mark.parametrize("nq,nprobe,ht,k", [(1, 64, 24, 100), (1, 8, 64, 10), (3, 33, 26, 64), (8, 64, 28, 130),
                                             (8, 1, 20, 1), (5, 300, 30, 100)])
 def test_ivf_search_with_a_handful_of_queries(ivf_many_lists, nq, nprobe, ht, k):
-    """Up to 32 queries run the coarse stage built for latency (many workgroups per query for the
+    """A handful of queries (the same kernels serve up to 512) run the coarse stage built for latency (many workgroups per query for the
     distances, a whole workgroup per query for the selection of the lists) and, from k = 64, the
     selecting merge."""
     _check_ivf_search(ivf_many_lists, nprobe, ht, k, nq=nq)
@@ -178,10 +178,10 @@ def test_probe_selection_with_tied_coarse_distances():
 
 
 @pytest.mark.parametrize("route", ["mfma", "popcount"])
-@pytest.mark.parametrize("nq,nprobe,ht,k", [(300, 8, 24, 10), (1000, 8, 20, 100), (700, 37, 26, 136), (500, 5, 0, 1),
-                                            (2100, 1, 30, 7)])
+@pytest.mark.parametrize("nq,nprobe,ht,k", [(600, 8, 24, 10), (1000, 8, 20, 100), (700, 37, 26, 136), (900, 5, 0, 1),
+                                            (4200, 1, 30, 7)])
 def test_grouped_ivf_scan_on_both_filter_routes(ivf, monkeypatch, route, nq, nprobe, ht, k):
-    """More than 2048 (query, list) jobs are grouped by list; the Hamming test of the grouped scan
+    """More than 4096 (query, list) jobs are grouped by list; the Hamming test of the grouped scan
     runs either as xor/popcount (tiles of 4 jobs) or on the matrix cores (tiles of 16 jobs): same
     survivors, same results."""
     monkeypatch.setenv("PSC_FILTER_ROUTE", route)
@@ -209,7 +209,7 @@ def test_grouped_ivf_scan_with_ragged_lists(monkeypatch, route):
     lcodes = W.random_codes(n, 8, seed=4)
     lids = rng.permutation(n).astype(np.int32)
     idx.ivf_set_lists(_dev(offsets), _dev(lcodes), _dev(lids))
-    nq = 150                                          # 150 x 15 = 2250 jobs
+    nq = 300                                          # 300 x 15 = 4500 jobs
     xq = (rng.random(size=(nq, 128)) * 100).astype(np.float32)
     for ht, k in ((26, 50), (63, 100)):
         ids, d, probed, qcodes = idx.ivf_search(_dev(xq), nlist, ht, k, want_debug=True)
@@ -243,7 +243,7 @@ def test_ivf_search_with_a_batch_of_300(ivf):
     _check_ivf_search(ivf, 8, 24, 10, nq=300)
 
 
-@pytest.mark.parametrize("dim,nq", [(32, 300), (64, 300), (96, 300), (48, 5), (16, 3), (96, 8), (48, 40)])
+@pytest.mark.parametrize("dim,nq", [(32, 300), (64, 300), (96, 300), (48, 5), (16, 3), (96, 8), (48, 40), (48, 600)])
 def test_probed_lists_in_other_dimensions(dim, nq):
     """The coarse stage in other dimensions -- those the matrix-core kernels are built for (batches of
     300 queries), and a handful or a few dozen queries in dimensions that are no multiple of 32 (the

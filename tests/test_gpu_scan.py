@@ -179,7 +179,7 @@ def test_many_slices_for_few_queries(psc):
                                              (8, 400_009, 128, "float"), (2, 70_001, 1024, "int"),
                                              (1, 300, 500, "int")])
 def test_selecting_merge_for_a_handful_of_queries(psc, nq, n, k, lut_kind):
-    """Up to 32 queries and k >= 64: the partial lists of the slices are merged by a workgroup that
+    """A handful of queries (up to 32, or 512 with many lists each) and k >= 64: the partial lists of the slices are merged by a workgroup that
     selects the k smallest (distance, id) pairs.  Integer tables put hundreds of entries at the
     k-th distance, so the last place is decided by the id; short databases leave padding."""
     codes, qcodes, lut = _rand_problem(8, n, nq, seed=77 + k, lut_kind=lut_kind)
