@@ -184,3 +184,25 @@ def test_kmeans_ends_on_a_fixed_point():
         assert (a == c).any()
         assert np.allclose(cent[c], x[a == c].mean(axis=0), rtol=0, atol=1e-9)
     assert np.isclose(obj[-1], d.min(axis=1).sum(), rtol=1e-12)
+
+
+def test_kmeans_from_a_given_start():
+    """`start` replaces the seeded draw: one iteration from hand-built centroids has a closed-form
+    result (the seed must then play no part), including the order of the returned rows, the
+    objective measured at the assignment step, and the refill of a cell the start leaves empty."""
+    pts = np.array([[0.0, 0.0], [2.0, 0.0], [0.0, 2.0], [10.0, 10.0], [12.0, 10.0], [20.0, 0.0]])
+    start = np.array([[11.0, 9.0], [1.0, 1.0], [21.0, 1.0]])   # cell 0: rows 3,4; cell 1: rows 0,1,2; cell 2: row 5
+    for seed in (0, 1, 99):
+        cent, obj = O.kmeans(pts, 3, 1, seed=seed, start=start)
+        assert np.array_equal(cent, [[11.0, 10.0], [2.0 / 3.0, 2.0 / 3.0], [20.0, 0.0]])
+        # squared distances to the *starting* centroids: rows 0-2 -> 2 each, rows 3,4 -> 2 each, row 5 -> 2
+        assert obj == [12.0]
+    cent, obj = O.kmeans(pts, 3, 2, seed=5, start=start)
+    assert np.allclose(obj, [12.0, 2.0 + (4 * 2 / 9 + 2 * (16 / 9 + 4 / 9)) + 0.0], rtol=1e-14)
+    assert not np.shares_memory(cent, start) and start[0, 0] == 11.0   # the caller's array is left alone
+    # a start that leaves cell 1 empty (ties and nearer rows all go to cell 0): it takes the member
+    # of the crowded cell that lies farthest from that cell's centroid, here row 3
+    line = np.array([[0.0], [1.0], [2.0], [9.0]])
+    cent, obj = O.kmeans(line, 2, 1, seed=0, start=np.array([[1.0], [50.0]]))
+    assert obj == [1.0 + 0.0 + 1.0 + 64.0]
+    assert cent[:, 0].tolist() == [3.0, 9.0]   # donor mean still counts the row it gives away
