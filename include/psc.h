@@ -14,7 +14,14 @@
  *   - Pointers named *_dev are device (HBM) pointers, *_host are host pointers.
  *     Every buffer is owned by the caller; the library allocates no device
  *     memory on the search path (workspaces are passed in and sized by the
- *     *_workspace_bytes functions).
+ *     *_workspace_bytes functions).  The one exception is the index's own device
+ *     image (codebook, coarse centroids, per-list tables): the first device call
+ *     after the codebook or the coarse centroids changed uploads it, which
+ *     allocates and blocks (it waits for all earlier work of the device, so that
+ *     no kernel still reads the image it replaces).  psc_prepare does that upload
+ *     ahead of time.
+ *   - An index may be used from several host threads; training and set_* calls
+ *     must not run concurrently with other calls on the same index.
  *   - All arrays are dense, row-major.  A product quantizer has m sub-quantizers
  *     (m = 8 or 16) of exactly 256 centroids; a code is m bytes, byte j holding
  *     the index chosen by sub-quantizer j.  Code arrays and query-code arrays
@@ -113,6 +120,11 @@ int psc_optimize_index_assignment(psc_index *idx, int64_t n_iter, double t0, dou
 int psc_set_codebook(psc_index *idx, const float *cb_host);
 int psc_get_codebook(const psc_index *idx, float *cb_host);
 
+/* Bring the index's device image up to date now (codebook; coarse centroids and per-list tables
+ * if an inverted file is set up), so that later device calls neither allocate nor block.
+ * Synchronous. */
+int psc_prepare(const psc_index *idx, psc_stream stream);
+
 /* ------------------------------------------------------------------ device operations */
 /* PQ encoding: codes_dev [n][m], byte j = nearest centroid of sub-quantizer j
  * to sub-vector j of x_dev [n][dim] (float32), lowest index on equal distance.
@@ -162,9 +174,16 @@ int psc_threshold_for_rate(const int64_t *hist_host, int nbits, double max_keep_
  * query's current k-th best distance.
  * The Hamming test is exact on every route the library takes: xor / popcount on the vector
  * units, or (64-bit codes, 9 queries or more, selective thresholds) an int8 dot product of
- * +-1 expansions on the matrix cores, whose sign gives the same verdict.  The environment
- * variable PSC_FILTER_ROUTE = "popcount" | "mfma", read at every call, forces one of the two
- * where both apply (a measurement aid; results do not depend on it). */
+ * +-1 expansions on the matrix cores, whose sign gives the same verdict.
+ * psc_set_filter_route forces one of the two where both apply (process-wide; a measurement aid,
+ * results do not depend on it); psc_last_scan_route names the kernel, tile shape, database
+ * slices and workgroup count the calling thread's last scan launched, e.g.
+ * "scan_mfma_kernel m=8 tq=16 waves=16 slices=2 tiles=738" ("" before the first scan). */
+#define PSC_ROUTE_AUTO 0
+#define PSC_ROUTE_POPCOUNT 1
+#define PSC_ROUTE_MFMA 2
+int psc_set_filter_route(int route);
+const char *psc_last_scan_route(void);
 size_t psc_scan_workspace_bytes(int m, int64_t nq, int64_t n, int k);
 int psc_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t nq,
              const uint8_t *codes_dev, int64_t n, int ht, int k, int64_t *ids_dev,
@@ -214,7 +233,8 @@ int psc_ivf_assign_encode(const psc_index *idx, const float *x_dev, int64_t n, i
  * stored code, offsets_dev [nlist+1] (int64, device memory) list l = rows offsets[l] ..
  * offsets[l+1]-1.  codes_dev must be 16-byte aligned.  The call copies the offsets to the host
  * once (synchronously) to check them (0 first, n last, never decreasing) and to note the longest
- * list, which decides which scan kernels can serve the index. */
+ * list, which decides which scan kernels can serve the index.  No list may hold more than 2^27
+ * codes (PSC_EINVAL): the scan addresses a code by its position inside its list. */
 int psc_ivf_set_lists(psc_index *idx, const int64_t *offsets_dev, const uint8_t *codes_dev,
                       const int32_t *ids_dev, int64_t n);
 
@@ -225,7 +245,7 @@ int psc_ivf_set_lists(psc_index *idx, const int64_t *offsets_dev, const uint8_t 
  * (distance, id) over the union of the probed lists, ids taken from ids_dev.  No cap on lists
  * or distance evaluations.  Both exact forms of the Hamming test of psc_scan exist here too (the
  * matrix-core one is taken for 64-bit codes, thresholds up to 17 and a dozen or more (query,
- * list) pairs per list; PSC_FILTER_ROUTE overrides as for psc_scan).
+ * list) pairs per list; psc_set_filter_route overrides as for psc_scan).
  * probed_out_dev (may be NULL) [nq][nprobe] int32 receives the probed lists in ascending
  * coarse distance; qcodes_out_dev (may be NULL) [nq][nprobe][m] the per-list query codes.
  * The tables are never stored per (query, list): with o the mean coarse centroid they split

@@ -10,9 +10,11 @@ from .binding import (  # noqa: F401
     exported_symbols,
     hamming_filter,
     hamming_histogram,
+    last_scan_route,
     lib_path,
     scan,
     scan_workspace_bytes,
+    set_filter_route,
     threshold_for_rate,
     version,
     workspace_status,

@@ -35,3 +35,56 @@ def trained_index(psc, cfg, train_rows, threads=16):
     idx.optimize_index_assignment(seed=cfg.seed)
     log(f"[setup] PQ + index assignment in {time.time() - t0:.1f}s")
     return idx
+
+
+def encode_database(idx, cfg, n, dev, chunk=1_000_000, threads=16):
+    """Codes [n][m] of the workload's database stream, generated and encoded chunk by chunk so the
+    raw vectors are never resident all at once."""
+    import torch
+
+    codes = torch.empty((n, cfg.m), dtype=torch.uint8, device=dev)
+    for s in range(0, n, chunk):
+        c = min(chunk, n - s)
+        idx.encode(torch.from_numpy(cfg.vectors("db", n=c, start=s, threads=threads)).to(dev), out=codes[s:s + c])
+    return codes
+
+
+def build_ivf_workload(psc, cfg, n, dev, coarse_train=500_000, coarse_iters=10, pq_train=None, pq_iters=20,
+                       sa_iters=500_000, threads=16, chunk=4_000_000):
+    """The inverted-file workload (Section 4.3): coarse quantizer, product quantizer of the
+    residuals with optimised index assignment, and the n database vectors -- drawn on the GPU --
+    assigned, encoded and grouped into lists.  Returns (index, offsets, list codes, list ids, list
+    sizes); the index borrows the three tensors."""
+    import torch
+
+    import workloads as W
+
+    t0 = time.time()
+    idx = psc.Index(cfg.dim, cfg.m)
+    idx.ivf_train_coarse(W.sift_like(coarse_train, cfg.seed, 7, threads=threads), cfg.nlist, iters=coarse_iters,
+                         seed=cfg.seed)
+    coarse = idx.ivf_get_coarse()
+    xt = cfg.vectors("train", n=pq_train, threads=threads)
+    lt, _ = idx.ivf_assign_encode(torch.from_numpy(xt).to(dev), want_codes=False)
+    idx.train_pq(xt - coarse[lt.cpu().numpy()], iters=pq_iters, seed=cfg.seed)   # PQ of the residuals
+    idx.optimize_index_assignment(n_iter=sa_iters, seed=cfg.seed)
+    log(f"[setup] coarse quantizer, residual PQ, index assignment in {time.time() - t0:.1f}s")
+    t0 = time.time()
+    list_no = torch.empty(n, dtype=torch.int32, device=dev)
+    codes = torch.empty((n, cfg.m), dtype=torch.uint8, device=dev)
+    for s in range(0, n, chunk):
+        c = min(chunk, n - s)
+        ln, cd = idx.ivf_assign_encode(W.sift_like_torch(c, cfg.seed, 2, start=s, device=dev))
+        list_no[s:s + c] = ln
+        codes[s:s + c] = cd
+    order = torch.sort(list_no.to(torch.int64), stable=True).indices
+    counts = torch.bincount(list_no.to(torch.int64), minlength=cfg.nlist)
+    offsets = torch.zeros(cfg.nlist + 1, dtype=torch.int64, device=dev)
+    offsets[1:] = torch.cumsum(counts, 0)
+    lcodes, lids = codes[order].contiguous(), order.to(torch.int32).contiguous()
+    del codes, order, list_no
+    idx.ivf_set_lists(offsets, lcodes, lids)
+    torch.cuda.synchronize()
+    log(f"[setup] {n} vectors assigned, encoded and grouped into lists in {time.time() - t0:.1f}s "
+        f"(list sizes {counts.min().item()} / {counts.float().mean().item():.0f} / {counts.max().item()})")
+    return idx, offsets, lcodes, lids, counts

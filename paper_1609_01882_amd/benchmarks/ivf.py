@@ -20,7 +20,7 @@ def main():
 
     import paper_1609_01882_amd as psc
     import workloads as W
-    from ._common import log, time_ms
+    from ._common import build_ivf_workload, log, time_ms
 
     cfg = W.get_config("ivf")
     n = args.n or cfg.n_db
@@ -28,34 +28,7 @@ def main():
     threads = min(16, os.cpu_count() or 1)
     dev = torch.device("cuda:0")
 
-    t0 = time.time()
-    xt = cfg.vectors("train", threads=threads)
-    idx = psc.Index(cfg.dim, cfg.m)
-    idx.ivf_train_coarse(W.sift_like(500_000, cfg.seed, 7, threads=threads), nlist, iters=10, seed=cfg.seed)
-    coarse = idx.ivf_get_coarse()
-    lt, _ = idx.ivf_assign_encode(torch.from_numpy(xt).to(dev), want_codes=False)
-    idx.train_pq(xt - coarse[lt.cpu().numpy()], iters=20, seed=cfg.seed)   # PQ of the residuals
-    idx.optimize_index_assignment(seed=cfg.seed)
-    log(f"[setup] coarse quantizer, residual PQ, index assignment in {time.time() - t0:.1f}s")
-
-    t0 = time.time()
-    list_no = torch.empty(n, dtype=torch.int32, device=dev)
-    codes = torch.empty((n, cfg.m), dtype=torch.uint8, device=dev)
-    for s in range(0, n, 4_000_000):
-        c = min(4_000_000, n - s)
-        ln, cd = idx.ivf_assign_encode(W.sift_like_torch(c, cfg.seed, 2, start=s, device=dev))
-        list_no[s:s + c] = ln
-        codes[s:s + c] = cd
-    order = torch.sort(list_no.to(torch.int64), stable=True).indices
-    counts = torch.bincount(list_no.to(torch.int64), minlength=nlist)
-    offsets = torch.zeros(nlist + 1, dtype=torch.int64, device=dev)
-    offsets[1:] = torch.cumsum(counts, 0)
-    lcodes, lids = codes[order].contiguous(), order.to(torch.int32).contiguous()
-    del codes, order, list_no
-    idx.ivf_set_lists(offsets, lcodes, lids)
-    torch.cuda.synchronize()
-    log(f"[setup] {n} vectors assigned, encoded and grouped into lists in {time.time() - t0:.1f}s "
-        f"(list sizes {counts.min().item()} / {counts.float().mean().item():.0f} / {counts.max().item()})")
+    idx, offsets, lcodes, lids, counts = build_ivf_workload(psc, cfg, n, dev, threads=threads)
 
     xq = torch.from_numpy(cfg.vectors("query", n=nq, threads=threads)).to(dev)
     ws = torch.empty(idx.ivf_search_workspace_bytes(nq, nprobe, k), dtype=torch.uint8, device=dev)

@@ -39,6 +39,9 @@ def _load():
     sigs = {
         "psc_version": (i32, []),
         "psc_last_error": (C.c_char_p, []),
+        "psc_set_filter_route": (i32, [i32]),
+        "psc_last_scan_route": (C.c_char_p, []),
+        "psc_prepare": (i32, [vp, vp]),
         "psc_create": (i32, [C.POINTER(vp), i32, i32]),
         "psc_destroy": (None, [vp]),
         "psc_train_pq": (i32, [vp, vp, i64, i32, u64]),
@@ -78,7 +81,7 @@ def _load():
 def exported_symbols():
     """Names this binding expects the library to export."""
     _load()
-    return ["psc_version", "psc_last_error", "psc_create", "psc_destroy", "psc_train_pq",
+    return ["psc_version", "psc_last_error", "psc_set_filter_route", "psc_last_scan_route", "psc_prepare", "psc_create", "psc_destroy", "psc_train_pq",
             "psc_train_pq_device", "psc_ivf_train_coarse_device",
             "psc_optimize_index_assignment", "psc_set_codebook", "psc_get_codebook", "psc_encode",
             "psc_build_lut", "psc_hamming_filter", "psc_hamming_histogram", "psc_threshold_for_rate",
@@ -110,6 +113,19 @@ def _workspace(nbytes: int, device) -> torch.Tensor:
 
 def version() -> int:
     return _load().psc_version()
+
+
+ROUTES = {"auto": 0, "popcount": 1, "mfma": 2}
+
+
+def set_filter_route(route: str) -> None:
+    """Force one of the two exact Hamming filters where both apply ("auto": the library's rule)."""
+    _check(_load().psc_set_filter_route(ROUTES[route]))
+
+
+def last_scan_route() -> str:
+    """Kernel, tile shape, slices and workgroups of this thread's last scan."""
+    return _load().psc_last_scan_route().decode()
 
 
 class Index:
@@ -163,6 +179,10 @@ class Index:
         cb = np.empty((self.m, 256, self.dsub), dtype=np.float32)
         _check(_load().psc_get_codebook(self._h, cb.ctypes.data_as(C.c_void_p)))
         return cb
+
+    def prepare(self):
+        """Upload the index's device image now, so that later calls neither allocate nor block."""
+        _check(_load().psc_prepare(self._h, _stream()))
 
     # -- device operations
     def encode(self, x: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:

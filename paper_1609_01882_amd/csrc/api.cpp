@@ -1,6 +1,7 @@
 // C ABI of libpsc: argument checking and dispatch.  See include/psc.h for the contract.
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <thread>
@@ -33,6 +34,7 @@ static int mark_codebook_changed(psc_index *idx)
 
 static int sync_codebook_to_device(const psc_index *idx)
 {
+    std::lock_guard<std::mutex> guard(idx->image_lock);
     if (idx->dev_current) return PSC_OK;
     // device image: the codebook, the codebook centred on each sub-quantizer's mean centroid,
     // and those means (the last two feed the matrix-core table kernel)
@@ -51,6 +53,7 @@ static int sync_codebook_to_device(const psc_index *idx)
                 img[n + j * sq + (size_t)c * idx->dsub + t] = idx->cb_host[j * sq + (size_t)c * idx->dsub + t] - mu[t];
     }
     if (!idx->cb_dev) PSC_HIP_TRY(hipMalloc((void **)&idx->cb_dev, img.size() * sizeof(float)));
+    else PSC_HIP_TRY(hipDeviceSynchronize());  // kernels enqueued earlier on any stream may still read the old image
     PSC_HIP_TRY(hipMemcpy(idx->cb_dev, img.data(), img.size() * sizeof(float), hipMemcpyHostToDevice));
     idx->dev_current = true;
     return PSC_OK;
@@ -88,6 +91,16 @@ extern "C" {
 int psc_version(void) { return 100; }
 
 const char *psc_last_error(void) { return g_error.c_str(); }
+
+int psc_set_filter_route(int route)
+{
+    PSC_REQUIRE(route == PSC_ROUTE_AUTO || route == PSC_ROUTE_POPCOUNT || route == PSC_ROUTE_MFMA,
+                "route must be PSC_ROUTE_AUTO, PSC_ROUTE_POPCOUNT or PSC_ROUTE_MFMA");
+    g_filter_route.store(route, std::memory_order_relaxed);
+    return PSC_OK;
+}
+
+const char *psc_last_scan_route(void) { return last_scan_route(); }
 
 int psc_create(psc_index **out, int dim, int m)
 {
@@ -401,6 +414,7 @@ int psc_knn_graph(const psc_index *idx, const float *x_dev, const uint8_t *codes
 // ---------------------------------------------------------------------------------------------
 static int sync_coarse_to_device(const psc_index *idx)
 {
+    std::lock_guard<std::mutex> guard(idx->image_lock);
     if (idx->coarse_current) return PSC_OK;
     // device image: the nlist centroids, then their mean (the origin the search's tables are taken from)
     const size_t dim = (size_t)idx->dim, nl = (size_t)idx->nlist;
@@ -413,6 +427,7 @@ static int sync_coarse_to_device(const psc_index *idx)
     }
     const size_t bytes = img.size() * sizeof(float);
     if (idx->coarse_dev) {
+        PSC_HIP_TRY(hipDeviceSynchronize());  // earlier kernels may still read the old centroids
         PSC_HIP_TRY(hipFree(idx->coarse_dev));
         idx->coarse_dev = nullptr;
     }
@@ -426,7 +441,9 @@ static int sync_coarse_to_device(const psc_index *idx)
 // codebook or the coarse centroids changed (blocking, as their uploads are).
 static int sync_list_tables(const psc_index *idx, hipStream_t s)
 {
+    std::lock_guard<std::mutex> guard(idx->image_lock);
     if (idx->list_tab_current) return PSC_OK;
+    if (idx->list_tab_dev) PSC_HIP_TRY(hipDeviceSynchronize());  // earlier searches may still read the old tables
     if (idx->list_tab_dev && idx->list_tab_nlist != idx->nlist) {
         PSC_HIP_TRY(hipFree(idx->list_tab_dev));
         idx->list_tab_dev = nullptr;
@@ -450,6 +467,16 @@ static int need_coarse(const psc_index *idx)
         return PSC_ESTATE;
     }
     return sync_coarse_to_device(idx);
+}
+
+int psc_prepare(const psc_index *idx, psc_stream stream)
+{
+    int rc = need_codebook(idx);
+    if (rc != PSC_OK) return rc;
+    if (idx->nlist == 0) return PSC_OK;
+    rc = need_coarse(idx);
+    if (rc != PSC_OK) return rc;
+    return sync_list_tables(idx, (hipStream_t)stream);
 }
 
 int psc_ivf_set_coarse(psc_index *idx, const float *centroids_host, int nlist)
@@ -731,6 +758,7 @@ int psc_ivf_set_lists(psc_index *idx, const int64_t *offsets_dev, const uint8_t 
         set_error("out of host memory");
         return PSC_ENOMEM;
     }
+    PSC_REQUIRE(longest <= ((int64_t)1 << 27), "a list holds %lld codes; at most 2^27 per list", (long long)longest);
     idx->list_off_dev = offsets_dev;
     idx->list_codes_dev = codes_dev;
     idx->list_ids_dev = ids_dev;

@@ -3,9 +3,11 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <mutex>
 #include <vector>
 
 #include "psc.h"
@@ -62,6 +64,10 @@ int launch_lut_mfma(const float *cbc_dev, const float *mu_dev, int dim, int m, c
 int launch_row_argmin(const float *lut_dev, int64_t nrows_total, uint8_t *codes_dev, hipStream_t s);
 
 // ---- device launchers (kernels_scan.hip)
+// Which Hamming filter the scans take where both apply: PSC_ROUTE_* of psc_set_filter_route.
+extern std::atomic<int> g_filter_route;
+// The kernel and tile shape the calling thread's last scan launched ("" before the first).
+const char *last_scan_route();
 struct ScanPlan {
     int tq = 0;          // queries per workgroup tile
     int nwaves = 0;      // waves per workgroup
@@ -175,6 +181,9 @@ int launch_mean_centroid(float *cent_dev, int ncent, int dim, hipStream_t s);
 }  // namespace psc
 
 struct psc_index {
+    // guards the lazily refreshed device image below (the `mutable` members): two host threads
+    // may issue their first device call on one index at the same time
+    mutable std::mutex image_lock;
     int dim = 0, m = 0, dsub = 0;
     int device = 0;
     bool has_codebook = false;

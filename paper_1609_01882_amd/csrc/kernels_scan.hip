@@ -21,6 +21,7 @@
 // Partial lists (one per query and slice) go to the workspace; a second kernel merges them.
 //
 // Ordering everywhere: (distance, id) ascending, lower id first on equal distance.
+#include <atomic>
 #include <cstdlib>
 #include <cstring>
 #include <type_traits>
@@ -1903,7 +1904,19 @@ int dispatch_scan(int m, int tq, int nwaves, const ScanArgs &a, int64_t ntiles, 
 
 constexpr size_t kLdsBudget = 160 * 1024;
 
+thread_local char g_route[96] = "";
+
+void note_route(const char *kernel, int m, int tq, int nwaves, int nslice, int64_t ntiles)
+{
+    snprintf(g_route, sizeof g_route, "%s m=%d tq=%d waves=%d slices=%d tiles=%lld", kernel, m, tq, nwaves, nslice,
+             (long long)ntiles);
+}
+
 }  // namespace
+
+std::atomic<int> g_filter_route{PSC_ROUTE_AUTO};
+
+const char *last_scan_route() { return g_route; }
 
 // Tile shape and database slices.
 // Shapes (queries per tile x waves per workgroup), per kind of scan, first one that fits:
@@ -2077,12 +2090,11 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
     // Matrix-core filter: 64-bit codes, more than one tile of queries, k small enough for its
     // 16-query tile, and few survivors (beyond about one pair in ten the queue and the lists
     // decide the time and the two filters tie: measured equal at ht = 26, behind at ht = 28).
-    // PSC_FILTER_ROUTE=popcount|mfma in the environment overrides the rule (for measurements).
+    // psc_set_filter_route overrides the rule (for measurements).
     bool mfma = !dense && m == 8 && nq >= kMfmaMinQueries && random_code_survival(8 * m, ht) < 0.10;
-    if (const char *route = std::getenv("PSC_FILTER_ROUTE")) {
-        if (!std::strcmp(route, "popcount")) mfma = false;
-        if (!std::strcmp(route, "mfma")) mfma = !dense && m == 8 && nq >= kMfmaMinQueries;
-    }
+    const int forced = g_filter_route.load(std::memory_order_relaxed);
+    if (forced == PSC_ROUTE_POPCOUNT) mfma = false;
+    if (forced == PSC_ROUTE_MFMA) mfma = !dense && m == 8 && nq >= kMfmaMinQueries;
     if (mfma) {
         rc = plan_scan(m, nq, n, k, kScanFusedMfma, &p);
         mfma = rc == PSC_OK;  // (k too large for the shape: the popcount kernel's shapes take over)
@@ -2154,6 +2166,8 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
         rc = p.nslice >= 4 ? dispatch_scan<false, true>(m, p.tq, p.nwaves, a, p.ntiles, p.lds_bytes, s)
                            : dispatch_scan<false, false>(m, p.tq, p.nwaves, a, p.ntiles, p.lds_bytes, s);
     if (rc != PSC_OK) return rc;
+    note_route(ht >= nbits ? "adc_kernel" : dense ? "adc_kernel+filter" : mfma ? "scan_mfma_kernel" : "scan_kernel",
+               m, p.tq, p.nwaves, p.nslice, p.ntiles);
     return launch_merge(a.part_d, a.part_i, nq, p.nslice, k, a.status, ids_dev, dists_dev, s);
 }
 
@@ -2166,15 +2180,14 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
 // / 10k queries x 64 probes, k = 100, whole search, xor/popcount against matrix cores:
 // ht = 0: 5.2 / 4.5 ms, 16: 5.4 / 4.9, 20: 7.1 / 9.0, 24: 8.6 / 10.5 (k = 1: 6.2 / 6.2).
 // Hence thresholds that let fewer than one random pair in 10^4 through (ht <= 17).
-// PSC_FILTER_ROUTE=popcount|mfma overrides the rule where the kernel can run at all.
+// psc_set_filter_route overrides the rule where the kernel can run at all.
 bool ivf_scan_on_matrix_cores(int m, int ht, int k, int64_t njobs, int nlist, int64_t max_list_len, ScanPlan *plan)
 {
     if (m != 8 || ht >= 64 || max_list_len > kMfmaMaxSliceLen || njobs < kMfmaMinQueries) return false;
     bool take = njobs >= 12 * (int64_t)nlist && random_code_survival(64, ht) < 1e-4;
-    if (const char *route = std::getenv("PSC_FILTER_ROUTE")) {
-        if (!std::strcmp(route, "popcount")) take = false;
-        if (!std::strcmp(route, "mfma")) take = true;
-    }
+    const int forced = g_filter_route.load(std::memory_order_relaxed);
+    if (forced == PSC_ROUTE_POPCOUNT) take = false;
+    if (forced == PSC_ROUTE_MFMA) take = true;
     if (!take) return false;
     ScanPlan p;
     if (plan_scan(m, njobs, max_list_len, k, kScanFusedMfma, &p) != PSC_OK) return false;  // (k too large)
@@ -2242,6 +2255,7 @@ int launch_ivf_scan(int m, int tq, int nwaves, int kpad, size_t lds_bytes, const
         }
         if (rc != PSC_OK) return rc;
     }
+    note_route(on_matrix_cores ? "scan_mfma_kernel+lists" : "scan_kernel+lists", m, tq, nwaves, 1, max_tiles);
     return launch_merge(part_d, part_i, nq, nprobe, k, status, ids_dev, dists_dev, s);
 }
 

@@ -12,6 +12,14 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X")
 
 
+@pytest.fixture
+def force_route():
+    """Force one of the two exact Hamming filters for the duration of a test."""
+    import paper_1609_01882_amd as psc
+    yield psc.set_filter_route
+    psc.set_filter_route("auto")
+
+
 @pytest.fixture(scope="session")
 def tiny_pq():
     """A small trained product quantizer + polysemous renumbering from the oracle, on

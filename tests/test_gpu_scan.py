@@ -78,16 +78,19 @@ def test_scan_random_codes(psc, m, n, nq, k, lut_kind):
     (50_000, 16, 100, "float"),     # exactly one full tile
     (1_000_001, 48, 20, "float"),   # several slices per query tile
 ])
-def test_both_filter_routes(psc, monkeypatch, route, n, nq, k, lut_kind):
+def test_both_filter_routes(psc, force_route, route, n, nq, k, lut_kind):
     """The Hamming test runs either as xor/popcount or on the matrix cores; the library picks by
-    shape and threshold.  Here each route is forced in turn (PSC_FILTER_ROUTE) on 64-bit codes
+    shape and threshold.  Here each route is forced in turn (psc_set_filter_route) on 64-bit codes
     with 9 queries or more and must give the oracle's result at every threshold, including
     those the rule would hand to the other route."""
-    monkeypatch.setenv("PSC_FILTER_ROUTE", route)
+    force_route(route)
     codes, qcodes, lut = _rand_problem(8, n, nq, seed=900 + k, lut_kind=lut_kind)
     for ht in (0, 9, 16, 22, 24, 27, 31, 33):
         print(f"case route={route} n={n} nq={nq} k={k} ht={ht}", flush=True)
         got_ids, got_d = _run(psc, lut, qcodes, codes, ht, k)
+        # the library says which kernel it launched: the forced filter below the dense route's thresholds
+        took = psc.last_scan_route().split()[0]
+        assert took == ("adc_kernel+filter" if ht >= 31 else "scan_mfma_kernel" if route == "mfma" else "scan_kernel"), took
         ref = O.scan(lut.astype(np.float64), qcodes, codes, ht, k)
         nd = assert_topk_matches(got_ids, got_d, ref, lut.astype(np.float64), qcodes, codes, ht,
                                  what=f"route={route} ht={ht} k={k}")
@@ -95,10 +98,10 @@ def test_both_filter_routes(psc, monkeypatch, route, n, nq, k, lut_kind):
             assert nd == 0 and np.array_equal(got_d[ref["ids"] >= 0], ref["dists"][ref["ids"] >= 0])
 
 
-def test_survivor_set_on_the_matrix_cores(psc, monkeypatch):
+def test_survivor_set_on_the_matrix_cores(psc, force_route):
     """k above the number of survivors: the matrix-core route lists exactly the survivor set, for
     thresholds on both sides of every bit count the +-1 dot product can take near them."""
-    monkeypatch.setenv("PSC_FILTER_ROUTE", "mfma")
+    force_route("mfma")
     codes, qcodes, lut = _rand_problem(8, 40_000, 33, seed=77, lut_kind="float")
     for ht in (17, 18, 19, 20):
         ref = O.scan(lut.astype(np.float64), qcodes, codes, ht, 136, want_bitmap=True)
@@ -109,12 +112,12 @@ def test_survivor_set_on_the_matrix_cores(psc, monkeypatch):
 
 
 @pytest.mark.parametrize("route", ["mfma", "popcount"])
-def test_nested_prefix_patterns_at_every_threshold(psc, monkeypatch, route):
+def test_nested_prefix_patterns_at_every_threshold(psc, force_route, route):
     """Database row r = the first r bits set (r = 0..64, repeated to fill several blocks), query q =
     the first 3q bits set: their Hamming distance is |r - 3q| exactly, so the survivor set at every
     threshold is known in closed form.  Both filters, every threshold up to where the dense route
     takes over; the table makes the distance itself the score."""
-    monkeypatch.setenv("PSC_FILTER_ROUTE", route)
+    force_route(route)
     m, reps, nq = 8, 7, 20
     def prefix(r):
         c = np.zeros(m, np.uint8)
@@ -146,11 +149,11 @@ def test_nested_prefix_patterns_at_every_threshold(psc, monkeypatch, route):
 
 
 @pytest.mark.parametrize("route", ["mfma", "popcount"])
-def test_whole_and_sliced_query_tiles_in_one_launch(psc, monkeypatch, route):
+def test_whole_and_sliced_query_tiles_in_one_launch(psc, force_route, route):
     """More query tiles than workgroups run at a time: the tiles of the whole rounds scan the
     database in one piece, those of the last partial round in slices.  Queries from both regions
     (and the last, ragged tile) against the oracle."""
-    monkeypatch.setenv("PSC_FILTER_ROUTE", route)
+    force_route(route)
     n, nq, k = 150_011, 4100 + 13, 20
     codes, qcodes, lut = _rand_problem(8, n, nq, seed=4242, lut_kind="float")
     sel = np.array([0, 1, 15, 16, 2047, 4079, 4080, 4095, 4096, 4097, 4111, 4112])

@@ -98,3 +98,49 @@ def test_whole_search_matches_oracle(setup, m):
         gd = d.cpu().numpy()[same_codes]
         fin = np.isfinite(ref2["dists"][same_codes])
         assert np.allclose(gd[fin], ref2["dists"][same_codes][fin], rtol=RTOL)
+
+
+def test_tiny_workload_as_configured():
+    """The smallest named workload, whole: 10k training vectors, product quantizer with optimised
+    index assignment (the paper's annealing constants), 100 000 database vectors, 100 queries,
+    ht = 24, k = 10 -- every query checked against the oracle, on the library's tables and on the
+    oracle's own double-precision path from the raw vectors; recall@10 of both sides coincides."""
+    import paper_1609_01882_amd as psc
+    cfg = W.get_config("tiny")
+    assert (cfg.n_train, cfg.n_db, cfg.n_query, cfg.hts, cfg.k) == (10_000, 100_000, 100, (24,), 10)
+    xt, xb, xq = cfg.vectors("train"), cfg.vectors("db"), cfg.vectors("query")
+    idx = psc.Index(cfg.dim, cfg.m)
+    idx.train_pq(xt, iters=20, seed=cfg.seed)
+    idx.optimize_index_assignment(seed=cfg.seed)
+    cb = idx.get_codebook()
+    ht, k = cfg.hts[0], cfg.k
+    codes = idx.encode(_dev(xb))
+    ids, d = idx.search(_dev(xq), codes, ht, k)
+    lut, qc = idx.build_lut(_dev(xq))
+    torch.cuda.synchronize()
+    ids, d, codes_h = ids.cpu().numpy(), d.cpu().numpy(), codes.cpu().numpy()
+    lut64, qc = lut.cpu().numpy().astype(np.float64), qc.cpu().numpy()
+    # same tables and bit strings on both sides: survivor counts exact, ids and distances to the bar
+    ref = O.scan(lut64, qc, codes_h, ht, k)
+    assert_topk_matches(ids, d, ref, lut64, qc, codes_h, ht, what="tiny")
+    ns = psc.hamming_filter(_dev(qc), codes, ht)
+    assert np.array_equal(ns.cpu().numpy(), ref["nsurv"])
+    # the oracle's own path from the raw vectors (its encoding, its tables, its query codes)
+    ref_codes = O.encode(xb, cb)
+    bad = np.argwhere(ref_codes != codes_h)
+    assert len(bad) < 50
+    dsub = cfg.dim // cfg.m
+    for i, j in bad:  # only near-ties may be encoded differently
+        v = xb[i, j * dsub:(j + 1) * dsub].astype(np.float64)
+        da, db = ((v - cb[j, codes_h[i, j]]) ** 2).sum(), ((v - cb[j, ref_codes[i, j]]) ** 2).sum()
+        assert abs(da - db) <= RTOL * db
+    own = O.search_flat(xq, cb, codes_h, ht, k)
+    same = np.all(O.query_codes(O.build_lut(xq, cb)) == qc, axis=1)
+    assert same.mean() >= 0.95
+    fin = np.isfinite(own["dists"][same])
+    assert np.allclose(d[same][fin], own["dists"][same][fin], rtol=RTOL)
+    assert np.array_equal(np.isfinite(d[same]), fin)
+    truth = O.exact_knn(xb, xq, 1)[0][:, 0]
+    r_gpu, r_orc = O.recall_at(ids, truth, 10), O.recall_at(ref["ids"], truth, 10)
+    print(f"tiny: recall@10 gpu {r_gpu:.3f} oracle {r_orc:.3f}, survivors/query {ref['nsurv'].mean():.0f}", flush=True)
+    assert r_gpu == r_orc

@@ -43,6 +43,7 @@ def test_binding_constants_match_the_header(psc):
     from paper_1609_01882_amd import binding
     text = open(os.path.join(ROOT, "include", "psc.h")).read()
     defs = {k: int(v.strip("()")) for k, v in re.findall(r"^#define (PSC_[A-Z_]+) (\(?-?\d+\)?)$", text, flags=re.M)}
+    assert {k: defs[f"PSC_ROUTE_{k.upper()}"] for k in binding.ROUTES} == binding.ROUTES
     assert defs["PSC_MAX_K"] == binding.PSC_MAX_K == psc.PSC_MAX_K
     assert (defs["PSC_START_SEEDED"], defs["PSC_START_CURRENT"]) == (binding.PSC_START_SEEDED, binding.PSC_START_CURRENT)
     assert defs["PSC_OK"] == 0 and all(defs[e] < 0 for e in ("PSC_EINVAL", "PSC_ESTATE", "PSC_EHIP", "PSC_ENOMEM"))
