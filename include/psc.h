@@ -189,6 +189,21 @@ int psc_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t nq,
              const uint8_t *codes_dev, int64_t n, int ht, int k, int64_t *ids_dev,
              float *dists_dev, void *workspace_dev, size_t workspace_bytes, psc_stream stream);
 
+/* psc_scan for callers that cannot allocate device memory or pass a workspace (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, kernels
+ * and results as psc_scan, but the scan's scratch memory (status word, shared thresholds, partial
+ * result lists) is a fixed array of PSC_STATIC_SCRATCH_BYTES that the library holds in the
+ * device's global memory from load time until the process ends -- one copy per GPU.  The call
+ * allocates and frees nothing.  Sizes whose psc_scan_workspace_bytes exceeds the array are
+ * rejected with PSC_EINVAL.  Every call on a GPU uses that GPU's one array (the call clears what
+ * must start cleared): calls that overlap on one GPU -- two streams, two threads -- race; issue
+ * them on one stream.  The first call on a device looks the array's address up; the HIP runtime
+ * places the array in that device's memory at that moment, once per process. */
+#define PSC_STATIC_SCRATCH_BYTES (32u << 20)
+int psc_scan_static(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t nq,
+                    const uint8_t *codes_dev, int64_t n, int ht, int k, int64_t *ids_dev,
+                    float *dists_dev, psc_stream stream);
+
 /* Whole flat search from raw queries q_dev [nq][dim]: psc_build_lut + psc_scan,
  * tables and query codes living in the workspace (psc_search_workspace_bytes). */
 size_t psc_search_workspace_bytes(const psc_index *idx, int64_t nq, int64_t n, int k);

@@ -13,7 +13,9 @@ from .binding import (  # noqa: F401
     last_scan_route,
     lib_path,
     scan,
+    scan_static,
     scan_workspace_bytes,
+    PSC_STATIC_SCRATCH_BYTES,
     set_filter_route,
     threshold_for_rate,
     version,

@@ -56,6 +56,7 @@ def _load():
         "psc_threshold_for_rate": (i32, [vp, i32, dbl]),
         "psc_scan_workspace_bytes": (sz, [i32, i64, i64, i32]),
         "psc_scan": (i32, [i32, vp, vp, i64, vp, i64, i32, i32, vp, vp, vp, sz, vp]),
+        "psc_scan_static": (i32, [i32, vp, vp, i64, vp, i64, i32, i32, vp, vp, vp]),
         "psc_search_workspace_bytes": (sz, [vp, i64, i64, i32]),
         "psc_search": (i32, [vp, vp, i64, vp, i64, i32, i32, vp, vp, vp, sz, vp]),
         "psc_knn_graph_workspace_bytes": (sz, [vp, i64, i32]),
@@ -85,7 +86,7 @@ def exported_symbols():
             "psc_train_pq_device", "psc_ivf_train_coarse_device",
             "psc_optimize_index_assignment", "psc_set_codebook", "psc_get_codebook", "psc_encode",
             "psc_build_lut", "psc_hamming_filter", "psc_hamming_histogram", "psc_threshold_for_rate",
-            "psc_scan_workspace_bytes", "psc_scan",
+            "psc_scan_workspace_bytes", "psc_scan", "psc_scan_static",
             "psc_search_workspace_bytes", "psc_search", "psc_knn_graph_workspace_bytes",
             "psc_knn_graph", "psc_ivf_train_coarse", "psc_ivf_set_coarse", "psc_ivf_get_coarse",
             "psc_ivf_assign_encode", "psc_ivf_set_lists", "psc_ivf_search_workspace_bytes",
@@ -324,6 +325,20 @@ def scan(lut: torch.Tensor, qcodes: torch.Tensor, codes: torch.Tensor, ht: int, 
                         _dev(codes, torch.uint8, "codes"), n, ht, k, _dev(ids, torch.int64, "ids"),
                         _dev(dists, torch.float32, "dists"), _dev(ws, torch.uint8, "workspace"),
                         ws.numel(), _stream()))
+    return ids, dists
+
+
+PSC_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def scan_static(lut: torch.Tensor, qcodes: torch.Tensor, codes: torch.Tensor, ht: int, k: int, out):
+    """`scan` on the library's static scratch array: no workspace, no allocation (results go to
+    the caller's `out` = (ids [nq,k] int64, dists [nq,k] float32))."""
+    nq, m = qcodes.shape
+    ids, dists = out
+    _check(_load().psc_scan_static(m, _dev(lut, torch.float32, "lut"), _dev(qcodes, torch.uint8, "qcodes"), nq,
+                                   _dev(codes, torch.uint8, "codes"), codes.shape[0], ht, k,
+                                   _dev(ids, torch.int64, "ids"), _dev(dists, torch.float32, "dists"), _stream()))
     return ids, dists
 
 

@@ -302,6 +302,58 @@ int psc_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t nq,
                        workspace_dev, workspace_bytes, (hipStream_t)stream);
 }
 
+}  // extern "C"
+
+// ---------------------------------------------------------------------------------------------
+// psc_scan without a caller's workspace and without any allocation: the scan's scratch memory is
+// a fixed array in the device's global memory.  In host code the array's name stands for the
+// symbol, not for a device address: the address is looked up once per device and only that
+// pointer is handed to kernels.
+// ---------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[PSC_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void *g_scratch_ptr[kMaxDevices] = {};  // per device: where that device's copy of `scratch` lives
+
+int static_scratch(void **out)
+{
+    int dev = -1;
+    PSC_HIP_TRY(hipGetDevice(&dev));
+    PSC_REQUIRE(dev >= 0 && dev < kMaxDevices, "device ordinal %d out of range", dev);
+    std::lock_guard<std::mutex> guard(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        PSC_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        PSC_REQUIRE(p != nullptr && ((uintptr_t)p & 255) == 0, "static scratch array has no usable device address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return PSC_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int psc_scan_static(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t nq,
+                    const uint8_t *codes_dev, int64_t n, int ht, int k, int64_t *ids_dev,
+                    float *dists_dev, psc_stream stream)
+{
+    const size_t need = flat_scan_workspace_bytes(m, nq, n, k);
+    PSC_REQUIRE(need != 0, "%s", psc_last_error());
+    PSC_REQUIRE(need <= (size_t)PSC_STATIC_SCRATCH_BYTES,
+                "this scan needs %zu bytes of scratch memory, the static array holds %u: use psc_scan with a workspace",
+                need, (unsigned)PSC_STATIC_SCRATCH_BYTES);
+    void *ws = nullptr;
+    int rc = static_scratch(&ws);
+    if (rc != PSC_OK) return rc;
+    // (launch_scan clears the status word and the shared thresholds with a small kernel, and the
+    //  scan kernels write every partial list they later merge: nothing of the previous call is read)
+    return launch_scan(m, lut_dev, qcodes_dev, nq, codes_dev, n, ht, k, -1, true, ids_dev, dists_dev, ws,
+                       (size_t)PSC_STATIC_SCRATCH_BYTES, (hipStream_t)stream);
+}
+
 static size_t round256(size_t v) { return (v + 255) / 256 * 256; }
 
 size_t psc_search_workspace_bytes(const psc_index *idx, int64_t nq, int64_t n, int k)
