@@ -136,9 +136,10 @@ int psc_encode(const psc_index *idx, const float *x_dev, int64_t n, uint8_t *cod
  * lut[q][j][c] = squared Euclidean distance between sub-vector j of query q and
  * centroid c of sub-quantizer j.  For even dim/m the tables are computed on the matrix cores
  * (full float32 MFMA) as |q'|^2 - 2 q'.c' + |c'|^2 with both sides centred on the
- * sub-quantizer's mean centroid, clamped at 0: an entry is accurate to float32 rounding of
- * those three terms (about 2e-6 x the largest entry of its row), sums of m entries to well
- * below 1e-5 relative.  qcodes_dev (may be NULL) [nq][m] receives the query's own code = per
+ * sub-quantizer's mean centroid, clamped at 0; an entry that comes out below 1/16 of
+ * |q'|^2 + |c'|^2 (the terms have cancelled: a centroid close to the query) is recomputed by
+ * direct differences, so that every entry is accurate to a few 1e-6 of its own value.
+ * qcodes_dev (may be NULL) [nq][m] receives the query's own code = per
  * row the index of the smallest entry of that very table (lowest on ties). */
 int psc_build_lut(const psc_index *idx, const float *q_dev, int64_t nq, float *lut_dev,
                   uint8_t *qcodes_dev, psc_stream stream);
@@ -263,12 +264,18 @@ int psc_ivf_set_lists(psc_index *idx, const int64_t *offsets_dev, const uint8_t 
  * list) pairs per list; psc_set_filter_route overrides as for psc_scan).
  * probed_out_dev (may be NULL) [nq][nprobe] int32 receives the probed lists in ascending
  * coarse distance; qcodes_out_dev (may be NULL) [nq][nprobe][m] the per-list query codes.
- * The tables are never stored per (query, list): with o the mean coarse centroid they split
- * into ||(q-o)_j - c||^2 (one table per query), 2 (centroid[l]-o)_j . c (one per list) and a
- * number per (query, list, j), which are added up as a list is scanned; the bit string is the
- * arg-min of the summed float32 rows, lowest index on ties.
+ * The tables are normally not stored per (query, list): with o the mean coarse centroid they split
+ * into ||c||^2 - 2 (q-o)_j . c (one table per query), 2 (centroid[l]-o)_j . c (one per list) and
+ * the number ||(q-centroid[l])_j||^2 per (query, list, j), which are added up as a list is scanned;
+ * the bit string is the arg-min of the summed float32 rows, lowest index on ties.  The two cross
+ * terms are larger than the entries they add up to by about rho = 2 |centroid[l]-o|_j /
+ * (sqrt(dim/m) x rms norm of the centroids of sub-quantizer j); an index whose largest rho exceeds
+ * 16 (coarse centroids spread very far apart compared with the residuals) would lose too many
+ * bits, so for such an index every (query, list) table is built by direct differences and stored
+ * (slower; nq*nprobe*m KiB more workspace) -- psc_last_scan_route then ends in "+direct-tables".
  * The per-list tables (nlist*m KiB) belong to the index's device image and are rebuilt by the
- * first search after the codebook or the coarse centroids changed (that call blocks).
+ * first search after the codebook or the coarse centroids changed (that call blocks; see
+ * psc_prepare).
  * Up to 4096 (query, list) pairs are scanned one per workgroup in order of coarse rank (low
  * latency for a few queries); larger batches are grouped by list so that up to 16 queries share
  * every code load.

@@ -1,5 +1,6 @@
 // C ABI of libpsc: argument checking and dispatch.  See include/psc.h for the contract.
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -29,6 +30,7 @@ static int mark_codebook_changed(psc_index *idx)
     idx->has_codebook = true;
     idx->dev_current = false;
     idx->list_tab_current = false;
+    idx->direct_tables = -1;
     return PSC_OK;
 }
 
@@ -244,10 +246,10 @@ int psc_build_lut(const psc_index *idx, const float *q_dev, int64_t nq, float *l
     if (idx->dsub % 2 == 0) {
         // the dense contraction of the path: matrix cores
         const size_t n = idx->cb_host.size();
-        rc = launch_lut_mfma(idx->cb_dev + n, idx->cb_dev + 2 * n, idx->dim, idx->m, q_dev, nq, lut_dev,
+        rc = launch_lut_mfma(idx->cb_dev, idx->cb_dev + n, idx->cb_dev + 2 * n, idx->dim, idx->m, q_dev, nq, lut_dev,
                              (hipStream_t)stream);
     } else {
-        rc = launch_lut(idx->cb_dev, idx->dim, idx->m, q_dev, nq, RowMap{}, lut_dev, (hipStream_t)stream);
+        rc = launch_lut(idx->cb_dev, idx->dim, idx->m, q_dev, nq, RowMap{}, false, lut_dev, (hipStream_t)stream);
     }
     if (rc != PSC_OK) return rc;
     if (qcodes_dev) rc = launch_row_argmin(lut_dev, nq * idx->m, qcodes_dev, (hipStream_t)stream);
@@ -446,10 +448,10 @@ int psc_knn_graph(const psc_index *idx, const float *x_dev, const uint8_t *codes
         const int64_t qc = (n - c0) < kGraphChunk ? (n - c0) : kGraphChunk;
         if (idx->dsub % 2 == 0) {
             const size_t nc = idx->cb_host.size();
-            rc = launch_lut_mfma(idx->cb_dev + nc, idx->cb_dev + 2 * nc, idx->dim, idx->m,
+            rc = launch_lut_mfma(idx->cb_dev, idx->cb_dev + nc, idx->cb_dev + 2 * nc, idx->dim, idx->m,
                                  x_dev + (size_t)c0 * idx->dim, qc, lut, (hipStream_t)stream);
         } else {
-            rc = launch_lut(idx->cb_dev, idx->dim, idx->m, x_dev + (size_t)c0 * idx->dim, qc, RowMap{}, lut,
+            rc = launch_lut(idx->cb_dev, idx->dim, idx->m, x_dev + (size_t)c0 * idx->dim, qc, RowMap{}, false, lut,
                             (hipStream_t)stream);
         }
         if (rc != PSC_OK) return rc;
@@ -511,6 +513,50 @@ static int sync_list_tables(const psc_index *idx, hipStream_t s)
     return PSC_OK;
 }
 
+// Whether the inverted-file search builds the residual tables one (query, list) pair at a time by
+// direct differences instead of adding up a per-query share, a per-list share and a number.
+// The shares are cross terms of the size |g~_j| |c| (g~ = coarse centroid minus the mean coarse
+// centroid, c = a centroid of sub-quantizer j), rounded to float32, while the entries they add up
+// to are of the size |c|^2: with rho = 2 |g~_j| / (sqrt(dsub) |c|_rms) the sum loses about
+// log2(rho) bits.  Measured on the SIFT-like workloads rho is 1 to 2 (distance errors below 1e-6);
+// beyond 16 the 1e-5 contract would have less than a factor 3 to spare, so from there the tables
+// are built directly (slower: one table per pair is written and read).
+constexpr double kDirectTablesRho = 16.0;
+
+static bool ivf_direct_tables(const psc_index *idx)
+{
+    std::lock_guard<std::mutex> guard(idx->image_lock);
+    if (idx->direct_tables >= 0) return idx->direct_tables != 0;
+    const int dim = idx->dim, m = idx->m, dsub = idx->dsub, nl = idx->nlist;
+    std::vector<double> o((size_t)dim, 0.0);
+    for (int l = 0; l < nl; ++l)
+        for (int t = 0; t < dim; ++t) o[(size_t)t] += idx->coarse_host[(size_t)l * dim + t];
+    for (int t = 0; t < dim; ++t) o[(size_t)t] /= nl;
+    double rho = 0.0;
+    for (int j = 0; j < m; ++j) {
+        double c2 = 0.0;
+        for (int c = 0; c < kCentroids; ++c)
+            for (int t = 0; t < dsub; ++t) {
+                const double v = idx->cb_host[((size_t)j * kCentroids + c) * dsub + t];
+                c2 += v * v;
+            }
+        const double crms = std::sqrt(c2 / kCentroids);
+        double g2max = 0.0;
+        for (int l = 0; l < nl; ++l) {
+            double g2 = 0.0;
+            for (int t = j * dsub; t < (j + 1) * dsub; ++t) {
+                const double v = idx->coarse_host[(size_t)l * dim + t] - o[(size_t)t];
+                g2 += v * v;
+            }
+            g2max = std::max(g2max, g2);
+        }
+        const double num = 2.0 * std::sqrt(g2max), den = std::sqrt((double)dsub) * crms;
+        rho = std::max(rho, num <= kDirectTablesRho * den ? (den > 0.0 ? num / den : 0.0) : 2.0 * kDirectTablesRho);
+    }
+    idx->direct_tables = rho > kDirectTablesRho ? 1 : 0;
+    return idx->direct_tables != 0;
+}
+
 static int need_coarse(const psc_index *idx)
 {
     PSC_REQUIRE(idx != nullptr, "null index");
@@ -528,7 +574,7 @@ int psc_prepare(const psc_index *idx, psc_stream stream)
     if (idx->nlist == 0) return PSC_OK;
     rc = need_coarse(idx);
     if (rc != PSC_OK) return rc;
-    return sync_list_tables(idx, (hipStream_t)stream);
+    return ivf_direct_tables(idx) ? PSC_OK : sync_list_tables(idx, (hipStream_t)stream);
 }
 
 int psc_ivf_set_coarse(psc_index *idx, const float *centroids_host, int nlist)
@@ -545,6 +591,7 @@ int psc_ivf_set_coarse(psc_index *idx, const float *centroids_host, int nlist)
     idx->nlist = nlist;
     idx->coarse_current = false;
     idx->list_tab_current = false;
+    idx->direct_tables = -1;
     idx->list_off_dev = nullptr;  // lists built for another quantizer no longer apply
     idx->list_codes_dev = nullptr;
     idx->list_ids_dev = nullptr;
@@ -822,6 +869,7 @@ int psc_ivf_set_lists(psc_index *idx, const int64_t *offsets_dev, const uint8_t 
 namespace {
 struct IvfLayout {
     ScanPlan plan;
+    bool direct;
     int64_t njobs, nblk, max_tiles;
     size_t off_status, off_gthr, off_dist, off_probed, off_hist, off_list_begin, off_tile_begin, off_job_q, off_job_list,
         off_job_slot, off_tiles, off_lut, off_qcodes, off_part_d, off_part_i, total;
@@ -857,7 +905,9 @@ int ivf_layout(const psc_index *idx, int64_t nq, int nprobe, int k, IvfLayout *L
     L->off_job_list = take((size_t)L->njobs * sizeof(int32_t));
     L->off_job_slot = take((size_t)L->njobs * sizeof(int32_t));
     L->off_tiles = take((size_t)L->max_tiles * 16);
-    L->off_lut = take((size_t)nq * idx->m * kCentroids * sizeof(float));
+    // the queries' share of the tables, or (direct tables) one table per (query, list) pair
+    L->direct = idx->has_codebook && ivf_direct_tables(idx);
+    L->off_lut = take((size_t)(L->direct ? L->njobs : nq) * idx->m * kCentroids * sizeof(float));
     L->off_qcodes = take((size_t)L->njobs * idx->m);
     L->off_part_d = take((size_t)L->njobs * k * sizeof(float));
     L->off_part_i = take((size_t)L->njobs * k * sizeof(int64_t));
@@ -928,12 +978,21 @@ int psc_ivf_search(const psc_index *idx, const float *q_dev, int64_t nq, int npr
     // 3. the queries' and the lists' shares of the residual tables (put together per tile by the
     //    scan, which also derives each job's query code from them)
     RowMap map;
-    map.sub = idx->coarse_dev + (size_t)idx->nlist * idx->dim;  // the mean coarse centroid
-    rc = launch_lut(idx->cb_dev, idx->dim, idx->m, q_dev, nq, map, lut, s);
-    if (rc != PSC_OK) return rc;
-    rc = sync_list_tables(idx, s);
-    if (rc != PSC_OK) return rc;
-    const float *list_tab = idx->list_tab_dev;
+    const float *list_tab = nullptr;
+    if (L.direct) {  // one finished table per job: row = the job's query minus its list's centroid
+        map.row_idx = jb.job_q;
+        map.sub = idx->coarse_dev;
+        map.sub_idx = jb.job_list;
+        rc = launch_lut(idx->cb_dev, idx->dim, idx->m, q_dev, L.njobs, map, false, lut, s);
+        if (rc != PSC_OK) return rc;
+    } else {
+        map.sub = idx->coarse_dev + (size_t)idx->nlist * idx->dim;  // the mean coarse centroid
+        rc = launch_lut(idx->cb_dev, idx->dim, idx->m, q_dev, nq, map, true, lut, s);
+        if (rc != PSC_OK) return rc;
+        rc = sync_list_tables(idx, s);
+        if (rc != PSC_OK) return rc;
+        list_tab = idx->list_tab_dev;
+    }
     // 4. the fused scan over the tiles, 5. one merge per query over its nprobe partial lists
     rc = launch_ivf_scan(idx->m, plan.tq, plan.nwaves, plan.kpad, plan.lds_bytes, lut, list_tab, q_dev, idx->coarse_dev,
                          idx->dim, idx->nlist, qcodes, idx->list_codes_dev, idx->list_n, ht, k, jb.tiles,

@@ -53,14 +53,16 @@ struct RowMap {
     const float *sub = nullptr;       // [*][dim] vectors to subtract (coarse centroids)
     const int32_t *sub_idx = nullptr; // which one, per row (none: the first, for every row)
 };
+// cross: write || c ||^2 - 2 v . c instead of || v - c ||^2 (the inverted-file scan's per-query share).
 int launch_lut(const float *cb_dev, int dim, int m, const float *x_dev, int64_t nrows,
-               const RowMap &map, float *lut_dev, hipStream_t s);
+               const RowMap &map, bool cross, float *lut_dev, hipStream_t s);
 int launch_encode(const float *cb_dev, int dim, int m, const float *x_dev, int64_t nrows,
                   const RowMap &map, uint8_t *codes_dev, hipStream_t s);
 // Tables on the matrix cores from the centred codebook cbc [m][256][dsub] and the per-sub-quantizer
-// mean centroids mu [m][dsub]; and the arg-min of every table row (nrows_total = rows x m).
-int launch_lut_mfma(const float *cbc_dev, const float *mu_dev, int dim, int m, const float *x_dev,
-                    int64_t nrows, float *lut_dev, hipStream_t s);
+// mean centroids mu [m][dsub] (entries that cancel badly are redone from the codebook cb by direct
+// differences); and the arg-min of every table row (nrows_total = rows x m).
+int launch_lut_mfma(const float *cb_dev, const float *cbc_dev, const float *mu_dev, int dim, int m,
+                    const float *x_dev, int64_t nrows, float *lut_dev, hipStream_t s);
 int launch_row_argmin(const float *lut_dev, int64_t nrows_total, uint8_t *codes_dev, hipStream_t s);
 
 // ---- device launchers (kernels_scan.hip)
@@ -200,6 +202,7 @@ struct psc_index {
     mutable float *list_tab_dev = nullptr;
     mutable int list_tab_nlist = 0;
     mutable bool list_tab_current = false;
+    mutable int direct_tables = -1;  // 1: residual tables built per (query, list) pair; -1: not decided yet
     const int64_t *list_off_dev = nullptr;  // [nlist+1]
     const uint8_t *list_codes_dev = nullptr;
     const int32_t *list_ids_dev = nullptr;

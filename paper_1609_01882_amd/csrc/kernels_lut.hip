@@ -22,7 +22,10 @@ __device__ __forceinline__ float sub_term(const RowMap &map, int64_t r, int dim,
 // One workgroup = one sub-quantizer j and ROWS consecutive rows; thread c owns centroid c,
 // held in registers (DSUB known at compile time) so the inner loop is pure VALU.
 // Table writes are coalesced over c.
-template <int DSUB, int ROWS>
+// CROSS: instead of the squared distance, the part of it that depends on the centroid,
+//   || c ||^2 - 2 v . c  =  sum_t c_t (c_t - 2 v_t),
+// which the inverted-file scan completes with a per-list table and a number per (query, list).
+template <int DSUB, int ROWS, bool CROSS>
 __global__ void __launch_bounds__(256)
 lut_kernel(const float *__restrict__ cb, int dim, int m, const float *__restrict__ x, int64_t nrows,
            RowMap map, float *__restrict__ lut)
@@ -54,8 +57,12 @@ lut_kernel(const float *__restrict__ cb, int dim, int m, const float *__restrict
         float acc = 0.f;
 #pragma unroll
         for (int t = 0; t < DSUB; ++t) {
-            const float df = vq[rr][t] - cen[t];
-            acc = fmaf(df, df, acc);
+            if constexpr (CROSS) {
+                acc = fmaf(cen[t], cen[t] - 2.0f * vq[rr][t], acc);
+            } else {
+                const float df = vq[rr][t] - cen[t];
+                acc = fmaf(df, df, acc);
+            }
         }
         lut[(r * m + j) * kCentroids + c] = acc;
     }
@@ -111,11 +118,15 @@ encode_kernel(const float *__restrict__ cb, int dim, int m, const float *__restr
 // i = 8 * (v / 4) + 4 * (l / 32) + v % 4, column j = l % 32.
 // ---------------------------------------------------------------------------------------------
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+// Entries below this share of || q' ||^2 + || c' ||^2 are recomputed by direct differences; the
+// others keep a relative error of a few float32 roundings x 16 (about 3e-6 at worst).
+constexpr float kRefineBelow = 1.0f / 16.0f;
 
 template <int DSUB>
 __global__ void __launch_bounds__(256)
-lut_mfma_kernel(const float *__restrict__ cbc /* centred codebook */, const float *__restrict__ mu, int dim,
-                int m, const float *__restrict__ x, int64_t nrows, float *__restrict__ lut)
+lut_mfma_kernel(const float *__restrict__ cb, const float *__restrict__ cbc /* centred codebook */,
+                const float *__restrict__ mu, int dim, int m, const float *__restrict__ x, int64_t nrows,
+                float *__restrict__ lut)
 {
     static_assert(DSUB % 2 == 0, "two coordinates per MFMA step");
     constexpr int KS = DSUB / 2;
@@ -163,7 +174,24 @@ lut_mfma_kernel(const float *__restrict__ cbc /* centred codebook */, const floa
             const int i = 8 * (v / 4) + 4 * half + v % 4;
             const int64_t r = r0 + i;
             if (r < nrows) {
-                const float d = fmaf(-2.0f, acc[v], qn_s[wave][i] + cn);
+                const float sum = qn_s[wave][i] + cn;
+                float d = fmaf(-2.0f, acc[v], sum);
+                if (d < kRefineBelow * sum) {
+                    // the three terms have cancelled to less than a sixteenth of their size: what
+                    // is left has lost four bits or more, so this entry (a centroid close to the
+                    // query -- the entries that decide the query's code and its nearest
+                    // neighbours) is taken by direct differences instead, in the operation order
+                    // of the encoding kernel
+                    const float *xr = x + r * dim + j * DSUB;
+                    const float *cr2 = cb + ((int64_t)j * kCentroids + c0 + col) * DSUB;
+                    float e = 0.f;
+#pragma unroll
+                    for (int t = 0; t < DSUB; ++t) {
+                        const float df = xr[t] - cr2[t];
+                        e = fmaf(df, df, e);
+                    }
+                    d = e;
+                }
                 lut[(r * m + j) * kCentroids + c0 + col] = d > 0.f ? d : 0.f;
             }
         }
@@ -197,22 +225,25 @@ row_argmin_kernel(const float *__restrict__ lut, int64_t nrows_total, uint8_t *_
 }
 
 template <int DSUB>
-int run_lut_mfma(const float *cbc, const float *mu, int dim, int m, const float *x, int64_t nrows, float *lut,
-                 hipStream_t s)
+int run_lut_mfma(const float *cb, const float *cbc, const float *mu, int dim, int m, const float *x, int64_t nrows,
+                 float *lut, hipStream_t s)
 {
     dim3 grid((unsigned)((nrows + 31) / 32), (unsigned)m);
-    hipLaunchKernelGGL((lut_mfma_kernel<DSUB>), grid, dim3(256), 0, s, cbc, mu, dim, m, x, nrows, lut);
+    hipLaunchKernelGGL((lut_mfma_kernel<DSUB>), grid, dim3(256), 0, s, cb, cbc, mu, dim, m, x, nrows, lut);
     PSC_HIP_TRY(hipGetLastError());
     return PSC_OK;
 }
 
 template <int DSUB>
-int run_lut(const float *cb, int dim, int m, const float *x, int64_t nrows, const RowMap &map,
+int run_lut(const float *cb, int dim, int m, const float *x, int64_t nrows, const RowMap &map, bool cross,
             float *lut, hipStream_t s)
 {
     constexpr int ROWS = 16;
     dim3 grid((unsigned)((nrows + ROWS - 1) / ROWS), (unsigned)m);
-    hipLaunchKernelGGL((lut_kernel<DSUB, ROWS>), grid, dim3(256), 0, s, cb, dim, m, x, nrows, map, lut);
+    if (cross)
+        hipLaunchKernelGGL((lut_kernel<DSUB, ROWS, true>), grid, dim3(256), 0, s, cb, dim, m, x, nrows, map, lut);
+    else
+        hipLaunchKernelGGL((lut_kernel<DSUB, ROWS, false>), grid, dim3(256), 0, s, cb, dim, m, x, nrows, map, lut);
     PSC_HIP_TRY(hipGetLastError());
     return PSC_OK;
 }
@@ -248,20 +279,20 @@ int run_encode(const float *cb, int dim, int m, const float *x, int64_t nrows, c
     }
 
 int launch_lut(const float *cb_dev, int dim, int m, const float *x_dev, int64_t nrows,
-               const RowMap &map, float *lut_dev, hipStream_t s)
+               const RowMap &map, bool cross, float *lut_dev, hipStream_t s)
 {
     if (nrows == 0) return PSC_OK;
     if ((nrows + 15) / 16 > 0x7fffffffLL) {
         set_error("too many rows for one table launch");
         return PSC_EINVAL;
     }
-#define CALL(DS) run_lut<DS>(cb_dev, dim, m, x_dev, nrows, map, lut_dev, s)
+#define CALL(DS) run_lut<DS>(cb_dev, dim, m, x_dev, nrows, map, cross, lut_dev, s)
     PSC_DSUB_SWITCH(dim / m, CALL)
 #undef CALL
 }
 
-int launch_lut_mfma(const float *cbc_dev, const float *mu_dev, int dim, int m, const float *x_dev,
-                    int64_t nrows, float *lut_dev, hipStream_t s)
+int launch_lut_mfma(const float *cb_dev, const float *cbc_dev, const float *mu_dev, int dim, int m,
+                    const float *x_dev, int64_t nrows, float *lut_dev, hipStream_t s)
 {
     if (nrows == 0) return PSC_OK;
     if ((nrows + 31) / 32 > 0x7fffffffLL) {
@@ -269,16 +300,16 @@ int launch_lut_mfma(const float *cbc_dev, const float *mu_dev, int dim, int m, c
         return PSC_EINVAL;
     }
     switch (dim / m) {
-    case 2: return run_lut_mfma<2>(cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
-    case 4: return run_lut_mfma<4>(cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
-    case 6: return run_lut_mfma<6>(cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
-    case 8: return run_lut_mfma<8>(cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
-    case 12: return run_lut_mfma<12>(cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
-    case 16: return run_lut_mfma<16>(cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
-    case 24: return run_lut_mfma<24>(cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
-    case 32: return run_lut_mfma<32>(cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
-    case 48: return run_lut_mfma<48>(cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
-    case 64: return run_lut_mfma<64>(cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
+    case 2: return run_lut_mfma<2>(cb_dev, cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
+    case 4: return run_lut_mfma<4>(cb_dev, cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
+    case 6: return run_lut_mfma<6>(cb_dev, cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
+    case 8: return run_lut_mfma<8>(cb_dev, cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
+    case 12: return run_lut_mfma<12>(cb_dev, cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
+    case 16: return run_lut_mfma<16>(cb_dev, cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
+    case 24: return run_lut_mfma<24>(cb_dev, cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
+    case 32: return run_lut_mfma<32>(cb_dev, cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
+    case 48: return run_lut_mfma<48>(cb_dev, cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
+    case 64: return run_lut_mfma<64>(cb_dev, cbc_dev, mu_dev, dim, m, x_dev, nrows, lut_dev, s);
     default:
         set_error("the matrix-core table kernel needs an even sub-vector length, got %d", dim / m);
         return PSC_EINVAL;

@@ -73,11 +73,14 @@ struct ScanArgs {
     const int64_t *list_off;  // [nlist+1] list boundaries in `codes`
     const int32_t *ext_ids;   // [n] id of each stored code
     const int32_t *job_slot;  // [njobs] partial list (query * nprobe + probe) a job writes
-    // Residual tables of the inverted file, never stored per job.  With o the mean coarse
+    // Residual tables of the inverted file, not stored per job.  With o the mean coarse
     // centroid, q~ = q - o and g~ = g - o for the coarse centroid g of the tile's list,
-    //   ||(q - g)_j - c||^2 = ||q~_j - c||^2  +  2 g~_j . c  +  g~_j . (g~_j - 2 q~_j)
+    //   ||(q - g)_j - c||^2 = (||c||^2 - 2 q~_j . c)  +  2 g~_j . c  +  ||(q - g)_j||^2
     //                       = lut[query][j][c] + list_tab[list][j][c] + (one number per job and j),
-    // which a tile puts together in LDS.  The query code of a job is the arg-min of those rows.
+    // which a tile puts together in LDS (the first two, whose sum ||c||^2 - 2 (q - g)_j . c is of
+    // the size of the result, before the third).  The query code of a job is the arg-min of those
+    // rows.  list_tab == nullptr: `lut` holds one finished table per job, in job order (indexes
+    // whose coarse centroids lie so far apart that the sum above would lose too many bits).
     const float *list_tab;    // [nlist][M][256]
     const float *queries;     // [nq][dim] raw query vectors
     const float *coarse;      // [nlist + 1][dim] coarse centroids, then their mean
@@ -652,36 +655,41 @@ __device__ __forceinline__ void stage_list_tables(const Lds<M, TQ> &s, const Sca
     const int tid = (int)threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int dsub = a.dim / M;
-    // the list's centroid and the jobs' queries, both minus the mean centroid, staged where
-    // the tables will go (all loads of the workgroup in flight together; (TQ + 1) * dim floats
-    // fit: dim <= 1024 = a quarter of one job's tables at M = 8)
-    PSC_LDS float *gs = (PSC_LDS float *)s.lut, *xs = gs + a.dim;
-    for (int e = tid; e < (nvq + 1) * a.dim; e += NW * 64) {
-        const int q = e / a.dim - 1, t = e % a.dim;
-        const float *row = q < 0 ? a.coarse + (int64_t)tile_list * a.dim
-                                 : a.queries + (int64_t)a.job_q[q0 + q] * a.dim;
-        gs[e] = row[t] - a.coarse[(int64_t)a.nlist * a.dim + t];
-    }
-    __syncthreads();
-    float sterm = 0.f;
-    if (tid < TQ * M) {  // the per-job constant g~_j . (g~_j - 2 q~_j)
-        const int q = tid / M, j = tid - q * M;
-        if (q < nvq) {
-            for (int t = j * dsub; t < (j + 1) * dsub; ++t) {
-                const float g = gs[t], x = xs[q * a.dim + t];
-                sterm = fmaf(g, g - 2.0f * x, sterm);
+    // direct: the jobs' tables were built one by one by direct differences (a.lut holds them in job
+    // order); nothing to put together
+    const bool direct = a.list_tab == nullptr;
+    if (!direct) {
+        // the list's centroid and the jobs' queries staged where the tables will go (all loads of the
+        // workgroup in flight together; (TQ + 1) * dim floats fit: dim <= 1024 = a quarter of one
+        // job's tables at M = 8)
+        PSC_LDS float *gs = (PSC_LDS float *)s.lut, *xs = gs + a.dim;
+        for (int e = tid; e < (nvq + 1) * a.dim; e += NW * 64) {
+            const int q = e / a.dim - 1, t = e % a.dim;
+            const float *row = q < 0 ? a.coarse + (int64_t)tile_list * a.dim
+                                     : a.queries + (int64_t)a.job_q[q0 + q] * a.dim;
+            gs[e] = row[t];
+        }
+        __syncthreads();
+        float sterm = 0.f;
+        if (tid < TQ * M) {  // the per-job constant || (q - g)_j ||^2, from the raw vectors
+            const int q = tid / M, j = tid - q * M;
+            if (q < nvq) {
+                for (int t = j * dsub; t < (j + 1) * dsub; ++t) {
+                    const float df = xs[q * a.dim + t] - gs[t];
+                    sterm = fmaf(df, df, sterm);
+                }
             }
         }
+        __syncthreads();  // (the staged vectors are read; their place is the tables' from here on)
+        if (tid < TQ * M) s.sterm[tid] = sterm;
+        __syncthreads();
     }
-    __syncthreads();  // (the staged vectors are read; their place is the tables' from here on)
-    if (tid < TQ * M) s.sterm[tid] = sterm;
-    __syncthreads();
     {
         // the jobs' share and the list's share of every table entry, four entries per thread at
         // a time: their loads first, the sums after
         constexpr int kTurns = (TQ * M * 64 + NW * 64 - 1) / (NW * 64);
         constexpr int kChunk = kTurns < 4 ? kTurns : 4;
-        const f32x4 *tab = (const f32x4 *)(a.list_tab + (int64_t)tile_list * (M * 256));
+        const f32x4 *tab = direct ? nullptr : (const f32x4 *)(a.list_tab + (int64_t)tile_list * (M * 256));
         PSC_LDS f32x4 *dst = (PSC_LDS f32x4 *)s.lut;
 #pragma unroll 1
         for (int u0 = 0; u0 < kTurns; u0 += kChunk) {
@@ -693,8 +701,8 @@ __device__ __forceinline__ void stage_list_tables(const Lds<M, TQ> &s, const Sca
                 xv[u] = f32x4{0.f, 0.f, 0.f, 0.f};
                 tv[u] = xv[u];
                 if (e < TQ * (M * 64) && q < nvq) {
-                    xv[u] = ((const f32x4 *)(a.lut + (int64_t)s.gidx[q] * (M * 256)))[r];
-                    tv[u] = tab[r];
+                    xv[u] = ((const f32x4 *)(a.lut + (direct ? q0 + q : (int64_t)s.gidx[q]) * (M * 256)))[r];
+                    if (!direct) tv[u] = tab[r];
                 }
             }
 #pragma unroll
@@ -703,7 +711,7 @@ __device__ __forceinline__ void stage_list_tables(const Lds<M, TQ> &s, const Sca
                 const int q = e / (M * 64), r = e - q * (M * 64);
                 if (e < TQ * (M * 64)) {
                     f32x4 v = {0.f, 0.f, 0.f, 0.f};
-                    if (q < nvq) v = (xv[u] + tv[u]) + s.sterm[q * M + (r >> 6)];
+                    if (q < nvq) v = direct ? xv[u] : (xv[u] + tv[u]) + s.sterm[q * M + (r >> 6)];
                     dst[e] = v;
                 }
             }
@@ -2255,7 +2263,9 @@ int launch_ivf_scan(int m, int tq, int nwaves, int kpad, size_t lds_bytes, const
         }
         if (rc != PSC_OK) return rc;
     }
-    note_route(on_matrix_cores ? "scan_mfma_kernel+lists" : "scan_kernel+lists", m, tq, nwaves, 1, max_tiles);
+    note_route(on_matrix_cores ? (list_tab_dev ? "scan_mfma_kernel+lists" : "scan_mfma_kernel+lists+direct-tables")
+                               : (list_tab_dev ? "scan_kernel+lists" : "scan_kernel+lists+direct-tables"),
+               m, tq, nwaves, 1, max_tiles);
     return launch_merge(part_d, part_i, nq, nprobe, k, status, ids_dev, dists_dev, s);
 }
 

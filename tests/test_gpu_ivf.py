@@ -379,3 +379,56 @@ def test_list_offsets_are_checked():
         off = torch.tensor([0, big, big, big + 3], dtype=torch.int64, device="cuda")
         binding._check(binding._load().psc_ivf_set_lists(idx._h, C.c_void_p(off.data_ptr()), C.c_void_p(codes.data_ptr()),
                                                          C.c_void_p(ids.data_ptr()), big + 3))
+
+
+def _spread_ivf(psc, spread, sigma, n=40_000, nlist=48, nq=33, seed=31):
+    """An index whose coarse centroids are uniform in [0, spread]^128 while the vectors lie within
+    sigma of them: coarse centroids = the mixture centres, residual PQ trained by the library."""
+    rng = np.random.default_rng(seed)
+    cent = (rng.random((nlist, 128)) * spread).astype(np.float32)
+
+    def draw(count):
+        return (cent[rng.integers(0, nlist, size=count)] + rng.normal(0, sigma, size=(count, 128))).astype(np.float32)
+    xt, xb, xq = draw(5000), draw(n), draw(nq)
+    idx = psc.Index(128, 8)
+    idx.ivf_set_coarse(cent)
+    lt, _ = idx.ivf_assign_encode(_dev(xt), want_codes=False)
+    idx.train_pq(xt - cent[lt.cpu().numpy()], iters=5, seed=4)
+    list_no, codes = idx.ivf_assign_encode(_dev(xb))
+    order = torch.sort(list_no.to(torch.int64), stable=True).indices
+    offsets = torch.zeros(nlist + 1, dtype=torch.int64, device="cuda")
+    offsets[1:] = torch.cumsum(torch.bincount(list_no.to(torch.int64), minlength=nlist), 0)
+    lcodes, lids = codes[order].contiguous(), order.to(torch.int32).contiguous()
+    idx.ivf_set_lists(offsets, lcodes, lids)
+    s = dict(idx=idx, cb=idx.get_codebook(), coarse=cent, offsets=offsets.cpu().numpy(), lcodes=lcodes.cpu().numpy(),
+             lids=lids.cpu().numpy())
+    return s, xq
+
+
+@pytest.mark.parametrize("spread,sigma,direct", [(100.0, 15.0, False), (400.0, 10.0, False), (3000.0, 10.0, True),
+                                                 (30000.0, 3.0, True)])
+@pytest.mark.parametrize("nq", [5, 700])
+def test_ivf_distances_when_coarse_centroids_lie_far_apart(spread, sigma, direct, nq):
+    """The 1e-5 bound on distances away from the comfortable data scale: coarse centroids 7 to
+    10000 times farther from their mean than the residuals are long.  The search adds its tables up
+    from a per-query and a per-list share while that loses few bits, and builds them per (query,
+    list) pair by direct differences beyond (the library says which); either way distances, ids and
+    per-list bit strings agree with the float64 oracle, for one job per tile and for the grouped scan."""
+    import paper_1609_01882_amd as psc
+    s, _ = _spread_ivf(psc, spread, sigma, nq=1)
+    rng = np.random.default_rng(int(spread) + nq)
+    xq = (s["coarse"][rng.integers(0, len(s["coarse"]), size=nq)] + rng.normal(0, sigma, size=(nq, 128))).astype(np.float32)
+    idx = s["idx"]
+    for nprobe, ht, k in ((8, 26, 20), (3, 64, 50)):
+        ids, d, probed, qcodes = idx.ivf_search(_dev(xq), nprobe, ht, k, want_debug=True)
+        torch.cuda.synchronize()
+        assert psc.last_scan_route().split()[0].endswith("+direct-tables") == direct, psc.last_scan_route()
+        probed, qcodes = probed.cpu().numpy(), qcodes.cpu().numpy()
+        ref = O.ivf_search(xq, s["cb"], s["coarse"], s["offsets"], s["lcodes"], s["lids"], nprobe, ht, k,
+                           probed_in=probed, qcodes_in=qcodes)
+        assert_ivf_topk_matches(ids.cpu().numpy(), d.cpu().numpy(), ref, xq, s["cb"], s["coarse"], s["offsets"],
+                                s["lcodes"], s["lids"], probed, qcodes, ht, O.build_lut,
+                                what=f"spread {spread} nq {nq} nprobe {nprobe}")
+        # the bit strings are the oracle's own except on near-ties of a table row
+        own = O.ivf_search(xq, s["cb"], s["coarse"], s["offsets"], s["lcodes"], s["lids"], nprobe, ht, k, probed_in=probed)
+        assert (own["nsurv"] != ref["nsurv"]).sum() <= max(1, 0.1 * nq)
