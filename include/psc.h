@@ -120,8 +120,21 @@ int psc_optimize_index_assignment(psc_index *idx, int64_t n_iter, double t0, dou
 int psc_set_codebook(psc_index *idx, const float *cb_host);
 int psc_get_codebook(const psc_index *idx, float *cb_host);
 
-/* Bring the index's device image up to date now (codebook; coarse centroids and per-list tables
- * if an inverted file is set up), so that later device calls neither allocate nor block.
+/* ------------------------------------------------------------------ transformation in front of the quantizer */
+/* Section 4.3 applies an optimized rotation before encoding with the product quantizer; the
+ * additional results also reduce the dimension inside that transformation (128-D to 64-D in front
+ * of 8 sub-quantizers, 96-D to 80-D in front of 20).  psc_set_rotation installs the matrix
+ * r_host [dim][dim_in] (float32, row-major; dim = the index's dimension, 1 <= dim_in <= 4096; any
+ * matrix: a rotation, a projection, their product) -- learning it is the caller's business.
+ * psc_rotate computes y_dev [n][dim] = x_dev [n][dim_in] . r^T on the matrix cores in full float32
+ * (products accumulated in ascending coordinate order): the step in front of psc_encode,
+ * psc_build_lut, psc_search, psc_knn_graph, psc_ivf_assign_encode and psc_ivf_search, which all
+ * take vectors of the index's own dimension.  Both buffers are the caller's. */
+int psc_set_rotation(psc_index *idx, const float *r_host, int dim_in);
+int psc_rotate(const psc_index *idx, const float *x_dev, int64_t n, float *y_dev, psc_stream stream);
+
+/* Bring the index's device image up to date now (codebook; transformation matrix; coarse centroids
+ * and per-list tables if an inverted file is set up), so that later device calls neither allocate nor block.
  * Synchronous. */
 int psc_prepare(const psc_index *idx, psc_stream stream);
 

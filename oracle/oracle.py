@@ -28,7 +28,7 @@ __all__ = [
     "search_flat", "ivf_search", "knn_graph", "exact_knn", "recall_at", "train_pq",
     "centroid_distances", "distance_stats", "f_map", "targets_weights", "polyd_loss",
     "swap_delta", "anneal", "apply_assignment", "optimize_index_assignment", "draw_u64",
-    "ivf_train_coarse", "ivf_build_lists", "kmeans", "nearest", "num_threads",
+    "ivf_train_coarse", "ivf_build_lists", "kmeans", "nearest", "num_threads", "rotate",
 ]
 
 _lib = None
@@ -113,6 +113,16 @@ def threshold_for_rate(hist, max_keep_fraction: float) -> int:
         else:
             break
     return ht
+
+
+# ----------------------------------------------------------------------------- transformation before the quantizer
+def rotate(x, r) -> np.ndarray:
+    """The linear map applied to every vector before the product quantizer (Section 4.3: an
+    optimized rotation before encoding; the additional results also reduce the dimension with it):
+    y [n, dout] = x [n, din] . r^T for r [dout, din], in double precision."""
+    x, r = _f64(x), _f64(r)
+    assert x.shape[1] == r.shape[1]
+    return x @ r.T
 
 
 # ----------------------------------------------------------------------------- PQ codes, tables

@@ -42,6 +42,8 @@ def _load():
         "psc_set_filter_route": (i32, [i32]),
         "psc_last_scan_route": (C.c_char_p, []),
         "psc_prepare": (i32, [vp, vp]),
+        "psc_set_rotation": (i32, [vp, vp, i32]),
+        "psc_rotate": (i32, [vp, vp, i64, vp, vp]),
         "psc_create": (i32, [C.POINTER(vp), i32, i32]),
         "psc_destroy": (None, [vp]),
         "psc_train_pq": (i32, [vp, vp, i64, i32, u64]),
@@ -82,7 +84,7 @@ def _load():
 def exported_symbols():
     """Names this binding expects the library to export."""
     _load()
-    return ["psc_version", "psc_last_error", "psc_set_filter_route", "psc_last_scan_route", "psc_prepare", "psc_create", "psc_destroy", "psc_train_pq",
+    return ["psc_version", "psc_last_error", "psc_set_filter_route", "psc_last_scan_route", "psc_prepare", "psc_set_rotation", "psc_rotate", "psc_create", "psc_destroy", "psc_train_pq",
             "psc_train_pq_device", "psc_ivf_train_coarse_device",
             "psc_optimize_index_assignment", "psc_set_codebook", "psc_get_codebook", "psc_encode",
             "psc_build_lut", "psc_hamming_filter", "psc_hamming_histogram", "psc_threshold_for_rate",
@@ -180,6 +182,21 @@ class Index:
         cb = np.empty((self.m, 256, self.dsub), dtype=np.float32)
         _check(_load().psc_get_codebook(self._h, cb.ctypes.data_as(C.c_void_p)))
         return cb
+
+    def set_rotation(self, r: np.ndarray):
+        """Install the transformation r [dim, dim_in] applied by `rotate`."""
+        r = np.ascontiguousarray(r, dtype=np.float32)
+        assert r.ndim == 2 and r.shape[0] == self.dim
+        _check(_load().psc_set_rotation(self._h, r.ctypes.data_as(C.c_void_p), r.shape[1]))
+        self.dim_in = r.shape[1]
+
+    def rotate(self, x: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+        """y [n, dim] = x [n, dim_in] . r^T."""
+        n = x.shape[0]
+        if out is None:
+            out = torch.empty((n, self.dim), dtype=torch.float32, device=x.device)
+        _check(_load().psc_rotate(self._h, _dev(x, torch.float32, "x"), n, _dev(out, torch.float32, "y"), _stream()))
+        return out
 
     def prepare(self):
         """Upload the index's device image now, so that later calls neither allocate nor block."""

@@ -136,6 +136,7 @@ void psc_destroy(psc_index *idx)
     if (idx->cb_dev) (void)hipFree(idx->cb_dev);
     if (idx->coarse_dev) (void)hipFree(idx->coarse_dev);
     if (idx->list_tab_dev) (void)hipFree(idx->list_tab_dev);
+    if (idx->rot_dev) (void)hipFree(idx->rot_dev);
     delete idx;
 }
 
@@ -567,10 +568,67 @@ static int need_coarse(const psc_index *idx)
     return sync_coarse_to_device(idx);
 }
 
+static int sync_rotation_to_device(const psc_index *idx)
+{
+    std::lock_guard<std::mutex> guard(idx->image_lock);
+    if (idx->rot_current) return PSC_OK;
+    if (idx->rot_dev) {
+        PSC_HIP_TRY(hipDeviceSynchronize());  // earlier kernels may still read the old matrix
+        PSC_HIP_TRY(hipFree(idx->rot_dev));
+        idx->rot_dev = nullptr;
+    }
+    const size_t bytes = idx->rot_host.size() * sizeof(float);
+    PSC_HIP_TRY(hipMalloc((void **)&idx->rot_dev, bytes));
+    PSC_HIP_TRY(hipMemcpy(idx->rot_dev, idx->rot_host.data(), bytes, hipMemcpyHostToDevice));
+    idx->rot_current = true;
+    return PSC_OK;
+}
+
+int psc_set_rotation(psc_index *idx, const float *r_host, int dim_in)
+{
+    PSC_REQUIRE(idx && r_host, "null pointer");
+    PSC_REQUIRE(dim_in >= 1 && dim_in <= 4096, "input dimension must be in [1, 4096], got %d", dim_in);
+    const int dout = idx->dim;
+    const int din_pad = (dim_in + 63) / 64 * 64, dout_pad = (dout + 31) / 32 * 32;
+    try {
+        idx->rot_host.assign((size_t)din_pad * dout_pad, 0.f);
+    } catch (const std::bad_alloc &) {
+        set_error("out of host memory");
+        return PSC_ENOMEM;
+    }
+    for (int c = 0; c < dout; ++c)
+        for (int t = 0; t < dim_in; ++t) idx->rot_host[(size_t)t * dout_pad + c] = r_host[(size_t)c * dim_in + t];
+    idx->rot_din = dim_in;
+    idx->rot_din_pad = din_pad;
+    idx->rot_dout_pad = dout_pad;
+    idx->rot_current = false;
+    return PSC_OK;
+}
+
+int psc_rotate(const psc_index *idx, const float *x_dev, int64_t n, float *y_dev, psc_stream stream)
+{
+    PSC_REQUIRE(idx != nullptr, "null index");
+    if (idx->rot_din == 0) {
+        set_error("no transformation: call psc_set_rotation first");
+        return PSC_ESTATE;
+    }
+    PSC_REQUIRE(n >= 0, "negative n");
+    if (n == 0) return PSC_OK;
+    PSC_REQUIRE(x_dev && y_dev, "null pointer");
+    int rc = sync_rotation_to_device(idx);
+    if (rc != PSC_OK) return rc;
+    return launch_rotate(x_dev, n, idx->rot_din, idx->rot_dev, idx->rot_din_pad, idx->dim, idx->rot_dout_pad, y_dev,
+                         (hipStream_t)stream);
+}
+
 int psc_prepare(const psc_index *idx, psc_stream stream)
 {
     int rc = need_codebook(idx);
     if (rc != PSC_OK) return rc;
+    if (idx->rot_din != 0) {
+        rc = sync_rotation_to_device(idx);
+        if (rc != PSC_OK) return rc;
+    }
     if (idx->nlist == 0) return PSC_OK;
     rc = need_coarse(idx);
     if (rc != PSC_OK) return rc;

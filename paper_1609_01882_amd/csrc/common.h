@@ -65,6 +65,12 @@ int launch_lut_mfma(const float *cb_dev, const float *cbc_dev, const float *mu_d
                     const float *x_dev, int64_t nrows, float *lut_dev, hipStream_t s);
 int launch_row_argmin(const float *lut_dev, int64_t nrows_total, uint8_t *codes_dev, hipStream_t s);
 
+// ---- linear transformation in front of the quantizer (kernels_rotate.hip)
+// y [n][dout] = x [n][din] . R^T with the matrix stored transposed and zero-padded:
+// rt [din_pad][dout_pad], din_pad a multiple of 64, dout_pad of 32.
+int launch_rotate(const float *x_dev, int64_t n, int din, const float *rt_dev, int din_pad, int dout, int dout_pad,
+                  float *y_dev, hipStream_t s);
+
 // ---- device launchers (kernels_scan.hip)
 // Which Hamming filter the scans take where both apply: PSC_ROUTE_* of psc_set_filter_route.
 extern std::atomic<int> g_filter_route;
@@ -192,6 +198,12 @@ struct psc_index {
     std::vector<float> cb_host;  // [m][256][dsub], the master copy
     mutable float *cb_dev = nullptr;   // [m][256][dsub], then the centred copy, then mu [m][dsub]
     mutable bool dev_current = false;  // device copy matches cb_host
+    // linear transformation in front of the quantizer (psc_set_rotation): the matrix transposed and
+    // zero-padded, [rot_din_pad][rot_dout_pad]; rot_din = 0: none set
+    int rot_din = 0, rot_din_pad = 0, rot_dout_pad = 0;
+    std::vector<float> rot_host;
+    mutable float *rot_dev = nullptr;
+    mutable bool rot_current = false;
     // inverted file: coarse centroids (owned) and borrowed views of the caller's lists
     int nlist = 0;
     std::vector<float> coarse_host;  // [nlist][dim]
