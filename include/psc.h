@@ -116,6 +116,18 @@ int psc_optimize_index_assignment(psc_index *idx, int64_t n_iter, double t0, dou
                                   double alpha, uint64_t seed, uint8_t *perm_out_host,
                                   double *loss_out_host);
 
+/* The same annealing on the ranking loss of Section 3.1 ("PolyR" in Section 4.2): the loss of an
+ * assignment is the sum over ordered pairs of centroids (i, j), j != i, of
+ * alpha_rank(i,j) * ell_r, with alpha_r = 1/r and ell_r = 1 + 1/2 + ... + 1/r, where rank(i,j) is
+ * the place of j among the centroids ordered by distance to i (the nearest other centroid has rank
+ * 1) and r = the number of centroids that lie farther from i than j does, yet whose index is
+ * nearer to pi[i] in Hamming distance than pi[j] is.  Same proposals, acceptance rule, random
+ * draws, renumbering and outputs as psc_optimize_index_assignment; an iteration recounts all 65536
+ * pairs (about 0.1 ms), so the paper's 500000 iterations take about a minute per sub-quantizer
+ * (one host thread each).  A comparison baseline: the paper retains the distance-estimator loss. */
+int psc_optimize_index_assignment_ranking(psc_index *idx, int64_t n_iter, double t0, double t_decay,
+                                          uint64_t seed, uint8_t *perm_out_host, double *loss_out_host);
+
 /* Install / read back the codebook, cb_host [m][256][dim/m] float32. */
 int psc_set_codebook(psc_index *idx, const float *cb_host);
 int psc_get_codebook(const psc_index *idx, float *cb_host);

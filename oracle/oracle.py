@@ -29,6 +29,8 @@ __all__ = [
     "centroid_distances", "distance_stats", "f_map", "targets_weights", "polyd_loss",
     "swap_delta", "anneal", "apply_assignment", "optimize_index_assignment", "draw_u64",
     "ivf_train_coarse", "ivf_build_lists", "kmeans", "nearest", "num_threads", "rotate",
+    "disidx", "neighbour_ranks", "rank_violations", "ell", "polyr_loss", "polyr_swap_delta", "anneal_ranking",
+    "optimize_index_assignment_ranking", "search_by_code_distance",
 ]
 
 _lib = None
@@ -41,6 +43,9 @@ def _L():
         _lib.orc_f.restype = C.c_double
         _lib.orc_polyd_loss.restype = C.c_double
         _lib.orc_swap_delta.restype = C.c_double
+        _lib.orc_ell.restype = C.c_double
+        _lib.orc_polyr_loss.restype = C.c_double
+        _lib.orc_polyr_swap_delta.restype = C.c_double
         _lib.orc_draw_u64.restype = C.c_uint64
         _lib.orc_draw_u64.argtypes = [C.c_uint64, C.c_uint64]
     return _lib
@@ -163,8 +168,20 @@ def query_codes(lut) -> np.ndarray:
 
 
 # ----------------------------------------------------------------------------- scans
-def scan(lut, qcodes, codes, ht: int, k: int, ext_ids=None, skip_id=None, want_bitmap=False):
-    """Hamming filter (keep iff distance <= ht), ADC on survivors, first k by (dist, id).
+def disidx(a, b) -> int:
+    """Number of sub-quantizers whose index differs (Section 3.3, second paragraph)."""
+    a, b = _u8(a).ravel(), _u8(b).ravel()
+    assert a.size == b.size
+    return int(_L().orc_disidx(_p(a), _p(b), C.c_int(a.size)))
+
+
+FILTERS = {"hamming": 0, "disidx": 1}
+
+
+def scan(lut, qcodes, codes, ht: int, k: int, ext_ids=None, skip_id=None, want_bitmap=False, filter="hamming"):
+    """Filter (keep iff distance <= ht), ADC on survivors, first k by (dist, id).  filter:
+    "hamming" = Hamming distance between the codes read as bit strings (the polysemous filter);
+    "disidx" = number of differing indexes (the comparison baseline of Section 4.2).
 
     Returns dict(ids [nq,k] int64, dists [nq,k] float64, nsurv [nq] int64[, bitmap [nq,n] uint8]).
     """
@@ -178,15 +195,44 @@ def scan(lut, qcodes, codes, ht: int, k: int, ext_ids=None, skip_id=None, want_b
     ext = np.ascontiguousarray(ext_ids, dtype=np.int64) if ext_ids is not None else None
     skip = np.ascontiguousarray(skip_id, dtype=np.int64) if skip_id is not None else None
     bitmap = np.zeros((nq, n), dtype=np.uint8) if want_bitmap else None
-    rc = _L().orc_scan(C.c_int(m), _p(lut), _p(qcodes), C.c_int64(nq), _p(codes), C.c_int64(n),
-                       C.c_int(ht), C.c_int(k), _p(ext), _p(skip), _p(ids), _p(dists), _p(nsurv),
-                       _p(bitmap))
+    if filter == "hamming":
+        rc = _L().orc_scan(C.c_int(m), _p(lut), _p(qcodes), C.c_int64(nq), _p(codes), C.c_int64(n),
+                           C.c_int(ht), C.c_int(k), _p(ext), _p(skip), _p(ids), _p(dists), _p(nsurv),
+                           _p(bitmap))
+    else:
+        rc = _L().orc_scan_filtered(C.c_int(m), _p(lut), _p(qcodes), C.c_int64(nq), _p(codes), C.c_int64(n),
+                                    C.c_int(FILTERS[filter]), C.c_int(ht), C.c_int(k), _p(ext), _p(skip),
+                                    _p(ids), _p(dists), _p(nsurv), _p(bitmap))
     if rc != 0:
         raise MemoryError("oracle scan")
     out = dict(ids=ids, dists=dists, nsurv=nsurv)
     if want_bitmap:
         out["bitmap"] = bitmap
     return out
+
+
+def search_by_code_distance(qcodes, codes, k: int, kind: str = "hamming", chunk: int = 256):
+    """The code-only comparison methods of Section 4.2: rank the database by the distance between
+    codes alone -- "hamming" = Hamming distance between the codes read as bit strings ("binary"),
+    "disidx" = number of differing indexes -- first k by (distance, id).  Returns (ids [nq,k] int64,
+    distances [nq,k] int32), padded with -1 when the database is shorter than k."""
+    qcodes, codes = _u8(qcodes), _u8(codes)
+    nq, n = qcodes.shape[0], codes.shape[0]
+    ids = np.full((nq, k), -1, dtype=np.int64)
+    dist = np.full((nq, k), -1, dtype=np.int32)
+    for s in range(0, nq, chunk):
+        qc = qcodes[s:s + chunk]
+        if kind == "hamming":
+            d = hamming_matrix(qc, codes)
+        elif kind == "disidx":
+            d = (qc[:, None, :] != codes[None, :, :]).sum(axis=2).astype(np.int32)
+        else:
+            raise ValueError(kind)
+        for q in range(qc.shape[0]):
+            order = np.lexsort((np.arange(n), d[q]))[:k]
+            ids[s + q, :len(order)] = order
+            dist[s + q, :len(order)] = d[q][order]
+    return ids, dist
 
 
 def search_flat(queries, codebook, codes, ht: int, k: int, **kw):
@@ -422,6 +468,63 @@ def optimize_index_assignment(codebook, n_iter=500_000, t0=0.7, t_decay=0.9 ** (
     li, lf = np.empty(m), np.empty(m)
     for j in range(m):
         r = anneal(cb[j], n_iter, t0, t_decay, alpha, seed + j)
+        pis[j], li[j], lf[j] = r["pi"], r["loss_init"], r["loss_final"]
+        out[j] = apply_assignment(cb[j], r["pi"])
+    return out, pis, (li, lf)
+
+
+# ----------------------------------------------------------------------------- ranking loss
+def neighbour_ranks(dmat) -> np.ndarray:
+    """rank[i, j] = place of centroid j among the centroids ordered by distance to i (the nearest
+    other centroid has rank 1; rank[i, i] = 0)."""
+    dmat = _f64(dmat)
+    rank = np.empty((256, 256), dtype=np.int32)
+    _L().orc_neighbour_ranks(_p(dmat), _p(rank))
+    return rank
+
+
+def rank_violations(dmat, pi, i: int, j: int) -> int:
+    return int(_L().orc_rank_violations(_p(_f64(dmat)), _p(_u8(pi)), C.c_int(i), C.c_int(j)))
+
+
+def ell(r: int) -> float:
+    return float(_L().orc_ell(C.c_int(r)))
+
+
+def polyr_loss(dmat, rank, pi) -> float:
+    rank = np.ascontiguousarray(rank, dtype=np.int32)
+    return float(_L().orc_polyr_loss(_p(_f64(dmat)), _p(rank), _p(_u8(pi))))
+
+
+def polyr_swap_delta(dmat, rank, pi, a: int, b: int) -> float:
+    rank = np.ascontiguousarray(rank, dtype=np.int32)
+    return float(_L().orc_polyr_swap_delta(_p(_f64(dmat)), _p(rank), _p(_u8(pi)), C.c_int(a), C.c_int(b)))
+
+
+def anneal_ranking(cent, n_iter=500_000, t0=0.7, t_decay=0.9 ** (1.0 / 500.0), seed=0, want_trace=False):
+    """Simulated annealing of one sub-quantizer's index assignment on the ranking loss (Sections
+    3.1 and 3.2).  Returns dict(pi [256] uint8, loss_init, loss_final[, trace])."""
+    cent = _f64(cent)
+    pi = np.empty(256, dtype=np.uint8)
+    li, lf = C.c_double(), C.c_double()
+    trace = np.empty(n_iter + 1, dtype=np.float64) if want_trace else None
+    _L().orc_anneal_ranking(_p(cent), C.c_int(cent.shape[1]), C.c_int64(n_iter), C.c_double(t0),
+                            C.c_double(t_decay), C.c_uint64(seed), _p(pi), C.byref(li), C.byref(lf), _p(trace))
+    out = dict(pi=pi, loss_init=li.value, loss_final=lf.value)
+    if want_trace:
+        out["trace"] = trace
+    return out
+
+
+def optimize_index_assignment_ranking(codebook, n_iter=2000, t0=0.7, t_decay=0.9 ** (1.0 / 500.0), seed=0):
+    """`optimize_index_assignment` on the ranking loss (slow: an iteration costs milliseconds here)."""
+    cb = _f64(codebook)
+    m = cb.shape[0]
+    out = np.empty_like(cb)
+    pis = np.empty((m, 256), dtype=np.uint8)
+    li, lf = np.empty(m), np.empty(m)
+    for j in range(m):
+        r = anneal_ranking(cb[j], n_iter, t0, t_decay, seed + j)
         pis[j], li[j], lf[j] = r["pi"], r["loss_init"], r["loss_final"]
         out[j] = apply_assignment(cb[j], r["pi"])
     return out, pis, (li, lf)

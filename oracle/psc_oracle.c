@@ -192,6 +192,7 @@ static int cand_cmp(const void *pa, const void *pb)
 }
 
 /*
+ * (Arguments of orc_scan and orc_scan_filtered.)
  * lut [nq][m][256] (double), qcodes [nq][m], codes [n][m].
  * ext_ids: NULL -> the id of database row i is i; else the id is ext_ids[i].
  * skip_id: NULL -> nothing skipped; else for query q the row whose id equals
@@ -202,9 +203,34 @@ static int cand_cmp(const void *pa, const void *pb)
  * surv_bitmap (may be NULL): [nq][n] bytes, 1 where the code survives.
  * Returns 0, or -1 on allocation failure.
  */
+/* The alternative filter of Section 3.3 (second paragraph; "disidx" in Section 4.2): how many   */
+/* sub-quantizers give an index different from the query's -- a Hamming distance between vectors */
+/* of indexes, not of bits.                                                                      */
+int orc_disidx(const uint8_t *a, const uint8_t *b, int nbytes)
+{
+    int h = 0;
+    for (int j = 0; j < nbytes; ++j)
+        h += (a[j] != b[j]);
+    return h;
+}
+
+int orc_scan_filtered(int m, const double *lut, const uint8_t *qcodes, int64_t nq, const uint8_t *codes,
+                      int64_t n, int filter, int ht, int k, const int64_t *ext_ids, const int64_t *skip_id,
+                      int64_t *ids, double *dists, int64_t *nsurv, uint8_t *surv_bitmap);
+
 int orc_scan(int m, const double *lut, const uint8_t *qcodes, int64_t nq, const uint8_t *codes,
              int64_t n, int ht, int k, const int64_t *ext_ids, const int64_t *skip_id,
              int64_t *ids, double *dists, int64_t *nsurv, uint8_t *surv_bitmap)
+{
+    return orc_scan_filtered(m, lut, qcodes, nq, codes, n, 0, ht, k, ext_ids, skip_id, ids, dists, nsurv,
+                             surv_bitmap);
+}
+
+/* filter = 0: Hamming distance over the bits (the polysemous filter, "dual");                   */
+/* filter = 1: number of differing indexes ("disidx"), kept iff that number is <= ht.            */
+int orc_scan_filtered(int m, const double *lut, const uint8_t *qcodes, int64_t nq, const uint8_t *codes,
+                      int64_t n, int filter, int ht, int k, const int64_t *ext_ids, const int64_t *skip_id,
+                      int64_t *ids, double *dists, int64_t *nsurv, uint8_t *surv_bitmap)
 {
     int failed = 0;
 #pragma omp parallel for schedule(dynamic, 1)
@@ -220,7 +246,7 @@ int orc_scan(int m, const double *lut, const uint8_t *qcodes, int64_t nq, const 
         int64_t ns = 0, nc = 0;
         for (int64_t i = 0; i < n; ++i) {
             const uint8_t *code = codes + i * m;
-            int h = orc_hamming(qc, code, m);
+            int h = filter == 1 ? orc_disidx(qc, code, m) : orc_hamming(qc, code, m);
             int keep = (h <= ht);
             if (surv_bitmap)
                 surv_bitmap[q * n + i] = (uint8_t)keep;
@@ -574,4 +600,140 @@ void orc_apply_assignment(const double *cent_in, int dsub, const uint8_t *pi, do
 {
     for (int i = 0; i < NCENT; ++i)
         memcpy(cent_out + (int64_t)pi[i] * dsub, cent_in + (int64_t)i * dsub, sizeof(double) * dsub);
+}
+
+
+/* ------------------------------------------------------------------------- */
+/* Ranking loss (Section 3.1, "Ranking loss") and its annealing.              */
+/*                                                                            */
+/*   rank(i,j)  = position of j in the list of centroids ordered by distance  */
+/*                to i: the number of centroids k with d_ik < d_ij.  Centroid  */
+/*                i itself (d_ii = 0) is one of them, so the nearest other     */
+/*                centroid has rank 1.  (The printed formula counts the        */
+/*                centroids FARTHER than j; the text next to it calls it the   */
+/*                rank of j among the neighbours of i and uses it to weigh     */
+/*                far-away j down, which only the count of nearer ones does.)  */
+/*   r_pi(i,j)  = number of k that are farther from i than j by centroid       */
+/*                distance but nearer than j by Hamming distance of indexes:   */
+/*                sum_k [d_ij < d_ik] [h(pi_i,pi_j) > h(pi_i,pi_k)]            */
+/*   alpha_r    = 1/r,   ell_r = alpha_1 + ... + alpha_r  (ell_0 = 0)          */
+/*   L(pi)      = sum_{i != j} alpha_rank(i,j) * ell_{r_pi(i,j)}               */
+/* ------------------------------------------------------------------------- */
+void orc_neighbour_ranks(const double *dmat, int32_t *rank /*256x256*/)
+{
+    for (int i = 0; i < NCENT; ++i)
+        for (int j = 0; j < NCENT; ++j) {
+            int r = 0;
+            for (int k = 0; k < NCENT; ++k)
+                r += dmat[i * NCENT + k] < dmat[i * NCENT + j];
+            rank[i * NCENT + j] = r;
+        }
+}
+
+int orc_rank_violations(const double *dmat, const uint8_t *pi, int i, int j)
+{
+    int r = 0;
+    int hij = hamming_idx(pi[i], pi[j]);
+    for (int k = 0; k < NCENT; ++k)
+        r += (dmat[i * NCENT + j] < dmat[i * NCENT + k]) && (hij > hamming_idx(pi[i], pi[k]));
+    return r;
+}
+
+double orc_ell(int r)
+{
+    double s = 0.0;
+    for (int t = 1; t <= r; ++t)
+        s += 1.0 / (double)t;
+    return s;
+}
+
+/* Full evaluation, O(2^{3d}).  Pairs with rank 0 (j = i, or an exact duplicate of centroid i) have */
+/* no weight alpha_0 and are left out. */
+double orc_polyr_loss(const double *dmat, const int32_t *rank, const uint8_t *pi)
+{
+    double L = 0.0;
+    for (int i = 0; i < NCENT; ++i)
+        for (int j = 0; j < NCENT; ++j) {
+            if (j == i || rank[i * NCENT + j] == 0)
+                continue;
+            L += orc_ell(orc_rank_violations(dmat, pi, i, j)) / (double)rank[i * NCENT + j];
+        }
+    return L;
+}
+
+/* Loss change if entries a and b of pi were swapped, O(2^{2d}): for a pair (i,j) with i, j outside */
+/* {a,b} only the two terms k = a and k = b of r_pi(i,j) can change; pairs with i or j in {a,b} are */
+/* counted afresh.  Pairs whose count does not change contribute exactly nothing.                  */
+double orc_polyr_swap_delta(const double *dmat, const int32_t *rank, const uint8_t *pi, int a, int b)
+{
+    uint8_t pj[NCENT];
+    memcpy(pj, pi, NCENT);
+    pj[a] = pi[b];
+    pj[b] = pi[a];
+    double delta = 0.0;
+    for (int i = 0; i < NCENT; ++i)
+        for (int j = 0; j < NCENT; ++j) {
+            if (j == i || rank[i * NCENT + j] == 0)
+                continue;
+            int r_old, r_new;
+            if (i == a || i == b || j == a || j == b) {
+                r_old = orc_rank_violations(dmat, pi, i, j);
+                r_new = orc_rank_violations(dmat, pj, i, j);
+                if (r_old == r_new)
+                    continue;
+            } else {
+                /* only k = a and k = b see another index; h(pi_i, pi_j) is unchanged */
+                int hij = hamming_idx(pi[i], pi[j]);
+                int fa = dmat[i * NCENT + j] < dmat[i * NCENT + a];
+                int fb = dmat[i * NCENT + j] < dmat[i * NCENT + b];
+                int before = (fa && hij > hamming_idx(pi[i], pi[a])) + (fb && hij > hamming_idx(pi[i], pi[b]));
+                int after = (fa && hij > hamming_idx(pi[i], pj[a])) + (fb && hij > hamming_idx(pi[i], pj[b]));
+                if (before == after)
+                    continue;
+                r_old = orc_rank_violations(dmat, pi, i, j);
+                r_new = r_old - before + after;
+            }
+            delta += (orc_ell(r_new) - orc_ell(r_old)) / (double)rank[i * NCENT + j];
+        }
+    return delta;
+}
+
+/* The annealing of Section 3.2 on the ranking loss: same loop, same random draws as orc_anneal. */
+void orc_anneal_ranking(const double *cent, int dsub, int64_t n_iter, double t0, double t_decay,
+                        uint64_t seed, uint8_t *pi_out, double *loss_init, double *loss_final,
+                        double *loss_trace)
+{
+    double *dmat = (double *)malloc(sizeof(double) * NCENT * NCENT);
+    int32_t *rank = (int32_t *)malloc(sizeof(int32_t) * NCENT * NCENT);
+    orc_centroid_distances(cent, dsub, dmat);
+    orc_neighbour_ranks(dmat, rank);
+    uint8_t pi[NCENT];
+    for (int i = 0; i < NCENT; ++i)
+        pi[i] = (uint8_t)i;
+    double L = orc_polyr_loss(dmat, rank, pi);
+    if (loss_init)
+        *loss_init = L;
+    double t = t0;
+    for (int64_t it = 0; it < n_iter; ++it) {
+        if (loss_trace)
+            loss_trace[it] = L;
+        int i = (int)(draw_u64(seed, 3 * (uint64_t)it) % NCENT);
+        int j = (int)((i + 1 + draw_u64(seed, 3 * (uint64_t)it + 1) % (NCENT - 1)) % NCENT);
+        double u = (double)(draw_u64(seed, 3 * (uint64_t)it + 2) >> 11) * (1.0 / 9007199254740992.0);
+        double dC = orc_polyr_swap_delta(dmat, rank, pi, i, j);
+        if (dC < 0.0 || u < t) {
+            uint8_t tmp = pi[i];
+            pi[i] = pi[j];
+            pi[j] = tmp;
+            L += dC;
+        }
+        t *= t_decay;
+    }
+    if (loss_trace)
+        loss_trace[n_iter] = L;
+    if (loss_final)
+        *loss_final = orc_polyr_loss(dmat, rank, pi);
+    memcpy(pi_out, pi, NCENT);
+    free(dmat);
+    free(rank);
 }

@@ -49,6 +49,7 @@ def _load():
         "psc_train_pq": (i32, [vp, vp, i64, i32, u64]),
         "psc_train_pq_device": (i32, [vp, vp, i64, i32, u64, i32, vp, vp]),
         "psc_optimize_index_assignment": (i32, [vp, i64, dbl, dbl, dbl, u64, vp, vp]),
+        "psc_optimize_index_assignment_ranking": (i32, [vp, i64, dbl, dbl, u64, vp, vp]),
         "psc_set_codebook": (i32, [vp, vp]),
         "psc_get_codebook": (i32, [vp, vp]),
         "psc_encode": (i32, [vp, vp, i64, vp, vp]),
@@ -86,7 +87,7 @@ def exported_symbols():
     _load()
     return ["psc_version", "psc_last_error", "psc_set_filter_route", "psc_last_scan_route", "psc_prepare", "psc_set_rotation", "psc_rotate", "psc_create", "psc_destroy", "psc_train_pq",
             "psc_train_pq_device", "psc_ivf_train_coarse_device",
-            "psc_optimize_index_assignment", "psc_set_codebook", "psc_get_codebook", "psc_encode",
+            "psc_optimize_index_assignment", "psc_optimize_index_assignment_ranking", "psc_set_codebook", "psc_get_codebook", "psc_encode",
             "psc_build_lut", "psc_hamming_filter", "psc_hamming_histogram", "psc_threshold_for_rate",
             "psc_scan_workspace_bytes", "psc_scan", "psc_scan_static",
             "psc_search_workspace_bytes", "psc_search", "psc_knn_graph_workspace_bytes",
@@ -171,6 +172,16 @@ class Index:
         _check(_load().psc_optimize_index_assignment(self._h, n_iter, t0, t_decay, alpha, seed,
                                                      pi.ctypes.data_as(C.c_void_p),
                                                      loss.ctypes.data_as(C.c_void_p)))
+        return pi, loss
+
+    def optimize_index_assignment_ranking(self, n_iter: int = 500_000, t0: float = 0.7,
+                                          t_decay: float = 0.9 ** (1.0 / 500.0), seed: int = 0):
+        """The annealing on the ranking loss.  Returns (pi [m,256] uint8, losses [m,2] = before/after)."""
+        pi = np.empty((self.m, 256), dtype=np.uint8)
+        loss = np.empty((self.m, 2), dtype=np.float64)
+        _check(_load().psc_optimize_index_assignment_ranking(self._h, n_iter, t0, t_decay, seed,
+                                                             pi.ctypes.data_as(C.c_void_p),
+                                                             loss.ctypes.data_as(C.c_void_p)))
         return pi, loss
 
     def set_codebook(self, cb: np.ndarray):

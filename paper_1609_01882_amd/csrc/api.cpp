@@ -162,9 +162,24 @@ int psc_train_pq(psc_index *idx, const float *x_host, int64_t n, int iters, uint
     return mark_codebook_changed(idx);
 }
 
+static int optimize_assignment(psc_index *idx, bool ranking, int64_t n_iter, double t0, double t_decay, double alpha,
+                               uint64_t seed, uint8_t *perm_out_host, double *loss_out_host);
+
 int psc_optimize_index_assignment(psc_index *idx, int64_t n_iter, double t0, double t_decay,
                                   double alpha, uint64_t seed, uint8_t *perm_out_host,
                                   double *loss_out_host)
+{
+    return optimize_assignment(idx, false, n_iter, t0, t_decay, alpha, seed, perm_out_host, loss_out_host);
+}
+
+int psc_optimize_index_assignment_ranking(psc_index *idx, int64_t n_iter, double t0, double t_decay, uint64_t seed,
+                                          uint8_t *perm_out_host, double *loss_out_host)
+{
+    return optimize_assignment(idx, true, n_iter, t0, t_decay, 0.5, seed, perm_out_host, loss_out_host);
+}
+
+static int optimize_assignment(psc_index *idx, bool ranking, int64_t n_iter, double t0, double t_decay, double alpha,
+                               uint64_t seed, uint8_t *perm_out_host, double *loss_out_host)
 {
     PSC_REQUIRE(idx != nullptr, "null index");
     if (!idx->has_codebook) {
@@ -182,7 +197,10 @@ int psc_optimize_index_assignment(psc_index *idx, int64_t n_iter, double t0, dou
             std::vector<float> renum(sq);
             uint8_t pi[kCentroids];
             double before = 0.0, after = 0.0;
-            host_anneal(cent, idx->dsub, n_iter, t0, t_decay, alpha, seed + (uint64_t)j, pi, &before, &after);
+            if (ranking)
+                host_anneal_ranking(cent, idx->dsub, n_iter, t0, t_decay, seed + (uint64_t)j, pi, &before, &after);
+            else
+                host_anneal(cent, idx->dsub, n_iter, t0, t_decay, alpha, seed + (uint64_t)j, pi, &before, &after);
             for (int i = 0; i < kCentroids; ++i)
                 std::memcpy(&renum[(size_t)pi[i] * idx->dsub], cent + (size_t)i * idx->dsub,
                             sizeof(float) * idx->dsub);

@@ -45,6 +45,10 @@ void kmeans_start_rows(int64_t n, int ncent, uint64_t seed, int64_t *rows);
 void host_anneal(const float *cent, int dsub, int64_t n_iter, double t0, double t_decay,
                  double alpha, uint64_t seed, uint8_t *pi, double *loss_before, double *loss_after);
 
+// The same annealing on the ranking loss (Section 3.1 "Ranking loss").
+void host_anneal_ranking(const float *cent, int dsub, int64_t n_iter, double t0, double t_decay, uint64_t seed,
+                         uint8_t *pi, double *loss_before, double *loss_after);
+
 // ---- device launchers (kernels_lut.hip)
 // Row selection for tables / codes built from "virtual" rows:
 //   row r uses vector x[row_idx ? row_idx[r] : r] minus (sub ? sub[sub_idx[r]] : 0).

@@ -213,6 +213,149 @@ struct Objective {
 
 }  // namespace
 
+namespace {
+
+// The ranking objective of Section 3.1: sum over ordered pairs (i, j), j != i, of
+// alpha_rank(i,j) * ell_{r_pi(i,j)}, alpha_r = 1/r, ell_r = 1 + 1/2 + ... + 1/r, where rank(i,j)
+// is the place of j among the centroids ordered by distance to i (the nearest other centroid has
+// rank 1) and r_pi(i,j) counts the centroids k that are farther from i than j by centroid
+// distance yet nearer than j by Hamming distance between indices.
+// Sets of centroids are 256-bit masks: far[i][j] = {k : d_ij < d_ik} is fixed; for the current
+// assignment nearer[i][h] = {k : h(pi_i, pi_k) < h}, so r_pi(i,j) = |far[i][j] & nearer[i][h(pi_i,pi_j)]|
+// -- four and/popcount steps -- and a proposal is scored by recounting every pair.
+struct RankingObjective {
+    struct Mask {
+        uint64_t w[4];
+    };
+    std::vector<Mask> far;           // [256][256]
+    std::vector<int32_t> rank;       // [256][256]
+    std::vector<uint16_t> viol;      // [256][256] r_pi of the current assignment
+    std::vector<Mask> nearer;        // [256][9]
+    double ell[kCentroids + 1];
+    uint8_t hd[kCentroids][kCentroids];
+
+    RankingObjective(const float *cent, int dsub)
+        : far((size_t)kCentroids * kCentroids), rank((size_t)kCentroids * kCentroids),
+          viol((size_t)kCentroids * kCentroids), nearer((size_t)kCentroids * 9)
+    {
+        for (int a = 0; a < kCentroids; ++a)
+            for (int b = 0; b < kCentroids; ++b) hd[a][b] = (uint8_t)__builtin_popcount(a ^ b);
+        ell[0] = 0.0;
+        for (int r = 1; r <= kCentroids; ++r) {  // each ell_r summed from 1/1 upwards
+            double acc = 0.0;
+            for (int t = 1; t <= r; ++t) acc += 1.0 / (double)t;
+            ell[r] = acc;
+        }
+        std::vector<double> dist((size_t)kCentroids * kCentroids);
+        for (int i = 0; i < kCentroids; ++i)
+            for (int j = 0; j < kCentroids; ++j) {
+                double acc = 0.0;
+                for (int t = 0; t < dsub; ++t) {
+                    double df = (double)cent[(size_t)i * dsub + t] - (double)cent[(size_t)j * dsub + t];
+                    acc += df * df;
+                }
+                dist[(size_t)i * kCentroids + j] = std::sqrt(acc);
+            }
+        for (int i = 0; i < kCentroids; ++i)
+            for (int j = 0; j < kCentroids; ++j) {
+                Mask f = {{0, 0, 0, 0}};
+                int nearer_than_j = 0;
+                const double dij = dist[(size_t)i * kCentroids + j];
+                for (int k = 0; k < kCentroids; ++k) {
+                    const double dik = dist[(size_t)i * kCentroids + k];
+                    if (dij < dik) f.w[k >> 6] |= 1ull << (k & 63);
+                    nearer_than_j += dik < dij;
+                }
+                far[(size_t)i * kCentroids + j] = f;
+                rank[(size_t)i * kCentroids + j] = nearer_than_j;
+            }
+    }
+
+    void build_nearer(const uint8_t *pi, std::vector<Mask> &out) const
+    {
+        for (int i = 0; i < kCentroids; ++i) {
+            Mask eq[9];
+            std::memset(eq, 0, sizeof eq);
+            for (int k = 0; k < kCentroids; ++k) eq[hd[pi[i]][pi[k]]].w[k >> 6] |= 1ull << (k & 63);
+            Mask run = {{0, 0, 0, 0}};
+            for (int h = 0; h < 9; ++h) {  // nearer[h] = union of eq[0 .. h-1]
+                out[(size_t)i * 9 + h] = run;
+                for (int w = 0; w < 4; ++w) run.w[w] |= eq[h].w[w];
+            }
+        }
+    }
+
+    static int count(const Mask &a, const Mask &b)
+    {
+        return __builtin_popcountll(a.w[0] & b.w[0]) + __builtin_popcountll(a.w[1] & b.w[1]) +
+               __builtin_popcountll(a.w[2] & b.w[2]) + __builtin_popcountll(a.w[3] & b.w[3]);
+    }
+
+    void count_all(const uint8_t *pi, const std::vector<Mask> &nr, std::vector<uint16_t> &out) const
+    {
+        for (int i = 0; i < kCentroids; ++i)
+            for (int j = 0; j < kCentroids; ++j)
+                out[(size_t)i * kCentroids + j] =
+                    (uint16_t)count(far[(size_t)i * kCentroids + j], nr[(size_t)i * 9 + hd[pi[i]][pi[j]]]);
+    }
+
+    void set_assignment(const uint8_t *pi)
+    {
+        build_nearer(pi, nearer);
+        count_all(pi, nearer, viol);
+    }
+
+    double loss() const
+    {
+        double L = 0.0;
+        for (int i = 0; i < kCentroids; ++i)
+            for (int j = 0; j < kCentroids; ++j) {
+                const size_t e = (size_t)i * kCentroids + j;
+                if (j == i || rank[e] == 0) continue;
+                L += ell[viol[e]] / (double)rank[e];
+            }
+        return L;
+    }
+};
+
+}  // namespace
+
+void host_anneal_ranking(const float *cent, int dsub, int64_t n_iter, double t0, double t_decay, uint64_t seed,
+                         uint8_t *pi, double *loss_before, double *loss_after)
+{
+    RankingObjective obj(cent, dsub);
+    for (int i = 0; i < kCentroids; ++i) pi[i] = (uint8_t)i;
+    obj.set_assignment(pi);
+    if (loss_before) *loss_before = obj.loss();
+    std::vector<RankingObjective::Mask> nr_try(obj.nearer.size());
+    std::vector<uint16_t> viol_try(obj.viol.size());
+    double temperature = t0;
+    for (int64_t it = 0; it < n_iter; ++it) {
+        const uint64_t c = 3 * (uint64_t)it;
+        const int a = (int)(counter_draw(seed, c) % kCentroids);
+        const int b = (int)((a + 1 + counter_draw(seed, c + 1) % (kCentroids - 1)) % kCentroids);
+        const double u = (double)(counter_draw(seed, c + 2) >> 11) * 0x1.0p-53;
+        std::swap(pi[a], pi[b]);
+        obj.build_nearer(pi, nr_try);
+        obj.count_all(pi, nr_try, viol_try);
+        double delta = 0.0;  // pairs whose count is unchanged contribute exactly nothing
+        for (int i = 0; i < kCentroids; ++i)
+            for (int j = 0; j < kCentroids; ++j) {
+                const size_t e = (size_t)i * kCentroids + j;
+                if (j == i || obj.rank[e] == 0 || viol_try[e] == obj.viol[e]) continue;
+                delta += (obj.ell[viol_try[e]] - obj.ell[obj.viol[e]]) / (double)obj.rank[e];
+            }
+        if (delta < 0.0 || u < temperature) {
+            obj.nearer.swap(nr_try);
+            obj.viol.swap(viol_try);
+        } else {
+            std::swap(pi[a], pi[b]);
+        }
+        temperature *= t_decay;
+    }
+    if (loss_after) *loss_after = obj.loss();
+}
+
 void host_anneal(const float *cent, int dsub, int64_t n_iter, double t0, double t_decay,
                  double alpha, uint64_t seed, uint8_t *pi, double *loss_before, double *loss_after)
 {

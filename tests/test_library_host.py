@@ -120,6 +120,73 @@ def test_annealing_matches_oracle_trajectory(psc):
     assert np.all(loss[:, 1] < loss[:, 0])
 
 
+def test_ranking_annealing_matches_oracle_trajectory(psc):
+    """The library anneals the ranking loss with sets of centroids as bit masks, the oracle with
+    plain loops; same draws and the same double-precision terms, so both walk the same way."""
+    xt = W.sift_like(3000, seed=13, stream=1)
+    cb0 = O.train_pq(xt, 8, iters=3, seed=5).astype(np.float32)
+    idx = psc.Index(128, 8)
+    idx.set_codebook(cb0)
+    pi, loss = idx.optimize_index_assignment_ranking(n_iter=120, seed=31)
+    for j in (0, 5):
+        r = O.anneal_ranking(cb0[j].astype(np.float64), n_iter=120, seed=31 + j)
+        assert np.array_equal(pi[j], r["pi"]), j
+        assert np.isclose(loss[j, 0], r["loss_init"], rtol=1e-12) and np.isclose(loss[j, 1], r["loss_final"], rtol=1e-12)
+    # a longer run, checked through the oracle's full evaluation of the loss
+    idx.set_codebook(cb0)
+    pi, loss = idx.optimize_index_assignment_ranking(n_iter=8000, seed=32)
+    for j in (1, 6):
+        dmat = O.centroid_distances(cb0[j].astype(np.float64))
+        assert sorted(pi[j].tolist()) == list(range(256))
+        assert np.isclose(O.polyr_loss(dmat, O.neighbour_ranks(dmat), pi[j]), loss[j, 1], rtol=1e-12)
+    assert np.all(loss[:, 1] < loss[:, 0])   # (8000 iterations end at temperature 0.13: still a warm walk)
+    assert np.array_equal(idx.get_codebook()[3][pi[3]], cb0[3])     # new row pi[i] = old row i
+
+
+def test_shape_of_the_comparison_of_methods(psc):
+    """The shape of Table 1 (Section 4.2) on synthetic data without cluster structure (one wide
+    Gaussian, 32-D, 8-byte codes), recall@100 of the true nearest neighbour:
+    ranking by code distance alone -- PQ/binary < PQ/disidx < PolyR/binary <= PolyD/binary;
+    filter set to remove >= 95 % of the training pairs, then ADC -- PQ/dual far below PolyR/dual <=
+    PolyD/dual <= PQ/ADC.  The index assignments come from the library's host annealing (distance
+    loss: the paper's schedule cut to 100k iterations; ranking loss: a faster cooling, 12k
+    iterations), everything else from the oracle."""
+    kw = dict(seed=31, n_centres=1, sigma=30.0, dim=32)
+    xt = W.sift_like(4000, stream=1, **kw)
+    xb = W.sift_like(8000, stream=2, **kw) + np.random.default_rng(1).random((8000, 32)).astype(np.float32) * 0.5
+    xq = W.sift_like(200, stream=3, **kw)
+    cb_pq = O.train_pq(xt, 8, iters=8, seed=3)
+    idx = psc.Index(32, 8)
+    idx.set_codebook(cb_pq.astype(np.float32))
+    idx.optimize_index_assignment(n_iter=100_000, seed=17)
+    cb_d = idx.get_codebook().astype(np.float64)
+    idx.set_codebook(cb_pq.astype(np.float32))
+    _, loss_r = idx.optimize_index_assignment_ranking(n_iter=12_000, t_decay=0.9 ** (1.0 / 50.0), seed=17)
+    cb_r = idx.get_codebook().astype(np.float64)
+    assert np.all(loss_r[:, 1] < 0.85 * loss_r[:, 0])
+    truth = O.exact_knn(xb, xq, 1)[0][:, 0]
+    res = {}
+    for name, cbk in (("PQ", cb_pq), ("PolyD", cb_d), ("PolyR", cb_r)):
+        codes = O.encode(xb, cbk)
+        lut = O.build_lut(xq, cbk)
+        qc = O.query_codes(lut)
+        res[name + "/binary"] = O.recall_at(O.search_by_code_distance(qc, codes, 100, "hamming")[0], truth, 100)
+        tc = O.encode(xt[:1500], cbk)
+        ht = O.threshold_for_rate(O.hamming_histogram(tc[:100], tc), 0.05)
+        r = O.scan(lut, qc, codes, ht, 100)
+        assert r["nsurv"].mean() / len(xb) < 0.08
+        res[name + "/dual"] = O.recall_at(r["ids"], truth, 100)
+        if name == "PQ":
+            res["PQ/disidx"] = O.recall_at(O.search_by_code_distance(qc, codes, 100, "disidx")[0], truth, 100)
+            res["PQ/ADC"] = O.recall_at(O.scan(lut, qc, codes, 64, 100)["ids"], truth, 100)
+    print("recall@100:", {k: round(v, 3) for k, v in res.items()})
+    assert res["PQ/binary"] < res["PQ/disidx"] < res["PolyR/binary"] <= res["PolyD/binary"] + 0.03
+    assert res["PolyD/binary"] > 3 * res["PQ/binary"]
+    assert res["PolyD/dual"] > 3 * res["PQ/dual"] and res["PolyR/dual"] > 2 * res["PQ/dual"]
+    assert res["PolyR/dual"] <= res["PolyD/dual"] + 0.03 and res["PolyD/dual"] <= res["PQ/ADC"]
+    assert res["PolyD/dual"] > res["PolyD/binary"]      # the second stage repairs the ranking of the survivors
+
+
 def test_threshold_for_rate_agrees_with_the_oracle():
     """Host-only entry point: same choice as the oracle's rule on random and hand-built histograms."""
     import paper_1609_01882_amd as psc
