@@ -31,6 +31,7 @@ __all__ = [
     "ivf_train_coarse", "ivf_build_lists", "kmeans", "nearest", "num_threads", "rotate",
     "disidx", "neighbour_ranks", "rank_violations", "ell", "polyr_loss", "polyr_swap_delta", "anneal_ranking",
     "optimize_index_assignment_ranking", "search_by_code_distance",
+    "imi_train_coarse", "imi_build_lists", "imi_search",
 ]
 
 _lib = None
@@ -275,6 +276,64 @@ def ivf_search(queries, codebook, coarse, offsets, codes, list_ids, nprobe: int,
     if want_coarse:
         out["coarse_d"] = cd
     return out
+
+
+def imi_train_coarse(x, k1: int, k2: int, iters: int = 10, seed: int = 0):
+    """Product coarse quantizer of the inverted multi-index: one k-means per half of the vectors."""
+    x = _f64(x)
+    half = x.shape[1] // 2
+    return kmeans(x[:, :half], k1, iters, seed)[0], kmeans(x[:, half:], k2, iters, seed + 1)[0]
+
+
+def imi_build_lists(x, coarse1, coarse2, codebook, base_id: int = 0):
+    """Each vector goes to cell (a, b) = nearest centroid of each half (number a * K2 + b); its
+    residual to the cell centroid is encoded; vectors are grouped by cell in their original order.
+    Returns offsets [K1*K2+1] int64, codes [n, m] uint8, ids [n] int32, cell_no [n] int32."""
+    x, c1, c2 = _f64(x), _f64(coarse1), _f64(coarse2)
+    half = x.shape[1] // 2
+    a, b = nearest(x[:, :half], c1)[0], nearest(x[:, half:], c2)[0]
+    cell = (a * c2.shape[0] + b).astype(np.int32)
+    res = x - np.concatenate([c1[a], c2[b]], axis=1)
+    codes = encode(res, codebook)
+    order = np.argsort(cell, kind="stable")
+    offsets = np.zeros(c1.shape[0] * c2.shape[0] + 1, dtype=np.int64)
+    offsets[1:] = np.cumsum(np.bincount(cell, minlength=c1.shape[0] * c2.shape[0]))
+    return offsets, codes[order], (order + base_id).astype(np.int32), cell
+
+
+def imi_search(queries, codebook, coarse1, coarse2, offsets, codes, list_ids, max_lists: int, max_codes: int,
+               ht: int, k: int, cells_in=None, qcodes_in=None):
+    """Inverted multi-index search with caps on visited cells and on the codes they hold
+    (max_codes <= 0: no cap).  cells_in [nq, max_lists] (padded with -1) / qcodes_in
+    [nq, max_lists, m] replace the oracle's own cell order / per-cell bit strings.
+    Returns dict(ids, dists, nsurv, cells [nq, max_lists] (-1 padded), ncodes [nq])."""
+    q, cb, c1, c2 = _f64(queries), _f64(codebook), _f64(coarse1), _f64(coarse2)
+    m, _, dsub = cb.shape
+    D = m * dsub
+    assert D % 2 == 0 and c1.shape[1] == D // 2 and c2.shape[1] == D // 2 and max_lists >= 1
+    offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+    assert offsets.size == c1.shape[0] * c2.shape[0] + 1
+    codes = _u8(codes)
+    list_ids = np.ascontiguousarray(list_ids, dtype=np.int32)
+    nq = q.shape[0]
+    ids = np.empty((nq, k), dtype=np.int64)
+    dists = np.empty((nq, k), dtype=np.float64)
+    nsurv = np.zeros(nq, dtype=np.int64)
+    cells = np.empty((nq, max_lists), dtype=np.int32)
+    ncodes = np.zeros(nq, dtype=np.int64)
+    cin = np.ascontiguousarray(cells_in, dtype=np.int32) if cells_in is not None else None
+    qin = _u8(qcodes_in) if qcodes_in is not None else None
+    if cin is not None:
+        assert cin.shape == (nq, max_lists)
+    if qin is not None:
+        assert qin.shape == (nq, max_lists, m)
+    rc = _L().orc_imi_search(C.c_int(D), C.c_int(m), _p(cb), _p(c1), C.c_int(c1.shape[0]), _p(c2),
+                             C.c_int(c2.shape[0]), _p(offsets), _p(codes), _p(list_ids), _p(q), C.c_int64(nq),
+                             C.c_int(max_lists), C.c_int64(max_codes), C.c_int(ht), C.c_int(k), _p(cin), _p(qin),
+                             _p(ids), _p(dists), _p(nsurv), _p(cells), _p(ncodes))
+    if rc != 0:
+        raise MemoryError("oracle multi-index search")
+    return dict(ids=ids, dists=dists, nsurv=nsurv, cells=cells, ncodes=ncodes)
 
 
 def knn_graph(x, codebook, codes, ht: int, k: int, rows=None, chunk: int = 1024):

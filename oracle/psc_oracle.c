@@ -397,6 +397,121 @@ int orc_ivf_search(int D, int m, const double *cb, const double *coarse, int nli
 }
 
 /* ------------------------------------------------------------------------- */
+/* Inverted multi-index (Section 2 "Non-exhaustive search", Section 4.3 and   */
+/* the caption of Table 2): the coarse level is a product quantizer -- the    */
+/* first half of a vector is quantized with K1 centroids, the second half     */
+/* with K2 -- so there are K1*K2 cells, cell (a,b) = number a*K2 + b, with    */
+/* centroid (coarse1[a], coarse2[b]).  A query visits the cells in            */
+/* non-decreasing order of its squared distance to the cell centroid, which   */
+/* is d1[a] + d2[b] (lower cell number first on equal distance), until        */
+/* max_lists cells have been taken or the cells taken so far hold max_codes   */
+/* codes or more (max_codes <= 0: no such cap; the cell that reaches the cap   */
+/* is still scanned whole; an empty cell counts as a visited cell).  Inside a  */
+/* cell everything is as in orc_ivf_search: residual to the cell centroid,     */
+/* tables and bit string from the residual, Hamming filter, ADC; one ranking   */
+/* over all visited cells.                                                     */
+/* offsets [K1*K2+1]; cells [nq][max_lists] (may be NULL) receives the cells    */
+/* taken, in order, padded with -1; ncodes [nq] (may be NULL) the codes they    */
+/* hold.  cells_in (may be NULL) [nq][max_lists], padded with -1: take exactly  */
+/* these cells instead; qcodes_in (may be NULL) [nq][max_lists][m]: these bit    */
+/* strings.                                                                    */
+/* ------------------------------------------------------------------------- */
+int orc_imi_search(int D, int m, const double *cb, const double *coarse1, int K1, const double *coarse2, int K2,
+                   const int64_t *offsets, const uint8_t *codes, const int32_t *list_ids,
+                   const double *queries, int64_t nq, int max_lists, int64_t max_codes, int ht, int k,
+                   const int32_t *cells_in, const uint8_t *qcodes_in,
+                   int64_t *ids, double *dists, int64_t *nsurv, int32_t *cells, int64_t *ncodes)
+{
+    int dsub = D / m, half = D / 2;
+    int64_t ncell = (int64_t)K1 * K2;
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t q = 0; q < nq; ++q) {
+        const double *qv = queries + q * D;
+        coarse_t *cl = (coarse_t *)malloc(sizeof(coarse_t) * (size_t)ncell);
+        int32_t *take = (int32_t *)malloc(sizeof(int32_t) * (size_t)(max_lists > 0 ? max_lists : 1));
+        double *res = (double *)malloc(sizeof(double) * (size_t)D);
+        double *tab = (double *)malloc(sizeof(double) * (size_t)m * 256);
+        uint8_t *qc = (uint8_t *)malloc((size_t)m);
+        int ntake = 0;
+        int64_t total = 0;
+        if (cl && take) {
+            if (cells_in) {
+                for (int p = 0; p < max_lists && cells_in[q * max_lists + p] >= 0; ++p) {
+                    take[ntake++] = cells_in[q * max_lists + p];
+                    total += offsets[take[ntake - 1] + 1] - offsets[take[ntake - 1]];
+                }
+            } else {
+                for (int a = 0; a < K1; ++a) {
+                    double d1 = sqdist(qv, coarse1 + (int64_t)a * half, half);
+                    for (int b = 0; b < K2; ++b) {
+                        cl[(int64_t)a * K2 + b].dist = d1 + sqdist(qv + half, coarse2 + (int64_t)b * half, half);
+                        cl[(int64_t)a * K2 + b].list = (int)((int64_t)a * K2 + b);
+                    }
+                }
+                qsort(cl, (size_t)ncell, sizeof(coarse_t), coarse_cmp);
+                for (int64_t t = 0; t < ncell; ++t) {
+                    if (ntake == max_lists || (max_codes > 0 && total >= max_codes))
+                        break;
+                    take[ntake++] = cl[t].list;
+                    total += offsets[cl[t].list + 1] - offsets[cl[t].list];
+                }
+            }
+        }
+        cand_t *cand = (cand_t *)malloc(sizeof(cand_t) * (size_t)(total > 0 ? total : 1));
+        if (!cl || !take || !res || !tab || !qc || !cand) {
+#pragma omp atomic write
+            failed = 1;
+            free(cl); free(take); free(res); free(tab); free(qc); free(cand);
+            continue;
+        }
+        int64_t ns = 0, nc = 0;
+        for (int p = 0; p < max_lists; ++p)
+            if (cells)
+                cells[q * max_lists + p] = p < ntake ? take[p] : -1;
+        for (int p = 0; p < ntake; ++p) {
+            int cell = take[p], a = cell / K2, b = cell % K2;
+            for (int d = 0; d < half; ++d) {
+                res[d] = qv[d] - coarse1[(int64_t)a * half + d];
+                res[half + d] = qv[half + d] - coarse2[(int64_t)b * half + d];
+            }
+            for (int j = 0; j < m; ++j) {
+                int best = 0;
+                for (int c = 0; c < 256; ++c) {
+                    tab[j * 256 + c] = sqdist(res + j * dsub, cb + ((int64_t)j * 256 + c) * dsub, dsub);
+                    if (tab[j * 256 + c] < tab[j * 256 + best])
+                        best = c;
+                }
+                qc[j] = qcodes_in ? qcodes_in[(q * max_lists + p) * m + j] : (uint8_t)best;
+            }
+            for (int64_t i = offsets[cell]; i < offsets[cell + 1]; ++i) {
+                const uint8_t *code = codes + i * m;
+                if (orc_hamming(qc, code, m) > ht)
+                    continue;
+                ++ns;
+                double dd = 0.0;
+                for (int j = 0; j < m; ++j)
+                    dd += tab[j * 256 + code[j]];
+                cand[nc].dist = dd;
+                cand[nc].id = list_ids[i];
+                ++nc;
+            }
+        }
+        qsort(cand, (size_t)nc, sizeof(cand_t), cand_cmp);
+        for (int r = 0; r < k; ++r) {
+            ids[q * k + r] = r < nc ? cand[r].id : -1;
+            dists[q * k + r] = r < nc ? cand[r].dist : INFINITY;
+        }
+        if (nsurv)
+            nsurv[q] = ns;
+        if (ncodes)
+            ncodes[q] = total;
+        free(cl); free(take); free(res); free(tab); free(qc); free(cand);
+    }
+    return failed ? -1 : 0;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Exact k nearest neighbours on raw vectors (ground truth for recall@R,      */
 /* Section 4.1): squared L2, (distance, id) ascending.  skip_self != 0: row q */
 /* of the queries is database row q and is not its own neighbour.             */
