@@ -312,6 +312,46 @@ int psc_ivf_search(const psc_index *idx, const float *q_dev, int64_t nq, int npr
                    int64_t *ids_dev, float *dists_dev, int32_t *probed_out_dev, uint8_t *qcodes_out_dev,
                    void *workspace_dev, size_t workspace_bytes, psc_stream stream);
 
+/* ------------------------------------------------------------------ inverted multi-index (Section 4.3, Table 2) */
+/* The coarse level is a product quantizer: the first dim/2 coordinates are quantized with k1
+ * centroids c1_host [k1][dim/2], the others with k2 centroids c2_host [k2][dim/2] (k1, k2 <= 16384,
+ * k1*k2 < 2^31; dim % 8 == 0, m even), which gives k1*k2 cells; cell (a, b) has number a*k2 + b and
+ * centroid (c1[a], c2[b]).  Training the two halves is two plain coarse trainings in dimension
+ * dim/2 (psc_ivf_train_coarse* on an index of that dimension).  The call forgets earlier cell lists. */
+int psc_imi_set_coarse(psc_index *idx, const float *c1_host, int k1, const float *c2_host, int k2);
+
+/* Index construction: cell_no_dev [n] (int32) = the cell of each row of x_dev [n][dim] (per half the
+ * nearest centroid, squared L2 in float32, lowest number on ties); rescodes_dev (may be NULL)
+ * [n][m] = PQ code of the residual x - cell centroid.  Rows are processed 2^20 at a time through
+ * the workspace (psc_imi_assign_workspace_bytes). */
+size_t psc_imi_assign_workspace_bytes(const psc_index *idx, int64_t n);
+int psc_imi_assign_encode(const psc_index *idx, const float *x_dev, int64_t n, int32_t *cell_no_dev,
+                          uint8_t *rescodes_dev, void *workspace_dev, size_t workspace_bytes, psc_stream stream);
+
+/* The cells' lists, borrowed like the lists of psc_ivf_set_lists: offsets_dev [k1*k2+1] (int64,
+ * device memory; copied to the host once to be checked), codes_dev [n][m] grouped by cell (16-byte
+ * aligned), ids_dev [n] (int32, >= 0). */
+int psc_imi_set_lists(psc_index *idx, const int64_t *offsets_dev, const uint8_t *codes_dev, const int32_t *ids_dev,
+                      int64_t n);
+
+/* Search: every query takes cells in non-decreasing order of its squared distance to the cell
+ * centroid, d1[a] + d2[b] (float32; lower cell number first on equal sums), until max_lists cells
+ * (1 .. 1024) are taken or the cells taken hold max_codes codes or more (max_codes <= 0: no such
+ * cap; the cell that reaches it is scanned whole; empty cells count as taken) -- the two caps of
+ * Table 2.  Inside a cell: bit string and ADC tables from the residual q - cell centroid, codes
+ * filtered (Hamming <= ht) and scored as in psc_scan; one ranking by (distance, id) over all cells
+ * taken.  cells_out_dev (may be NULL) [nq][max_lists] int32 receives the cells taken, in order,
+ * padded with -1; qcodes_out_dev (may be NULL) [nq][max_lists][m] the bit strings of those cells.
+ * One workgroup serves one query from its first cell to its last (cells of a multi-index hold a
+ * handful of codes each and queries rarely share one), so a single query and a batch take the same
+ * path.  The tables are put together per cell from the query's share, the two half-centroids'
+ * shares (k1 + k2 half tables, part of the index's device image as for psc_ivf_search) and
+ * ||(q - cell centroid)_j||^2, or by direct differences under the rule stated at psc_ivf_search. */
+size_t psc_imi_search_workspace_bytes(const psc_index *idx, int64_t nq, int max_lists);
+int psc_imi_search(const psc_index *idx, const float *q_dev, int64_t nq, int max_lists, int64_t max_codes, int ht,
+                   int k, int64_t *ids_dev, float *dists_dev, int32_t *cells_out_dev, uint8_t *qcodes_out_dev,
+                   void *workspace_dev, size_t workspace_bytes, psc_stream stream);
+
 /* Synchronise `stream` and report whether any scan that used this workspace since
  * the last call gave up on an internal wait (never expected; results of such a
  * scan are marked with id -2).  Returns 0 if clean, PSC_EHIP otherwise. */

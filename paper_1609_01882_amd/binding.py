@@ -72,6 +72,12 @@ def _load():
         "psc_ivf_set_lists": (i32, [vp, vp, vp, vp, i64]),
         "psc_ivf_search_workspace_bytes": (sz, [vp, i64, i32, i32]),
         "psc_ivf_search": (i32, [vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]),
+        "psc_imi_set_coarse": (i32, [vp, vp, i32, vp, i32]),
+        "psc_imi_assign_workspace_bytes": (sz, [vp, i64]),
+        "psc_imi_assign_encode": (i32, [vp, vp, i64, vp, vp, vp, sz, vp]),
+        "psc_imi_set_lists": (i32, [vp, vp, vp, vp, i64]),
+        "psc_imi_search_workspace_bytes": (sz, [vp, i64, i32]),
+        "psc_imi_search": (i32, [vp, vp, i64, i32, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]),
         "psc_workspace_status": (i32, [vp, vp]),
     }
     for name, (res, args) in sigs.items():
@@ -93,7 +99,8 @@ def exported_symbols():
             "psc_search_workspace_bytes", "psc_search", "psc_knn_graph_workspace_bytes",
             "psc_knn_graph", "psc_ivf_train_coarse", "psc_ivf_set_coarse", "psc_ivf_get_coarse",
             "psc_ivf_assign_encode", "psc_ivf_set_lists", "psc_ivf_search_workspace_bytes",
-            "psc_ivf_search", "psc_workspace_status"]
+            "psc_ivf_search", "psc_imi_set_coarse", "psc_imi_assign_workspace_bytes", "psc_imi_assign_encode",
+            "psc_imi_set_lists", "psc_imi_search_workspace_bytes", "psc_imi_search", "psc_workspace_status"]
 
 
 def _check(rc: int):
@@ -324,6 +331,54 @@ class Index:
                                   _dev(qcodes, torch.uint8, "qcodes") if want_debug else None,
                                   _dev(ws, torch.uint8, "workspace"), ws.numel(), _stream()))
         return (ids, dists, probed, qcodes) if want_debug else (ids, dists)
+
+    # -- inverted multi-index
+    def imi_set_coarse(self, c1: np.ndarray, c2: np.ndarray):
+        c1, c2 = np.ascontiguousarray(c1, dtype=np.float32), np.ascontiguousarray(c2, dtype=np.float32)
+        assert c1.ndim == 2 and c2.ndim == 2 and c1.shape[1] == self.dim // 2 and c2.shape[1] == self.dim // 2
+        _check(_load().psc_imi_set_coarse(self._h, c1.ctypes.data_as(C.c_void_p), c1.shape[0],
+                                          c2.ctypes.data_as(C.c_void_p), c2.shape[0]))
+        self.imi_k = (c1.shape[0], c2.shape[0])
+
+    def imi_assign_encode(self, x: torch.Tensor, want_codes: bool = True, workspace=None):
+        n = x.shape[0]
+        lib = _load()
+        ws = workspace if workspace is not None else _workspace(lib.psc_imi_assign_workspace_bytes(self._h, n), x.device)
+        cell = torch.empty(n, dtype=torch.int32, device=x.device)
+        codes = torch.empty((n, self.m), dtype=torch.uint8, device=x.device) if want_codes else None
+        _check(lib.psc_imi_assign_encode(self._h, _dev(x, torch.float32, "x"), n, _dev(cell, torch.int32, "cell"),
+                                         _dev(codes, torch.uint8, "codes") if want_codes else None,
+                                         _dev(ws, torch.uint8, "workspace"), ws.numel(), _stream()))
+        return cell, codes
+
+    def imi_set_lists(self, offsets: torch.Tensor, codes: torch.Tensor, ids: torch.Tensor):
+        """Borrow the caller's cell lists; the tensors are kept referenced by this object."""
+        _check(_load().psc_imi_set_lists(self._h, _dev(offsets, torch.int64, "offsets"), _dev(codes, torch.uint8, "codes"),
+                                         _dev(ids, torch.int32, "ids"), codes.shape[0]))
+        self._imi_lists = (offsets, codes, ids)
+
+    def imi_search_workspace_bytes(self, nq: int, max_lists: int) -> int:
+        return int(_load().psc_imi_search_workspace_bytes(self._h, nq, max_lists))
+
+    def imi_search(self, q: torch.Tensor, max_lists: int, max_codes: int, ht: int, k: int, workspace=None, out=None,
+                   want_debug: bool = False):
+        nq = q.shape[0]
+        lib = _load()
+        need = lib.psc_imi_search_workspace_bytes(self._h, nq, max_lists)
+        if need == 0:
+            _check(-1)
+        ws = workspace if workspace is not None else _workspace(need, q.device)
+        ids, dists = out if out is not None else (
+            torch.empty((nq, k), dtype=torch.int64, device=q.device),
+            torch.empty((nq, k), dtype=torch.float32, device=q.device))
+        cells = torch.empty((nq, max_lists), dtype=torch.int32, device=q.device) if want_debug else None
+        qcodes = torch.empty((nq, max_lists, self.m), dtype=torch.uint8, device=q.device) if want_debug else None
+        _check(lib.psc_imi_search(self._h, _dev(q, torch.float32, "q"), nq, max_lists, max_codes, ht, k,
+                                  _dev(ids, torch.int64, "ids"), _dev(dists, torch.float32, "dists"),
+                                  _dev(cells, torch.int32, "cells") if want_debug else None,
+                                  _dev(qcodes, torch.uint8, "qcodes") if want_debug else None,
+                                  _dev(ws, torch.uint8, "workspace"), ws.numel(), _stream()))
+        return (ids, dists, cells, qcodes) if want_debug else (ids, dists)
 
     def knn_graph_workspace_bytes(self, n: int, k: int) -> int:
         return int(_load().psc_knn_graph_workspace_bytes(self._h, n, k))

@@ -31,6 +31,8 @@ static int mark_codebook_changed(psc_index *idx)
     idx->dev_current = false;
     idx->list_tab_current = false;
     idx->direct_tables = -1;
+    idx->imi_tab_current = false;
+    idx->imi_direct = -1;
     return PSC_OK;
 }
 
@@ -137,6 +139,8 @@ void psc_destroy(psc_index *idx)
     if (idx->coarse_dev) (void)hipFree(idx->coarse_dev);
     if (idx->list_tab_dev) (void)hipFree(idx->list_tab_dev);
     if (idx->rot_dev) (void)hipFree(idx->rot_dev);
+    if (idx->imi_dev) (void)hipFree(idx->imi_dev);
+    if (idx->imi_tab_dev) (void)hipFree(idx->imi_tab_dev);
     delete idx;
 }
 
@@ -1079,6 +1083,335 @@ int psc_ivf_search(const psc_index *idx, const float *q_dev, int64_t nq, int npr
     if (rc != PSC_OK) return rc;
     if (qcodes_out_dev) rc = launch_unsort_rows(qcodes, jb.job_slot, L.njobs, idx->m, qcodes_out_dev, s);
     return rc;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Inverted multi-index (Section 4.3; caption of Table 2)
+// ---------------------------------------------------------------------------------------------
+int psc_imi_set_coarse(psc_index *idx, const float *c1_host, int k1, const float *c2_host, int k2)
+{
+    PSC_REQUIRE(idx && c1_host && c2_host, "null pointer");
+    PSC_REQUIRE(k1 >= 1 && k1 <= 16384 && k2 >= 1 && k2 <= 16384, "k1 and k2 must be in [1, 16384], got %d x %d", k1, k2);
+    PSC_REQUIRE((int64_t)k1 * k2 < (1LL << 31), "too many cells");
+    PSC_REQUIRE(idx->dim % 8 == 0 && idx->dim <= 2048, "the multi-index needs dim %% 8 == 0 and dim <= 2048");
+    const size_t half = (size_t)idx->dim / 2;
+    try {
+        idx->imi_c1_host.assign(c1_host, c1_host + (size_t)k1 * half);
+        idx->imi_c2_host.assign(c2_host, c2_host + (size_t)k2 * half);
+    } catch (const std::bad_alloc &) {
+        set_error("out of host memory");
+        return PSC_ENOMEM;
+    }
+    idx->imi_k1 = k1;
+    idx->imi_k2 = k2;
+    idx->imi_current = false;
+    idx->imi_tab_current = false;
+    idx->imi_direct = -1;
+    idx->imi_off_dev = nullptr;  // cells built for another quantizer no longer apply
+    idx->imi_codes_dev = nullptr;
+    idx->imi_ids_dev = nullptr;
+    idx->imi_n = 0;
+    return PSC_OK;
+}
+
+namespace {
+// device image of the product coarse quantizer: [k1 + 1][half] (last row: the mean of the rows),
+// [k2 + 1][half], then the two means again as one vector of dim floats
+struct ImiImage {
+    const float *c1, *mu1, *c2, *mu2, *origin;
+};
+
+ImiImage imi_image(const psc_index *idx)
+{
+    const size_t half = (size_t)idx->dim / 2, k1 = (size_t)idx->imi_k1, k2 = (size_t)idx->imi_k2;
+    ImiImage im;
+    im.c1 = idx->imi_dev;
+    im.mu1 = im.c1 + k1 * half;
+    im.c2 = im.mu1 + half;
+    im.mu2 = im.c2 + k2 * half;
+    im.origin = im.mu2 + half;
+    return im;
+}
+
+int sync_imi_to_device(const psc_index *idx)
+{
+    std::lock_guard<std::mutex> guard(idx->image_lock);
+    if (idx->imi_current) return PSC_OK;
+    const size_t half = (size_t)idx->dim / 2, k1 = (size_t)idx->imi_k1, k2 = (size_t)idx->imi_k2;
+    std::vector<float> img((k1 + 1 + k2 + 1 + 2) * half);
+    auto put = [&](const std::vector<float> &src, size_t k, float *dst) {
+        std::memcpy(dst, src.data(), k * half * sizeof(float));
+        for (size_t t = 0; t < half; ++t) {
+            double acc = 0.0;
+            for (size_t c = 0; c < k; ++c) acc += src[c * half + t];
+            dst[k * half + t] = (float)(acc / (double)k);
+        }
+    };
+    put(idx->imi_c1_host, k1, img.data());
+    put(idx->imi_c2_host, k2, img.data() + (k1 + 1) * half);
+    std::memcpy(&img[(k1 + 1 + k2 + 1) * half], &img[k1 * half], half * sizeof(float));
+    std::memcpy(&img[(k1 + 1 + k2 + 1) * half + half], &img[(k1 + 1 + k2) * half], half * sizeof(float));
+    if (idx->imi_dev) {
+        PSC_HIP_TRY(hipDeviceSynchronize());  // earlier kernels may still read the old centroids
+        PSC_HIP_TRY(hipFree(idx->imi_dev));
+        idx->imi_dev = nullptr;
+    }
+    PSC_HIP_TRY(hipMalloc((void **)&idx->imi_dev, img.size() * sizeof(float)));
+    PSC_HIP_TRY(hipMemcpy(idx->imi_dev, img.data(), img.size() * sizeof(float), hipMemcpyHostToDevice));
+    idx->imi_current = true;
+    return PSC_OK;
+}
+
+// The half-centroids' shares of the residual tables (see kernels_imi.hip), rebuilt after the
+// codebook or the coarse quantizer changed.
+int sync_imi_tables(const psc_index *idx, hipStream_t s)
+{
+    std::lock_guard<std::mutex> guard(idx->image_lock);
+    if (idx->imi_tab_current) return PSC_OK;
+    const size_t per = (size_t)(idx->m / 2) * kCentroids;
+    if (idx->imi_tab_dev) {
+        PSC_HIP_TRY(hipDeviceSynchronize());
+        PSC_HIP_TRY(hipFree(idx->imi_tab_dev));
+        idx->imi_tab_dev = nullptr;
+    }
+    PSC_HIP_TRY(hipMalloc((void **)&idx->imi_tab_dev, (size_t)(idx->imi_k1 + idx->imi_k2) * per * sizeof(float)));
+    const ImiImage im = imi_image(idx);
+    const int half = idx->dim / 2, mh = idx->m / 2;
+    int rc = launch_list_tables(idx->cb_dev, half, mh, im.c1, idx->imi_k1, idx->imi_tab_dev, s);
+    if (rc != PSC_OK) return rc;
+    rc = launch_list_tables(idx->cb_dev + (size_t)mh * kCentroids * idx->dsub, half, mh, im.c2, idx->imi_k2,
+                            idx->imi_tab_dev + (size_t)idx->imi_k1 * per, s);
+    if (rc != PSC_OK) return rc;
+    PSC_HIP_TRY(hipStreamSynchronize(s));
+    idx->imi_tab_current = true;
+    return PSC_OK;
+}
+
+// Same rule as for the plain inverted file (kDirectTablesRho), with the half-centroids in the
+// place of the coarse centroids.
+bool imi_direct_tables(const psc_index *idx)
+{
+    std::lock_guard<std::mutex> guard(idx->image_lock);
+    if (idx->imi_direct >= 0) return idx->imi_direct != 0;
+    const int half = idx->dim / 2, m = idx->m, dsub = idx->dsub;
+    double rho = 0.0;
+    for (int j = 0; j < m; ++j) {
+        double c2 = 0.0;
+        for (int c = 0; c < kCentroids; ++c)
+            for (int t = 0; t < dsub; ++t) {
+                const double v = idx->cb_host[((size_t)j * kCentroids + c) * dsub + t];
+                c2 += v * v;
+            }
+        const double crms = std::sqrt(c2 / kCentroids);
+        const std::vector<float> &cent = j < m / 2 ? idx->imi_c1_host : idx->imi_c2_host;
+        const int k = j < m / 2 ? idx->imi_k1 : idx->imi_k2;
+        const int t0 = (j < m / 2 ? j : j - m / 2) * dsub;
+        double g2max = 0.0;
+        std::vector<double> o((size_t)dsub, 0.0);
+        for (int l = 0; l < k; ++l)
+            for (int t = 0; t < dsub; ++t) o[(size_t)t] += cent[(size_t)l * half + t0 + t];
+        for (int t = 0; t < dsub; ++t) o[(size_t)t] /= k;
+        for (int l = 0; l < k; ++l) {
+            double g2 = 0.0;
+            for (int t = 0; t < dsub; ++t) {
+                const double v = cent[(size_t)l * half + t0 + t] - o[(size_t)t];
+                g2 += v * v;
+            }
+            g2max = std::max(g2max, g2);
+        }
+        const double num = 2.0 * std::sqrt(g2max), den = std::sqrt((double)dsub) * crms;
+        rho = std::max(rho, num <= kDirectTablesRho * den ? (den > 0.0 ? num / den : 0.0) : 2.0 * kDirectTablesRho);
+    }
+    idx->imi_direct = rho > kDirectTablesRho ? 1 : 0;
+    return idx->imi_direct != 0;
+}
+
+int need_imi(const psc_index *idx)
+{
+    PSC_REQUIRE(idx != nullptr, "null index");
+    if (idx->imi_k1 == 0) {
+        set_error("no product coarse quantizer: call psc_imi_set_coarse first");
+        return PSC_ESTATE;
+    }
+    PSC_REQUIRE(idx->m % 2 == 0, "the multi-index needs an even number of sub-quantizers");
+    return sync_imi_to_device(idx);
+}
+
+constexpr int64_t kImiAssignChunk = 1 << 20;  // rows per pass of psc_imi_assign_encode
+}  // namespace
+
+size_t psc_imi_assign_workspace_bytes(const psc_index *idx, int64_t n)
+{
+    if (!idx || n < 0) return 0;
+    const int64_t rows = std::max<int64_t>(1, std::min(n, kImiAssignChunk));
+    return round256((size_t)rows * idx->dim * sizeof(float)) + 2 * round256((size_t)rows * sizeof(int32_t));
+}
+
+int psc_imi_assign_encode(const psc_index *idx, const float *x_dev, int64_t n, int32_t *cell_no_dev,
+                          uint8_t *rescodes_dev, void *workspace_dev, size_t workspace_bytes, psc_stream stream)
+{
+    int rc = need_imi(idx);
+    if (rc != PSC_OK) return rc;
+    PSC_REQUIRE(n >= 0, "negative n");
+    if (n == 0) return PSC_OK;
+    PSC_REQUIRE(x_dev && cell_no_dev, "null pointer");
+    const size_t need = psc_imi_assign_workspace_bytes(idx, n);
+    PSC_REQUIRE(workspace_dev && workspace_bytes >= need, "workspace too small: need %zu bytes, got %zu", need,
+                workspace_bytes);
+    PSC_REQUIRE(((uintptr_t)workspace_dev & 255) == 0, "workspace must be 256-byte aligned");
+    if (rescodes_dev) {
+        rc = need_codebook(idx);
+        if (rc != PSC_OK) return rc;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    const ImiImage im = imi_image(idx);
+    const int half = idx->dim / 2;
+    const int64_t rows_max = std::min(n, kImiAssignChunk);
+    char *w = (char *)workspace_dev;
+    float *h1 = (float *)w, *h2 = h1 + (size_t)rows_max * half;
+    int32_t *a = (int32_t *)(w + round256((size_t)rows_max * idx->dim * sizeof(float)));
+    int32_t *b = (int32_t *)((char *)a + round256((size_t)rows_max * sizeof(int32_t)));
+    for (int64_t r0 = 0; r0 < n; r0 += kImiAssignChunk) {
+        const int64_t rows = std::min(kImiAssignChunk, n - r0);
+        PSC_TRY(launch_split_halves(x_dev + (size_t)r0 * idx->dim, rows, idx->dim, h1, h2, s));
+        PSC_TRY(launch_nearest_centroid(h1, rows, half, im.c1, idx->imi_k1, im.mu1, a, s));
+        PSC_TRY(launch_nearest_centroid(h2, rows, half, im.c2, idx->imi_k2, im.mu2, b, s));
+        PSC_TRY(launch_combine_cells(a, b, rows, idx->imi_k2, cell_no_dev + r0, s));
+    }
+    if (!rescodes_dev) return PSC_OK;
+    RowMap map;
+    map.sub = im.c1;
+    map.sub_b = im.c2;
+    map.sub_idx = cell_no_dev;
+    map.k2 = idx->imi_k2;
+    return launch_encode(idx->cb_dev, idx->dim, idx->m, x_dev, n, map, rescodes_dev, s);
+}
+
+int psc_imi_set_lists(psc_index *idx, const int64_t *offsets_dev, const uint8_t *codes_dev, const int32_t *ids_dev,
+                      int64_t n)
+{
+    PSC_REQUIRE(idx != nullptr, "null index");
+    if (idx->imi_k1 == 0) {
+        set_error("no product coarse quantizer");
+        return PSC_ESTATE;
+    }
+    PSC_REQUIRE(offsets_dev && n >= 0 && (n == 0 || (codes_dev && ids_dev)), "null pointer");
+    PSC_REQUIRE(((uintptr_t)codes_dev & 15) == 0, "cell codes must be 16-byte aligned");
+    const size_t ncell = (size_t)idx->imi_k1 * idx->imi_k2;
+    try {
+        std::vector<int64_t> off(ncell + 1);
+        PSC_HIP_TRY(hipMemcpy(off.data(), offsets_dev, off.size() * sizeof(int64_t), hipMemcpyDeviceToHost));
+        PSC_REQUIRE(off[0] == 0 && off[ncell] == n, "cell offsets must start at 0 and end at n");
+        for (size_t l = 0; l < ncell; ++l)
+            PSC_REQUIRE(off[l + 1] >= off[l], "cell offsets must not decrease (cell %zu)", l);
+    } catch (const std::bad_alloc &) {
+        set_error("out of host memory");
+        return PSC_ENOMEM;
+    }
+    idx->imi_off_dev = offsets_dev;
+    idx->imi_codes_dev = codes_dev;
+    idx->imi_ids_dev = ids_dev;
+    idx->imi_n = n;
+    return PSC_OK;
+}
+
+namespace {
+struct ImiLayout {
+    int l1, l2;
+    bool direct;
+    size_t off_h1, off_h2, off_d1, off_d2, off_s1, off_s2, off_cells, off_ncells, off_lut, total;
+};
+
+int imi_layout(const psc_index *idx, int64_t nq, int max_lists, ImiLayout *L)
+{
+    PSC_REQUIRE(idx && idx->imi_k1 > 0, "no product coarse quantizer");
+    PSC_REQUIRE(nq >= 0 && max_lists >= 1 && max_lists <= 1024, "max_lists must be in [1, 1024]");
+    L->l1 = std::min(max_lists, idx->imi_k1);
+    L->l2 = std::min(max_lists, idx->imi_k2);
+    L->direct = idx->has_codebook && imi_direct_tables(idx);
+    const size_t half = (size_t)idx->dim / 2;
+    size_t o = 256;  // the status word psc_workspace_status reads
+    auto take = [&](size_t bytes) {
+        size_t at = o;
+        o += round256(bytes);
+        return at;
+    };
+    L->off_h1 = take((size_t)nq * half * sizeof(float));
+    L->off_h2 = take((size_t)nq * half * sizeof(float));
+    L->off_d1 = take((size_t)nq * idx->imi_k1 * sizeof(float));
+    L->off_d2 = take((size_t)nq * idx->imi_k2 * sizeof(float));
+    L->off_s1 = take((size_t)nq * L->l1 * sizeof(int32_t));
+    L->off_s2 = take((size_t)nq * L->l2 * sizeof(int32_t));
+    L->off_cells = take((size_t)nq * max_lists * sizeof(int32_t));
+    L->off_ncells = take((size_t)nq * sizeof(int32_t));
+    L->off_lut = take((size_t)nq * idx->m * kCentroids * sizeof(float));
+    L->total = o;
+    return PSC_OK;
+}
+}  // namespace
+
+size_t psc_imi_search_workspace_bytes(const psc_index *idx, int64_t nq, int max_lists)
+{
+    ImiLayout L;
+    if (imi_layout(idx, nq, max_lists, &L) != PSC_OK) return 0;
+    return L.total;
+}
+
+int psc_imi_search(const psc_index *idx, const float *q_dev, int64_t nq, int max_lists, int64_t max_codes, int ht,
+                   int k, int64_t *ids_dev, float *dists_dev, int32_t *cells_out_dev, uint8_t *qcodes_out_dev,
+                   void *workspace_dev, size_t workspace_bytes, psc_stream stream)
+{
+    int rc = need_codebook(idx);
+    if (rc != PSC_OK) return rc;
+    rc = need_imi(idx);
+    if (rc != PSC_OK) return rc;
+    if (!idx->imi_off_dev) {
+        set_error("no cell lists: call psc_imi_set_lists first");
+        return PSC_ESTATE;
+    }
+    PSC_REQUIRE(ht >= 0 && k >= 1 && k <= PSC_MAX_K, "ht must be >= 0 and k in [1, %d]", PSC_MAX_K);
+    ImiLayout L;
+    rc = imi_layout(idx, nq, max_lists, &L);
+    if (rc != PSC_OK) return rc;
+    if (nq == 0) return PSC_OK;
+    PSC_REQUIRE(q_dev && ids_dev && dists_dev, "null pointer");
+    PSC_REQUIRE(workspace_dev && workspace_bytes >= L.total, "workspace too small: need %zu bytes, got %zu", L.total,
+                workspace_bytes);
+    PSC_REQUIRE(((uintptr_t)workspace_dev & 255) == 0, "workspace must be 256-byte aligned");
+    hipStream_t s = (hipStream_t)stream;
+    const ImiImage im = imi_image(idx);
+    const int half = idx->dim / 2;
+    char *w = (char *)workspace_dev;
+    float *h1 = (float *)(w + L.off_h1), *h2 = (float *)(w + L.off_h2);
+    float *d1 = (float *)(w + L.off_d1), *d2 = (float *)(w + L.off_d2);
+    int32_t *s1 = (int32_t *)(w + L.off_s1), *s2 = (int32_t *)(w + L.off_s2);
+    int32_t *cells = (int32_t *)(w + L.off_cells), *ncells = (int32_t *)(w + L.off_ncells);
+    float *lut = (float *)(w + L.off_lut);
+    // 1. the two halves of the coarse quantization, each with its nearest centroids in order
+    PSC_TRY(launch_split_halves(q_dev, nq, idx->dim, h1, h2, s));
+    PSC_TRY(launch_coarse_distances(h1, nq, half, im.c1, idx->imi_k1, im.mu1, d1, s));
+    PSC_TRY(launch_coarse_distances(h2, nq, half, im.c2, idx->imi_k2, im.mu2, d2, s));
+    PSC_TRY(launch_select_probes(d1, nq, idx->imi_k1, L.l1, s1, s));
+    PSC_TRY(launch_select_probes(d2, nq, idx->imi_k2, L.l2, s2, s));
+    // 2. the cells in order of d1 + d2, cut by the caps
+    PSC_TRY(launch_imi_cells(s1, d1, idx->imi_k1, L.l1, s2, d2, idx->imi_k2, L.l2, max_lists, max_codes,
+                             idx->imi_off_dev, nq, cells, ncells, (int *)workspace_dev, s));
+    if (cells_out_dev)
+        PSC_HIP_TRY(hipMemcpyAsync(cells_out_dev, cells, (size_t)nq * max_lists * sizeof(int32_t),
+                                   hipMemcpyDeviceToDevice, s));
+    // 3. the queries' share of the residual tables; 4. one workgroup per query over its cells
+    const float *tab1 = nullptr, *tab2 = nullptr;
+    if (!L.direct) {
+        RowMap map;
+        map.sub = im.origin;
+        PSC_TRY(launch_lut(idx->cb_dev, idx->dim, idx->m, q_dev, nq, map, true, lut, s));
+        PSC_TRY(sync_imi_tables(idx, s));
+        tab1 = idx->imi_tab_dev;
+        tab2 = tab1 + (size_t)idx->imi_k1 * (idx->m / 2) * kCentroids;
+    }
+    return launch_imi_scan(idx->m, lut, tab1, tab2, idx->cb_dev, q_dev, im.c1, im.c2, idx->dim, idx->imi_k2, cells,
+                           ncells, max_lists, idx->imi_off_dev, idx->imi_codes_dev, idx->imi_ids_dev, ht, k, L.direct,
+                           nq, qcodes_out_dev, ids_dev, dists_dev, s);
 }
 
 int psc_workspace_status(void *workspace_dev, psc_stream stream)

@@ -56,6 +56,10 @@ struct RowMap {
     const int32_t *row_idx = nullptr;
     const float *sub = nullptr;       // [*][dim] vectors to subtract (coarse centroids)
     const int32_t *sub_idx = nullptr; // which one, per row (none: the first, for every row)
+    // k2 > 0 (inverted multi-index): sub_idx[r] = a * k2 + b and the vector to subtract is
+    // (sub[a], sub_b[b]), two half-length centroids
+    const float *sub_b = nullptr;
+    int k2 = 0;
 };
 // cross: write || c ||^2 - 2 v . c instead of || v - c ||^2 (the inverted-file scan's per-query share).
 int launch_lut(const float *cb_dev, int dim, int m, const float *x_dev, int64_t nrows,
@@ -162,6 +166,21 @@ int launch_list_tables(const float *cb_dev, int dim, int m, const float *coarse_
 int launch_unsort_rows(const uint8_t *src_dev, const int32_t *job_slot_dev, int64_t njobs, int row_bytes,
                        uint8_t *dst_dev, hipStream_t s);
 
+// ---- inverted multi-index (kernels_imi.hip)
+int launch_split_halves(const float *x_dev, int64_t n, int dim, float *h1_dev, float *h2_dev, hipStream_t s);
+int launch_combine_cells(const int32_t *a_dev, const int32_t *b_dev, int64_t n, int k2, int32_t *cell_dev, hipStream_t s);
+// Per query the cells to visit, in order, from the sorted nearest half-centroids (sel*) and all
+// half distances (dist*): cells [nq][lmax] (-1 padded), ncells [nq].
+int launch_imi_cells(const int32_t *sel1_dev, const float *dist1_dev, int k1, int l1, const int32_t *sel2_dev,
+                     const float *dist2_dev, int k2, int l2, int lmax, int64_t max_codes, const int64_t *offsets_dev,
+                     int64_t nq, int32_t *cells_dev, int32_t *ncells_dev, int *status_dev, hipStream_t s);
+// One workgroup per query over its cells: residual tables, bit strings, filter, ADC, best k.
+int launch_imi_scan(int m, const float *lut_dev, const float *tab1_dev, const float *tab2_dev, const float *cb_dev,
+                    const float *queries_dev, const float *c1_dev, const float *c2_dev, int dim, int k2,
+                    const int32_t *cells_dev, const int32_t *ncells_dev, int lmax, const int64_t *offsets_dev,
+                    const uint8_t *codes_dev, const int32_t *ext_ids_dev, int ht, int k, bool direct, int64_t nq,
+                    uint8_t *qcodes_out_dev, int64_t *ids_dev, float *dists_dev, hipStream_t s);
+
 // ---- k-means on the device (kernels_train.hip)
 // One Lloyd step of all m sub-quantizers: per row and sub-quantizer the nearest centroid
 // (cell [n][m]) and its squared distance (dmin [n][m]); per cell the sum of its members
@@ -219,6 +238,18 @@ struct psc_index {
     mutable int list_tab_nlist = 0;
     mutable bool list_tab_current = false;
     mutable int direct_tables = -1;  // 1: residual tables built per (query, list) pair; -1: not decided yet
+    // inverted multi-index: product coarse quantizer (owned), half tables, borrowed cell lists
+    int imi_k1 = 0, imi_k2 = 0;
+    std::vector<float> imi_c1_host, imi_c2_host;  // [k1][dim/2], [k2][dim/2]
+    mutable float *imi_dev = nullptr;    // [k1+1][dim/2] (mean last), [k2+1][dim/2], then the two means as one [dim] vector
+    mutable bool imi_current = false;
+    mutable float *imi_tab_dev = nullptr;  // [k1][m/2][256] then [k2][m/2][256]
+    mutable bool imi_tab_current = false;
+    mutable int imi_direct = -1;
+    const int64_t *imi_off_dev = nullptr;  // [k1*k2+1]
+    const uint8_t *imi_codes_dev = nullptr;
+    const int32_t *imi_ids_dev = nullptr;
+    int64_t imi_n = 0;
     const int64_t *list_off_dev = nullptr;  // [nlist+1]
     const uint8_t *list_codes_dev = nullptr;
     const int32_t *list_ids_dev = nullptr;

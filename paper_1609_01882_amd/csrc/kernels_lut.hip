@@ -16,6 +16,11 @@ namespace {
 
 __device__ __forceinline__ float sub_term(const RowMap &map, int64_t r, int dim, int col)
 {
+    if (map.k2 > 0) {  // multi-index cell a * k2 + b: the cell centroid is (sub[a], sub_b[b]), dim / 2 floats each
+        const int cell = map.sub_idx[r], half = dim / 2;
+        const int a = cell / map.k2, b = cell - a * map.k2;
+        return col < half ? map.sub[(int64_t)a * half + col] : map.sub_b[(int64_t)b * half + col - half];
+    }
     return map.sub ? map.sub[(int64_t)(map.sub_idx ? map.sub_idx[r] : 0) * dim + col] : 0.0f;
 }
 
