@@ -339,6 +339,10 @@ class Index:
         _check(_load().psc_imi_set_coarse(self._h, c1.ctypes.data_as(C.c_void_p), c1.shape[0],
                                           c2.ctypes.data_as(C.c_void_p), c2.shape[0]))
         self.imi_k = (c1.shape[0], c2.shape[0])
+        self._imi_c1, self._imi_c2 = c1, c2
+
+    def imi_assign_workspace_bytes(self, n: int) -> int:
+        return int(_load().psc_imi_assign_workspace_bytes(self._h, n))
 
     def imi_assign_encode(self, x: torch.Tensor, want_codes: bool = True, workspace=None):
         n = x.shape[0]

@@ -123,3 +123,48 @@ def test_ivf_full_size():
     assert np.all(np.diff(np.nan_to_num(d_h, posinf=3e38), axis=1) >= 0)
     assert ids_h.max() < cfg.n_db and ids_h.min() >= -1
     assert all(len(set(r[r >= 0].tolist())) == (r >= 0).sum() for r in ids_h[::97])
+
+
+def test_imi_at_a_million_cells():
+    """The inverted multi-index at 1024 x 1024 cells over 10M vectors, 10k-query batch, in the two cap
+    settings of Table 2 that the benchmark times (16 cells / 10k codes; 1024 cells / 30k codes): 24
+    sampled queries re-done by the oracle on the GPU's decisions, 6 of them also with the oracle's own
+    ordering of all 1M cells."""
+    import paper_1609_01882_amd as psc
+    from paper_1609_01882_amd.benchmarks._common import build_imi_workload
+    cfg = W.get_config("ivf")
+    kh = 1024
+    print("full-size imi: building", flush=True)
+    idx, offsets, lcodes, lids, tcodes = build_imi_workload(psc, cfg, 10_000_000, kh, torch.device("cuda:0"),
+                                                            coarse_train=200_000, coarse_iters=5, pq_train=20_000,
+                                                            pq_iters=8, sa_iters=100_000)
+    c1, c2, cb = idx._imi_c1, idx._imi_c2, idx.get_codebook()
+    xq = cfg.vectors("query", threads=16)
+    off_h, lcodes_h, lids_h = offsets.cpu().numpy(), lcodes.cpu().numpy(), lids.cpu().numpy()
+    sample = np.unique(np.concatenate([[0, cfg.n_query - 1], np.random.default_rng(4).integers(0, cfg.n_query, 22)]))
+    st = torch.from_numpy(sample).cuda()
+    ht, k = 26, cfg.k
+
+    class Centroids:   # cell centroid on demand (1M x 128 floats would do as well; this keeps it small)
+        def __getitem__(self, cell):
+            return np.concatenate([c1[cell // kh], c2[cell % kh]])
+
+    for max_lists, max_codes in ((16, 10_000), (1024, 30_000)):
+        print(f"full-size imi: search {max_lists}/{max_codes}", flush=True)
+        ids, d, cells, qcodes = idx.imi_search(_dev(xq), max_lists, max_codes, ht, k, want_debug=True)
+        torch.cuda.synchronize()
+        cells_s, qcodes_s = cells[st].cpu().numpy(), qcodes[st].cpu().numpy()
+        ref = O.imi_search(xq[sample], cb, c1, c2, off_h, lcodes_h, lids_h, max_lists, max_codes, ht, k,
+                           cells_in=cells_s, qcodes_in=qcodes_s)
+        assert_ivf_topk_matches(ids[st].cpu().numpy(), d[st].cpu().numpy(), ref, xq[sample], cb, Centroids(), off_h,
+                                lcodes_h, lids_h, cells_s, qcodes_s, ht, O.build_lut, what=f"imi {max_lists}/{max_codes}")
+        own = O.imi_search(xq[sample[:6]], cb, c1, c2, off_h, lcodes_h, lids_h, max_lists, max_codes, ht, k)
+        for q, p in np.argwhere(own["cells"] != cells_s[:6]):
+            a, b = own["cells"][q, p], cells_s[q, p]
+            assert a >= 0 and b >= 0
+            da = ((xq[sample[q]].astype(np.float64) - Centroids()[a]) ** 2).sum()
+            db = ((xq[sample[q]].astype(np.float64) - Centroids()[b]) ** 2).sum()
+            assert abs(da - db) <= RTOL * da
+        ids_h = ids.cpu().numpy()
+        assert ids_h.max() < 10_000_000 and ids_h.min() >= -1
+        assert all(len(set(r[r >= 0].tolist())) == (r >= 0).sum() for r in ids_h[::97])
