@@ -780,7 +780,7 @@ scan_kernel(ScanArgs a)
         slice_end = t.slice_end;
     }
 
-    const bool spread = IVF && a.spread_lists != 0 && nvq == 1;  // (workgroup-uniform)
+    const bool spread = a.spread_lists != 0 && nvq == 1;  // (workgroup-uniform)
     // ---- per-slot state
     if (tid < TQ) {
         const int job = spread ? 0 : tid;
@@ -817,6 +817,7 @@ scan_kernel(ScanArgs a)
         for (int e = tid; e < TQ * (M * 256 / 4); e += NW * 64) {
             f32x4 v = {0.f, 0.f, 0.f, 0.f};
             if (e < nvec) v = src[e];
+            else if (spread) v = src[e % (M * 256 / 4)];  // a single query: every slot gets its tables
             dst[e] = v;
         }
         // ---- query codes -> scalar registers
@@ -1014,7 +1015,7 @@ scan_kernel(ScanArgs a)
             cnt[t] = s.lock[t];
             total += cnt[t];
         }
-        const int64_t o = (int64_t)a.job_slot[q0] * a.k;
+        const int64_t o = IVF ? (int64_t)a.job_slot[q0] * a.k : (q0 * a.nslice + slice) * a.k;
         for (int e = tid; e < TQ * a.k; e += NW * 64) {
             const int t = e / a.k, p = e - t * a.k;
             int mine = 0;
@@ -1035,7 +1036,7 @@ scan_kernel(ScanArgs a)
             }
             if (rank < a.k) {
                 a.part_d[o + rank] = entry_dist(ent);
-                a.part_i[o + rank] = (int64_t)entry_id(ent);
+                a.part_i[o + rank] = IVF ? (int64_t)entry_id(ent) : slice_begin + (int64_t)entry_id(ent);
             }
         }
         for (int r = tid; r < a.k; r += NW * 64)
@@ -1609,12 +1610,22 @@ merge_select_kernel(const float *__restrict__ part_d, const int64_t *__restrict_
     const int64_t *pi = part_i + q * total;
     const bool poisoned = *status != 0;
     constexpr uint32_t kNone = 0xffffffffu;  // padding and places past the end; real keys stay below
+    // (Places a list does not fill hold distance +infinity, which no scored code has: the distances
+    //  alone tell them apart, so all loads of a thread are independent of one another and in flight
+    //  together -- one trip to memory instead of one per entry.)
     uint32_t dk[KPL];
+    {
+        float dv[KPL];
 #pragma unroll
-    for (int i = 0; i < KPL; ++i) {
-        const int e = i * 1024 + tid;
-        dk[i] = kNone;
-        if (e < total && pi[e] >= 0) dk[i] = min(dist_key(pd[e]), kNone - 1u);
+        for (int i = 0; i < KPL; ++i) {
+            const int e = i * 1024 + tid;
+            dv[i] = pd[e < total ? e : total - 1];
+        }
+#pragma unroll
+        for (int i = 0; i < KPL; ++i) {
+            const int e = i * 1024 + tid;
+            dk[i] = (e < total && dv[i] != __builtin_inff()) ? min(dist_key(dv[i]), kNone - 1u) : kNone;
+        }
     }
     if (tid == 0) nsel = 0u;
     int turn = 0;
@@ -1631,8 +1642,64 @@ merge_select_kernel(const float *__restrict__ part_d, const int64_t *__restrict_
         turn ^= 1;
         return all;
     };
+    // A bound on the k-th smallest key from one row of the (sorted) lists: if t lists have their
+    // r-th entry at or below v, at least t (r + 1) entries lie at or below v; with r the first row for
+    // which nslice (r + 1) >= k and t = ceil(k / (r + 1)), the t-th smallest key of row r bounds the
+    // k-th smallest of all.  With hundreds of lists that leaves a few hundred entries of tens of
+    // thousands, which are ranked directly instead of being searched bit by bit (three barriers
+    // instead of forty).  Every wave finds the bound for itself from the row in LDS.
+    __shared__ uint32_t rowk[1024];
+    const int row = (k + nslice - 1) / nslice - 1;  // (nslice <= 1024, so the row has at most 1024 keys)
+    if (tid < nslice) {
+        const float v = pd[(int64_t)tid * k + row];
+        rowk[tid] = v != __builtin_inff() ? min(dist_key(v), kNone - 1u) : kNone;
+    }
+    __syncthreads();
+    uint32_t bound = 0;  // the t-th smallest key of the row (kNone when the row has fewer than t entries)
+    {
+        const uint32_t t = (uint32_t)((k + row) / (row + 1));
+        uint32_t rk[16];  // the row, 16 keys to a lane
+#pragma unroll
+        for (int i = 0; i < 16; ++i) rk[i] = i * 64 + lane < nslice ? rowk[i * 64 + lane] : kNone;
+        const int nreg = (nslice + 63) >> 6;  // (wave-uniform)
+        for (int b = 31; b >= 0; --b) {
+            const uint32_t mid = bound | (1u << b);
+            uint32_t cnt = 0;
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                if (i < nreg) cnt += rk[i] < mid ? 1u : 0u;
+            if (wave_sum_u32(cnt) < t) bound = mid;
+        }
+    }
     const uint32_t have = count([&](int i) { return dk[i] != kNone; });
     const uint32_t kk = have < (uint32_t)k ? have : (uint32_t)k;  // entries to return
+    const uint32_t near = bound == kNone ? 1025u : count([&](int i) { return dk[i] <= bound; });
+    if (kk > 0 && near <= 1024u) {
+        // (near >= kk: the bound is at or above the k-th smallest key)
+#pragma unroll
+        for (int i = 0; i < KPL; ++i) {
+            if (dk[i] > bound) continue;
+            const uint32_t slot = atomicAdd(&nsel, 1u);
+            selk[slot] = dk[i];
+            seli[slot] = pi[i * 1024 + tid];
+        }
+        __syncthreads();
+        if (tid < (int)near) {
+            const uint32_t key = selk[tid];
+            const int64_t id = seli[tid];
+            int rank = 0;
+            for (int j = 0; j < (int)near; ++j) rank += (selk[j] < key || (selk[j] == key && seli[j] < id)) ? 1 : 0;
+            if (rank < (int)kk) {
+                ids[q * k + rank] = poisoned ? (int64_t)-2 : id;
+                dists[q * k + rank] = key_dist(key);
+            }
+        }
+        if (tid >= (int)kk && tid < k) {
+            ids[q * k + tid] = poisoned ? (int64_t)-2 : (int64_t)-1;
+            dists[q * k + tid] = __builtin_inff();
+        }
+        return;
+    }
     if (kk > 0) {
         uint32_t pivot = 0;  // the kk-th smallest key
         for (int b = 31; b >= 0; --b) {
@@ -2150,6 +2217,11 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
     a.part_i = (int64_t *)((char *)a.part_d + (((size_t)nq * p.nslice * k * sizeof(float) + 255) / 256 * 256));
     hipLaunchKernelGGL(init_scan_kernel, dim3((unsigned)((nq + 255) / 256)), dim3(256), 0, s, a.gthr, nq,
                        clear_status ? a.status : (int *)nullptr);
+    // A single query leaves three of the narrowest tile's four query slots empty: they take copies of
+    // its tables and code, every wave feeds the list of slot wave % 4, and the four lists are merged
+    // when the slice ends -- a list's lock is then shared by 4 waves instead of 16 while the lists
+    // fill (1 x 400M codes, ht = 20, k = 100: 0.61 -> see the benchmark's small_batch).
+    a.spread_lists = (nq == 1 && skip_first < 0) ? 1 : 0;
     a.list_tab = nullptr;
     a.queries = nullptr;
     a.coarse = nullptr;

@@ -194,6 +194,24 @@ def test_selecting_merge_for_a_handful_of_queries(psc, nq, n, k, lut_kind):
             assert nd == 0  # exact sums: ties must resolve exactly as in the oracle
 
 
+@pytest.mark.parametrize("m,n,k,lut_kind", [(8, 2_000_003, 100, "int"), (8, 2_000_003, 130, "int"), (8, 900, 100, "float"),
+                                            (8, 5_000_001, 1, "float"), (16, 700_001, 100, "int"), (8, 300_001, 64, "int"),
+                                            (16, 200_003, 200, "float")])
+def test_a_single_query_spreads_its_candidates_over_four_lists(psc, m, n, k, lut_kind):
+    """One query: the three empty slots of the tile hold copies of its tables, every wave feeds the
+    list of slot wave % 4 and the four lists are merged when the slice ends (one slice for small
+    databases, 256 for large ones).  Exact ties (small-integer tables) must come out in id order."""
+    codes, qcodes, lut = _rand_problem(m, n, 1, seed=400 + k, lut_kind=lut_kind)
+    nb = 8 * m
+    for ht in (nb // 4, nb * 3 // 8, nb // 2 - 3):
+        print(f"single query m={m} n={n} k={k} ht={ht}", flush=True)
+        got_ids, got_d = _run(psc, lut, qcodes, codes, ht, k)
+        ref = O.scan(lut.astype(np.float64), qcodes, codes, ht, k)
+        nd = assert_topk_matches(got_ids, got_d, ref, lut.astype(np.float64), qcodes, codes, ht, what=f"single m={m} ht={ht}")
+        if lut_kind == "int":
+            assert nd == 0
+
+
 @pytest.mark.parametrize("m", [8, 16])
 def test_hamming_filter_is_bit_exact(psc, m):
     codes, qcodes, _ = _rand_problem(m, 20_011, 23, seed=7 + m, lut_kind="int")
