@@ -1629,10 +1629,15 @@ merge_select_kernel(const float *__restrict__ part_d, const int64_t *__restrict_
     }
     if (tid == 0) nsel = 0u;
     int turn = 0;
-    auto count = [&](auto pred) {  // number of the workgroup's entries for which pred(i) holds
+    // number of the workgroup's entries for which pred(i) holds (a second predicate is counted in
+    // the high half of the word)
+    auto count = [&](auto pred, auto... more) {
         uint32_t cnt = 0;
 #pragma unroll
-        for (int i = 0; i < KPL; ++i) cnt += pred(i) ? 1u : 0u;
+        for (int i = 0; i < KPL; ++i) {
+            cnt += pred(i) ? 1u : 0u;
+            ((cnt += more(i) ? 0x10000u : 0u), ...);
+        }
         cnt = wave_sum_u32(cnt);
         if (lane == 0) part[turn][wave] = cnt;
         __syncthreads();
@@ -1649,31 +1654,38 @@ merge_select_kernel(const float *__restrict__ part_d, const int64_t *__restrict_
     // thousands, which are ranked directly instead of being searched bit by bit (three barriers
     // instead of forty).  Every wave finds the bound for itself from the row in LDS.
     __shared__ uint32_t rowk[1024];
+    __shared__ uint32_t bound_s;
     const int row = (k + nslice - 1) / nslice - 1;  // (nslice <= 1024, so the row has at most 1024 keys)
     if (tid < nslice) {
         const float v = pd[(int64_t)tid * k + row];
         rowk[tid] = v != __builtin_inff() ? min(dist_key(v), kNone - 1u) : kNone;
     }
     __syncthreads();
-    uint32_t bound = 0;  // the t-th smallest key of the row (kNone when the row has fewer than t entries)
-    {
+    if (wave == 0) {  // (one wave: sixteen doing the same search would only take issue slots from each other)
+        uint32_t b0 = 0;  // the t-th smallest key of the row (kNone when the row has fewer than t entries)
         const uint32_t t = (uint32_t)((k + row) / (row + 1));
         uint32_t rk[16];  // the row, 16 keys to a lane
 #pragma unroll
         for (int i = 0; i < 16; ++i) rk[i] = i * 64 + lane < nslice ? rowk[i * 64 + lane] : kNone;
         const int nreg = (nslice + 63) >> 6;  // (wave-uniform)
         for (int b = 31; b >= 0; --b) {
-            const uint32_t mid = bound | (1u << b);
+            const uint32_t mid = b0 | (1u << b);
             uint32_t cnt = 0;
 #pragma unroll
             for (int i = 0; i < 16; ++i)
                 if (i < nreg) cnt += rk[i] < mid ? 1u : 0u;
-            if (wave_sum_u32(cnt) < t) bound = mid;
+            if (wave_sum_u32(cnt) < t) b0 = mid;
         }
+        if (lane == 0) bound_s = b0;
     }
-    const uint32_t have = count([&](int i) { return dk[i] != kNone; });
+    __syncthreads();
+    const uint32_t bound = bound_s;
+    // entries that exist (low half) and entries at or below the bound (high half), in one count
+    // (at most 32768 entries: each half fits 16 bits)
+    const uint32_t both = count([&](int i) { return dk[i] != kNone; }, [&](int i) { return bound != kNone && dk[i] <= bound; });
+    const uint32_t have = both & 0xffffu;
     const uint32_t kk = have < (uint32_t)k ? have : (uint32_t)k;  // entries to return
-    const uint32_t near = bound == kNone ? 1025u : count([&](int i) { return dk[i] <= bound; });
+    const uint32_t near = bound == kNone ? 1025u : both >> 16;
     if (kk > 0 && near <= 1024u) {
         // (near >= kk: the bound is at or above the k-th smallest key)
 #pragma unroll
@@ -2220,7 +2232,7 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
     // A single query leaves three of the narrowest tile's four query slots empty: they take copies of
     // its tables and code, every wave feeds the list of slot wave % 4, and the four lists are merged
     // when the slice ends -- a list's lock is then shared by 4 waves instead of 16 while the lists
-    // fill (1 x 400M codes, ht = 20, k = 100: 0.61 -> see the benchmark's small_batch).
+    // fill.
     a.spread_lists = (nq == 1 && skip_first < 0) ? 1 : 0;
     a.list_tab = nullptr;
     a.queries = nullptr;
