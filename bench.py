@@ -8,9 +8,10 @@ codebook and codes already resident in HBM.  Inputs are seeded and synthetic (SI
 mixture, see workloads/).  Prints ONE JSON line: the headline workload at the top level
 (`value`, `roofline`, `cpu_baseline`, `sweep`, `small_batch`) and the four other named workloads
 under `workloads` (tiny, flat128, ivf, graph), each with its own time per step, pairs/s, roofline
-block and oracle baseline on a stated sample, whose ids are compared with the GPU's.
+block and oracle baseline on a stated sample, whose ids are compared with the GPU's; `imi` there is
+the inverted multi-index over the ivf workload's vectors (Table 2's cap settings).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--ht 24] [--workloads flat64,tiny,flat128,ivf,graph]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--ht 24] [--workloads flat64,tiny,flat128,ivf,graph,imi]
                     [--small] [--no-sweep] [--no-cpu] [--no-small-batch] [--filter-route auto|popcount|mfma]
 """
 from __future__ import annotations
@@ -41,8 +42,8 @@ OPS_PER_PAIR = {8: 5, 16: 9}
 # slices, workgroups): a change of kernel or shape makes the figure null instead of stale.
 # Sources: profiles/scan_mfma_kernel_flat64_ht24.md, profiles/scan_kernel_flat64_ht24.md.
 MEASURED_TRAFFIC_BYTES = {
-    ("flat64", 24, "scan_mfma_kernel m=8 tq=16 waves=16 slices=2 tiles=738"): 1.9229e10,
-    ("flat64", 24, "scan_kernel m=8 tq=8 waves=8 slices=2 tiles=1476"): 9.7279e10,
+    ("flat64", 24, "scan_mfma_kernel m=8 tq=16 waves=16 slices=2 tiles=738"): 1.9502e10,
+    ("flat64", 24, "scan_kernel m=8 tq=8 waves=8 slices=2 tiles=1476"): 9.8135e10,
 }
 
 
