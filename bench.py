@@ -464,6 +464,7 @@ def bench_imi(args):
         ms1 = time_ms(lambda: idx.imi_search(xs, max_lists, max_codes, ht, k, workspace=ws1, out=out1), 20, 3)
         row = dict(max_lists=max_lists, max_codes=max_codes, ms_per_batch=round(ms, 3), us_per_query_batch=round(ms * 1e3 / nq, 3),
                    ms_per_batch_without_filter=round(ms_nofilter, 3), ms_single_query=round(ms1, 4),
+                   kernel=psc.last_scan_route(),
                    cells_per_query=float((cells >= 0).float().sum(dim=1).mean().item()), codes_per_query=pairs / nq,
                    pairs_per_s=pairs / (ms * 1e-3))
         if not args.no_cpu and max_lists == 16 and max_codes == 10_000:

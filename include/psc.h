@@ -346,7 +346,8 @@ int psc_imi_set_lists(psc_index *idx, const int64_t *offsets_dev, const uint8_t 
  * handful of codes each and queries rarely share one), so a single query and a batch take the same
  * path.  The tables are put together per cell from the query's share, the two half-centroids'
  * shares (k1 + k2 half tables, part of the index's device image as for psc_ivf_search) and
- * ||(q - cell centroid)_j||^2, or by direct differences under the rule stated at psc_ivf_search. */
+ * ||(q - cell centroid)_j||^2, or by direct differences under the rule stated at psc_ivf_search
+ * (psc_last_scan_route then starts with "imi_scan_kernel+direct-tables"). */
 size_t psc_imi_search_workspace_bytes(const psc_index *idx, int64_t nq, int max_lists);
 int psc_imi_search(const psc_index *idx, const float *q_dev, int64_t nq, int max_lists, int64_t max_codes, int ht,
                    int k, int64_t *ids_dev, float *dists_dev, int32_t *cells_out_dev, uint8_t *qcodes_out_dev,

@@ -84,6 +84,7 @@ int launch_rotate(const float *x_dev, int64_t n, int din, const float *rt_dev, i
 extern std::atomic<int> g_filter_route;
 // The kernel and tile shape the calling thread's last scan launched ("" before the first).
 const char *last_scan_route();
+void note_scan_route(const char *text);  // (for the searches whose kernels live in other files)
 struct ScanPlan {
     int tq = 0;          // queries per workgroup tile
     int nwaves = 0;      // waves per workgroup

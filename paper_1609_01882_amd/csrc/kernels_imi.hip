@@ -394,6 +394,10 @@ int launch_imi_scan(int m, const float *lut_dev, const float *tab1_dev, const fl
         hipLaunchKernelGGL(imi_scan_kernel<16>, dim3((unsigned)nq), dim3(256), lds, s, a);
     }
     PSC_HIP_TRY(hipGetLastError());
+    char text[96];
+    snprintf(text, sizeof text, "imi_scan_kernel%s m=%d cells<=%d pool=%d queries=%lld", direct ? "+direct-tables" : "", m, lmax,
+             cap, (long long)nq);
+    note_scan_route(text);
     return PSC_OK;
 }
 

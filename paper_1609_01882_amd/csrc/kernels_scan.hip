@@ -210,7 +210,7 @@ struct Lds {
     }
 };
 
-// ---- the Hamming test of Section 3.1, hand-written ------------------------------------------
+// ---- the Hamming test of Section 3.3, hand-written ------------------------------------------
 // For one code (words w) and NQ queries whose code words sit in scalar registers: per pair one
 // v_xor and one v_bcnt (population count plus accumulator) per 32-bit word, the accumulator
 // starting at `bias` = 0x7fffffff - ht so that its sign bit says "farther than ht", and one
@@ -1068,7 +1068,7 @@ scan_kernel(ScanArgs a)
 }
 
 // ---------------------------------------------------------------------------------------------
-// The fused scan with the Hamming test of Section 3.1 on the matrix cores (64-bit codes, tiles
+// The fused scan with the Hamming test of Section 3.3 ("dual" in Section 4.2) on the matrix cores (64-bit codes, tiles
 // of 16 queries, flat and graph mode).  With every bit b written as the byte +1 (b = 0) or -1
 // (b = 1), the dot product of two codes is 64 - 2 * (Hamming distance), so
 //     distance <= ht   <=>   (2 * ht - 64) + dot >= 0,
@@ -1339,7 +1339,7 @@ scan_mfma_kernel(ScanArgs a)
 // lut4[g][j][c] = (T_{4g}[j][c], .., T_{4g+3}[j][c]): one 16-byte read serves four queries of
 // the tile, and a code's m byte offsets are computed once for all TQ queries.
 // Same tiling (query tile x database slice), lists, ordering and outputs as scan_kernel.
-// FILTER: the Hamming test of Section 3.1 is still applied, as one more condition on every pair.
+// FILTER: the Hamming test of Section 3.3 is still applied, as one more condition on every pair.
 // This is the cheaper route when the threshold lets a large share of the codes through: scoring
 // everything from the interleaved tables then costs less than queueing the survivors one by one.
 // ---------------------------------------------------------------------------------------------
@@ -2004,6 +2004,8 @@ void note_route(const char *kernel, int m, int tq, int nwaves, int nslice, int64
 std::atomic<int> g_filter_route{PSC_ROUTE_AUTO};
 
 const char *last_scan_route() { return g_route; }
+
+void note_scan_route(const char *text) { snprintf(g_route, sizeof g_route, "%s", text); }
 
 // Tile shape and database slices.
 // Shapes (queries per tile x waves per workgroup), per kind of scan, first one that fits:

@@ -181,3 +181,44 @@ def test_imi_argument_errors():
     out = idx.imi_search(q, 6, 0, 64, 12)
     torch.cuda.synchronize()
     assert sorted(out[0][0][:10].tolist()) == list(range(10)) and out[0][0][10:].tolist() == [-1, -1]
+
+
+@pytest.mark.parametrize("spread,sigma,direct", [(300.0, 10.0, False), (4000.0, 10.0, True)])
+def test_imi_distances_when_the_half_centroids_lie_far_apart(spread, sigma, direct):
+    """The 1e-5 bound away from the comfortable data scale, as for the inverted file: half-centroids
+    uniform in [0, spread]^64 with the vectors within sigma of a cell centroid.  Below the rule's
+    limit the cell tables are added up from the query's and the half-centroids' shares, above it they
+    are built by direct differences; both agree with the float64 oracle."""
+    import paper_1609_01882_amd as psc
+    rng = np.random.default_rng(int(spread))
+    k1, k2, n, nq = 9, 7, 20_000, 40
+    c1 = (rng.random((k1, 64)) * spread).astype(np.float32)
+    c2 = (rng.random((k2, 64)) * spread).astype(np.float32)
+
+    def draw(count):
+        a, b = rng.integers(0, k1, size=count), rng.integers(0, k2, size=count)
+        return (np.concatenate([c1[a], c2[b]], axis=1) + rng.normal(0, sigma, size=(count, 128))).astype(np.float32)
+    xt, xb, xq = draw(4000), draw(n), draw(nq)
+    idx = psc.Index(128, 8)
+    idx.imi_set_coarse(c1, c2)
+    ct = idx.imi_assign_encode(_dev(xt), want_codes=False)[0].cpu().numpy()
+    idx.train_pq(xt - np.concatenate([c1[ct // k2], c2[ct % k2]], axis=1), iters=5, seed=4)
+    cell, codes = idx.imi_assign_encode(_dev(xb))
+    order = torch.sort(cell.to(torch.int64), stable=True).indices
+    offsets = torch.zeros(k1 * k2 + 1, dtype=torch.int64, device="cuda")
+    offsets[1:] = torch.cumsum(torch.bincount(cell.to(torch.int64), minlength=k1 * k2), 0)
+    lcodes, lids = codes[order].contiguous(), order.to(torch.int32).contiguous()
+    idx.imi_set_lists(offsets, lcodes, lids)
+    cc = np.concatenate([np.repeat(c1, k2, axis=0), np.tile(c2, (k1, 1))], axis=1)
+    cb, off_h, lc_h, li_h = idx.get_codebook(), offsets.cpu().numpy(), lcodes.cpu().numpy(), lids.cpu().numpy()
+    for max_lists, ht, k in ((6, 26, 20), (3, 64, 50)):
+        ids, d, cells, qcodes = idx.imi_search(_dev(xq), max_lists, 0, ht, k, want_debug=True)
+        torch.cuda.synchronize()
+        cells, qcodes = cells.cpu().numpy(), qcodes.cpu().numpy()
+        ref = O.imi_search(xq, cb, c1, c2, off_h, lc_h, li_h, max_lists, 0, ht, k, cells_in=cells, qcodes_in=qcodes)
+        assert_ivf_topk_matches(ids.cpu().numpy(), d.cpu().numpy(), ref, xq, cb, cc, off_h, lc_h, li_h, cells, qcodes, ht,
+                                O.build_lut, what=f"imi spread {spread}")
+        own = O.imi_search(xq, cb, c1, c2, off_h, lc_h, li_h, max_lists, 0, ht, k)
+        assert (own["cells"] != cells).mean() < 0.02
+    # which path ran (the rule's ratio is about 0.03 x spread for sigma = 10, its limit 16)
+    assert psc.last_scan_route().split()[0] == ("imi_scan_kernel+direct-tables" if direct else "imi_scan_kernel")
