@@ -492,6 +492,52 @@ def bench_imi(args):
     return res
 
 
+# --------------------------------------------------------------------------------------------- what the filter keeps
+def bench_quality(args):
+    """On the dictated mixture neither recall nor the share of the unfiltered top 10 that the filter
+    keeps says anything (both are fixed by the cluster structure, see `sweep`).  This leg puts the
+    quantities Table 1 contrasts on data where they move: one wide Gaussian without clusters, 64-bit
+    codes, 1M vectors, 1000 queries; index assignment left as k-means numbered it ("PQ") against
+    optimised ("PolyD"); threshold = the paper's rule (removes >= 95 % of the training pairs)."""
+    import torch
+
+    import paper_1609_01882_amd as psc
+    import workloads as W
+
+    dev = torch.device("cuda:0")
+    threads = min(16, os.cpu_count() or 1)
+    n, nq, k, dim, m = (200_000 if args.small else 1_000_000), 1000, 10, 128, 8
+    kw = dict(seed=4242, n_centres=1, sigma=30.0, dim=dim, threads=threads)
+    xt = W.sift_like(100_000, stream=1, **kw)
+    xb = torch.from_numpy(W.sift_like(n, stream=2, **kw)).to(dev)
+    xq = torch.from_numpy(W.sift_like(nq, stream=3, **kw)).to(dev)
+    d = (xq * xq).sum(1)[:, None] - 2.0 * (xq @ xb.T) + (xb * xb).sum(1)[None, :]   # integer-valued: exact
+    truth = d.argmin(dim=1)
+    del d
+    idx = psc.Index(dim, m)
+    idx.train_pq(xt, iters=20, seed=7)
+    res = dict(workload="quality", n_db=n, n_query=nq, k=k, code_bits=64, data="one Gaussian, sigma 30, 128-D (no clusters)")
+    top_adc = None
+    for name in ("PQ", "PolyD"):
+        if name == "PolyD":
+            idx.optimize_index_assignment(seed=7)
+        tcodes = idx.encode(torch.from_numpy(xt).to(dev))
+        ht = psc.threshold_for_rate(psc.hamming_histogram(tcodes[:1000].contiguous(), tcodes), 0.05)
+        codes = idx.encode(xb)
+        adc = idx.search(xq, codes, 64, k)[0]
+        if top_adc is None:
+            top_adc = adc.clone()     # (the ADC ranking does not depend on the numbering)
+        dual = idx.search(xq, codes, ht, k)[0]
+        nsurv = psc.hamming_filter(idx.build_lut(xq[:256])[1], codes, ht)
+        torch.cuda.synchronize()
+        res[name] = dict(ht=ht, survivor_rate=float(nsurv.double().mean()) / n,
+                         adc_recall_at_10=float((adc == truth[:, None]).any(1).float().mean()),
+                         dual_recall_at_10=float((dual == truth[:, None]).any(1).float().mean()),
+                         pure_adc_top10_kept=kept_of(top_adc, dual))
+    log(f"[quality] {res}")
+    return res
+
+
 # --------------------------------------------------------------------------------------------- k-NN graph
 def bench_graph(args):
     import numpy as np
@@ -558,9 +604,10 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--ht", type=int, default=24)
-    ap.add_argument("--workloads", default="flat64,tiny,flat128,ivf,graph,imi",
+    ap.add_argument("--workloads", default="flat64,tiny,flat128,ivf,graph,imi,quality",
                     help="comma-separated subset of flat64 (the headline; always first),tiny,flat128,ivf,graph,imi "
-                         "(imi = the inverted multi-index over the ivf workload's vectors, beyond the five named ones)")
+                         "(imi = the inverted multi-index over the ivf workload's vectors; quality = what the filter keeps "
+                         "on data without cluster structure: both beyond the five named workloads)")
     ap.add_argument("--small", action="store_true", help="reduced sizes (quick check; not a valid measurement)")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
@@ -587,7 +634,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.backends.cuda.matmul.allow_tf32 = False
     want = [w for w in args.workloads.split(",") if w]
-    unknown = set(want) - {"flat64", "tiny", "flat128", "ivf", "graph", "imi"}
+    unknown = set(want) - {"flat64", "tiny", "flat128", "ivf", "graph", "imi", "quality"}
     if unknown:
         log(f"bench.py: unknown workloads {sorted(unknown)}")
         sys.exit(2)
@@ -596,7 +643,7 @@ def main():
     head = bench_flat("flat64", args, headline=True) if "flat64" in want else None
     others = {}
     for name, fn in (("tiny", bench_tiny), ("flat128", lambda a: bench_flat("flat128", a, headline=False)),
-                     ("ivf", bench_ivf), ("graph", bench_graph), ("imi", bench_imi)):
+                     ("ivf", bench_ivf), ("graph", bench_graph), ("imi", bench_imi), ("quality", bench_quality)):
         if name in want:
             t0 = time.time()
             psc.set_filter_route(args.filter_route)
