@@ -95,6 +95,7 @@ struct ScanPlan {
     int64_t tiles_one = 0;  // leading query tiles that scan the whole database in one piece
     int64_t ntiles = 0;
     size_t lds_bytes = 0;
+    int pub_slots = 1;      // words per query in the shared thresholds
     size_t gthr_bytes = 0;  // per-query shared thresholds
     size_t part_bytes = 0;  // partial result lists
     size_t total_bytes = 0; // whole workspace

@@ -41,6 +41,7 @@ constexpr int64_t kMfmaMaxSliceLen = (int64_t)1 << kMfmaRelBits;
 constexpr int64_t kMfmaMinQueries = 9;  // fewer queries than this take the narrower xor/popcount tiles
 constexpr int kMfmaTableBytes = 256 * 8;  // the bits-to-elements table of the matrix-core filter
 constexpr int kSpinLimit = 1 << 22;   // bounded wait on a list lock (each turn sleeps)
+constexpr int kManySlices = 4;        // slices per query from which the lists exchange more than their k-th best
 
 struct IvfTile {
     int32_t job_begin, njobs, list, pad;
@@ -90,6 +91,14 @@ struct ScanArgs {
     // job, each wave feeding the list of slot wave % TQ, so that a list's lock is shared by a
     // quarter of the waves while the lists fill; the lists are merged when the tile ends.
     int spread_lists = 0;
+    // Many slices per query (a handful of queries over a large database: every slice's list
+    // would otherwise warm up on its own share only).  gthr then holds pub_slots words per query;
+    // a list with pub_r entries or more keeps the key of its pub_r-th best in word slice %
+    // pub_slots (atomic minimum over the lists that share the word).  Lists of different words
+    // hold different codes, so a value v with pub_kth words at or below it has pub_kth * pub_r
+    // >= k codes at or below it: nothing farther than v is in the query's top k.  With one word,
+    // pub_r = k and pub_kth = 1 this is the plain exchange of k-th best distances.
+    int pub_slots = 1, pub_r = 0, pub_kth = 1;
 };
 
 // Flat mode: which queries and which part of the database a workgroup works on.  Query tiles
@@ -196,6 +205,7 @@ struct Lds {
     lds_u32 *qcw;    // [TQ][M/4] inverted file: the jobs' query codes
     lds_u32 *queue;  // [nwaves][kQueueCap]; private to a wave: LDS keeps a wave's accesses in order
     lds_u32 *dump;   // [nwaves][64] where lanes with nothing to queue write
+    int slot = 0;    // word of the query's shared thresholds this workgroup's lists publish to
     __device__ __forceinline__ Lds(PSC_LDS unsigned char *base, int kpad, int nwaves)
     {
         lut = (lds_f32 *)base;
@@ -324,6 +334,21 @@ __device__ __forceinline__ void lower_threshold(lds_vf32 *p, float v)
     (void)__hip_atomic_fetch_min((lds_f32 *)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
+// An upper bound on the kth smallest (kth >= 1) of the keys held by the 64 lanes, the same in
+// every lane: the key's upper 20 bits are found one by one, by counting the lanes at or below
+// the value tried (sign, exponent and 11 bits of mantissa: within 0.05% of the exact value),
+// the rest is filled with ones.  kKeyInf or above: fewer than kth lanes hold a finite key.
+__device__ __forceinline__ uint32_t wave_kth_smallest_bound(uint32_t v, int kth)
+{
+    uint32_t prefix = 0u;
+#pragma unroll 1
+    for (int bit = 31; bit >= 12; --bit) {
+        const uint32_t trial = prefix | ((1u << bit) - 1u);
+        if (__builtin_popcountll(ballot64(v <= trial)) < kth) prefix |= 1u << bit;
+    }
+    return prefix | 0xfffu;
+}
+
 // Insert the candidates held by the lanes in `mine` (all for query slot q) into q's sorted list.
 // Executed by the whole wave; mine is wave-uniform.  The slot's lock word doubles as the entry
 // count, so taking the lock also fetches the count and releasing it stores the new one.
@@ -367,15 +392,24 @@ __device__ __forceinline__ void insert_candidates(const Lds<M, TQ> &s, const Sca
     // the lock is given back, so the trip to memory overlaps the work on the list.
     uint32_t seen = kKeyInf;
     int gi = -1;
+    const bool many = SHARE && a.pub_slots > 1;  // (wave-uniform) the exchange over many slices
+    uint32_t slots_seen = kKeyInf;               // many: lane l holds word l of the query
     if constexpr (SHARE) {
-        if (lane == 0) {
+        if (many) {
+            gi = __builtin_amdgcn_readfirstlane(s.gidx[q]);
+            if (lane < a.pub_slots)
+                slots_seen = __hip_atomic_load(&a.gthr[(int64_t)gi * a.pub_slots + lane], __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_AGENT);
+        } else if (lane == 0) {
             gi = s.gidx[q];
             if constexpr (EAGER) seen = __hip_atomic_load(&a.gthr[gi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
     lds_vu64 *list = s.top + q * a.kpad;
     const int k = a.k;
+    const int pr = a.pub_r;      // (1 <= pub_r <= k whenever `many`)
     uint32_t own_key = kKeyInf;  // the list's k-th best once it is full
+    uint32_t pub_key = kKeyInf;  // many: the list's pub_r-th best once it has that many entries
     bool changed = false;
     float thr_old;
     if (k <= 128) {
@@ -403,6 +437,7 @@ __device__ __forceinline__ void insert_candidates(const Lds<M, TQ> &s, const Sca
             if (changed) {
                 if (i0 < cnt) list[i0] = e0;
                 if (cnt == k) own_key = (uint32_t)(lane_value_u64(e0, (k - 1) & 63) >> 32);  // (k <= 64 here)
+                if (many && cnt >= pr) pub_key = (uint32_t)(lane_value_u64(e0, (pr - 1) & 63) >> 32);  // (pr <= cnt <= 64)
             }
         } else {
             if (i1 < cnt) e1 = list[i1];
@@ -426,6 +461,7 @@ __device__ __forceinline__ void insert_candidates(const Lds<M, TQ> &s, const Sca
                 if (i0 < cnt) list[i0] = e0;
                 if (i1 < cnt) list[i1] = e1;
                 if (cnt == k) own_key = (uint32_t)(lane_value_u64(k <= 64 ? e0 : e1, (k - 1) & 63) >> 32);
+                if (many && cnt >= pr) pub_key = (uint32_t)(lane_value_u64(pr <= 64 ? e0 : e1, (pr - 1) & 63) >> 32);
             }
         }
     } else {
@@ -460,6 +496,7 @@ __device__ __forceinline__ void insert_candidates(const Lds<M, TQ> &s, const Sca
             __builtin_amdgcn_wave_barrier();
         }
         if (changed && cnt == k) own_key = (uint32_t)(list[k - 1] >> 32);
+        if (changed && many && cnt >= pr) pub_key = (uint32_t)(list[pr - 1] >> 32);
     }
     const float own = key_dist(own_key);
     const bool lowered = own < thr_old;  // this list's k-th best is below everything known so far
@@ -469,9 +506,27 @@ __device__ __forceinline__ void insert_candidates(const Lds<M, TQ> &s, const Sca
         __hip_atomic_store(&s.lock[q], cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         // Outside the lock: adopt what the others had reached, and tell them (no answer awaited).
         if constexpr (SHARE) {
-            if (seen != kKeyInf && key_dist(seen) < (lowered ? own : thr_old)) lower_threshold(&s.thr[q], key_dist(seen));
-            if (lowered && own_key < seen)
-                (void)__hip_atomic_fetch_min(&a.gthr[gi], own_key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (!many) {
+                if (seen != kKeyInf && key_dist(seen) < (lowered ? own : thr_old))
+                    lower_threshold(&s.thr[q], key_dist(seen));
+                if (lowered && own_key < seen)
+                    (void)__hip_atomic_fetch_min(&a.gthr[gi], own_key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+    if constexpr (SHARE) {
+        if (many) {
+            // the word of this list first (as read at the start, or what the list has just reached)
+            if (lane == s.slot) {
+                if (pub_key < slots_seen) {
+                    slots_seen = pub_key;
+                    (void)__hip_atomic_fetch_min(&a.gthr[(int64_t)gi * a.pub_slots + lane], pub_key, __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+            const uint32_t bound = wave_kth_smallest_bound(slots_seen, a.pub_kth);
+            if (lane == 0 && bound < kKeyInf && key_dist(bound) < (lowered ? own : thr_old))
+                lower_threshold(&s.thr[q], key_dist(bound));
         }
     }
     __builtin_amdgcn_s_setprio(0);
@@ -487,6 +542,7 @@ __device__ __forceinline__ uint32_t ask_shared_thresholds(const Lds<M, TQ> &s, c
 {
     const int lane = lane_id();
     uint32_t g = kKeyInf;
+    if (a.pub_slots > 1) return g;  // (the exchange over many slices happens where lists change)
     if (lane < TQ) {
         const int gi = s.gidx[lane];
         if (gi >= 0) g = __hip_atomic_load(&a.gthr[gi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -743,7 +799,7 @@ __global__ void __launch_bounds__(NW * 64)
 scan_kernel(ScanArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    const Lds<M, TQ> s((PSC_LDS unsigned char *)smem, a.kpad, NW);
+    Lds<M, TQ> s((PSC_LDS unsigned char *)smem, a.kpad, NW);
     constexpr int WPC = M / 4;       // 32-bit words per code
     constexpr int CB = 32 / TQ;      // codes per lane and block: one survivor bit per (code, query)
     constexpr int NLD = CB * M / 16; // 16-byte loads per lane and block
@@ -772,6 +828,7 @@ scan_kernel(ScanArgs a)
     } else {
         const FlatTile t = flat_tile(a, blockIdx.x, TQ);
         slice = t.slice;
+        s.slot = slice % a.pub_slots;
         whole_db = t.whole;
         q0 = t.q0;
         nvq = (int)((a.nq - q0) < TQ ? (a.nq - q0) : TQ);
@@ -787,7 +844,8 @@ scan_kernel(ScanArgs a)
         const int gi = job < nvq ? (int)(IVF ? (int64_t)a.job_q[q0 + job] : q0 + job) : -1;
         float t0 = __builtin_inff();
         if constexpr (SHARE) {
-            if (gi >= 0) t0 = key_dist(__hip_atomic_load(&a.gthr[gi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            if (gi >= 0 && a.pub_slots == 1)
+                t0 = key_dist(__hip_atomic_load(&a.gthr[gi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
         }
         s.thr[tid] = t0;
         s.lock[tid] = 0;
@@ -1109,7 +1167,7 @@ scan_mfma_kernel(ScanArgs a)
     extern __shared__ __align__(16) unsigned char smem[];
     // [256] byte -> eight bytes of +-1, at LDS address 0 so that a look-up address is just byte * 8
     PSC_LDS u32x2 *xtab = (PSC_LDS u32x2 *)smem;
-    const Lds<M, TQ> s((PSC_LDS unsigned char *)smem + kMfmaTableBytes, a.kpad, NW);
+    Lds<M, TQ> s((PSC_LDS unsigned char *)smem + kMfmaTableBytes, a.kpad, NW);
     const int tid = (int)threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1130,6 +1188,7 @@ scan_mfma_kernel(ScanArgs a)
     } else {
         ft = flat_tile(a, blockIdx.x, TQ);
         slice = ft.slice;
+        s.slot = slice % a.pub_slots;
         q0 = ft.q0;
         nvq = (int)((a.nq - q0) < TQ ? (a.nq - q0) : TQ);
         slice_begin = ft.slice_begin;
@@ -1146,7 +1205,8 @@ scan_mfma_kernel(ScanArgs a)
         const int gi = tid < nvq ? (int)(IVF ? (int64_t)a.job_q[q0 + tid] : q0 + tid) : -1;
         float t0 = __builtin_inff();
         if constexpr (SHARE) {
-            if (gi >= 0) t0 = key_dist(__hip_atomic_load(&a.gthr[gi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            if (gi >= 0 && a.pub_slots == 1)
+                t0 = key_dist(__hip_atomic_load(&a.gthr[gi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
         }
         s.thr[tid] = t0;
         s.lock[tid] = 0;
@@ -1349,7 +1409,7 @@ adc_kernel(ScanArgs a)
 {
     static_assert(TQ % 4 == 0, "four queries per table entry");
     extern __shared__ __align__(16) unsigned char smem[];
-    const Lds<M, TQ> s((PSC_LDS unsigned char *)smem, a.kpad, NW);
+    Lds<M, TQ> s((PSC_LDS unsigned char *)smem, a.kpad, NW);
     typedef float f32x4 __attribute__((ext_vector_type(4)));
     constexpr int G = TQ / 4;
     constexpr int WPC = M / 4;
@@ -1360,6 +1420,7 @@ adc_kernel(ScanArgs a)
 
     const FlatTile ft = flat_tile(a, blockIdx.x, TQ);
     const int slice = ft.slice;
+    s.slot = slice % a.pub_slots;
     const int64_t q0 = ft.q0;
     const int nvq = (int)((a.nq - q0) < TQ ? (a.nq - q0) : TQ);
     const int64_t slice_begin = ft.slice_begin;
@@ -1376,7 +1437,7 @@ adc_kernel(ScanArgs a)
         if (tid < TQ) {
             float t0 = __builtin_inff();
             if constexpr (SHARE) {
-                if (tid < nvq)
+                if (tid < nvq && a.pub_slots == 1)
                     t0 = key_dist(__hip_atomic_load(&a.gthr[q0 + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
             }
             s.thr[tid] = t0;
@@ -2144,7 +2205,9 @@ int plan_scan(int m, int64_t nq, int64_t n, int k, int kind, ScanPlan *plan)
     p.ntiles = tiles_one + (nqt - tiles_one) * nslice;
     const size_t dist_bytes = ((size_t)nq * nslice * k * sizeof(float) + 255) / 256 * 256;
     p.part_bytes = dist_bytes + (size_t)nq * nslice * k * sizeof(int64_t);
-    p.gthr_bytes = ((size_t)nq * sizeof(uint32_t) + 255) / 256 * 256;
+    // a query cut into many slices exchanges one word per 64th of them (see ScanArgs::pub_slots)
+    p.pub_slots = nslice >= kManySlices ? (int)std::min<int64_t>(nslice, 64) : 1;
+    p.gthr_bytes = ((size_t)nq * p.pub_slots * sizeof(uint32_t) + 255) / 256 * 256;
     p.total_bytes = 256 + p.gthr_bytes + p.part_bytes;
     *plan = p;
     return PSC_OK;
@@ -2229,7 +2292,18 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
     a.job_q = nullptr;
     a.part_d = (float *)((char *)ws + 256 + p.gthr_bytes);
     a.part_i = (int64_t *)((char *)a.part_d + (((size_t)nq * p.nslice * k * sizeof(float) + 255) / 256 * 256));
-    hipLaunchKernelGGL(init_scan_kernel, dim3((unsigned)((nq + 255) / 256)), dim3(256), 0, s, a.gthr, nq,
+    // which entry the lists of a many-slice query publish, and which of the published values bounds
+    // the k-th best: pub_kth words x pub_r entries >= k, with pub_kth about 0.4 of the words (the
+    // value then sits near the (1.3 k)-th best of everything scanned so far)
+    a.pub_slots = p.pub_slots;
+    a.pub_r = k;
+    a.pub_kth = 1;
+    if (p.pub_slots > 1) {
+        a.pub_r = std::min(k, std::max(1, (5 * k + 2 * p.pub_slots - 1) / (2 * p.pub_slots)));
+        a.pub_kth = (k + a.pub_r - 1) / a.pub_r;
+    }
+    const int64_t nwords = nq * p.pub_slots;
+    hipLaunchKernelGGL(init_scan_kernel, dim3((unsigned)((nwords + 255) / 256)), dim3(256), 0, s, a.gthr, nwords,
                        clear_status ? a.status : (int *)nullptr);
     // A single query leaves three of the narrowest tile's four query slots empty: they take copies of
     // its tables and code, every wave feeds the list of slot wave % 4, and the four lists are merged

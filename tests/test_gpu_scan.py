@@ -178,6 +178,36 @@ def test_many_slices_for_few_queries(psc):
         assert_topk_matches(got_ids, got_d, ref, lut.astype(np.float64), qcodes, codes, ht, what=f"many slices ht={ht}")
 
 
+@pytest.mark.parametrize("case", ["all tied", "best in one slice", "wide range"])
+@pytest.mark.parametrize("nq,k", [(1, 100), (3, 7), (12, 1), (5, 640)])
+def test_what_the_slices_tell_each_other_costs_no_result(psc, case, nq, k):
+    """Queries cut into many slices prune with a bound taken from the other slices' lists (the
+    r-th best of each, and the value enough of them have reached).  Where that bound equals the
+    k-th distance (everything tied), where one slice holds the whole answer, and where distances
+    span sixty binary orders of magnitude (the bound is rounded up in the float's bits), the result
+    is still the oracle's."""
+    n, m = 1_200_007, 8
+    rng = np.random.default_rng(900 + k)
+    codes, qcodes, lut = _rand_problem(m, n, nq, seed=901 + k, lut_kind="int")
+    if case == "all tied":
+        lut[:] = 2.0
+    elif case == "best in one slice":
+        # the last 2000 codes are the only ones with small distances: byte 0 below 16 there only
+        codes[:, 0] |= 16
+        codes[-2000:, 0] &= 15
+        lut[:, 0, :16] = 0.0
+        lut[:, 0, 16:] = 50.0
+    else:
+        lut = np.exp2(rng.uniform(-30.0, 30.0, size=(nq, m, 256))).astype(np.float32)
+    for ht in (26, 64):
+        got_ids, got_d = _run(psc, lut, qcodes, codes, ht, k)
+        ref = O.scan(lut.astype(np.float64), qcodes, codes, ht, k)
+        nd = assert_topk_matches(got_ids, got_d, ref, lut.astype(np.float64), qcodes, codes, ht,
+                                 what=f"{case} nq={nq} k={k} ht={ht}")
+        if case != "wide range":
+            assert nd == 0
+
+
 @pytest.mark.parametrize("nq,n,k,lut_kind", [(1, 3_000_001, 100, "int"), (3, 1_000_003, 64, "int"),
                                              (8, 400_009, 128, "float"), (2, 70_001, 1024, "int"),
                                              (1, 300, 500, "int")])
