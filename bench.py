@@ -398,7 +398,7 @@ def bench_ivf(args):
                                           "in profiles/ivf_100M_search_kernels.md"))
     # small batches: latency of one call (the paper's single-query mode, Section 4.3 / Table 2)
     small = []
-    for nqs in (1, 16, 256):
+    for nqs in (1, 4, 16, 64, 256):
         xs = xq[:nqs].contiguous()
         wss = torch.empty(idx.ivf_search_workspace_bytes(nqs, nprobe, k), dtype=torch.uint8, device=dev)
         outs = (torch.empty((nqs, k), dtype=torch.int64, device=dev), torch.empty((nqs, k), dtype=torch.float32, device=dev))

@@ -975,7 +975,7 @@ int ivf_layout(const psc_index *idx, int64_t nq, int nprobe, int k, IvfLayout *L
         return at;
     };
     L->off_status = take(256);
-    L->off_gthr = take((size_t)nq * sizeof(uint32_t));
+    L->off_gthr = take((size_t)nq * shared_threshold_words(nprobe) * sizeof(uint32_t));
     L->off_dist = take((size_t)nq * idx->nlist * sizeof(float));
     L->off_probed = take((size_t)L->njobs * sizeof(int32_t));
     L->off_hist = take((size_t)L->nblk * 2 * idx->nlist * sizeof(int32_t));

@@ -103,6 +103,9 @@ struct ScanPlan {
 // kind: which scan the plan is for (the shapes differ)
 enum { kScanFused = 0, kScanDense = 1, kScanLists = 2, kScanDenseFiltered = 3, kScanFusedMfma = 4 };
 int plan_scan(int m, int64_t nq, int64_t n, int k, int kind, ScanPlan *plan);
+// Words per query of the thresholds the lists of one query share, given how many lists (database
+// slices, probed inverted lists) a query has.
+int shared_threshold_words(int64_t lists_per_query);
 // Workspace that serves a flat scan whatever route (fused or dense) the threshold selects.
 size_t flat_scan_workspace_bytes(int m, int64_t nq, int64_t n, int k);
 // skip_first >= 0: query q never returns database row skip_first + q (k-NN-graph mode).
