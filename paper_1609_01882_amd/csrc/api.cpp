@@ -1044,7 +1044,7 @@ int psc_ivf_search(const psc_index *idx, const float *q_dev, int64_t nq, int npr
     rc = launch_coarse_distances(q_dev, nq, idx->dim, idx->coarse_dev, idx->nlist,
                                  idx->coarse_dev + (size_t)idx->nlist * idx->dim, dist, s);
     if (rc != PSC_OK) return rc;
-    rc = launch_select_probes(dist, nq, idx->nlist, nprobe, probed, s);
+    rc = launch_select_probes(dist, nq, idx->nlist, nprobe, nullptr, probed, s);
     if (rc != PSC_OK) return rc;
     if (probed_out_dev)
         PSC_HIP_TRY(hipMemcpyAsync(probed_out_dev, probed, (size_t)L.njobs * sizeof(int32_t),
@@ -1391,11 +1391,23 @@ int psc_imi_search(const psc_index *idx, const float *q_dev, int64_t nq, int max
     PSC_TRY(launch_split_halves(q_dev, nq, idx->dim, h1, h2, s));
     PSC_TRY(launch_coarse_distances(h1, nq, half, im.c1, idx->imi_k1, im.mu1, d1, s));
     PSC_TRY(launch_coarse_distances(h2, nq, half, im.c2, idx->imi_k2, im.mu2, d2, s));
-    PSC_TRY(launch_select_probes(d1, nq, idx->imi_k1, L.l1, s1, s));
-    PSC_TRY(launch_select_probes(d2, nq, idx->imi_k2, L.l2, s2, s));
-    // 2. the cells in order of d1 + d2, cut by the caps
-    PSC_TRY(launch_imi_cells(s1, d1, idx->imi_k1, L.l1, s2, d2, idx->imi_k2, L.l2, max_lists, max_codes,
-                             idx->imi_off_dev, nq, cells, ncells, (int *)workspace_dev, s));
+    // 2. the cells in order of d1 + d2, cut by the caps.  With a cap on codes most queries are done
+    // after a few dozen cells however many are allowed: a first pass orders 64 cells (from as many
+    // nearest half-centroids), a second one 256, and only the queries these do not settle go through
+    // the selection of all L.l1 / L.l2 half-centroids and the full order.
+    const int schedule[3] = {64, 256, max_lists};
+    bool marked = false;  // a pass before this one has left queries marked (ncells = -1)
+    for (int pass = 0; pass < 3; ++pass) {
+        const int lcur = schedule[pass];
+        const bool last = pass == 2;
+        if (!last && (lcur >= max_lists || max_codes <= 0)) continue;
+        const int f1 = std::min(L.l1, lcur), f2 = std::min(L.l2, lcur);
+        PSC_TRY(launch_select_probes(d1, nq, idx->imi_k1, f1, marked ? ncells : nullptr, s1, s));
+        PSC_TRY(launch_select_probes(d2, nq, idx->imi_k2, f2, marked ? ncells : nullptr, s2, s));
+        PSC_TRY(launch_imi_cells(s1, d1, idx->imi_k1, f1, s2, d2, idx->imi_k2, f2, max_lists, lcur, marked, max_codes,
+                                 idx->imi_off_dev, nq, cells, ncells, (int *)workspace_dev, s));
+        marked = true;
+    }
     if (cells_out_dev)
         PSC_HIP_TRY(hipMemcpyAsync(cells_out_dev, cells, (size_t)nq * max_lists * sizeof(int32_t),
                                    hipMemcpyDeviceToDevice, s));

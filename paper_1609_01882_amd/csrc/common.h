@@ -139,8 +139,9 @@ int launch_hamming_filter(int m, const uint8_t *qcodes_dev, int64_t nq, const ui
 int launch_coarse_distances(const float *x_dev, int64_t n, int dim, const float *cent_dev, int nlist,
                             const float *mu_dev, float *dist_dev, hipStream_t s);
 // Per row the nprobe smallest of dist [n][nlist] by (distance, list number) -> probed [n][nprobe].
-int launch_select_probes(const float *dist_dev, int64_t n, int nlist, int nprobe, int32_t *probed_dev,
-                         hipStream_t s);
+// settled_dev (or null): rows r with settled_dev[r] >= 0 are left out (their row of probed is not written).
+int launch_select_probes(const float *dist_dev, int64_t n, int nlist, int nprobe, const int32_t *settled_dev,
+                         int32_t *probed_dev, hipStream_t s);
 // Nearest centroid of each row (lowest number on ties) -> assign [n] (int32).
 int launch_nearest_centroid(const float *x_dev, int64_t n, int dim, const float *cent_dev, int nlist,
                             const float *mu_dev, int32_t *assign_dev, hipStream_t s);
@@ -174,11 +175,15 @@ int launch_unsort_rows(const uint8_t *src_dev, const int32_t *job_slot_dev, int6
 // ---- inverted multi-index (kernels_imi.hip)
 int launch_split_halves(const float *x_dev, int64_t n, int dim, float *h1_dev, float *h2_dev, hipStream_t s);
 int launch_combine_cells(const int32_t *a_dev, const int32_t *b_dev, int64_t n, int k2, int32_t *cell_dev, hipStream_t s);
-// Per query the cells to visit, in order, from the sorted nearest half-centroids (sel*) and all
-// half distances (dist*): cells [nq][lmax] (-1 padded), ncells [nq].
+// Per query the cells to visit, in order, from the l1 / l2 nearest half-centroids in order (sel*,
+// rows of l1 / l2 entries) and all half distances (dist*): cells [nq][lmax] (-1 padded), ncells [nq].
+// One pass over the first lcur <= lmax cells of the order.  lcur < lmax: queries whose cap on codes
+// is not reached within those cells get ncells = -1 and no cells; only_marked: only queries with
+// ncells = -1 are worked on.
 int launch_imi_cells(const int32_t *sel1_dev, const float *dist1_dev, int k1, int l1, const int32_t *sel2_dev,
-                     const float *dist2_dev, int k2, int l2, int lmax, int64_t max_codes, const int64_t *offsets_dev,
-                     int64_t nq, int32_t *cells_dev, int32_t *ncells_dev, int *status_dev, hipStream_t s);
+                     const float *dist2_dev, int k2, int l2, int lmax, int lcur, bool only_marked, int64_t max_codes,
+                     const int64_t *offsets_dev, int64_t nq, int32_t *cells_dev, int32_t *ncells_dev, int *status_dev,
+                     hipStream_t s);
 // One workgroup per query over its cells: residual tables, bit strings, filter, ADC, best k.
 int launch_imi_scan(int m, const float *lut_dev, const float *tab1_dev, const float *tab2_dev, const float *cb_dev,
                     const float *queries_dev, const float *c1_dev, const float *c2_dev, int dim, int k2,

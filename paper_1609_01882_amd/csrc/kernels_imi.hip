@@ -84,12 +84,17 @@ __global__ void combine_cells_kernel(const int32_t *__restrict__ a, const int32_
 
 // One workgroup per query.  sel1 [nq][l1] / sel2 [nq][l2]: the nearest half-centroids in ascending
 // (distance, number); dist1 [nq][k1] / dist2 [nq][k2]: all half distances.  Dynamic LDS: npad keys
-// (npad = the candidate count rounded up to a power of two), then l1 + 1 ints, then lmax int64.
+// (npad = the candidate count rounded up to a power of two), then l1 + 1 ints, then lcur int64.
+// The order is found for the first lcur <= lmax cells (candidates: (i+1)(j+1) <= lcur).  A pass
+// that is not the last one (lcur < lmax) settles the queries whose cap on codes is reached within
+// those cells -- with cells of hundreds of codes that is nearly all of them, at a fraction of the
+// sorting work -- and marks the others with ncells = -1; the last pass (lcur = lmax) then takes
+// only the marked ones (only_marked), or every query if it is the only pass.
 __global__ void __launch_bounds__(256)
 imi_cells_kernel(const int32_t *__restrict__ sel1, const float *__restrict__ dist1, int k1, int l1,
-                 const int32_t *__restrict__ sel2, const float *__restrict__ dist2, int k2, int l2, int lmax,
-                 int64_t max_codes, const int64_t *__restrict__ offsets, int npad, int32_t *__restrict__ cells,
-                 int32_t *__restrict__ ncells, int *__restrict__ status)
+                 const int32_t *__restrict__ sel2, const float *__restrict__ dist2, int k2, int l2, int lmax, int lcur,
+                 int only_marked, int64_t max_codes, const int64_t *__restrict__ offsets, int npad,
+                 int32_t *__restrict__ cells, int32_t *__restrict__ ncells, int *__restrict__ status)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned long long *keys = (unsigned long long *)smem;
@@ -98,11 +103,12 @@ imi_cells_kernel(const int32_t *__restrict__ sel1, const float *__restrict__ dis
     const int64_t q = blockIdx.x;
     const int tid = (int)threadIdx.x;
     if (q == 0 && tid == 0 && status) *status = 0;  // (nothing in this search waits on anything: always clean)
+    if (only_marked && ncells[q] >= 0) return;      // (settled by the pass before; uniform over the workgroup)
     if (tid == 0) {
         int run = 0;
         for (int i = 0; i < l1; ++i) {
             pre[i] = run;
-            const int jm = lmax / (i + 1);
+            const int jm = lcur / (i + 1);
             run += jm < l2 ? jm : l2;
         }
         pre[l1] = run;
@@ -125,7 +131,7 @@ imi_cells_kernel(const int32_t *__restrict__ sel1, const float *__restrict__ dis
         keys[e] = key;
     }
     bitonic_sort(keys, npad);
-    const int lc = nc < lmax ? nc : lmax;
+    const int lc = nc < lcur ? nc : lcur;
     for (int t = tid; t < lc; t += 256) {
         const int64_t cell = (int64_t)(uint32_t)keys[t];
         held[t] = offsets[cell + 1] - offsets[cell];
@@ -136,11 +142,15 @@ imi_cells_kernel(const int32_t *__restrict__ sel1, const float *__restrict__ dis
         long long total = 0;
         int t = 0;
         while (t < lc && !(max_codes > 0 && total >= max_codes)) total += held[t++];
+        // not the last pass, and the cap on codes is not reached within these cells: the cells after
+        // them are needed, leave the query to the next pass
+        if (lcur < lmax && !(max_codes > 0 && total >= max_codes)) t = -1;
         ntake_s = t;
         ncells[q] = t;
     }
     __syncthreads();
     const int ntake = ntake_s;
+    if (ntake < 0) return;
     for (int t = tid; t < lmax; t += 256) cells[q * lmax + t] = t < ntake ? (int32_t)(uint32_t)keys[t] : -1;
 }
 
@@ -322,16 +332,13 @@ static int64_t imi_candidates(int l1, int l2, int lmax)
 }
 
 int launch_imi_cells(const int32_t *sel1_dev, const float *dist1_dev, int k1, int l1, const int32_t *sel2_dev,
-                     const float *dist2_dev, int k2, int l2, int lmax, int64_t max_codes, const int64_t *offsets_dev,
-                     int64_t nq, int32_t *cells_dev, int32_t *ncells_dev, int *status_dev, hipStream_t s)
+                     const float *dist2_dev, int k2, int l2, int lmax, int lcur, bool only_marked, int64_t max_codes,
+                     const int64_t *offsets_dev, int64_t nq, int32_t *cells_dev, int32_t *ncells_dev, int *status_dev,
+                     hipStream_t s)
 {
     if (nq == 0) return PSC_OK;
-    PSC_REQUIRE(lmax >= 1 && lmax <= 1024 && l1 >= 1 && l2 >= 1 && nq <= 0x7fffffffLL, "bad multi-index shape");
-    const int64_t nc = imi_candidates(l1, l2, lmax);
-    int npad = 2;
-    while (npad < nc) npad <<= 1;
-    const size_t lds = (size_t)npad * 8 + (size_t)((l1 + 2) & ~1) * 4 + (size_t)lmax * 8;
-    PSC_REQUIRE(lds <= 96 * 1024, "too many candidate cells");
+    PSC_REQUIRE(lmax >= 1 && lmax <= 1024 && lcur >= 1 && lcur <= lmax && l1 >= 1 && l2 >= 1 && nq <= 0x7fffffffLL,
+                "bad multi-index shape");
     static bool configured = false;
     if (!configured) {
         // (up to 8192 keys + 1026 ints + 1024 counts; the kernel also has a few static words)
@@ -339,8 +346,14 @@ int launch_imi_cells(const int32_t *sel1_dev, const float *dist1_dev, int k1, in
                                         96 * 1024));
         configured = true;
     }
+    const int64_t nc = imi_candidates(l1, l2, lcur);
+    int npad = 2;
+    while (npad < nc) npad <<= 1;
+    const size_t lds = (size_t)npad * 8 + (size_t)((l1 + 2) & ~1) * 4 + (size_t)lcur * 8;
+    PSC_REQUIRE(lds <= 96 * 1024, "too many candidate cells");
     hipLaunchKernelGGL(imi_cells_kernel, dim3((unsigned)nq), dim3(256), lds, s, sel1_dev, dist1_dev, k1, l1, sel2_dev,
-                       dist2_dev, k2, l2, lmax, max_codes, offsets_dev, npad, cells_dev, ncells_dev, status_dev);
+                       dist2_dev, k2, l2, lmax, lcur, only_marked ? 1 : 0, max_codes, offsets_dev, npad, cells_dev,
+                       ncells_dev, status_dev);
     PSC_HIP_TRY(hipGetLastError());
     return PSC_OK;
 }

@@ -145,12 +145,13 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v)
 template <int KPL>
 __global__ void __launch_bounds__(256)
 select_probes_wave_kernel(const float *__restrict__ dist, int64_t n, int nlist, int nprobe,
-                          int32_t *__restrict__ probed)
+                          const int32_t *__restrict__ settled, int32_t *__restrict__ probed)
 {
     extern __shared__ __align__(16) uint64_t sel[];  // [4][nprobe]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t r = (int64_t)blockIdx.x * 4 + wave;
     if (r >= n) return;
+    if (settled && settled[r] >= 0) return;  // (the waves of a workgroup meet at no barrier)
     uint64_t *mine = sel + (size_t)wave * nprobe;
     uint32_t dk[KPL];
 #pragma unroll
@@ -201,13 +202,15 @@ select_probes_wave_kernel(const float *__restrict__ dist, int64_t n, int nlist, 
 // its rank.
 template <int KPL>
 __global__ void __launch_bounds__(1024)
-select_probes_block_kernel(const float *__restrict__ dist, int nlist, int nprobe, int32_t *__restrict__ probed)
+select_probes_block_kernel(const float *__restrict__ dist, int nlist, int nprobe, const int32_t *__restrict__ settled,
+                           int32_t *__restrict__ probed)
 {
     __shared__ uint32_t part[2][16];
     __shared__ uint64_t sel[1024];
     __shared__ uint32_t nsel;
     const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t r = blockIdx.x;
+    if (settled && settled[r] >= 0) return;  // (the whole workgroup: one row)
     uint32_t dk[KPL];
 #pragma unroll
     for (int i = 0; i < KPL; ++i) {
@@ -269,11 +272,13 @@ select_probes_block_kernel(const float *__restrict__ dist, int nlist, int nprobe
 // More than 4096 lists.  One workgroup per row: nprobe times take the smallest remaining
 // (distance, list) key.
 __global__ void __launch_bounds__(256)
-select_probes_kernel(const float *__restrict__ dist, int nlist, int nprobe, int32_t *__restrict__ probed)
+select_probes_kernel(const float *__restrict__ dist, int nlist, int nprobe, const int32_t *__restrict__ settled,
+                     int32_t *__restrict__ probed)
 {
     extern __shared__ __align__(16) uint64_t keys[];  // [nlist]
     __shared__ uint64_t wave_best[4];
     const int64_t r = blockIdx.x;
+    if (settled && settled[r] >= 0) return;  // (the whole workgroup: one row)
     for (int c = threadIdx.x; c < nlist; c += 256) keys[c] = order_key(dist[r * nlist + c], (uint32_t)c);
     __syncthreads();
     for (int p = 0; p < nprobe; ++p) {
@@ -753,8 +758,8 @@ int launch_coarse_distances(const float *x_dev, int64_t n, int dim, const float 
     return PSC_OK;
 }
 
-int launch_select_probes(const float *dist_dev, int64_t n, int nlist, int nprobe, int32_t *probed_dev,
-                         hipStream_t s)
+int launch_select_probes(const float *dist_dev, int64_t n, int nlist, int nprobe, const int32_t *settled_dev,
+                         int32_t *probed_dev, hipStream_t s)
 {
     PSC_REQUIRE(nprobe >= 1 && nprobe <= nlist && nlist <= 16384, "bad nprobe/nlist");
     if (n == 0) return PSC_OK;
@@ -768,10 +773,10 @@ int launch_select_probes(const float *dist_dev, int64_t n, int nlist, int nprobe
     if (n <= kFewRowsMax) {  // a workgroup per row: the latency of a single query
         if (nlist <= 4096)
             hipLaunchKernelGGL(select_probes_block_kernel<4>, dim3((unsigned)n), dim3(1024), 0, s, dist_dev, nlist,
-                               nprobe, probed_dev);
+                               nprobe, settled_dev, probed_dev);
         else
             hipLaunchKernelGGL(select_probes_block_kernel<16>, dim3((unsigned)n), dim3(1024), 0, s, dist_dev, nlist,
-                               nprobe, probed_dev);
+                               nprobe, settled_dev, probed_dev);
         PSC_HIP_TRY(hipGetLastError());
         return PSC_OK;
     }
@@ -779,13 +784,13 @@ int launch_select_probes(const float *dist_dev, int64_t n, int nlist, int nprobe
     const size_t wlds = (size_t)4 * nprobe * sizeof(uint64_t);
     if (nlist <= 1024)
         hipLaunchKernelGGL(select_probes_wave_kernel<16>, wgrid, dim3(256), wlds, s, dist_dev, n, nlist, nprobe,
-                           probed_dev);
+                           settled_dev, probed_dev);
     else if (nlist <= 4096)
         hipLaunchKernelGGL(select_probes_wave_kernel<64>, wgrid, dim3(256), wlds, s, dist_dev, n, nlist, nprobe,
-                           probed_dev);
+                           settled_dev, probed_dev);
     else
         hipLaunchKernelGGL(select_probes_kernel, dim3((unsigned)n), dim3(256), (size_t)nlist * sizeof(uint64_t), s,
-                           dist_dev, nlist, nprobe, probed_dev);
+                           dist_dev, nlist, nprobe, settled_dev, probed_dev);
     PSC_HIP_TRY(hipGetLastError());
     return PSC_OK;
 }

@@ -107,10 +107,13 @@ def imi_many_cells():
 
 
 @pytest.mark.parametrize("nq,max_lists,max_codes,ht,k", [(25, 16, 0, 24, 10), (40, 1024, 10_000, 26, 100), (7, 300, 500, 64, 50),
-                                                         (1, 1024, 0, 24, 100)])
+                                                         (1, 1024, 0, 24, 100), (60, 200, 60, 26, 10), (60, 1024, 90, 64, 20),
+                                                         (30, 65, 80, 24, 10), (30, 64, 80, 24, 10)])
 def test_imi_with_36000_cells(imi_many_cells, nq, max_lists, max_codes, ht, k):
     """Cells of one or two codes, most of them empty: the regime of a real multi-index (here 36000
-    cells for 50000 vectors), with up to 1024 cells per query and the cap on codes binding."""
+    cells for 50000 vectors), with up to 1024 cells per query and the cap on codes binding.  Caps of
+    60 to 90 codes are reached after about 64 cells: by some queries within the first pass over the
+    cell order, by others only in the full one."""
     _check(imi_many_cells, nq, max_lists, max_codes, ht, k)
 
 
