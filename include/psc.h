@@ -342,9 +342,12 @@ int psc_imi_set_lists(psc_index *idx, const int64_t *offsets_dev, const uint8_t 
  * filtered (Hamming <= ht) and scored as in psc_scan; one ranking by (distance, id) over all cells
  * taken.  cells_out_dev (may be NULL) [nq][max_lists] int32 receives the cells taken, in order,
  * padded with -1; qcodes_out_dev (may be NULL) [nq][max_lists][m] the bit strings of those cells.
- * One workgroup serves one query from its first cell to its last (cells of a multi-index hold a
- * handful of codes each and queries rarely share one), so a single query and a batch take the same
- * path.  The tables are put together per cell from the query's share, the two half-centroids'
+ * Cells of a multi-index hold a handful of codes each and queries rarely share one, so nothing is
+ * grouped by cell: in a batch one workgroup serves one query from its first cell to its last; up
+ * to 256 queries have their cells dealt out to several workgroups each (32 for a single query),
+ * whose lists are merged.  The order of the cells is found in passes over the first 64, 256 and
+ * max_lists cells; a pass settles the queries whose cap on codes is reached within its cells.
+ * The tables are put together per cell from the query's share, the two half-centroids'
  * shares (k1 + k2 half tables, part of the index's device image as for psc_ivf_search) and
  * ||(q - cell centroid)_j||^2, or by direct differences under the rule stated at psc_ivf_search
  * (psc_last_scan_route then starts with "imi_scan_kernel+direct-tables"). */

@@ -1319,8 +1319,17 @@ namespace {
 struct ImiLayout {
     int l1, l2;
     bool direct;
-    size_t off_h1, off_h2, off_d1, off_d2, off_s1, off_s2, off_cells, off_ncells, off_lut, total;
+    size_t off_h1, off_h2, off_d1, off_d2, off_s1, off_s2, off_cells, off_ncells, off_lut, off_part_d, off_part_i, total;
+    int split;  // workgroups per query in the scan over the cells
 };
+
+// A handful of queries leave most compute units idle with one workgroup each: their cells are dealt
+// out to up to 32 workgroups per query (about 512 in all), whose lists are merged.
+int imi_split(int64_t nq, int max_lists)
+{
+    if (nq > 256 || nq < 1) return 1;
+    return (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(32, max_lists), 512 / nq));
+}
 
 int imi_layout(const psc_index *idx, int64_t nq, int max_lists, ImiLayout *L)
 {
@@ -1345,6 +1354,12 @@ int imi_layout(const psc_index *idx, int64_t nq, int max_lists, ImiLayout *L)
     L->off_cells = take((size_t)nq * max_lists * sizeof(int32_t));
     L->off_ncells = take((size_t)nq * sizeof(int32_t));
     L->off_lut = take((size_t)nq * idx->m * kCentroids * sizeof(float));
+    L->split = imi_split(nq, max_lists);
+    L->off_part_d = L->off_part_i = 0;
+    if (L->split > 1) {  // (sized for the largest k, which the workspace query does not know)
+        L->off_part_d = take((size_t)nq * L->split * PSC_MAX_K * sizeof(float));
+        L->off_part_i = take((size_t)nq * L->split * PSC_MAX_K * sizeof(int64_t));
+    }
     L->total = o;
     return PSC_OK;
 }
@@ -1423,7 +1438,8 @@ int psc_imi_search(const psc_index *idx, const float *q_dev, int64_t nq, int max
     }
     return launch_imi_scan(idx->m, lut, tab1, tab2, idx->cb_dev, q_dev, im.c1, im.c2, idx->dim, idx->imi_k2, cells,
                            ncells, max_lists, idx->imi_off_dev, idx->imi_codes_dev, idx->imi_ids_dev, ht, k, L.direct,
-                           nq, qcodes_out_dev, ids_dev, dists_dev, s);
+                           nq, qcodes_out_dev, ids_dev, dists_dev, L.split, (float *)(w + L.off_part_d),
+                           (int64_t *)(w + L.off_part_i), (const int *)workspace_dev, s);
 }
 
 int psc_workspace_status(void *workspace_dev, psc_stream stream)

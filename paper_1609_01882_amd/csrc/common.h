@@ -103,6 +103,11 @@ struct ScanPlan {
 // kind: which scan the plan is for (the shapes differ)
 enum { kScanFused = 0, kScanDense = 1, kScanLists = 2, kScanDenseFiltered = 3, kScanFusedMfma = 4 };
 int plan_scan(int m, int64_t nq, int64_t n, int k, int kind, ScanPlan *plan);
+// Per query, the k best by (distance, id) of its nlists partial lists part_d / part_i [nq][nlists][k]
+// (each ascending, padded with +infinity / -1) -> ids / dists [nq][k].  status: the workspace's flag
+// (a scan that gave up on a wait poisons the results).
+int merge_partial_lists(const float *part_d, const int64_t *part_i, int64_t nq, int nlists, int k, const int *status,
+                        int64_t *ids, float *dists, hipStream_t s);
 // Words per query of the thresholds the lists of one query share, given how many lists (database
 // slices, probed inverted lists) a query has.
 int shared_threshold_words(int64_t lists_per_query);
@@ -184,12 +189,15 @@ int launch_imi_cells(const int32_t *sel1_dev, const float *dist1_dev, int k1, in
                      const float *dist2_dev, int k2, int l2, int lmax, int lcur, bool only_marked, int64_t max_codes,
                      const int64_t *offsets_dev, int64_t nq, int32_t *cells_dev, int32_t *ncells_dev, int *status_dev,
                      hipStream_t s);
-// One workgroup per query over its cells: residual tables, bit strings, filter, ADC, best k.
+// `split` workgroups per query (workgroup s over the query's cells s, s + split, ...): residual
+// tables, bit strings, filter, ADC, best k; split > 1: each writes a partial list (part_* [nq][split][k])
+// and the lists are merged.
 int launch_imi_scan(int m, const float *lut_dev, const float *tab1_dev, const float *tab2_dev, const float *cb_dev,
                     const float *queries_dev, const float *c1_dev, const float *c2_dev, int dim, int k2,
                     const int32_t *cells_dev, const int32_t *ncells_dev, int lmax, const int64_t *offsets_dev,
                     const uint8_t *codes_dev, const int32_t *ext_ids_dev, int ht, int k, bool direct, int64_t nq,
-                    uint8_t *qcodes_out_dev, int64_t *ids_dev, float *dists_dev, hipStream_t s);
+                    uint8_t *qcodes_out_dev, int64_t *ids_dev, float *dists_dev, int split, float *part_d_dev,
+                    int64_t *part_i_dev, const int *status_dev, hipStream_t s);
 
 // ---- k-means on the device (kernels_train.hip)
 // One Lloyd step of all m sub-quantizers: per row and sub-quantizer the nearest centroid

@@ -167,9 +167,12 @@ struct ImiScanArgs {
     const uint8_t *codes;    // [n][M]
     const int32_t *ext_ids;  // [n]
     uint8_t *qcodes_out;     // [nq][lmax][M] or null
-    int64_t *ids;            // [nq][k]
+    int64_t *ids;            // [nq][k]            (split == 1)
     float *dists;            // [nq][k]
+    int64_t *part_i;         // [nq][split][k]     (split > 1: one list per workgroup, merged afterwards)
+    float *part_d;           // [nq][split][k]
     int dim, k2, lmax, ht, k, cap, direct;
+    int split;               // workgroups per query: workgroup s of a query takes its cells s, s + split, ...
 };
 
 // Dynamic LDS: [M][256] query share, [M][256] cell table, dim floats (residual), M floats, M
@@ -188,7 +191,8 @@ imi_scan_kernel(ImiScanArgs a)
     __shared__ int count_s;
     __shared__ uint32_t qcw[M / 4];
     __shared__ float thr_s;
-    const int64_t q = blockIdx.x;
+    const int64_t q = blockIdx.x / a.split;
+    const int sub = (int)(blockIdx.x - q * a.split);
     const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = a.dim / 2, dsub = a.dim / M;
     constexpr int WPC = M / 4;
@@ -203,7 +207,7 @@ imi_scan_kernel(ImiScanArgs a)
     }
     __syncthreads();
     const int ncell = a.ncells[q];
-    for (int p = 0; p < ncell; ++p) {
+    for (int p = sub; p < ncell; p += a.split) {
         const int cell = a.cells[q * a.lmax + p];
         const int ca = cell / a.k2, cb_ = cell - ca * a.k2;
         const int64_t begin = a.offsets[cell], end = a.offsets[cell + 1];
@@ -294,10 +298,12 @@ imi_scan_kernel(ImiScanArgs a)
     }
     bitonic_sort(pool, a.cap);
     const int found = count_s < a.k ? count_s : a.k;
+    int64_t *ids = a.split > 1 ? a.part_i + (q * a.split + sub) * a.k : a.ids + q * a.k;
+    float *dists = a.split > 1 ? a.part_d + (q * a.split + sub) * a.k : a.dists + q * a.k;
     for (int r = tid; r < a.k; r += 256) {
         const unsigned long long key = pool[r];
-        a.ids[q * a.k + r] = r < found ? (int64_t)(int32_t)(uint32_t)key : -1;
-        a.dists[q * a.k + r] = r < found ? fkey_value((uint32_t)(key >> 32)) : __builtin_inff();
+        ids[r] = r < found ? (int64_t)(int32_t)(uint32_t)key : -1;
+        dists[r] = r < found ? fkey_value((uint32_t)(key >> 32)) : __builtin_inff();
     }
 }
 
@@ -362,10 +368,12 @@ int launch_imi_scan(int m, const float *lut_dev, const float *tab1_dev, const fl
                     const float *queries_dev, const float *c1_dev, const float *c2_dev, int dim, int k2,
                     const int32_t *cells_dev, const int32_t *ncells_dev, int lmax, const int64_t *offsets_dev,
                     const uint8_t *codes_dev, const int32_t *ext_ids_dev, int ht, int k, bool direct, int64_t nq,
-                    uint8_t *qcodes_out_dev, int64_t *ids_dev, float *dists_dev, hipStream_t s)
+                    uint8_t *qcodes_out_dev, int64_t *ids_dev, float *dists_dev, int split, float *part_d_dev,
+                    int64_t *part_i_dev, const int *status_dev, hipStream_t s)
 {
     if (nq == 0) return PSC_OK;
-    PSC_REQUIRE(nq <= 0x7fffffffLL, "too many queries");
+    PSC_REQUIRE(split >= 1 && nq * split <= 0x7fffffffLL, "too many queries");
+    PSC_REQUIRE(split == 1 || (part_d_dev && part_i_dev && status_dev), "no room for the partial lists");
     PSC_REQUIRE(((uintptr_t)codes_dev & 15) == 0 && ((uintptr_t)lut_dev & 15) == 0, "codes and tables must be 16-byte aligned");
     ImiScanArgs a;
     a.lut = lut_dev;
@@ -383,6 +391,9 @@ int launch_imi_scan(int m, const float *lut_dev, const float *tab1_dev, const fl
     a.qcodes_out = qcodes_out_dev;
     a.ids = ids_dev;
     a.dists = dists_dev;
+    a.part_i = part_i_dev;
+    a.part_d = part_d_dev;
+    a.split = split;
     a.dim = dim;
     a.k2 = k2;
     a.lmax = lmax;
@@ -396,7 +407,7 @@ int launch_imi_scan(int m, const float *lut_dev, const float *tab1_dev, const fl
     const size_t lds = (size_t)2 * m * 256 * 4 + (size_t)dim * 4 + (size_t)((m + 1) & ~1) * 4 + (size_t)4 * m * 8 + (size_t)cap * 8;
     PSC_REQUIRE(lds <= 96 * 1024, "dimension and k too large for the multi-index scan");
     if (m == 8) {
-        hipLaunchKernelGGL(imi_scan_kernel<8>, dim3((unsigned)nq), dim3(256), lds, s, a);
+        hipLaunchKernelGGL(imi_scan_kernel<8>, dim3((unsigned)(nq * split)), dim3(256), lds, s, a);
     } else {
         static bool configured = false;
         if (!configured) {
@@ -404,13 +415,14 @@ int launch_imi_scan(int m, const float *lut_dev, const float *tab1_dev, const fl
                                             96 * 1024));
             configured = true;
         }
-        hipLaunchKernelGGL(imi_scan_kernel<16>, dim3((unsigned)nq), dim3(256), lds, s, a);
+        hipLaunchKernelGGL(imi_scan_kernel<16>, dim3((unsigned)(nq * split)), dim3(256), lds, s, a);
     }
     PSC_HIP_TRY(hipGetLastError());
     char text[96];
-    snprintf(text, sizeof text, "imi_scan_kernel%s m=%d cells<=%d pool=%d queries=%lld", direct ? "+direct-tables" : "", m, lmax,
-             cap, (long long)nq);
+    snprintf(text, sizeof text, "imi_scan_kernel%s m=%d cells<=%d pool=%d queries=%lld x%d", direct ? "+direct-tables" : "", m,
+             lmax, cap, (long long)nq, split);
     note_scan_route(text);
+    if (split > 1) return merge_partial_lists(part_d_dev, part_i_dev, nq, split, k, status_dev, ids_dev, dists_dev, s);
     return PSC_OK;
 }
 

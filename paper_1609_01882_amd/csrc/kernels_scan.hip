@@ -2235,6 +2235,12 @@ int plan_scan(int m, int64_t nq, int64_t n, int k, int kind, ScanPlan *plan)
     return PSC_OK;
 }
 
+int merge_partial_lists(const float *part_d, const int64_t *part_i, int64_t nq, int nlists, int k, const int *status,
+                        int64_t *ids, float *dists, hipStream_t s)
+{
+    return launch_merge(part_d, part_i, nq, nlists, k, status, ids, dists, s);
+}
+
 int shared_threshold_words(int64_t lists_per_query)
 {
     return lists_per_query >= kManySlices ? (int)std::min<int64_t>(lists_per_query, 64) : 1;
