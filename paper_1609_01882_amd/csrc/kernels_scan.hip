@@ -1683,11 +1683,29 @@ merge_select_kernel(const float *__restrict__ part_d, const int64_t *__restrict_
                     const int *__restrict__ status, int64_t *__restrict__ ids, float *__restrict__ dists)
 {
     __shared__ uint32_t part[2][16];
-    __shared__ uint32_t selk[1024];
+    __shared__ __align__(16) uint32_t selk[1024];
     __shared__ int64_t seli[1024];
     __shared__ uint32_t nsel;
     const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t q = blockIdx.x;
+    // Rank of (key, id) among the n selected entries in LDS: keys are compared four to a read; the
+    // ids are looked at only by a thread whose key occurs more than once.
+    auto rank_among = [&](uint32_t key, int64_t id, int n) {
+        int lt = 0, eq = 0;
+        const int n4 = n & ~3;
+        for (int j = 0; j < n4; j += 4) {
+            const uint4 v = *(const uint4 *)&selk[j];
+            lt += (v.x < key ? 1 : 0) + (v.y < key ? 1 : 0) + (v.z < key ? 1 : 0) + (v.w < key ? 1 : 0);
+            eq += (v.x == key ? 1 : 0) + (v.y == key ? 1 : 0) + (v.z == key ? 1 : 0) + (v.w == key ? 1 : 0);
+        }
+        for (int j = n4; j < n; ++j) {
+            lt += selk[j] < key ? 1 : 0;
+            eq += selk[j] == key ? 1 : 0;
+        }
+        if (eq > 1)
+            for (int j = 0; j < n; ++j) lt += (selk[j] == key && seli[j] < id) ? 1 : 0;
+        return lt;
+    };
     const int total = nslice * k;
     const float *pd = part_d + q * total;
     const int64_t *pi = part_i + q * total;
@@ -1730,39 +1748,52 @@ merge_select_kernel(const float *__restrict__ part_d, const int64_t *__restrict_
         turn ^= 1;
         return all;
     };
-    // A bound on the k-th smallest key from one row of the (sorted) lists: if t lists have their
-    // r-th entry at or below v, at least t (r + 1) entries lie at or below v; with r the first row for
-    // which nslice (r + 1) >= k and t = ceil(k / (r + 1)), the t-th smallest key of row r bounds the
-    // k-th smallest of all.  With hundreds of lists that leaves a few hundred entries of tens of
-    // thousands, which are ranked directly instead of being searched bit by bit (three barriers
-    // instead of forty).  Every wave finds the bound for itself from the row in LDS.
-    __shared__ uint32_t rowk[1024];
-    __shared__ uint32_t bound_s;
-    const int row = (k + nslice - 1) / nslice - 1;  // (nslice <= 1024, so the row has at most 1024 keys)
-    if (tid < nslice) {
-        const float v = pd[(int64_t)tid * k + row];
-        rowk[tid] = v != __builtin_inff() ? min(dist_key(v), kNone - 1u) : kNone;
-    }
-    __syncthreads();
-    if (wave == 0) {  // (one wave: sixteen doing the same search would only take issue slots from each other)
-        uint32_t b0 = 0;  // the t-th smallest key of the row (kNone when the row has fewer than t entries)
-        const uint32_t t = (uint32_t)((k + row) / (row + 1));
-        uint32_t rk[16];  // the row, 16 keys to a lane
+    // A bound on the k-th smallest key from single rows of the (sorted) lists: if t lists have their
+    // r-th entry at or below v, at least t (r + 1) entries lie at or below v, so for any t <= nslice
+    // the t-th smallest key of row ceil(k / t) - 1 bounds the k-th smallest of all.  Lists of equal
+    // quality (the slices of a flat scan) make the widest t the sharpest -- with 256 lists the 100th
+    // smallest head --, lists of unequal quality (the probed lists of an inverted file: the
+    // nearest few hold nearly all of the answer) a small t on a deep row; wave w tries t = T >> w, T
+    // the widest, down to t = 1, and the smallest of their values is taken.  That usually leaves a
+    // few hundred entries of tens of thousands, which are ranked directly instead of being searched
+    // bit by bit (three barriers instead of forty).
+    __shared__ uint32_t bounds_s[16];
+    {
+        const int row0 = (k + nslice - 1) / nslice - 1;
+        const uint32_t t_widest = (uint32_t)((k + row0) / (row0 + 1));  // (<= nslice)
+        const uint32_t t = max(t_widest >> wave, 1u);
+        const bool active = wave == 0 || (t_widest >> (wave - 1)) > 1u;  // (t = 1 is tried once)
+        uint32_t b0 = kNone;
+        if (active) {
+            const int row = (k + (int)t - 1) / (int)t - 1;  // t (row + 1) >= k, row <= k - 1
+            uint32_t rk[16];  // the row, 16 keys to a lane (nslice <= 1024)
+            const int nreg = (nslice + 63) >> 6;  // (wave-uniform)
+            {
+                float rv[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) rk[i] = i * 64 + lane < nslice ? rowk[i * 64 + lane] : kNone;
-        const int nreg = (nslice + 63) >> 6;  // (wave-uniform)
-        for (int b = 31; b >= 0; --b) {
-            const uint32_t mid = b0 | (1u << b);
-            uint32_t cnt = 0;
+                for (int i = 0; i < 16; ++i) {
+                    const int l = i * 64 + lane;
+                    rv[i] = (i < nreg && l < nslice) ? pd[(int64_t)l * k + row] : __builtin_inff();
+                }
 #pragma unroll
-            for (int i = 0; i < 16; ++i)
-                if (i < nreg) cnt += rk[i] < mid ? 1u : 0u;
-            if (wave_sum_u32(cnt) < t) b0 = mid;
+                for (int i = 0; i < 16; ++i) rk[i] = rv[i] != __builtin_inff() ? min(dist_key(rv[i]), kNone - 1u) : kNone;
+            }
+            b0 = 0;  // the t-th smallest key of the row (kNone when the row has fewer than t entries)
+            for (int b = 31; b >= 0; --b) {
+                const uint32_t mid = b0 | (1u << b);
+                uint32_t cnt = 0;
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    if (i < nreg) cnt += rk[i] < mid ? 1u : 0u;
+                if (wave_sum_u32(cnt) < t) b0 = mid;
+            }
         }
-        if (lane == 0) bound_s = b0;
+        if (lane == 0) bounds_s[wave] = b0;
     }
     __syncthreads();
-    const uint32_t bound = bound_s;
+    uint32_t bound = bounds_s[0];
+#pragma unroll
+    for (int w = 1; w < 16; ++w) bound = min(bound, bounds_s[w]);
     // entries that exist (low half) and entries at or below the bound (high half), in one count
     // (at most 32768 entries: each half fits 16 bits)
     const uint32_t both = count([&](int i) { return dk[i] != kNone; }, [&](int i) { return bound != kNone && dk[i] <= bound; });
@@ -1782,8 +1813,7 @@ merge_select_kernel(const float *__restrict__ part_d, const int64_t *__restrict_
         if (tid < (int)near) {
             const uint32_t key = selk[tid];
             const int64_t id = seli[tid];
-            int rank = 0;
-            for (int j = 0; j < (int)near; ++j) rank += (selk[j] < key || (selk[j] == key && seli[j] < id)) ? 1 : 0;
+            const int rank = rank_among(key, id, (int)near);
             if (rank < (int)kk) {
                 ids[q * k + rank] = poisoned ? (int64_t)-2 : id;
                 dists[q * k + rank] = key_dist(key);
@@ -1832,8 +1862,7 @@ merge_select_kernel(const float *__restrict__ part_d, const int64_t *__restrict_
     if (tid < (int)kk) {
         const uint32_t key = selk[tid];
         const int64_t id = seli[tid];
-        int rank = 0;
-        for (int j = 0; j < (int)kk; ++j) rank += (selk[j] < key || (selk[j] == key && seli[j] < id)) ? 1 : 0;
+        const int rank = rank_among(key, id, (int)kk);
         ids[q * k + rank] = poisoned ? (int64_t)-2 : id;
         dists[q * k + rank] = key_dist(key);
     } else if (tid < k) {
