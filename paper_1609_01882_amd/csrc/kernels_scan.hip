@@ -1421,9 +1421,11 @@ scan_mfma_kernel(ScanArgs a)
 // lut4[g][j][c] = (T_{4g}[j][c], .., T_{4g+3}[j][c]): one 16-byte read serves four queries of
 // the tile, and a code's m byte offsets are computed once for all TQ queries.
 // Same tiling (query tile x database slice), lists, ordering and outputs as scan_kernel.
-// FILTER: the Hamming test of Section 3.3 is still applied, as one more condition on every pair.
-// This is the cheaper route when the threshold lets a large share of the codes through: scoring
-// everything from the interleaved tables then costs less than queueing the survivors one by one.
+// FILTER: the Hamming test of Section 3.3 is still applied -- to the pairs whose distance beats the
+// current k-th best, which are few; since that k-th best is taken among pairs that pass the test,
+// the outcome is the one of testing every pair first.  This is the cheaper route when the
+// threshold lets a large share of the codes through: scoring everything from the interleaved
+// tables then costs less than queueing the survivors one by one.
 // ---------------------------------------------------------------------------------------------
 template <int M, int TQ, int NW, bool SHARE, bool FILTER>
 __global__ void __launch_bounds__(NW * 64)
@@ -1526,21 +1528,27 @@ adc_kernel(ScanArgs a)
                     const int q = g * 4 + i;
                     const float thr = bcast_f(thr_v, q);
                     pass[i] = live && q < nvq && d[i] <= thr;
-                    if constexpr (FILTER) {  // bias + h overflows into the sign bit iff h > ht
-                        uint32_t acc = a.bias;
-#pragma unroll
-                        for (int ww = 0; ww < WPC; ++ww) acc += (uint32_t)__popc(w[c * WPC + ww] ^ qw[q][ww]);
-                        pass[i] = pass[i] && (int32_t)acc >= 0;
-                    }
                     if (skipping) pass[i] = pass[i] && rel != (uint32_t)((int32_t)skip_rel + q);
                     any |= ballot64(pass[i]);
                 }
                 if (any) {
-                    ask.wanted = true;
+                    // FILTER: the Hamming test is taken only here, on the few pairs whose distance
+                    // beats the threshold (which is the k-th best among the pairs that pass the test:
+                    // the result is that of testing every pair), not on every pair of the stream.
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
+                        if constexpr (FILTER) {  // bias + h overflows into the sign bit iff h > ht
+                            const int q = g * 4 + i;
+                            uint32_t acc = a.bias;
+#pragma unroll
+                            for (int ww = 0; ww < WPC; ++ww) acc += (uint32_t)__popc(w[c * WPC + ww] ^ qw[q][ww]);
+                            pass[i] = pass[i] && (int32_t)acc >= 0;
+                        }
                         const uint64_t mine = ballot64(pass[i]);
-                        if (mine) insert_candidates<M, TQ, SHARE, SHARE>(s, a, g * 4 + i, mine, d[i], rel);
+                        if (mine) {
+                            ask.wanted = true;
+                            insert_candidates<M, TQ, SHARE, SHARE>(s, a, g * 4 + i, mine, d[i], rel);
+                        }
                     }
                 }
             }
@@ -2131,8 +2139,8 @@ void note_scan_route(const char *text) { snprintf(g_route, sizeof g_route, "%s",
 //    which keeps a one-pass scan of few queries bound by memory bandwidth;
 //  * grouped inverted-file jobs: 4 x 8, three workgroups per compute unit (tiles are short, so
 //    their set-up and tail overlap better: 12.4 -> 9.3 ms on the 100M workload);
-//  * dense route with the Hamming test: 8 x 8 as well (103 -> 91 ms at ht=32); without it the
-//    16-wave shapes are ahead (70 against 76 ms), as they are for 128-bit codes.
+//  * dense route, with or without the Hamming test: the 16-wave shapes (70 against 76 ms for
+//    8 x 8 at 64 bits).
 int plan_scan(int m, int64_t nq, int64_t n, int k, int kind, ScanPlan *plan)
 {
     if (m != 8 && m != 16) {
@@ -2164,7 +2172,7 @@ int plan_scan(int m, int64_t nq, int64_t n, int k, int kind, ScanPlan *plan)
         options[nopt++] = Shape{16, 16, kLdsBudget};
     } else {
         if (m == 8 && kind == kScanLists) options[nopt++] = Shape{4, 8, kLdsBudget / 2};
-        if (m == 8 && (kind == kScanFused || kind == kScanDenseFiltered) && nq > 16)
+        if (m == 8 && kind == kScanFused && nq > 16)
             options[nopt++] = Shape{8, 8, kLdsBudget / 2};
         if (m == 8 && kind != kScanLists) options[nopt++] = Shape{16, 16, kLdsBudget};
         if (kind != kScanLists || m == 16) options[nopt++] = Shape{8, 16, kLdsBudget};
@@ -2307,9 +2315,11 @@ int launch_scan(int m, const float *lut_dev, const uint8_t *qcodes_dev, int64_t 
                 hipStream_t s)
 {
     PSC_REQUIRE(ht >= 0, "ht must be >= 0, got %d", ht);
-    // survivor share from which scoring every pair is the faster route (measured at 10M x 10k:
-    // 64-bit codes cross between ht = 30 and 31, 128-bit codes between ht = 61 and 62)
-    const double dense_from = 0.36;
+    // survivor share from which scoring every pair is the faster route: the dense kernel takes the
+    // same time whatever the threshold (it tests only the pairs that beat the k-th best), the fused
+    // one grows with the survivors (measured at 10M x 10k random codes, fused / dense: 64-bit codes
+    // ht = 29: 67.8 / 68.5 ms, ht = 30: 83.1 / 68.6; 128-bit codes ht = 60: 112 / 135, ht = 62: 152 / 135)
+    const double dense_from = 0.34;
     const bool dense = ht >= 8 * m || random_code_survival(8 * m, ht) >= dense_from;
     ScanPlan p;
     int rc = PSC_EINVAL;
