@@ -64,6 +64,33 @@ def test_flat_full_size(name, hts):
         assert all(len(set(r[r >= 0].tolist())) == (r >= 0).sum() for r in ids_h[::97])
 
 
+def test_few_queries_over_400M_codes():
+    """The memory-bound launches bench.py times (`small_batch`): 1 and 16 queries over 400M random
+    64-bit codes, ht = 20, k = 100 -- 256 database slices per query, which prune with what they
+    tell each other.  The oracle re-does the single query and three of the sixteen."""
+    import paper_1609_01882_amd as psc
+    n, m, k, ht = 400_000_000, 8, 100, 20
+    g = torch.Generator(device="cuda")
+    g.manual_seed(11)
+    codes = torch.randint(0, 2 ** 31, (n * m // 4,), dtype=torch.int32, device="cuda", generator=g).view(torch.uint8).view(n, m)
+    codes_h = codes.cpu().numpy()
+    for nq, sample in ((1, [0]), (16, [0, 7, 15])):
+        # queries near stored codes, so that the threshold lets a few thousand codes through
+        rows = torch.randint(0, n, (nq,), device="cuda", generator=g)
+        qc = codes[rows].clone()
+        qc[:, 0] ^= 0x55
+        lut = torch.rand((nq, m, 256), device="cuda", generator=g) * 1000.0
+        print(f"few queries: nq={nq} over {n} codes", flush=True)
+        ids, d = psc.scan(lut, qc, codes, ht, k)
+        torch.cuda.synchronize()
+        assert "slices=256" in psc.last_scan_route(), psc.last_scan_route()
+        lut64, qc_h = lut.cpu().numpy().astype(np.float64)[sample], qc.cpu().numpy()[sample]
+        ref = O.scan(lut64, qc_h, codes_h, ht, k)
+        assert (ref["nsurv"] > 1000).all()
+        assert_topk_matches(ids.cpu().numpy()[sample], d.cpu().numpy()[sample], ref, lut64, qc_h, codes_h, ht,
+                            what=f"{nq} queries over 400M codes")
+
+
 def test_graph_full_size():
     import paper_1609_01882_amd as psc
     cfg = W.get_config("graph")
