@@ -363,7 +363,7 @@ def bench_ivf(args):
 
     import paper_1609_01882_amd as psc
     import workloads as W
-    from paper_1609_01882_amd.benchmarks._common import build_ivf_workload, time_ms
+    from paper_1609_01882_amd.benchmarks._common import build_ivf_workload, graph_replay_ms, time_ms
 
     dev = torch.device("cuda:0")
     cfg = W.get_config("ivf")
@@ -402,9 +402,11 @@ def bench_ivf(args):
         xs = xq[:nqs].contiguous()
         wss = torch.empty(idx.ivf_search_workspace_bytes(nqs, nprobe, k), dtype=torch.uint8, device=dev)
         outs = (torch.empty((nqs, k), dtype=torch.int64, device=dev), torch.empty((nqs, k), dtype=torch.float32, device=dev))
-        mss = time_ms(lambda: idx.ivf_search(xs, nprobe, ht, k, workspace=wss, out=outs), 20, 3)
+        call = lambda: idx.ivf_search(xs, nprobe, ht, k, workspace=wss, out=outs)  # noqa: E731
+        mss = time_ms(call, 20, 3)
+        msg = graph_replay_ms(call, 20) if nqs <= 16 else None
         small.append({"n_query": nqs, "ms_per_call": round(mss, 4), "us_per_query": round(mss * 1e3 / nqs, 2),
-                      "kernel": psc.last_scan_route()})
+                      "ms_per_graph_replay": None if msg is None else round(msg, 4), "kernel": psc.last_scan_route()})
     res["small_batches"] = small
     if not args.no_cpu:
         import oracle as O
@@ -434,7 +436,7 @@ def bench_imi(args):
 
     import paper_1609_01882_amd as psc
     import workloads as W
-    from paper_1609_01882_amd.benchmarks._common import build_imi_workload, time_ms
+    from paper_1609_01882_amd.benchmarks._common import build_imi_workload, graph_replay_ms, time_ms
 
     dev = torch.device("cuda:0")
     cfg = W.get_config("ivf")
@@ -461,9 +463,12 @@ def bench_imi(args):
         xs = xq[:1].contiguous()
         ws1 = torch.empty(idx.imi_search_workspace_bytes(1, max_lists), dtype=torch.uint8, device=dev)
         out1 = (torch.empty((1, k), dtype=torch.int64, device=dev), torch.empty((1, k), dtype=torch.float32, device=dev))
-        ms1 = time_ms(lambda: idx.imi_search(xs, max_lists, max_codes, ht, k, workspace=ws1, out=out1), 20, 3)
+        call1 = lambda: idx.imi_search(xs, max_lists, max_codes, ht, k, workspace=ws1, out=out1)  # noqa: E731
+        ms1 = time_ms(call1, 20, 3)
+        ms1g = graph_replay_ms(call1, 20)
         row = dict(max_lists=max_lists, max_codes=max_codes, ms_per_batch=round(ms, 3), us_per_query_batch=round(ms * 1e3 / nq, 3),
                    ms_per_batch_without_filter=round(ms_nofilter, 3), ms_single_query=round(ms1, 4),
+                   ms_single_query_graph_replay=None if ms1g is None else round(ms1g, 4),
                    kernel=psc.last_scan_route(),
                    cells_per_query=float((cells >= 0).float().sum(dim=1).mean().item()), codes_per_query=pairs / nq,
                    pairs_per_s=pairs / (ms * 1e-3))

@@ -37,6 +37,24 @@ def trained_index(psc, cfg, train_rows, threads=16):
     return idx
 
 
+def graph_replay_ms(fn, steps, warmup=3):
+    """Mean milliseconds of one replay of fn() recorded into a HIP graph (fn must allocate nothing:
+    workspace and outputs handed in), or None when the recording fails.  The recorded call has run
+    eagerly before, so whatever happens once per process is done."""
+    import torch
+
+    try:
+        fn()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        return time_ms(g.replay, steps, warmup)
+    except Exception as exc:  # noqa: BLE001  (a figure less, not a failed benchmark)
+        log(f"[graph replay] not recorded: {exc}")
+        return None
+
+
 def encode_database(idx, cfg, n, dev, chunk=1_000_000, threads=16):
     """Codes [n][m] of the workload's database stream, generated and encoded chunk by chunk so the
     raw vectors are never resident all at once."""
