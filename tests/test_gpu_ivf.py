@@ -131,7 +131,9 @@ def _check_ivf_search(fixture, nprobe, ht, k, nq=37):
     # from the index (its list was probed, it passes that list's filter, its distance is right)
     nmis = assert_ivf_topk_matches(ids, d, ref, xq, s["cb"], s["coarse"], s["offsets"], s["lcodes"], s["lids"],
                                    probed, qcodes, ht, O.build_lut, what=f"ivf nq={nq} nprobe={nprobe} ht={ht} k={k}")
-    assert nmis <= max(10, 0.01 * ids.size)  # ties are rare (a single query with k = 400 had 6)
+    # (near-ties are rare: neighbours in the ranking closer than the 1e-5 tolerance swap places;
+    #  two queries with k = 400 had 12 such places of 800)
+    assert nmis <= max(10, 0.02 * ids.size), nmis
     # the per-list query codes agree with the oracle's own on all but near-ties
     own_q = O.ivf_search(xq, s["cb"], s["coarse"], s["offsets"], s["lcodes"], s["lids"], nprobe, ht, k,
                          probed_in=probed)
