@@ -17,7 +17,9 @@
 //     with the query's current bound on its k-th best distance;
 //   * the few candidates that pass are spliced into the query's sorted list in LDS by the whole
 //     wave, under a per-query lock (waves of the workgroup share the lists); workgroups of one
-//     query tell each other their k-th best distances through a word in global memory.
+//     query tell each other how far their lists have come through a few words in global memory
+//     (their k-th best distance, or -- a query cut into many slices -- an earlier entry of each
+//     list, from which a bound on the k-th best of all of them follows: ScanArgs::pub_slots).
 // Partial lists (one per query and slice) go to the workspace; a second kernel merges them.
 //
 // Ordering everywhere: (distance, id) ascending, lower id first on equal distance.
@@ -65,7 +67,7 @@ struct ScanArgs {
     // reached so far, as a sortable key (see dist_key).  Nothing farther than it can be in the
     // query's final top-k, so every workgroup of the query prunes with it: the partial lists
     // of one query behave like one stream instead of one warm-up per slice or list.
-    uint32_t *gthr;           // [number of queries]
+    uint32_t *gthr;           // [number of queries][pub_slots] (pub_slots = 1: as described; more: see pub_slots)
     const int32_t *job_q;     // inverted-file mode: query of each job (index into gthr)
     // inverted-file mode (Section 4.3): a tile = up to TQ (query, list) jobs of ONE list, rows
     // job_begin.. of the job-sorted tables / query codes; the scanned range is that list
