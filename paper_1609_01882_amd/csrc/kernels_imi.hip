@@ -41,6 +41,22 @@ __device__ __forceinline__ float fkey_value(uint32_t k)
     return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
 
+// Smallest value of v over the wave, in every lane: four row-local steps on the data-parallel
+// path, then the four row results through scalar registers.
+__device__ __forceinline__ uint32_t wave_min_key(uint32_t v)
+{
+    auto step = [](uint32_t x, uint32_t y) { return y < x ? y : x; };
+    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xB1, 0xf, 0xf, false));   // lane ^ 1
+    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x4E, 0xf, 0xf, false));   // lane ^ 2
+    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x141, 0xf, 0xf, false));  // mirror in 8
+    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x140, 0xf, 0xf, false));  // mirror in 16
+    const uint32_t r0 = (uint32_t)__builtin_amdgcn_readlane((int)v, 0);
+    const uint32_t r1 = (uint32_t)__builtin_amdgcn_readlane((int)v, 16);
+    const uint32_t r2 = (uint32_t)__builtin_amdgcn_readlane((int)v, 32);
+    const uint32_t r3 = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+    return step(step(r0, r1), step(r2, r3));
+}
+
 // Ascending bitonic sort of n (a power of two) 64-bit keys in LDS by the whole workgroup.
 __device__ __forceinline__ void bitonic_sort(unsigned long long *keys, int n)
 {
@@ -241,13 +257,12 @@ imi_scan_kernel(ImiScanArgs a)
                 v = (tq[j * 256 + tid] + th[tid]) + sterm[j];
             }
             cellt[j * 256 + tid] = v;
-            unsigned long long key = ((unsigned long long)fkey(v) << 32) | (unsigned)tid;  // lowest index on ties
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) {
-                const unsigned long long o = __shfl_xor(key, off, 64);
-                key = o < key ? o : key;
-            }
-            if (lane == 0) rowbest[wave * M + j] = key;
+            // the wave's smallest entry, lowest index on ties: minimum of the 32-bit keys on the
+            // data-parallel path, then the first lane that holds it
+            const uint32_t key = fkey(v);
+            const uint32_t wmin = wave_min_key(key);
+            const int first = __builtin_ctzll(__ballot(key == wmin));
+            if (lane == 0) rowbest[wave * M + j] = ((unsigned long long)wmin << 32) | (unsigned)(wave * 64 + first);
         }
         __syncthreads();
         if (tid < M) {
