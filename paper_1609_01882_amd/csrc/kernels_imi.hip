@@ -57,12 +57,39 @@ __device__ __forceinline__ uint32_t wave_min_key(uint32_t v)
     return step(step(r0, r1), step(r2, r3));
 }
 
+// Sum of v over the wave, the same in every lane (the same steps as wave_min_key).
+__device__ __forceinline__ float wave_sum_f32(float v)
+{
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xf, 0xf, false));   // lane ^ 1
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xf, 0xf, false));   // lane ^ 2
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xf, 0xf, false));  // mirror in 8
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xf, 0xf, false));  // mirror in 16
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    return (r0 + r1) + (r2 + r3);
+}
+
 // Ascending bitonic sort of n (a power of two) 64-bit keys in LDS by the whole workgroup.
+// With one pair per thread (n <= 2 * blockDim) wave w only touches keys 128 w .. 128 w + 127 in the
+// steps whose partners lie 64 places or less apart, and LDS serves a wave's accesses in the order
+// they were issued: such steps need no workgroup barrier between them, only the ones around a
+// step that reaches across waves do (3 of the 45 steps of a 512-key sort).
 __device__ __forceinline__ void bitonic_sort(unsigned long long *keys, int n)
 {
+    const bool one_pair = n <= 2 * (int)blockDim.x;  // (uniform)
+    bool across = true;                              // the step before this one reached across waves
     for (int size = 2; size <= n; size <<= 1)
         for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            __syncthreads();
+            const bool wide = !one_pair || stride > 64;
+            if (wide || across) {
+                __syncthreads();
+            } else {
+                __atomic_signal_fence(__ATOMIC_SEQ_CST);
+                __builtin_amdgcn_wave_barrier();
+            }
+            across = wide;
             for (int t = (int)threadIdx.x; t < n / 2; t += (int)blockDim.x) {
                 const int lo = 2 * t - (t & (stride - 1));  // t with a zero inserted at bit `stride`
                 const int hi = lo + stride;
@@ -193,6 +220,12 @@ struct ImiScanArgs {
 
 // Dynamic LDS: [M][256] query share, [M][256] cell table, dim floats (residual), M floats, M
 // (value, index) pairs per wave, cap keys.
+//
+// A cell is short work behind several trips to memory (its bounds, its two half-centroids, its
+// two half tables, its codes), so the trips are taken off the path of the cell they belong to: the
+// bounds of the workgroup's next kWindow cells are staged in LDS at once, and while one cell is
+// worked on every thread already holds, in registers, what it will need of the next one (its
+// element of the residual, its entry of each table row, its code of the first step).
 template <int M>
 __global__ void __launch_bounds__(256)
 imi_scan_kernel(ImiScanArgs a)
@@ -204,14 +237,18 @@ imi_scan_kernel(ImiScanArgs a)
     float *sterm = res + a.dim;
     unsigned long long *rowbest = (unsigned long long *)(sterm + ((M + 1) & ~1));  // [4 waves][M]
     unsigned long long *pool = rowbest + 4 * M;
+    constexpr int kWindow = 32;
     __shared__ int count_s;
     __shared__ uint32_t qcw[M / 4];
     __shared__ float thr_s;
+    __shared__ int win_cell[kWindow];
+    __shared__ long long win_begin[kWindow], win_end[kWindow];
     const int64_t q = blockIdx.x / a.split;
     const int sub = (int)(blockIdx.x - q * a.split);
     const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = a.dim / 2, dsub = a.dim / M;
     constexpr int WPC = M / 4;
+    constexpr int RPW = M / 4;  // table rows per wave: wave w builds rows w * RPW .. and finds their minima alone
 
     if (!a.direct)
         for (int e = tid; e < M * 64; e += 256)
@@ -221,96 +258,170 @@ imi_scan_kernel(ImiScanArgs a)
         count_s = 0;
         thr_s = __builtin_inff();
     }
-    __syncthreads();
     const int ncell = a.ncells[q];
-    for (int p = sub; p < ncell; p += a.split) {
-        const int cell = a.cells[q * a.lmax + p];
+    const int mine = ncell > sub ? (ncell - sub + a.split - 1) / a.split : 0;  // cells sub, sub + split, ...
+    const float qv = tid < a.dim ? a.queries[q * a.dim + tid] : 0.f;           // the thread's element of the query
+
+    // what a thread holds of a cell before the cell's turn
+    struct Inputs {
+        float g;            // its element of the cell centroid (tid < dim)
+        float th[M];        // its entries of the half tables' rows (not direct): rows of its wave, four each
+        uint32_t cw[WPC];   // its code of the cell's first 256
+        int32_t id;         // and that code's id
+    };
+    auto fetch = [&](int w, Inputs &in) {  // w: place in the window
+        const int cell = win_cell[w];
+        in.g = 0.f;
+#pragma unroll
+        for (int jj = 0; jj < M; ++jj) in.th[jj] = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < WPC; ++ww) in.cw[ww] = 0u;
+        in.id = 0;
+        if (cell < 0) return;
         const int ca = cell / a.k2, cb_ = cell - ca * a.k2;
-        const int64_t begin = a.offsets[cell], end = a.offsets[cell + 1];
-        if (begin == end && !a.qcodes_out) continue;  // (uniform over the workgroup)
-        // ---- residual to the cell centroid and its squared norm per sub-quantizer
-        for (int t = tid; t < a.dim; t += 256) {
-            const float g = t < half ? a.c1[(int64_t)ca * half + t] : a.c2[(int64_t)cb_ * half + t - half];
-            res[t] = a.queries[q * a.dim + t] - g;
-        }
-        __syncthreads();
-        if (tid < M) {
-            float s = 0.f;
-            for (int t = tid * dsub; t < (tid + 1) * dsub; ++t) s = fmaf(res[t], res[t], s);
-            sterm[tid] = s;
-        }
-        __syncthreads();
-        // ---- the cell's table, one centroid per thread and row; its row minima = the bit string
+        if (tid < a.dim) in.g = tid < half ? a.c1[(int64_t)ca * half + tid] : a.c2[(int64_t)cb_ * half + tid - half];
+        if (!a.direct) {
 #pragma unroll
-        for (int j = 0; j < M; ++j) {
-            float v;
-            if (a.direct) {
-                const float *cr = a.cb + ((int64_t)j * 256 + tid) * dsub;
-                v = 0.f;
-                for (int t = 0; t < dsub; ++t) {
-                    const float df = res[j * dsub + t] - cr[t];
-                    v = fmaf(df, df, v);
-                }
-            } else {
-                const float *th = j < M / 2 ? a.tab1 + ((int64_t)ca * (M / 2) + j) * 256
-                                            : a.tab2 + ((int64_t)cb_ * (M / 2) + j - M / 2) * 256;
-                v = (tq[j * 256 + tid] + th[tid]) + sterm[j];
+            for (int r = 0; r < RPW; ++r) {
+                const int jj = wave * RPW + r;  // (a wave's rows lie in one half: RPW divides M / 2)
+                const float *row = jj < M / 2 ? a.tab1 + ((int64_t)ca * (M / 2) + jj) * 256
+                                              : a.tab2 + ((int64_t)cb_ * (M / 2) + jj - M / 2) * 256;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) in.th[r * 4 + c] = row[c * 64 + lane];
             }
-            cellt[j * 256 + tid] = v;
-            // the wave's smallest entry, lowest index on ties: minimum of the 32-bit keys on the
-            // data-parallel path, then the first lane that holds it
-            const uint32_t key = fkey(v);
-            const uint32_t wmin = wave_min_key(key);
-            const int first = __builtin_ctzll(__ballot(key == wmin));
-            if (lane == 0) rowbest[wave * M + j] = ((unsigned long long)wmin << 32) | (unsigned)(wave * 64 + first);
         }
-        __syncthreads();
-        if (tid < M) {
-            unsigned long long key = rowbest[tid];
-            for (int w = 1; w < 4; ++w) key = rowbest[w * M + tid] < key ? rowbest[w * M + tid] : key;
-            ((volatile uint8_t *)qcw)[tid] = (uint8_t)(uint32_t)key;
-        }
-        __syncthreads();
-        if (a.qcodes_out && tid < M) a.qcodes_out[(q * a.lmax + p) * M + tid] = ((volatile uint8_t *)qcw)[tid];
-        uint32_t qw[WPC];
+        const long long i = win_begin[w] + tid;
+        if (i < win_end[w]) {
+            const uint32_t *src = (const uint32_t *)(a.codes + i * M);
 #pragma unroll
-        for (int w = 0; w < WPC; ++w) qw[w] = qcw[w];
-        // ---- the cell's codes, 256 at a time
-        for (int64_t i0 = begin; i0 < end; i0 += 256) {
-            const int64_t i = i0 + tid;
-            if (i < end) {
+            for (int ww = 0; ww < WPC; ++ww) in.cw[ww] = src[ww];
+            in.id = a.ext_ids[i];
+        }
+    };
+
+    for (int base = 0; base < mine; base += kWindow) {
+        __syncthreads();  // (the window of the round before is no longer read; first round: the set-up above)
+        if (tid < kWindow) {
+            int cell = -1;
+            long long b = 0, e = 0;
+            if (base + tid < mine) {
+                cell = a.cells[q * a.lmax + sub + (int64_t)(base + tid) * a.split];
+                b = a.offsets[cell];
+                e = a.offsets[cell + 1];
+            }
+            win_cell[tid] = cell;
+            win_begin[tid] = b;
+            win_end[tid] = e;
+        }
+        __syncthreads();
+        const int nwin = mine - base < kWindow ? mine - base : kWindow;
+        Inputs cur, nxt;
+        fetch(0, cur);
+        for (int w = 0; w < nwin; ++w) {
+            const int p = sub + (base + w) * a.split;  // the cell's place in the query's order
+            const long long begin = win_begin[w], end = win_end[w];
+            if (w + 1 < nwin) fetch(w + 1, nxt);
+            if (!(begin == end && !a.qcodes_out)) {  // (uniform over the workgroup)
+                // ---- residual to the cell centroid
+                if (tid < a.dim) res[tid] = qv - cur.g;
+                __syncthreads();
+                // ---- the cell's table: wave w builds rows w * RPW .., four entries of a row per lane;
+                //      the row's minimum (lowest index on ties) is the cell's bit string for that row
+#pragma unroll
+                for (int r = 0; r < RPW; ++r) {
+                    const int jj = wave * RPW + r;
+                    // || (q - cell centroid)_jj ||^2: a coordinate (or a few) per lane, summed over the wave
+                    float part = 0.f;
+                    for (int t = lane; t < dsub; t += 64) part = fmaf(res[jj * dsub + t], res[jj * dsub + t], part);
+                    const float sq = wave_sum_f32(part);
+                    uint32_t best = 0xffffffffu;
+                    int besti = 0;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const int e = c * 64 + lane;
+                        float v;
+                        if (a.direct) {
+                            const float *cr = a.cb + ((int64_t)jj * 256 + e) * dsub;
+                            v = 0.f;
+                            for (int t = 0; t < dsub; ++t) {
+                                const float df = res[jj * dsub + t] - cr[t];
+                                v = fmaf(df, df, v);
+                            }
+                        } else {
+                            v = (tq[jj * 256 + e] + cur.th[r * 4 + c]) + sq;
+                        }
+                        cellt[jj * 256 + e] = v;
+                        const uint32_t key = fkey(v);
+                        if (key < best) {  // (ascending e: the lowest index stays on ties)
+                            best = key;
+                            besti = e;
+                        }
+                    }
+                    // the smallest key of the wave, then the lowest index among the lanes that hold it
+                    const uint32_t wmin = wave_min_key(best);
+                    const uint32_t imin = wave_min_key(best == wmin ? (uint32_t)besti : 0xffffffffu);
+                    if (lane == 0) ((volatile uint8_t *)qcw)[jj] = (uint8_t)imin;
+                }
+                __syncthreads();
+                if (a.qcodes_out && tid < M) a.qcodes_out[(q * a.lmax + p) * M + tid] = ((volatile uint8_t *)qcw)[tid];
+                uint32_t qw[WPC];
+#pragma unroll
+                for (int ww = 0; ww < WPC; ++ww) qw[ww] = qcw[ww];
+                // ---- the cell's codes, 256 at a time (the first 256 are in registers already; every
+                //      step asks for the next one's before it works on its own)
                 uint32_t cw[WPC];
-                const uint32_t *src = (const uint32_t *)(a.codes + i * M);
 #pragma unroll
-                for (int w = 0; w < WPC; ++w) cw[w] = src[w];
-                int h = 0;
+                for (int ww = 0; ww < WPC; ++ww) cw[ww] = cur.cw[ww];
+                int32_t id = cur.id;  // (asked for with the code: a survivor's id is not one more trip to memory)
+                for (long long i0 = begin; i0 < end; i0 += 256) {
+                    const long long i = i0 + tid;
+                    uint32_t nw[WPC];
+                    int32_t nid = 0;
 #pragma unroll
-                for (int w = 0; w < WPC; ++w) h += __builtin_popcount(cw[w] ^ qw[w]);
-                if (h <= a.ht) {
-                    float d = 0.f;
+                    for (int ww = 0; ww < WPC; ++ww) nw[ww] = 0u;
+                    if (i + 256 < end) {
+                        const uint32_t *src = (const uint32_t *)(a.codes + (i + 256) * M);
 #pragma unroll
-                    for (int j = 0; j < M; ++j) d += cellt[j * 256 + ((cw[j >> 2] >> (8 * (j & 3))) & 0xffu)];
-                    if (!(d > thr_s)) {
-                        const int at = atomicAdd(&count_s, 1);
-                        pool[at] = ((unsigned long long)fkey(d) << 32) | (uint32_t)a.ext_ids[i];
+                        for (int ww = 0; ww < WPC; ++ww) nw[ww] = src[ww];
+                        nid = a.ext_ids[i + 256];
+                    }
+                    if (i < end) {
+                        int h = 0;
+#pragma unroll
+                        for (int ww = 0; ww < WPC; ++ww) h += __builtin_popcount(cw[ww] ^ qw[ww]);
+                        if (h <= a.ht) {
+                            float d = 0.f;
+#pragma unroll
+                            for (int jj = 0; jj < M; ++jj) d += cellt[jj * 256 + ((cw[jj >> 2] >> (8 * (jj & 3))) & 0xffu)];
+                            if (!(d > thr_s)) {
+                                const int at = atomicAdd(&count_s, 1);
+                                pool[at] = ((unsigned long long)fkey(d) << 32) | (uint32_t)id;
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int ww = 0; ww < WPC; ++ww) cw[ww] = nw[ww];
+                    id = nid;
+                    __syncthreads();
+                    if (count_s > a.cap - 256) {  // (uniform) no room for another step: keep the best k
+                        bitonic_sort(pool, a.cap);
+                        const int kept = count_s < a.k ? count_s : a.k;
+                        for (int e = kept + tid; e < a.cap; e += 256) pool[e] = ~0ull;
+                        __syncthreads();
+                        if (tid == 0) {
+                            count_s = kept;
+                            if (kept == a.k) thr_s = fkey_value((uint32_t)(pool[a.k - 1] >> 32));
+                        }
+                        __syncthreads();
                     }
                 }
+                // (no barrier here: the next cell writes the residual first, and nothing of this cell is
+                //  read after the barrier that ended its last step -- or, without codes, the one above)
             }
-            __syncthreads();
-            if (count_s > a.cap - 256) {  // (uniform) no room for another step: keep the best k
-                bitonic_sort(pool, a.cap);
-                const int kept = count_s < a.k ? count_s : a.k;
-                for (int e = kept + tid; e < a.cap; e += 256) pool[e] = ~0ull;
-                __syncthreads();
-                if (tid == 0) {
-                    count_s = kept;
-                    if (kept == a.k) thr_s = fkey_value((uint32_t)(pool[a.k - 1] >> 32));
-                }
-                __syncthreads();
-            }
+            cur = nxt;
         }
-        __syncthreads();  // (the next cell overwrites the table)
     }
+    __syncthreads();
     bitonic_sort(pool, a.cap);
     const int found = count_s < a.k ? count_s : a.k;
     int64_t *ids = a.split > 1 ? a.part_i + (q * a.split + sub) * a.k : a.ids + q * a.k;
