@@ -42,8 +42,8 @@ OPS_PER_PAIR = {8: 5, 16: 9}
 # slices, workgroups): a change of kernel or shape makes the figure null instead of stale.
 # Sources: profiles/scan_mfma_kernel_flat64_ht24.md, profiles/scan_kernel_flat64_ht24.md.
 MEASURED_TRAFFIC_BYTES = {
-    ("flat64", 24, "scan_mfma_kernel m=8 tq=16 waves=16 slices=2 tiles=738"): 1.9502e10,
-    ("flat64", 24, "scan_kernel m=8 tq=8 waves=8 slices=2 tiles=1476"): 9.8135e10,
+    ("flat64", 24, "scan_mfma_kernel m=8 tq=16 waves=16 slices=2 tiles=738"): 1.9387e10,
+    ("flat64", 24, "scan_kernel m=8 tq=8 waves=8 slices=2 tiles=1476"): 9.7082e10,
 }
 
 
