@@ -218,8 +218,7 @@ struct ImiScanArgs {
     int split;               // workgroups per query: workgroup s of a query takes its cells s, s + split, ...
 };
 
-// Dynamic LDS: [M][256] query share, [M][256] cell table, dim floats (residual), M floats, M
-// (value, index) pairs per wave, cap keys.
+// Dynamic LDS: [M][256] query share, [M][256] cell table, dim floats (residual; dim is even), cap keys.
 //
 // A cell is short work behind several trips to memory (its bounds, its two half-centroids, its
 // two half tables, its codes), so the trips are taken off the path of the cell they belong to: the
@@ -234,9 +233,7 @@ imi_scan_kernel(ImiScanArgs a)
     float *tq = (float *)smem;
     float *cellt = tq + M * 256;
     float *res = cellt + M * 256;
-    float *sterm = res + a.dim;
-    unsigned long long *rowbest = (unsigned long long *)(sterm + ((M + 1) & ~1));  // [4 waves][M]
-    unsigned long long *pool = rowbest + 4 * M;
+    unsigned long long *pool = (unsigned long long *)(res + a.dim);
     constexpr int kWindow = 32;
     __shared__ int count_s;
     __shared__ uint32_t qcw[M / 4];
@@ -322,8 +319,17 @@ imi_scan_kernel(ImiScanArgs a)
             const long long begin = win_begin[w], end = win_end[w];
             if (w + 1 < nwin) fetch(w + 1, nxt);
             if (!(begin == end && !a.qcodes_out)) {  // (uniform over the workgroup)
-                // ---- residual to the cell centroid
-                if (tid < a.dim) res[tid] = qv - cur.g;
+                // ---- residual to the cell centroid (one element per thread, held since the cell before;
+                //      vectors of more than 256 dimensions take theirs from memory here)
+                if (a.dim <= 256) {
+                    if (tid < a.dim) res[tid] = qv - cur.g;
+                } else {
+                    const int cell = win_cell[w];
+                    const int ca = cell / a.k2, cb_ = cell - ca * a.k2;
+                    for (int t = tid; t < a.dim; t += 256)
+                        res[t] = a.queries[q * a.dim + t] -
+                                 (t < half ? a.c1[(int64_t)ca * half + t] : a.c2[(int64_t)cb_ * half + t - half]);
+                }
                 __syncthreads();
                 // ---- the cell's table: wave w builds rows w * RPW .., four entries of a row per lane;
                 //      the row's minimum (lowest index on ties) is the cell's bit string for that row
@@ -530,7 +536,7 @@ int launch_imi_scan(int m, const float *lut_dev, const float *tab1_dev, const fl
     while (cap < k + 256) cap <<= 1;
     a.cap = cap;
     a.direct = direct ? 1 : 0;
-    const size_t lds = (size_t)2 * m * 256 * 4 + (size_t)dim * 4 + (size_t)((m + 1) & ~1) * 4 + (size_t)4 * m * 8 + (size_t)cap * 8;
+    const size_t lds = (size_t)2 * m * 256 * 4 + (size_t)dim * 4 + (size_t)cap * 8;  // (dim = 2 * m * ..: a multiple of 8 bytes)
     PSC_REQUIRE(lds <= 96 * 1024, "dimension and k too large for the multi-index scan");
     if (m == 8) {
         hipLaunchKernelGGL(imi_scan_kernel<8>, dim3((unsigned)(nq * split)), dim3(256), lds, s, a);

@@ -131,6 +131,15 @@ def test_imi_in_another_dimension_without_exact_ties():
     _check((psc, s), 50, 25, 2500, 26, 30)
 
 
+def test_imi_with_more_dimensions_than_threads():
+    """384-D vectors (48 dimensions per sub-quantizer, more dimensions than a workgroup has threads):
+    the residual is then put together in several turns per thread."""
+    import paper_1609_01882_amd as psc
+    s = build_imi(psc, 20_000, 11, 9, seed=85, dim=384, noise=0.7)
+    _check((psc, s), 30, 20, 3000, 28, 20)
+    _check((psc, s), 300, 8, 0, 64, 10)
+
+
 def test_one_centroid_in_the_second_half_is_the_inverted_file():
     """K2 = 1: the multi-index is an inverted file over the first-half centroids; the library's two
     searches agree on lists and results (distances to float32 rounding: different table kernels)."""
