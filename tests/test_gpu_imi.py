@@ -117,6 +117,21 @@ def test_imi_with_36000_cells(imi_many_cells, nq, max_lists, max_codes, ht, k):
     _check(imi_many_cells, nq, max_lists, max_codes, ht, k)
 
 
+def test_imi_settings_drawn_at_random(imi_many_cells):
+    """Caps, threshold, k and batch size drawn (seeded) from the values around which the library
+    changes what it does: 64 and 256 cells (the passes over the cell order), 256 queries (several
+    workgroups per query up to there), k beyond one pool."""
+    rng = np.random.default_rng(4242)
+    for _ in range(14):
+        max_lists = int(rng.choice([1, 3, 16, 63, 64, 65, 255, 256, 257, 600, 1024]))
+        max_codes = int(rng.choice([0, 1, 30, 80, 200, 1000, 5000, 40_000]))
+        ht = int(rng.choice([0, 16, 24, 28, 40, 64]))
+        k = int(rng.choice([1, 10, 100, 300, 1000]))
+        nq = int(rng.choice([1, 3, 20, 64, 256, 257]))
+        print(f"imi drawn: lists={max_lists} codes={max_codes} ht={ht} k={k} nq={nq}", flush=True)
+        _check(imi_many_cells, nq, max_lists, max_codes, ht, k)
+
+
 def test_imi_with_128_bit_codes():
     import paper_1609_01882_amd as psc
     s = build_imi(psc, 30_000, 10, 11, seed=83, m=16)
